@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark: SpMV throughput of the searched plans on the five synthetic matrices, on one MI355X.
+
+One "step" is one spmv_run on each configured matrix (inputs and plans resident in HBM before the
+timed region).  Prints ONE JSON line: whole-job GFLOP/s (2 * sum(nnz) / sum(time)), per-matrix
+GFLOP/s and achieved bandwidth as a fraction of the 8 TB/s HBM peak, the roofline record of the
+dominant kernel (timed live with HIP events on the launch stream), and the CPU oracle timed on the
+host cores as a baseline.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12   # bytes/s, MI355X published peak
+
+CONFIGS = {
+    "C1": ("uniform 10k x 10k, 10 nnz/row, fp64", "C1", "float64"),
+    "C2": ("2D 5-point Laplacian 1024x1024 grid, fp64", "C2", "float64"),
+    "C3": ("power-law 4.19M rows, mean 16 nnz/row, fp64", "C3", "float64"),
+    "C4": ("FEM-like 3x3 blocks, 1M block rows, fp64", "C4", "float64"),
+    "C5": ("hybrid 8.39M rows: 1000 rows x 100k + rows of 2-8, fp64", "C5", "float64"),
+    "C5f32": ("hybrid 8.39M rows: 1000 rows x 100k + rows of 2-8, fp32", "C5", "float32"),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--configs", default="C1,C2,C3,C4,C5,C5f32")
+    ap.add_argument("--budget-ms", type=float, default=8000.0, help="search budget per matrix")
+    ap.add_argument("--plan", default="", help="force this plan spec for every matrix (skips the search)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--verbose", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; SpMV here is a single-device kernel path and no "
+              "multi-GPU figure exists (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import inputs
+    import paper_2212_10432_amd as lib
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    lib.load()
+    names = [c for c in args.configs.split(",") if c]
+    log = (lambda *a: print(*a, file=sys.stderr, flush=True)) if args.verbose else (lambda *a: None)
+
+    items = []
+    cpu = {"seconds": 0.0, "flops": 0.0, "cores": 0, "sample": []}
+    cache = {}
+    for name in names:
+        desc, fam, dt = CONFIGS[name]
+        dt = np.dtype(dt)
+        t0 = time.time()
+        if fam not in cache:
+            cache.clear()
+            cache[fam] = inputs.FULL[fam]()
+        m = cache[fam]
+        vals = m.values.astype(dt)
+        x = inputs.vector(m.ncols).astype(dt)
+        t_gen = time.time() - t0
+        t0 = time.time()
+        plan = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, vals, force_plan=args.plan or None,
+                        search_budget_ms=args.budget_ms, verbosity=int(args.verbose))
+        t_plan = time.time() - t0
+        d = plan.describe()
+        b_plan, b_csr = plan.bytes()
+        tdt = torch.float64 if dt == np.float64 else torch.float32
+        footprint = b_plan
+        # matrices that fit the 256 MB Infinity Cache are rotated over independent copies so that the
+        # steady state streams from HBM; tiny ones (launch-latency bound) are left alone
+        copies = 1
+        if 16e6 < footprint < 512e6:
+            copies = int(math.ceil(640e6 / footprint))
+        plans = [plan] + [lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, vals, force_plan=d["spec"])
+                          for _ in range(copies - 1)]
+        xs = [torch.from_numpy(x).to(dev) for _ in range(copies)]
+        ys = [torch.empty(m.nrows, dtype=tdt, device=dev) for _ in range(copies)]
+        if not args.no_cpu:
+            import oracle
+            threads = len(os.sched_getaffinity(0))
+            oracle.spmv(m.row_ptr, m.col_idx, vals, x, threads=threads)          # warm-up
+            ts = []
+            for _ in range(3):
+                t0 = time.perf_counter()
+                oracle.spmv(m.row_ptr, m.col_idx, vals, x, threads=threads)
+                ts.append(time.perf_counter() - t0)
+            cpu["seconds"] += sorted(ts)[1]
+            cpu["flops"] += 2.0 * m.nnz
+            cpu["cores"] = threads
+            cpu["sample"].append(name)
+        items.append(dict(name=name, desc=desc, nnz=m.nnz, nrows=m.nrows, dtype=dt.name, plans=plans, xs=xs, ys=ys,
+                          copies=copies, b_plan=b_plan, b_csr=b_csr, spec=d["spec"], operators=d["operators"],
+                          launches=plan.launch_names(), gen_s=t_gen, plan_s=t_plan,
+                          search=[(c["spec"], c["run_us"], c["note"]) for c in d["search"]]))
+        log(f"{name}: nnz={m.nnz} gen {t_gen:.1f}s plan {t_plan:.1f}s -> {d['spec']} (copies={copies})")
+        del vals, x
+    cache.clear()
+
+    stream = torch.cuda.current_stream()
+
+    def step(k):
+        for it in items:
+            i = k % it["copies"]
+            it["plans"][i].run(it["xs"][i], it["ys"][i], stream.cuda_stream)
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    # the timed region: exactly --steps steps, bracketed by synchronisation
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(k)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-matrix and per-launch times with HIP events on the launch stream
+    for it in items:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(args.steps, 20)
+        e0.record(stream)
+        for k in range(reps):
+            i = k % it["copies"]
+            it["plans"][i].run(it["xs"][i], it["ys"][i], stream.cuda_stream)
+        e1.record(stream)
+        e1.synchronize()
+        it["ms"] = e0.elapsed_time(e1) / reps
+        # warm (cache-resident) figure for rotated matrices
+        if it["copies"] > 1:
+            e0.record(stream)
+            for k in range(reps):
+                it["plans"][0].run(it["xs"][0], it["ys"][0], stream.cuda_stream)
+            e1.record(stream)
+            e1.synchronize()
+            it["ms_warm"] = e0.elapsed_time(e1) / reps
+        per = np.zeros(len(it["launches"]))
+        nrep = 10
+        for k in range(nrep):
+            i = k % it["copies"]
+            per += np.array(it["plans"][i].run_timed(it["xs"][i], it["ys"][i], stream.cuda_stream))
+        it["launch_ms"] = (per / nrep).tolist()
+
+    per_config = []
+    tot_ms = sum(it["ms"] for it in items)
+    tot_nnz = sum(it["nnz"] for it in items)
+    for it in items:
+        credited = min(it["b_plan"], it["b_csr"])
+        t = it["ms"] * 1e-3
+        rec = dict(config=it["name"], workload=it["desc"], dtype=it["dtype"], nnz=it["nnz"], us=it["ms"] * 1e3,
+                   gflops=2.0 * it["nnz"] / t / 1e9, bytes_csr=it["b_csr"], bytes_plan=it["b_plan"],
+                   gbps_credited=credited / t / 1e9, hbm_frac=credited / t / HBM_PEAK,
+                   gbps_csr=it["b_csr"] / t / 1e9, gbps_plan=it["b_plan"] / t / 1e9,
+                   plan=it["spec"], operators=it["operators"], launches=it["launches"],
+                   launch_us=[v * 1e3 for v in it["launch_ms"]], rotated_copies=it["copies"],
+                   plan_create_s=it["plan_s"], search=it["search"])
+        if "ms_warm" in it:
+            rec["us_cache_warm"] = it["ms_warm"] * 1e3
+        per_config.append(rec)
+
+    def geomean(v):
+        return float(np.exp(np.mean(np.log(v)))) if len(v) else None
+
+    # dominant kernel: the launch with the largest share of a step
+    dom = max(((it, i) for it in items for i in range(len(it["launches"]))), key=lambda p: p[0]["launch_ms"][p[1]])
+    dit, di = dom
+    dshare = dit["launch_ms"][di] / max(sum(dit["launch_ms"]), 1e-12)
+    dom_bytes = min(dit["b_plan"], dit["b_csr"]) * dshare if len(dit["launches"]) > 1 else min(dit["b_plan"], dit["b_csr"])
+    achieved = dom_bytes / (dit["launch_ms"][di] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(dit["name"])
+        except Exception:
+            traffic = None
+    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK / 1e9, unit="GB/s", frac=achieved / (HBM_PEAK / 1e9),
+                    traffic=traffic, kernel=f"{dit['name']}:{dit['launches'][di]}",
+                    launch_us=dit["launch_ms"][di] * 1e3, algorithmic_bytes=dom_bytes)
+
+    out = {
+        "metric": "SpMV GFLOP/s (2*nnz/time) and achieved HBM GB/s (fraction of 8 TB/s peak) per matrix, 1 MI355X",
+        "value": 2.0 * tot_nnz / (tot_ms * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": tot_ms, "wall_ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64" if all(it["dtype"] == "float64" for it in items) else "f64+f32",
+        "data": "synthetic",
+        "config": {"workload": "+".join(names) + " (seeded synthetic stand-ins for SuiteSparse), one spmv_run per matrix per step"},
+        "geomean_gflops": geomean([r["gflops"] for r in per_config]),
+        "geomean_hbm_frac": geomean([r["hbm_frac"] for r in per_config]),
+        "geomean_hbm_frac_without_C1": geomean([r["hbm_frac"] for r in per_config if r["config"] != "C1"]),
+        "per_config": per_config,
+        "roofline": roofline,
+    }
+    if not args.no_cpu and cpu["seconds"] > 0:
+        out["cpu_baseline"] = dict(value=cpu["flops"] / cpu["seconds"] / 1e9, unit="GFLOP/s", cores=cpu["cores"],
+                                   kind="oracle", sample="one full oracle SpMV (median of 3) on each of " + ",".join(cpu["sample"]))
+    for it in items:
+        for p in it["plans"]:
+            p.destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

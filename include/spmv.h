@@ -1,0 +1,146 @@
+/*
+ * spmv.h -- C ABI of the MI355X (gfx950) SpMV plan/search library.
+ *
+ * The library computes y = A*x (paper, Section I) for a sparse matrix A given once in CSR.
+ * spmv_plan_create runs the paper's pipeline on the host and the device:
+ *   - a census of the sparsity pattern (row-length statistics, diagonals, dense blocks) that
+ *     prunes the candidate designs (Section VI-B, "Pruning");
+ *   - the converting and mapping operators of Table II (ROW_DIV / COL_DIV, SORT, SORT_SUB, BIN,
+ *     *_ROW_BLOCK, *_COL_BLOCK, *_PAD), plus the three strategies the paper lists as missing in
+ *     Section VII-F (HYB-like split of heavy rows, diagonal extraction, dense r x c blocks),
+ *     which turn the CSR arrays into the device layout of one candidate plan (Sections IV, V-A,
+ *     V-B);
+ *   - the search (Section VI-A, level two): every candidate plan is run and timed on the device
+ *     and the fastest is kept.
+ * spmv_run executes the kept plan: one or a few hand-written HIP kernels, each using one of the
+ * reduction strategies of the implementing stage (Table II: THREAD_TOTAL_RED, WARP_TOTAL_RED,
+ * GMEM_ATOM_RED, ...; Section V-C "Distribution" and "Reduction").
+ *
+ * Conventions
+ *   - Every function returns spmv_status_t; nothing throws, aborts or exits.  On failure
+ *     spmv_last_error() (thread-local) holds a message.
+ *   - "HOST" pointers are ordinary process memory; "DEVICE" pointers are HIP device memory on
+ *     the device that was current when the plan was created.
+ *   - Indices are int32; nnz must be < 2^31.  Values are float or double (spmv_dtype_t).
+ *   - Empty rows and an empty matrix are legal (y_i = +0).  Within a row the column order is
+ *     free and repeated columns are legal (they add).
+ *   - x must be finite: padded slots multiply an explicit 0 by an x element.
+ */
+#ifndef SPMV_MI355_H
+#define SPMV_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spmv_plan spmv_plan_t; /* opaque; owned by the library */
+
+typedef enum { SPMV_F32 = 0, SPMV_F64 = 1 } spmv_dtype_t;
+
+typedef enum {
+    SPMV_OK = 0,
+    SPMV_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad option or plan-spec string */
+    SPMV_ERR_BAD_CSR = 2,     /* row_ptr not monotone / wrong ends, column out of range */
+    SPMV_ERR_UNSUPPORTED = 3, /* nnz >= 2^31, unknown dtype, forced plan illegal for this matrix */
+    SPMV_ERR_ALLOC = 4,       /* host or device allocation failed */
+    SPMV_ERR_HIP = 5,         /* a HIP call failed; text in spmv_last_error() */
+    SPMV_ERR_INTERNAL = 6
+} spmv_status_t;
+
+/* All fields optional; a NULL options pointer, or a zeroed struct, means defaults. */
+typedef struct {
+    /* Plan-spec string ("key=value,key=value"): skip the search and build exactly this plan.
+     * NULL or "" = search.  The grammar is printed by spmv_plan_describe ("spec"). */
+    const char *force_plan;
+    /* Wall-clock cap for the search in milliseconds.  0 = default (8000).  Negative = no timing:
+     * the first candidate of the pruned list is taken (a deterministic function of the census). */
+    double search_budget_ms;
+    int search_repeats; /* timed runs per candidate; 0 = default (5) */
+    int host_threads;   /* threads of the host format builder; 0 = all available */
+    /* Device allocator pair, e.g. backed by the caller's framework.  NULL = hipMalloc/hipFree. */
+    void *(*dev_alloc)(size_t bytes, void *user);
+    void (*dev_free)(void *ptr, void *user);
+    void *user;
+    int verbosity; /* > 0: progress of the search on stderr */
+    /* Non-zero: build the format arrays in HOST memory only, touching no device, so that the
+     * layout can be inspected (spmv_plan_array_copy) on a machine without a GPU.  Needs
+     * force_plan or a negative search_budget_ms (nothing can be timed); spmv_run refuses such a
+     * plan with SPMV_ERR_UNSUPPORTED.  dev_alloc / dev_free are ignored. */
+    int host_only;
+} spmv_options_t;
+
+/*
+ * Build a plan for A (Sections IV-VI).  The CSR arrays are HOST memory, borrowed for the
+ * duration of the call only; the plan keeps its own device copy in its own layout.
+ *   row_ptr : nrows+1 entries, row_ptr[0] == 0, non-decreasing, row_ptr[nrows] == nnz
+ *   col_idx : nnz entries, 0 <= c < ncols
+ *   values  : nnz entries of `dtype`
+ * On success *out is a plan to be released with spmv_plan_destroy; on failure *out is NULL.
+ * Synchronises the device (uploads, timed candidate runs on a private stream).
+ */
+spmv_status_t spmv_plan_create(spmv_plan_t **out, int64_t nrows, int64_t ncols, int64_t nnz,
+                               const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                               spmv_dtype_t dtype, const spmv_options_t *opts);
+
+/*
+ * y = A*x with the plan's kernels (Section V-C), enqueued on `stream`; returns without
+ * synchronising.
+ *   x_dev  : DEVICE, ncols elements of the plan's dtype, finite; must not alias y_dev
+ *   y_dev  : DEVICE, nrows elements, every element OVERWRITTEN
+ *   stream : a hipStream_t (NULL = the default stream)
+ * No allocation, no host synchronisation.  A plan is immutable; concurrent runs of one plan on
+ * different streams are safe as long as their y buffers differ.
+ */
+spmv_status_t spmv_run(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream);
+
+/*
+ * Same as spmv_run, but records a HIP event on `stream` before the first and after every launch,
+ * waits for the last one (this call SYNCHRONISES the stream) and writes the duration of launch i
+ * in milliseconds to launch_ms[i] (spmv_plan_launch_count entries).  For benchmarks and profiles.
+ */
+spmv_status_t spmv_run_timed(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
+                             float *launch_ms);
+
+/* Free the plan's device arrays (through the allocator pair it was created with). NULL is OK. */
+spmv_status_t spmv_plan_destroy(spmv_plan_t *plan);
+
+/* ---- introspection (used by the parity tests and the benchmark) ------------------------- */
+
+/*
+ * JSON description: the plan-spec string, the same design spelled as a chain of the paper's
+ * operators (Table II names), census statistics, per-part sizes and the search log.
+ * Writes at most cap bytes including the terminating NUL; *needed (may be NULL) receives the
+ * full size including the NUL.
+ */
+spmv_status_t spmv_plan_describe(const spmv_plan_t *plan, char *buf, size_t cap, size_t *needed);
+
+/* The plan's device format arrays (Section V-B, "Format Construction"): count, metadata, copy. */
+spmv_status_t spmv_plan_array_count(const spmv_plan_t *plan, int *n);
+/* *name points into the plan and stays valid until spmv_plan_destroy. */
+spmv_status_t spmv_plan_array_info(const spmv_plan_t *plan, int i, const char **name,
+                                   int *elem_bytes, int64_t *count);
+/* Synchronous device-to-host copy of array i into host_dst (elem_bytes * count bytes). */
+spmv_status_t spmv_plan_array_copy(const spmv_plan_t *plan, int i, void *host_dst);
+
+/*
+ * Algorithmic bytes of one spmv_run:
+ *   *b_plan = bytes of the format arrays the plan's kernels read, plus x once and y once (plus
+ *             y again for every extra pass a plan makes over y);
+ *   *b_csr  = nnz*(v+4) + 4*(nrows+1) + v*ncols + v*nrows, the same for plain CSR (v = 4 or 8).
+ */
+spmv_status_t spmv_plan_bytes(const spmv_plan_t *plan, int64_t *b_plan, int64_t *b_csr);
+
+/* Number of kernel launches spmv_run makes for this plan, and the name of launch i. */
+spmv_status_t spmv_plan_launch_count(const spmv_plan_t *plan, int *n);
+spmv_status_t spmv_plan_launch_name(const spmv_plan_t *plan, int i, const char **name);
+
+/* Message of the last failure on the calling thread ("" if none). */
+const char *spmv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPMV_MI355_H */

@@ -1,0 +1,323 @@
+"""TEST ORACLE -- not part of the product.  Reference format builders and decoders in NumPy.
+
+The library's host builder (C++) turns CSR into operator-composed layouts.  This module restates
+each layout from its definition, independently and slowly, so that the library's index arrays can
+be compared bit for bit, and decodes any plan's arrays back to (row, col, value) triples so that
+"the layout still holds exactly the input matrix" can be checked for every plan.
+
+Operators follow Table II of the paper; the readings of what it leaves open are:
+  SORT / SORT_SUB  stable, decreasing row length; windows of sigma rows from the part's first row
+  *_PAD            pad every row of a 64-row slice to the slice's longest row with value 0 and the
+                   column of the row's last real entry (0 for an empty row)
+  BIN              three bins: length <= smax, <= 128, > 128
+  ROW_DIV (heavy)  rows longer than the threshold
+  COL_DIV (heavy)  stripes of `tile` columns; segments ordered stripe-major, then heavy row
+Diagonal extraction, heavy-row split and dense blocks are the strategies Section VII-F names as
+missing from the paper; they are built from their textbook definitions.
+
+Parity pins: tests/test_format_host.py checks these builders against closed forms (C1: stable sort
+is the identity and padding is zero; C2: five diagonals at {-g,-1,0,1,g} with 4g explicit zeros;
+C4: 3x3 fill is 100 %; C5: the heavy split selects exactly the generator's heavy rows) and checks
+that decode(reference arrays) reproduces the input matrix.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+WAVE = 64
+
+
+def parse_spec(spec: str) -> dict:
+    d = dict(dia=0, dia_fill=0.5, heavy=0, tile=8192, hlps=16, light="csrv", lpr=0, chunk=0,
+             sigma=0, block=3, smax=16, remap=0)
+    for tok in spec.split(","):
+        if not tok:
+            continue
+        k, v = tok.split("=")
+        d[k] = v if k == "light" else (float(v) if k == "dia_fill" else int(float(v)))
+    return d
+
+
+def _sort_rows(rows, lens, sigma):
+    rows = np.asarray(rows, dtype=np.int32)
+    if sigma == 0 or rows.size < 2:
+        return rows
+    win = rows.size if sigma < 0 else sigma
+    out = []
+    for b in range(0, rows.size, win):
+        w = rows[b:b + win]
+        out.append(w[np.argsort(-lens[w], kind="stable")])
+    return np.concatenate(out)
+
+
+def _row_entries(rp, r):
+    return slice(int(rp[r]), int(rp[r + 1]))
+
+
+def ref_sell(rp, ci, va, rows, sigma, nrows_total, name):
+    lens = np.diff(rp).astype(np.int64)
+    rows = np.asarray(rows, dtype=np.int32)
+    if rows.size == 0:
+        return {}
+    ident = sigma == 0 and rows.size == nrows_total and np.array_equal(rows, np.arange(nrows_total))
+    order = _sort_rows(rows, lens, sigma)
+    n = order.size
+    nsl = -(-n // WAVE)
+    slice_ptr = np.zeros(nsl + 1, dtype=np.int64)
+    for s in range(nsl):
+        slice_ptr[s + 1] = slice_ptr[s] + WAVE * lens[order[s * WAVE:(s + 1) * WAVE]].max()
+    cols = np.zeros(slice_ptr[-1], dtype=np.int32)
+    vals = np.zeros(slice_ptr[-1], dtype=va.dtype)
+    for s in range(nsl):
+        base, w = slice_ptr[s], (slice_ptr[s + 1] - slice_ptr[s]) // WAVE
+        for lane in range(WAVE):
+            i = s * WAVE + lane
+            pos = base + lane + WAVE * np.arange(w)
+            if i < n:
+                e = _row_entries(rp, order[i])
+                L = e.stop - e.start
+                cols[pos[:L]] = ci[e]
+                vals[pos[:L]] = va[e]
+                cols[pos[L:]] = ci[e.stop - 1] if L else 0
+    out = {name + ".slice_ptr": slice_ptr, name + ".cols": cols, name + ".vals": vals}
+    if not ident:
+        out[name + ".origin_rows"] = order
+    return out
+
+
+def ref_csrv(rp, ci, va, rows, lpr, chunk, sigma, acc, nrows_total, name, zero_rows):
+    lens = np.diff(rp).astype(np.int64)
+    rows = np.asarray(rows, dtype=np.int32)
+    if rows.size == 0:
+        return {}
+    split = chunk > 0 and lens[rows].max() > chunk
+    ident = (not split) and sigma == 0 and rows.size == nrows_total and np.array_equal(rows, np.arange(nrows_total))
+    if ident:
+        return {name + ".seg_ptr": np.asarray(rp, dtype=np.int32), name + ".cols": ci, name + ".vals": va}
+    order = _sort_rows(rows, lens, sigma)
+    seg_ptr, seg_row, cols, vals, pos = [], [], [], [], 0
+    for r in order:
+        e = _row_entries(rp, r)
+        L = e.stop - e.start
+        if split and L > chunk:
+            if not acc:
+                zero_rows.append(int(r))
+            for o in range(0, L, chunk):
+                seg_ptr.append(pos + o)
+                seg_row.append(~int(r))
+        else:
+            seg_ptr.append(pos)
+            seg_row.append(int(r))
+        cols.append(ci[e])
+        vals.append(va[e])
+        pos += L
+    seg_ptr.append(pos)
+    return {name + ".seg_ptr": np.array(seg_ptr, dtype=np.int32), name + ".seg_row": np.array(seg_row, dtype=np.int32),
+            name + ".cols": np.concatenate(cols).astype(np.int32), name + ".vals": np.concatenate(vals).astype(va.dtype)}
+
+
+def diag_census(nrows, ncols, rp, ci, fill=0.5):
+    """Offsets whose population (entries / rows where the offset stays inside the matrix) >= fill."""
+    r = np.repeat(np.arange(nrows, dtype=np.int64), np.diff(rp))
+    off, cnt = np.unique(ci.astype(np.int64) - r, return_counts=True)
+    keep = []
+    for o, c in zip(off, cnt):
+        valid = min(nrows, ncols - o) - max(0, -o)
+        if valid > 0 and c >= fill * valid and 2 * c >= valid:
+            keep.append(int(o))
+    return np.array(keep, dtype=np.int32)
+
+
+def ref_dia(nrows, ncols, rp, ci, va, offs):
+    ld = -(-nrows // WAVE) * WAVE
+    r = np.repeat(np.arange(nrows, dtype=np.int64), np.diff(rp))
+    off = ci.astype(np.int64) - r
+    on = np.isin(off, offs)
+    dv = np.zeros((len(offs), ld), dtype=va.dtype)
+    d_idx = np.searchsorted(offs, off[on])
+    np.add.at(dv, (d_idx, r[on]), va[on])
+    rem_rp = np.zeros(nrows + 1, dtype=np.int32)
+    np.cumsum(np.bincount(r[~on], minlength=nrows), out=rem_rp[1:])
+    return {"dia.offsets": np.asarray(offs, dtype=np.int32), "dia.vals": dv.reshape(-1)}, (rem_rp, ci[~on], va[~on])
+
+
+def ref_bsell(nrows, ncols, rp, ci, va, B, sigma):
+    nb = nrows // B
+    bcl = []
+    for br in range(nb):
+        e = slice(int(rp[br * B]), int(rp[(br + 1) * B]))
+        bcl.append(np.unique(ci[e] // B))
+    nblk = np.array([len(b) for b in bcl], dtype=np.int64)
+    order = _sort_rows(np.arange(nb, dtype=np.int32), nblk, sigma)
+    nsl = -(-nb // WAVE)
+    slice_ptr = np.zeros(nsl + 1, dtype=np.int64)
+    for s in range(nsl):
+        slice_ptr[s + 1] = slice_ptr[s] + WAVE * nblk[order[s * WAVE:(s + 1) * WAVE]].max()
+    bcols = np.zeros(slice_ptr[-1], dtype=np.int32)
+    vals = np.zeros(slice_ptr[-1] * B * B, dtype=va.dtype)
+    for s in range(nsl):
+        base, w = slice_ptr[s], (slice_ptr[s + 1] - slice_ptr[s]) // WAVE
+        for lane in range(WAVE):
+            i = s * WAVE + lane
+            if i >= nb:
+                continue
+            br = order[i]
+            bc = bcl[br]
+            L = len(bc)
+            bcols[base + lane + WAVE * np.arange(L)] = bc
+            bcols[base + lane + WAVE * np.arange(L, w)] = bc[-1] if L else 0
+            for ri in range(B):
+                e = _row_entries(rp, br * B + ri)
+                j = np.searchsorted(bc, ci[e] // B)
+                q = j * B * B + ri * B + (ci[e] % B)
+                np.add.at(vals, base * B * B + q * WAVE + lane, va[e])
+    out = {"bsell.slice_ptr": slice_ptr, "bsell.bcols": bcols, "bsell.vals": vals}
+    if sigma != 0:
+        out["bsell.origin_brows"] = order
+    return out
+
+
+def ref_stripe(ncols, rp, ci, va, hrows, tile):
+    nh = len(hrows)
+    if nh == 0:
+        return {}
+    ns = -(-ncols // tile)
+    segs = [[None] * nh for _ in range(ns)]
+    for h, r in enumerate(hrows):
+        e = _row_entries(rp, r)
+        c, v = ci[e], va[e]
+        s_of = c // tile
+        for s in np.unique(s_of):
+            m = s_of == s
+            segs[s][h] = ((c[m] - s * tile).astype(np.uint16), v[m])
+    seg_ptr, lcols, vals = [0], [], []
+    for s in range(ns):
+        for h in range(nh):
+            if segs[s][h] is not None:
+                lcols.append(segs[s][h][0])
+                vals.append(segs[s][h][1])
+                seg_ptr.append(seg_ptr[-1] + len(segs[s][h][0]))
+            else:
+                seg_ptr.append(seg_ptr[-1])
+    return {"heavy.seg_ptr": np.array(seg_ptr, dtype=np.int32), "heavy.lcols": np.concatenate(lcols),
+            "heavy.vals": np.concatenate(vals).astype(va.dtype), "heavy.rows": np.asarray(hrows, dtype=np.int32)}
+
+
+def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
+    """All format arrays of the plan `spec` for a CSR matrix with ascending columns in each row."""
+    p = parse_spec(spec)
+    out = {}
+    acc = False
+    if p["dia"]:
+        offs = diag_census(nrows, ncols, rp, ci, p["dia_fill"])
+        arrays, (rp, ci, va) = ref_dia(nrows, ncols, rp, ci, va, offs)
+        out.update(arrays)
+        acc = True
+        if ci.size == 0:
+            return out
+    lens = np.diff(rp).astype(np.int64)
+    if p["light"] == "bsell":
+        out.update(ref_bsell(nrows, ncols, rp, ci, va, p["block"], p["sigma"]))
+        return out
+    allrows = np.arange(nrows, dtype=np.int32)
+    heavy = allrows[lens > p["heavy"]] if p["heavy"] > 0 else allrows[:0]
+    is_light = np.ones(nrows, dtype=bool)
+    is_light[heavy] = False
+    if acc:
+        is_light &= lens > 0
+    light = allrows[is_light]
+    zero_rows = [] if acc else [int(r) for r in heavy]
+    if p["light"] == "csrv":
+        lpr = p["lpr"]
+        out.update(ref_csrv(rp, ci, va, light, lpr, p["chunk"], p["sigma"], acc, nrows, "csrv", zero_rows))
+    elif p["light"] == "sell":
+        out.update(ref_sell(rp, ci, va, light, p["sigma"], nrows, "sell"))
+    elif p["light"] == "bin":
+        L = lens[light]
+        out.update(ref_sell(rp, ci, va, light[L <= p["smax"]], p["sigma"], nrows, "bin0.sell"))
+        out.update(ref_csrv(rp, ci, va, light[(L > p["smax"]) & (L <= 128)], 8, 0, p["sigma"], acc, nrows, "bin1.csrv8", zero_rows))
+        out.update(ref_csrv(rp, ci, va, light[L > max(128, p["smax"])], 64, p["chunk"], 0, acc, nrows, "bin2.csrv64", zero_rows))
+    else:
+        raise ValueError(p["light"])
+    out.update(ref_stripe(ncols, rp, ci, va, heavy, p["tile"]))
+    if zero_rows:
+        out["zero.rows"] = np.array(sorted(zero_rows), dtype=np.int32)
+    return out
+
+
+# ---- decoding: plan arrays -> (row, col, value) triples --------------------------------------
+
+def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 8192):
+    """Every stored entry of every part as COO triples (padding included: it carries value 0).
+    The part kind is recognised from the array names."""
+    R, C, V = [], [], []
+    prefixes = sorted({k.rsplit(".", 1)[0] for k in arrays})
+    for pre in prefixes:
+        a = {k.rsplit(".", 1)[1]: v for k, v in arrays.items() if k.rsplit(".", 1)[0] == pre}
+        if pre == "zero":
+            continue
+        if pre == "dia":
+            offs, dv = a["offsets"], a["vals"]
+            ld = dv.size // max(len(offs), 1)
+            for d, off in enumerate(offs):
+                r = np.arange(nrows, dtype=np.int64)
+                c = r + int(off)
+                ok = (c >= 0) & (c < ncols)
+                R.append(r[ok]); C.append(c[ok]); V.append(dv[d * ld:d * ld + nrows][ok])
+        elif pre == "bsell":
+            sp, bc, vv = a["slice_ptr"], a["bcols"], a["vals"]
+            nb = nrows // block
+            order = a.get("origin_brows", np.arange(nb, dtype=np.int32))
+            BB = block * block
+            for s in range(len(sp) - 1):
+                base, w = int(sp[s]), int(sp[s + 1] - sp[s]) // WAVE
+                for lane in range(WAVE):
+                    i = s * WAVE + lane
+                    if i >= nb:
+                        continue
+                    br = int(order[i])
+                    for j in range(w):
+                        b = int(bc[base + j * WAVE + lane])
+                        for q in range(BB):
+                            R.append([br * block + q // block]); C.append([b * block + q % block])
+                            V.append([vv[base * BB + (j * BB + q) * WAVE + lane]])
+        elif "slice_ptr" in a:   # SELL
+            sp, cc, vv = a["slice_ptr"], a["cols"], a["vals"]
+            nsl = len(sp) - 1
+            order = a.get("origin_rows")
+            for s in range(nsl):
+                base, w = int(sp[s]), int(sp[s + 1] - sp[s]) // WAVE
+                for lane in range(WAVE):
+                    i = s * WAVE + lane
+                    if order is None:
+                        if i >= nrows:
+                            continue
+                        r = i
+                    else:
+                        if i >= len(order):
+                            continue
+                        r = int(order[i])
+                    pos = base + lane + WAVE * np.arange(w)
+                    R.append(np.full(w, r, dtype=np.int64)); C.append(cc[pos]); V.append(vv[pos])
+        elif "lcols" in a:       # heavy stripes
+            sp, lc, vv, hr = a["seg_ptr"], a["lcols"], a["vals"], a["rows"]
+            nh = len(hr)
+            for g in range(len(sp) - 1):
+                s, h = divmod(g, nh)
+                e = slice(int(sp[g]), int(sp[g + 1]))
+                n = e.stop - e.start
+                R.append(np.full(n, int(hr[h]), dtype=np.int64)); C.append(lc[e].astype(np.int64) + s * tile); V.append(vv[e])
+        else:                    # CSR segments
+            sp, cc, vv = a["seg_ptr"], a["cols"], a["vals"]
+            sr = a.get("seg_row")
+            for g in range(len(sp) - 1):
+                r = g if sr is None else int(sr[g])
+                if r < 0:
+                    r = ~r
+                e = slice(int(sp[g]), int(sp[g + 1]))
+                R.append(np.full(e.stop - e.start, r, dtype=np.int64)); C.append(cc[e]); V.append(vv[e])
+    if not R:
+        return np.zeros(0, np.int64), np.zeros(0, np.int64), np.zeros(0)
+    return (np.concatenate([np.asarray(x, dtype=np.int64) for x in R]),
+            np.concatenate([np.asarray(x, dtype=np.int64) for x in C]),
+            np.concatenate([np.asarray(x) for x in V]))

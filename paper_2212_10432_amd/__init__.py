@@ -1,0 +1,261 @@
+"""MI355X-native SpMV plan/search library: Python binding of the C ABI in include/spmv.h.
+
+The binding only marshals arguments (ctypes); every step of the path -- census, format
+construction, search, kernels -- runs inside libspmv_mi355.so.  PyTorch is used by callers for
+device buffers and streams only.  There is no CPU fallback: if the shared library is missing or
+cannot be loaded, importing this package's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import json
+import os
+
+import numpy as np
+
+from . import build as _build
+
+SPMV_F32, SPMV_F64 = 0, 1
+SPMV_OK, SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_CSR, SPMV_ERR_UNSUPPORTED = 0, 1, 2, 3
+SPMV_ERR_ALLOC, SPMV_ERR_HIP, SPMV_ERR_INTERNAL = 4, 5, 6
+_STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC", 5: "HIP", 6: "INTERNAL"}
+
+EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_timed", "spmv_plan_destroy", "spmv_plan_describe",
+           "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
+           "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error"]
+
+
+class SpmvError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"SPMV_ERR_{_STATUS.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
+
+
+class spmv_options_t(ctypes.Structure):
+    _fields_ = [("force_plan", ctypes.c_char_p), ("search_budget_ms", ctypes.c_double),
+                ("search_repeats", ctypes.c_int), ("host_threads", ctypes.c_int),
+                ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("user", ctypes.c_void_p),
+                ("verbosity", ctypes.c_int), ("host_only", ctypes.c_int)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Load libspmv_mi355.so (building it if no built library is present).  Raises on failure."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    try:
+        import torch  # noqa: F401  -- makes the process use the HIP runtime PyTorch ships
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(_build.LIB)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    P = ctypes.POINTER
+    lib.spmv_plan_create.restype = ci
+    lib.spmv_plan_create.argtypes = [P(vp), i64, i64, i64, vp, vp, vp, ci, P(spmv_options_t)]
+    lib.spmv_run.restype = ci
+    lib.spmv_run.argtypes = [vp, vp, vp, vp]
+    lib.spmv_run_timed.restype = ci
+    lib.spmv_run_timed.argtypes = [vp, vp, vp, vp, P(ctypes.c_float)]
+    lib.spmv_plan_destroy.restype = ci
+    lib.spmv_plan_destroy.argtypes = [vp]
+    lib.spmv_plan_describe.restype = ci
+    lib.spmv_plan_describe.argtypes = [vp, ctypes.c_char_p, ctypes.c_size_t, P(ctypes.c_size_t)]
+    lib.spmv_plan_array_count.restype = ci
+    lib.spmv_plan_array_count.argtypes = [vp, P(ci)]
+    lib.spmv_plan_array_info.restype = ci
+    lib.spmv_plan_array_info.argtypes = [vp, ci, P(ctypes.c_char_p), P(ci), P(i64)]
+    lib.spmv_plan_array_copy.restype = ci
+    lib.spmv_plan_array_copy.argtypes = [vp, ci, vp]
+    lib.spmv_plan_bytes.restype = ci
+    lib.spmv_plan_bytes.argtypes = [vp, P(i64), P(i64)]
+    lib.spmv_plan_launch_count.restype = ci
+    lib.spmv_plan_launch_count.argtypes = [vp, P(ci)]
+    lib.spmv_plan_launch_name.restype = ci
+    lib.spmv_plan_launch_name.argtypes = [vp, ci, P(ctypes.c_char_p)]
+    lib.spmv_last_error.restype = ctypes.c_char_p
+    lib.spmv_last_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def spmv_last_error() -> str:
+    return load().spmv_last_error().decode()
+
+
+def _check(status: int):
+    if status != SPMV_OK:
+        raise SpmvError(status, spmv_last_error())
+
+
+def _dtype_code(dt) -> int:
+    dt = np.dtype(dt)
+    if dt == np.float64:
+        return SPMV_F64
+    if dt == np.float32:
+        return SPMV_F32
+    raise SpmvError(SPMV_ERR_UNSUPPORTED, f"dtype {dt} (float32 or float64 only)")
+
+
+# ---- functions named after the C ABI ---------------------------------------------------------
+
+def spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, *, force_plan=None,
+                     search_budget_ms=0.0, search_repeats=0, host_threads=0, verbosity=0,
+                     host_only=False, nnz=None) -> int:
+    """Returns an opaque plan handle (int).  row_ptr / col_idx / values are host NumPy arrays."""
+    lib = load()
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
+    col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
+    values = np.ascontiguousarray(values)
+    code = _dtype_code(values.dtype)
+    if nnz is None:
+        nnz = int(values.size)
+    opts = spmv_options_t()
+    opts.force_plan = force_plan.encode() if force_plan else None
+    opts.search_budget_ms = float(search_budget_ms)
+    opts.search_repeats = int(search_repeats)
+    opts.host_threads = int(host_threads)
+    opts.verbosity = int(verbosity)
+    opts.host_only = int(bool(host_only))
+    handle = ctypes.c_void_p()
+    _check(lib.spmv_plan_create(ctypes.byref(handle), nrows, ncols, nnz, row_ptr.ctypes.data,
+                                col_idx.ctypes.data, values.ctypes.data, code, ctypes.byref(opts)))
+    return handle.value
+
+
+def spmv_run(plan: int, x_dev: int, y_dev: int, stream: int = 0) -> None:
+    """x_dev / y_dev are device addresses (tensor.data_ptr()); stream is a hipStream_t value."""
+    _check(load().spmv_run(plan, x_dev, y_dev, stream))
+
+
+def spmv_run_timed(plan: int, x_dev: int, y_dev: int, stream: int = 0):
+    """Runs once, synchronises the stream, returns the per-launch durations in milliseconds."""
+    lib = load()
+    n = ctypes.c_int()
+    _check(lib.spmv_plan_launch_count(plan, ctypes.byref(n)))
+    ms = (ctypes.c_float * max(n.value, 1))()
+    _check(lib.spmv_run_timed(plan, x_dev, y_dev, stream, ms))
+    return [ms[i] for i in range(n.value)]
+
+
+def spmv_plan_destroy(plan: int) -> None:
+    _check(load().spmv_plan_destroy(plan))
+
+
+def spmv_plan_describe(plan: int) -> dict:
+    lib = load()
+    need = ctypes.c_size_t()
+    _check(lib.spmv_plan_describe(plan, None, 0, ctypes.byref(need)))
+    buf = ctypes.create_string_buffer(need.value)
+    _check(lib.spmv_plan_describe(plan, buf, need.value, None))
+    return json.loads(buf.value.decode())
+
+
+def spmv_plan_array_count(plan: int) -> int:
+    n = ctypes.c_int()
+    _check(load().spmv_plan_array_count(plan, ctypes.byref(n)))
+    return n.value
+
+
+def spmv_plan_array_info(plan: int, i: int):
+    name, eb, cnt = ctypes.c_char_p(), ctypes.c_int(), ctypes.c_int64()
+    _check(load().spmv_plan_array_info(plan, i, ctypes.byref(name), ctypes.byref(eb), ctypes.byref(cnt)))
+    return name.value.decode(), eb.value, cnt.value
+
+
+def spmv_plan_array_copy(plan: int, i: int, value_dtype=np.float64) -> np.ndarray:
+    name, eb, cnt = spmv_plan_array_info(plan, i)
+    if name.endswith("vals"):
+        dt = np.dtype(value_dtype)
+    else:
+        dt = {2: np.dtype(np.uint16), 4: np.dtype(np.int32), 8: np.dtype(np.int64)}[eb]
+    assert dt.itemsize == eb, (name, dt, eb)
+    out = np.empty(cnt, dtype=dt)
+    _check(load().spmv_plan_array_copy(plan, i, out.ctypes.data))
+    return out
+
+
+def spmv_plan_bytes(plan: int):
+    a, b = ctypes.c_int64(), ctypes.c_int64()
+    _check(load().spmv_plan_bytes(plan, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
+def spmv_plan_launch_names(plan: int):
+    lib = load()
+    n = ctypes.c_int()
+    _check(lib.spmv_plan_launch_count(plan, ctypes.byref(n)))
+    out = []
+    for i in range(n.value):
+        s = ctypes.c_char_p()
+        _check(lib.spmv_plan_launch_name(plan, i, ctypes.byref(s)))
+        out.append(s.value.decode())
+    return out
+
+
+# ---- a small convenience wrapper over the handle -----------------------------------------------
+
+class Plan:
+    """Owns one plan handle.  `run` takes torch tensors on the plan's device."""
+
+    def __init__(self, nrows, ncols, row_ptr, col_idx, values, **kw):
+        self.nrows, self.ncols = int(nrows), int(ncols)
+        self.value_dtype = np.dtype(np.asarray(values).dtype)
+        self.handle = spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, **kw)
+
+    def run(self, x, y, stream=None):
+        if x.numel() != self.ncols or y.numel() != self.nrows:
+            raise SpmvError(SPMV_ERR_INVALID_ARG, "x / y have the wrong length")
+        if not (x.is_cuda and y.is_cuda and x.is_contiguous() and y.is_contiguous()):
+            raise SpmvError(SPMV_ERR_INVALID_ARG, "x / y must be contiguous device tensors")
+        want = "float64" if self.value_dtype == np.float64 else "float32"
+        if str(x.dtype) != "torch." + want or str(y.dtype) != "torch." + want:
+            raise SpmvError(SPMV_ERR_INVALID_ARG, "x / y dtype differs from the plan's")
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        spmv_run(self.handle, x.data_ptr(), y.data_ptr(), int(stream))
+        return y
+
+    def run_timed(self, x, y, stream=None):
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        return spmv_run_timed(self.handle, x.data_ptr(), y.data_ptr(), int(stream))
+
+    def describe(self) -> dict:
+        return spmv_plan_describe(self.handle)
+
+    def arrays(self) -> dict:
+        return {spmv_plan_array_info(self.handle, i)[0]: spmv_plan_array_copy(self.handle, i, self.value_dtype)
+                for i in range(spmv_plan_array_count(self.handle))}
+
+    def bytes(self):
+        return spmv_plan_bytes(self.handle)
+
+    def launch_names(self):
+        return spmv_plan_launch_names(self.handle)
+
+    def destroy(self):
+        if self.handle:
+            spmv_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

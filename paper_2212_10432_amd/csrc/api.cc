@@ -1,0 +1,334 @@
+// The C ABI of include/spmv.h: argument and CSR validation, exception -> status translation,
+// plan description.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdio>
+#include <sstream>
+
+#include "internal.h"
+
+struct spmv_plan {
+    std::unique_ptr<spmv::Plan> impl;
+};
+
+namespace spmv {
+
+static thread_local std::string g_last_error;
+
+static void *default_alloc(size_t bytes, void *) {
+    void *p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return p;
+}
+static void default_free(void *p, void *) { (void)hipFree(p); }
+static void *host_alloc(size_t bytes, void *) { return std::malloc(bytes); }
+static void host_free(void *p, void *) { std::free(p); }
+
+static void validate_csr(const HostCsr &A, int threads) {
+    if (A.row_ptr[0] != 0) fail(SPMV_ERR_BAD_CSR, "row_ptr[0] must be 0");
+    if ((int64_t)A.row_ptr[A.nrows] != A.nnz) fail(SPMV_ERR_BAD_CSR, "row_ptr[nrows] must equal nnz");
+    std::atomic<int> bad{0};
+    parallel_for(A.nrows, 1 << 14, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t r = b; r < e; ++r) {
+            const int64_t s = A.row_ptr[r], t = A.row_ptr[r + 1];
+            if (t < s || s < 0 || t > A.nnz) {
+                bad = 1;
+                return;
+            }
+            for (int64_t k = s; k < t; ++k)
+                if (A.col[k] < 0 || (int64_t)A.col[k] >= A.ncols) {
+                    bad = 2;
+                    return;
+                }
+        }
+    });
+    if (bad == 1) fail(SPMV_ERR_BAD_CSR, "row_ptr is not non-decreasing within [0, nnz]");
+    if (bad == 2) fail(SPMV_ERR_BAD_CSR, "a column index is outside [0, ncols)");
+}
+
+static std::string json_escape(const std::string &s) {
+    std::string o;
+    for (char ch : s) {
+        if (ch == '"' || ch == '\\') o += '\\';
+        o += ch;
+    }
+    return o;
+}
+
+std::string describe_json(const Plan &plan) {
+    std::ostringstream o;
+    const Census &c = plan.census;
+    o << "{\"spec\": \"" << json_escape(print_spec(plan.spec)) << "\", ";
+    o << "\"operators\": \"" << json_escape(operator_chain(plan.spec)) << "\", ";
+    o << "\"dtype\": \"" << (plan.dtype == SPMV_F64 ? "f64" : "f32") << "\", ";
+    o << "\"nrows\": " << plan.nrows << ", \"ncols\": " << plan.ncols << ", \"nnz\": " << plan.nnz << ", ";
+    o << "\"bytes_plan\": " << plan.bytes_plan() << ", \"bytes_csr\": " << plan.bytes_csr() << ", ";
+    o << "\"census\": {\"min_len\": " << c.min_len << ", \"max_len\": " << c.max_len
+      << ", \"mean_len\": " << c.mean_len << ", \"var_len\": " << c.var_len
+      << ", \"empty_rows\": " << c.empty_rows << ", \"irregular\": " << (c.var_len > 100 ? "true" : "false")
+      << ", \"cols_sorted\": " << (c.cols_sorted ? "true" : "false") << ", \"diag_offsets\": [";
+    for (size_t i = 0; i < c.diag_offsets.size(); ++i) o << (i ? ", " : "") << c.diag_offsets[i];
+    o << "], \"diag_nnz\": " << c.diag_nnz << ", \"block_fill\": {\"2\": " << c.block_fill[2]
+      << ", \"3\": " << c.block_fill[3] << ", \"4\": " << c.block_fill[4] << "}}, ";
+    o << "\"parts\": [";
+    for (size_t i = 0; i < plan.parts.size(); ++i) {
+        const Part &p = plan.parts[i];
+        o << (i ? ", " : "") << "{\"name\": \"" << p.name << "\", \"rows\": " << p.nrows
+          << ", \"nnz\": " << p.nnz << ", \"stored\": " << p.stored << ", \"units\": " << p.units
+          << ", \"lanes\": " << p.lanes << ", \"accumulate\": " << (p.accumulate ? "true" : "false")
+          << ", \"origin_rows\": " << (p.has_rows ? "true" : "false") << "}";
+    }
+    o << "], \"arrays\": [";
+    for (size_t i = 0; i < plan.arrays.size(); ++i) {
+        const DevArray &a = plan.arrays[i];
+        o << (i ? ", " : "") << "{\"name\": \"" << a.name << "\", \"elem_bytes\": " << a.elem_bytes
+          << ", \"count\": " << a.count << "}";
+    }
+    o << "], \"search\": [";
+    for (size_t i = 0; i < plan.log.size(); ++i) {
+        const CandidateLog &l = plan.log[i];
+        o << (i ? ", " : "") << "{\"spec\": \"" << json_escape(l.spec) << "\", \"build_ms\": " << l.build_ms
+          << ", \"run_us\": " << l.run_us << ", \"note\": \"" << json_escape(l.note) << "\"}";
+    }
+    o << "]}";
+    return o.str();
+}
+
+}  // namespace spmv
+
+using namespace spmv;
+
+#define API_BEGIN try {
+#define API_END                                                  \
+    }                                                            \
+    catch (const Error &e) {                                     \
+        g_last_error = e.msg;                                    \
+        return e.code;                                           \
+    }                                                            \
+    catch (const std::bad_alloc &) {                             \
+        g_last_error = "host allocation failed";                 \
+        return SPMV_ERR_ALLOC;                                   \
+    }                                                            \
+    catch (const std::exception &e) {                            \
+        g_last_error = std::string("internal error: ") + e.what(); \
+        return SPMV_ERR_INTERNAL;                                \
+    }                                                            \
+    catch (...) {                                                \
+        g_last_error = "internal error";                         \
+        return SPMV_ERR_INTERNAL;                                \
+    }
+
+extern "C" {
+
+const char *spmv_last_error(void) { return g_last_error.c_str(); }
+
+spmv_status_t spmv_plan_create(spmv_plan_t **out, int64_t nrows, int64_t ncols, int64_t nnz,
+                               const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                               spmv_dtype_t dtype, const spmv_options_t *opts) {
+    if (out) *out = nullptr;
+    API_BEGIN
+    if (!out) fail(SPMV_ERR_INVALID_ARG, "out is NULL");
+    if (nrows < 0 || ncols < 0 || nnz < 0) fail(SPMV_ERR_INVALID_ARG, "negative dimension");
+    if (!row_ptr) fail(SPMV_ERR_INVALID_ARG, "row_ptr is NULL");
+    if (nnz > 0 && (!col_idx || !values)) fail(SPMV_ERR_INVALID_ARG, "col_idx / values is NULL");
+    if (dtype != SPMV_F32 && dtype != SPMV_F64) fail(SPMV_ERR_UNSUPPORTED, "unknown dtype");
+    if (nnz >= ((int64_t)1 << 31) || nrows >= ((int64_t)1 << 31) - 64 || ncols >= ((int64_t)1 << 31) - 64)
+        fail(SPMV_ERR_UNSUPPORTED, "dimensions and nnz must be below 2^31");
+    spmv_options_t o;
+    std::memset(&o, 0, sizeof o);
+    if (opts) o = *opts;
+    if ((o.dev_alloc == nullptr) != (o.dev_free == nullptr))
+        fail(SPMV_ERR_INVALID_ARG, "dev_alloc and dev_free must be given together");
+    if (o.host_threads < 0 || o.search_repeats < 0) fail(SPMV_ERR_INVALID_ARG, "negative option");
+    Allocator mem;
+    mem.alloc = o.dev_alloc ? o.dev_alloc : default_alloc;
+    mem.free = o.dev_free ? o.dev_free : default_free;
+    mem.user = o.user;
+    if (o.host_only) {
+        mem.alloc = host_alloc;
+        mem.free = host_free;
+        mem.user = nullptr;
+        mem.host_only = true;
+    }
+    const int threads = o.host_threads > 0 ? o.host_threads : default_threads();
+
+    HostCsr A;
+    A.nrows = nrows;
+    A.ncols = ncols;
+    A.nnz = nnz;
+    A.row_ptr = row_ptr;
+    A.col = col_idx;
+    A.val = values;
+    A.dtype = dtype;
+    validate_csr(A, threads);
+
+    // a plan-spec string is parsed before anything touches the device
+    const bool forced = o.force_plan && o.force_plan[0];
+    PlanSpec spec;
+    if (forced) spec = parse_spec(o.force_plan);
+
+    if (o.host_only && !forced && !(o.search_budget_ms < 0))
+        fail(SPMV_ERR_INVALID_ARG, "host_only needs force_plan or a negative search_budget_ms");
+    int ndev = 0;
+    if (!o.host_only && (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0)) {
+        (void)hipGetLastError();
+        fail(SPMV_ERR_HIP, "no HIP device available");
+    }
+    const Census cen = take_census(A, threads);
+    std::unique_ptr<Plan> plan;
+    if (forced) {
+        plan = build_plan(A, cen, spec, mem, threads);
+        CandidateLog l;
+        l.spec = print_spec(spec);
+        l.note = "forced";
+        plan->log.push_back(l);
+    } else {
+        plan = search_plan(A, cen, o, mem, threads);
+    }
+    if (!o.host_only && hipDeviceSynchronize() != hipSuccess) fail(SPMV_ERR_HIP, "device error after plan construction");
+    plan->describe_cache = describe_json(*plan);
+    *out = new spmv_plan{std::move(plan)};
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_run(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream) {
+    API_BEGIN
+    if (!plan || !plan->impl) fail(SPMV_ERR_INVALID_ARG, "plan is NULL");
+    const Plan &p = *plan->impl;
+    if (p.mem.host_only) fail(SPMV_ERR_UNSUPPORTED, "the plan was built host-only and cannot run");
+    if ((!x_dev && p.ncols > 0) || (!y_dev && p.nrows > 0)) fail(SPMV_ERR_INVALID_ARG, "x or y is NULL");
+    if (x_dev && x_dev == y_dev) fail(SPMV_ERR_INVALID_ARG, "x and y must not alias");
+    for (const Part &part : p.parts) {
+        const int err = launch_part(part, p.dtype, p.nrows, p.ncols, x_dev, y_dev, stream);
+        if (err) fail(SPMV_ERR_HIP, std::string("launch of ") + part.name + " failed: " + hip_error_text(err));
+    }
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_run_timed(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
+                             float *launch_ms) {
+    API_BEGIN
+    if (!plan || !plan->impl || !launch_ms) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    const Plan &p = *plan->impl;
+    if (p.mem.host_only) fail(SPMV_ERR_UNSUPPORTED, "the plan was built host-only and cannot run");
+    if ((!x_dev && p.ncols > 0) || (!y_dev && p.nrows > 0)) fail(SPMV_ERR_INVALID_ARG, "x or y is NULL");
+    if (x_dev && x_dev == y_dev) fail(SPMV_ERR_INVALID_ARG, "x and y must not alias");
+    const size_t n = p.parts.size();
+    std::vector<hipEvent_t> ev(n + 1, nullptr);
+    auto drop = [&]() {
+        for (hipEvent_t e : ev)
+            if (e) (void)hipEventDestroy(e);
+    };
+    for (size_t i = 0; i <= n; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) {
+            drop();
+            fail(SPMV_ERR_HIP, "hipEventCreate failed");
+        }
+    (void)hipEventRecord(ev[0], (hipStream_t)stream);
+    for (size_t i = 0; i < n; ++i) {
+        const int err = launch_part(p.parts[i], p.dtype, p.nrows, p.ncols, x_dev, y_dev, stream);
+        if (err) {
+            drop();
+            fail(SPMV_ERR_HIP, std::string("launch of ") + p.parts[i].name + " failed: " + hip_error_text(err));
+        }
+        (void)hipEventRecord(ev[i + 1], (hipStream_t)stream);
+    }
+    if (hipEventSynchronize(ev[n]) != hipSuccess) {
+        drop();
+        fail(SPMV_ERR_HIP, "a kernel failed");
+    }
+    for (size_t i = 0; i < n; ++i) (void)hipEventElapsedTime(&launch_ms[i], ev[i], ev[i + 1]);
+    drop();
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_destroy(spmv_plan_t *plan) {
+    API_BEGIN
+    delete plan;
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_describe(const spmv_plan_t *plan, char *buf, size_t cap, size_t *needed) {
+    API_BEGIN
+    if (!plan || !plan->impl) fail(SPMV_ERR_INVALID_ARG, "plan is NULL");
+    const std::string &s = plan->impl->describe_cache;
+    if (needed) *needed = s.size() + 1;
+    if (buf && cap > 0) {
+        const size_t n = std::min(cap - 1, s.size());
+        std::memcpy(buf, s.data(), n);
+        buf[n] = 0;
+    }
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_array_count(const spmv_plan_t *plan, int *n) {
+    API_BEGIN
+    if (!plan || !plan->impl || !n) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    *n = (int)plan->impl->arrays.size();
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_array_info(const spmv_plan_t *plan, int i, const char **name,
+                                   int *elem_bytes, int64_t *count) {
+    API_BEGIN
+    if (!plan || !plan->impl) fail(SPMV_ERR_INVALID_ARG, "plan is NULL");
+    if (i < 0 || i >= (int)plan->impl->arrays.size()) fail(SPMV_ERR_INVALID_ARG, "array index out of range");
+    const DevArray &a = plan->impl->arrays[(size_t)i];
+    if (name) *name = a.name.c_str();
+    if (elem_bytes) *elem_bytes = a.elem_bytes;
+    if (count) *count = a.count;
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_array_copy(const spmv_plan_t *plan, int i, void *host_dst) {
+    API_BEGIN
+    if (!plan || !plan->impl || !host_dst) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    if (i < 0 || i >= (int)plan->impl->arrays.size()) fail(SPMV_ERR_INVALID_ARG, "array index out of range");
+    const DevArray &a = plan->impl->arrays[(size_t)i];
+    if (a.count > 0 && plan->impl->mem.host_only) {
+        std::memcpy(host_dst, a.ptr, (size_t)a.count * (size_t)a.elem_bytes);
+    } else if (a.count > 0) {
+        hipError_t err = hipMemcpy(host_dst, a.ptr, (size_t)a.count * (size_t)a.elem_bytes, hipMemcpyDeviceToHost);
+        if (err != hipSuccess) fail(SPMV_ERR_HIP, std::string("hipMemcpy D2H: ") + hipGetErrorString(err));
+    }
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_bytes(const spmv_plan_t *plan, int64_t *b_plan, int64_t *b_csr) {
+    API_BEGIN
+    if (!plan || !plan->impl) fail(SPMV_ERR_INVALID_ARG, "plan is NULL");
+    if (b_plan) *b_plan = plan->impl->bytes_plan();
+    if (b_csr) *b_csr = plan->impl->bytes_csr();
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_launch_count(const spmv_plan_t *plan, int *n) {
+    API_BEGIN
+    if (!plan || !plan->impl || !n) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    *n = (int)plan->impl->parts.size();
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_launch_name(const spmv_plan_t *plan, int i, const char **name) {
+    API_BEGIN
+    if (!plan || !plan->impl || !name) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    if (i < 0 || i >= (int)plan->impl->parts.size()) fail(SPMV_ERR_INVALID_ARG, "launch index out of range");
+    *name = plan->impl->parts[(size_t)i].name.c_str();
+    return SPMV_OK;
+    API_END
+}
+
+}  // extern "C"

@@ -1,0 +1,614 @@
+// Host format builder: CSR + plan spec -> device layout.
+//
+// This is the paper's Designer plus Format Construction (Sections IV, V-A, V-B): the converting
+// operators (ROW_DIV, COL_DIV, SORT, SORT_SUB, BIN) decide which rows go to which part and in
+// which order, the mapping operators (*_ROW_BLOCK, *_COL_BLOCK, *_PAD) decide which lane reads
+// which stored entry, and only the arrays the part's kernel reads are materialised.  Arrays that
+// follow a closed form by construction (first row of a slice = 64 * slice id, origin row of an
+// unsorted part = its position) are never built (Section V-D, model-driven compression).
+//
+// Readings of points the paper leaves open:
+//   - SORT / SORT_SUB are stable: rows of equal length keep ascending original order; the windows
+//     of SORT_SUB start at the first row of the part and the last one may be short.
+//   - PAD fills a slice to the longest row of that slice with value 0 and the column of the row's
+//     last real entry (column 0 for an empty row), so padded gathers stay in bounds and local.
+//   - A row cut by *_COL_BLOCK into several segments reduces through atomics into a y element that
+//     an earlier launch set to zero.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <numeric>
+
+#include "internal.h"
+
+namespace spmv {
+
+Plan::~Plan() {
+    for (DevArray &a : arrays)
+        if (a.ptr) mem.free(a.ptr, mem.user);
+}
+
+int64_t Plan::bytes_csr() const {
+    const int64_t v = (int64_t)vsize();
+    return nnz * (v + 4) + 4 * (nrows + 1) + v * ncols + v * nrows;
+}
+
+int64_t Plan::bytes_plan() const {
+    const int64_t v = (int64_t)vsize();
+    int64_t b = v * ncols;
+    for (const DevArray &a : arrays)
+        if (a.read_per_run) b += a.count * a.elem_bytes;
+    for (const Part &p : parts) {
+        const int64_t rows = (p.kind == K_BSELL) ? p.nrows * p.block : p.nrows;
+        if (p.kind == K_STRIPE) continue;   // its atomics land on rows counted by the zero part
+        b += rows * v * (p.accumulate ? 2 : 1) * p.y_passes;
+    }
+    return b;
+}
+
+namespace {
+
+template <typename V>
+struct HostBuf {   // uninitialised host storage (large arrays are written exactly once)
+    V *p = nullptr;
+    int64_t n = 0;
+    explicit HostBuf(int64_t count) : n(count) {
+        p = (V *)std::malloc((size_t)std::max<int64_t>(count, 1) * sizeof(V));
+        if (!p) fail(SPMV_ERR_ALLOC, "host allocation failed");
+    }
+    ~HostBuf() { std::free(p); }
+    HostBuf(const HostBuf &) = delete;
+    HostBuf &operator=(const HostBuf &) = delete;
+    V &operator[](int64_t i) { return p[i]; }
+};
+
+const void *upload(Plan &plan, const std::string &name, int elem_bytes, int64_t count,
+                   const void *host, bool read_per_run = true) {
+    const size_t bytes = (size_t)std::max<int64_t>(count, 1) * (size_t)elem_bytes;
+    void *d = plan.mem.alloc(bytes, plan.mem.user);
+    if (!d) fail(SPMV_ERR_ALLOC, "device allocation of " + std::to_string(bytes) + " bytes failed (" + name + ")");
+    DevArray a;
+    a.name = name;
+    a.ptr = d;
+    a.elem_bytes = elem_bytes;
+    a.count = count;
+    a.read_per_run = read_per_run;
+    plan.arrays.push_back(a);   // owned from here on, freed by ~Plan
+    if (count > 0 && plan.mem.host_only) {
+        std::memcpy(d, host, (size_t)count * (size_t)elem_bytes);
+    } else if (count > 0) {
+        hipError_t err = hipMemcpy(d, host, (size_t)count * (size_t)elem_bytes, hipMemcpyHostToDevice);
+        if (err != hipSuccess) fail(SPMV_ERR_HIP, std::string("hipMemcpy H2D (") + name + "): " + hipGetErrorString(err));
+    }
+    return d;
+}
+
+// Row order of a part: stable sort by decreasing length inside windows of sigma rows
+// (sigma == -1: one window; sigma == 0: untouched).
+void sort_rows(std::vector<int32_t> &rows, const std::vector<int64_t> &len_of_row, int sigma, int threads) {
+    if (sigma == 0 || rows.size() < 2) return;
+    const int64_t n = (int64_t)rows.size();
+    const int64_t win = sigma < 0 ? n : (int64_t)sigma;
+    const int64_t nwin = (n + win - 1) / win;
+    auto cmp = [&](int32_t a, int32_t b) { return len_of_row[(size_t)a] > len_of_row[(size_t)b]; };
+    if (nwin == 1) {
+        std::stable_sort(rows.begin(), rows.end(), cmp);
+        return;
+    }
+    parallel_for(nwin, 4, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t w = b; w < e; ++w)
+            std::stable_sort(rows.begin() + w * win, rows.begin() + std::min(n, (w + 1) * win), cmp);
+    });
+}
+
+bool is_identity(const std::vector<int32_t> &rows, int64_t nrows) {
+    if ((int64_t)rows.size() != nrows) return false;
+    for (int64_t i = 0; i < nrows; ++i)
+        if (rows[(size_t)i] != (int32_t)i) return false;
+    return true;
+}
+
+// ---- SELL: slices of 64 rows, lane-interleaved, padded per slice --------------------------------
+template <typename T>
+void build_sell(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int sigma, bool acc,
+                int remap, const std::string &name, const std::vector<int64_t> &lens, int threads) {
+    const int64_t n = (int64_t)rows.size();
+    if (n == 0) return;
+    const bool ident = (sigma == 0) && is_identity(rows, A.nrows);
+    sort_rows(rows, lens, sigma, threads);
+    const int64_t nsl = (n + kWave - 1) / kWave;
+    std::vector<int64_t> slice_ptr((size_t)nsl + 1, 0);
+    int64_t real = 0;
+    for (int64_t s = 0; s < nsl; ++s) {
+        int64_t w = 0;
+        for (int64_t i = s * kWave; i < std::min(n, (s + 1) * kWave); ++i) {
+            w = std::max(w, lens[(size_t)rows[(size_t)i]]);
+            real += lens[(size_t)rows[(size_t)i]];
+        }
+        slice_ptr[(size_t)s + 1] = slice_ptr[(size_t)s] + w * kWave;
+    }
+    const int64_t total = slice_ptr[(size_t)nsl];
+    if (total >= ((int64_t)1 << 33)) fail(SPMV_ERR_UNSUPPORTED, "sell: padded size too large");
+    HostBuf<int32_t> cols(total);
+    HostBuf<T> vals(total);
+    const T *av = (const T *)A.val;
+    parallel_for(nsl, 64, threads, [&](int64_t sb, int64_t se, int) {
+        for (int64_t s = sb; s < se; ++s) {
+            const int64_t base = slice_ptr[(size_t)s];
+            const int64_t w = (slice_ptr[(size_t)s + 1] - base) / kWave;
+            for (int lane = 0; lane < kWave; ++lane) {
+                const int64_t i = s * kWave + lane;
+                int64_t L = 0, src = 0;
+                if (i < n) {
+                    const int32_t r = rows[(size_t)i];
+                    L = lens[(size_t)r];
+                    src = A.row_ptr[r];
+                }
+                int64_t j = 0;
+                for (; j < L; ++j) {
+                    cols[base + j * kWave + lane] = A.col[src + j];
+                    vals[base + j * kWave + lane] = av[src + j];
+                }
+                const int32_t padc = L > 0 ? A.col[src + L - 1] : 0;
+                for (; j < w; ++j) {
+                    cols[base + j * kWave + lane] = padc;
+                    vals[base + j * kWave + lane] = T(0);
+                }
+            }
+        }
+    });
+    Part p;
+    p.kind = K_SELL;
+    p.name = name;
+    p.nrows = n;
+    p.nnz = real;
+    p.stored = total;
+    p.units = nsl;
+    p.accumulate = acc;
+    p.has_rows = !ident;
+    p.remap = remap;
+    p.p0 = upload(plan, name + ".slice_ptr", 8, nsl + 1, slice_ptr.data());
+    p.p1 = upload(plan, name + ".cols", 4, total, cols.p);
+    p.p2 = upload(plan, name + ".vals", (int)sizeof(T), total, vals.p);
+    if (p.has_rows) p.p3 = upload(plan, name + ".origin_rows", 4, n, rows.data());
+    plan.parts.push_back(p);
+}
+
+// ---- CSR segments ----------------------------------------------------------------------------
+// zero_rows collects the rows whose segments reduce through atomics.
+template <typename T>
+void build_csrv(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int lpr, int64_t chunk,
+                int sigma, bool acc, int remap, const std::string &name,
+                const std::vector<int64_t> &lens, std::vector<int32_t> &zero_rows, int threads) {
+    const int64_t n = (int64_t)rows.size();
+    if (n == 0) return;
+    int64_t total = 0, maxlen = 0;
+    for (int32_t r : rows) {
+        total += lens[(size_t)r];
+        maxlen = std::max(maxlen, lens[(size_t)r]);
+    }
+    if (lpr == 0) {   // about four entries per lane, from the mean length of the part
+        const double mean = (double)total / (double)n;
+        lpr = 1;
+        while (lpr < kWave && lpr * 4 < mean) lpr <<= 1;
+    }
+    const bool split = chunk > 0 && maxlen > chunk;
+    const bool ident = !split && sigma == 0 && is_identity(rows, A.nrows);
+    Part p;
+    p.kind = K_CSRV;
+    p.name = name;
+    p.nrows = n;
+    p.nnz = total;
+    p.stored = total;
+    p.accumulate = acc;
+    p.lanes = lpr;
+    p.remap = remap;
+    if (ident) {   // the input arrays already are the layout; origin row = segment id
+        p.units = n;
+        p.has_rows = false;
+        p.p0 = upload(plan, name + ".seg_ptr", 4, n + 1, A.row_ptr);
+        p.p2 = upload(plan, name + ".cols", 4, A.nnz, A.col);
+        p.p3 = upload(plan, name + ".vals", (int)sizeof(T), A.nnz, A.val);
+        plan.parts.push_back(p);
+        return;
+    }
+    sort_rows(rows, lens, sigma, threads);
+    std::vector<int32_t> seg_ptr, seg_row;
+    std::vector<int64_t> row_dst((size_t)n);
+    seg_ptr.reserve((size_t)n + 1);
+    seg_row.reserve((size_t)n);
+    int64_t pos = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const int32_t r = rows[(size_t)i];
+        const int64_t L = lens[(size_t)r];
+        row_dst[(size_t)i] = pos;
+        if (split && L > chunk) {
+            if (!acc) zero_rows.push_back(r);
+            for (int64_t o = 0; o < L; o += chunk) {
+                seg_ptr.push_back((int32_t)(pos + o));
+                seg_row.push_back(~r);
+            }
+        } else {
+            seg_ptr.push_back((int32_t)pos);
+            seg_row.push_back(r);
+        }
+        pos += L;
+    }
+    seg_ptr.push_back((int32_t)pos);
+    HostBuf<int32_t> cols(total);
+    HostBuf<T> vals(total);
+    const T *av = (const T *)A.val;
+    parallel_for(n, 1024, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t r = rows[(size_t)i];
+            const int64_t L = lens[(size_t)r], src = A.row_ptr[r], dst = row_dst[(size_t)i];
+            std::memcpy(cols.p + dst, A.col + src, (size_t)L * 4);
+            std::memcpy(vals.p + dst, av + src, (size_t)L * sizeof(T));
+        }
+    });
+    p.units = (int64_t)seg_row.size();
+    p.has_rows = true;
+    p.p0 = upload(plan, name + ".seg_ptr", 4, (int64_t)seg_ptr.size(), seg_ptr.data());
+    p.p1 = upload(plan, name + ".seg_row", 4, (int64_t)seg_row.size(), seg_row.data());
+    p.p2 = upload(plan, name + ".cols", 4, total, cols.p);
+    p.p3 = upload(plan, name + ".vals", (int)sizeof(T), total, vals.p);
+    plan.parts.push_back(p);
+}
+
+// ---- DIA extraction --------------------------------------------------------------------------
+// Entries on the selected diagonals move to a dense (ndiag x ld) array, duplicates add; everything
+// else goes to the remainder matrix.
+template <typename T>
+void build_dia(Plan &plan, const HostCsr &A, const std::vector<int32_t> &offs, OwnedCsr &rem,
+               int threads) {
+    const int64_t nd = (int64_t)offs.size();
+    const int64_t ld = (A.nrows + kWave - 1) / kWave * kWave;
+    HostBuf<T> dv(nd * ld);
+    const T *av = (const T *)A.val;
+    rem.row_ptr.assign((size_t)A.nrows + 1, 0);
+    // pass 1: fill the diagonals, count what is left per row
+    parallel_for(A.nrows, 1 << 13, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t r = b; r < e; ++r) {
+            for (int64_t d = 0; d < nd; ++d) dv[d * ld + r] = T(0);
+            int32_t left = 0;
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
+                const int32_t off = (int32_t)((int64_t)A.col[k] - r);
+                auto it = std::lower_bound(offs.begin(), offs.end(), off);
+                if (it != offs.end() && *it == off) dv[(int64_t)(it - offs.begin()) * ld + r] += av[k];
+                else ++left;
+            }
+            rem.row_ptr[(size_t)r + 1] = left;
+        }
+    });
+    for (int64_t d = 0; d < nd; ++d)
+        for (int64_t r = A.nrows; r < ld; ++r) dv[d * ld + r] = T(0);
+    for (int64_t r = 0; r < A.nrows; ++r) rem.row_ptr[(size_t)r + 1] += rem.row_ptr[(size_t)r];
+    const int64_t left = rem.row_ptr[(size_t)A.nrows];
+    rem.col.resize((size_t)left);
+    rem.val.resize((size_t)left * sizeof(T));
+    T *rv = (T *)rem.val.data();
+    parallel_for(A.nrows, 1 << 13, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t r = b; r < e; ++r) {
+            int64_t dst = rem.row_ptr[(size_t)r];
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
+                const int32_t off = (int32_t)((int64_t)A.col[k] - r);
+                if (!std::binary_search(offs.begin(), offs.end(), off)) {
+                    rem.col[(size_t)dst] = A.col[k];
+                    rv[dst] = av[k];
+                    ++dst;
+                }
+            }
+        }
+    });
+    rem.view = A;
+    rem.view.nnz = left;
+    rem.view.row_ptr = rem.row_ptr.data();
+    rem.view.col = rem.col.data();
+    rem.view.val = rem.val.data();
+    Part p;
+    p.kind = K_DIA;
+    p.name = "dia";
+    p.nrows = A.nrows;
+    p.nnz = A.nnz - left;
+    p.stored = nd * ld;
+    p.units = A.nrows;
+    p.ndiag = (int)nd;
+    p.ld = ld;
+    p.p0 = upload(plan, "dia.offsets", 4, nd, offs.data());
+    p.p1 = upload(plan, "dia.vals", (int)sizeof(T), nd * ld, dv.p);
+    plan.parts.push_back(p);
+}
+
+// ---- dense B x B blocks in SELL order ----------------------------------------------------------
+template <typename T>
+void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int threads) {
+    if (A.nrows % B || A.ncols % B)
+        fail(SPMV_ERR_UNSUPPORTED, "bsell: matrix dimensions are not multiples of the block edge");
+    const int64_t nb = A.nrows / B;
+    if (nb == 0) return;
+    // block columns of a block row: merge of the B rows' (col / B), ascending, distinct
+    auto block_cols = [&](int64_t br, std::vector<int32_t> &out) {
+        out.clear();
+        for (int64_t r = br * B; r < (br + 1) * B; ++r)
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) out.push_back(A.col[k] / B);
+        std::sort(out.begin(), out.end());
+        out.erase(std::unique(out.begin(), out.end()), out.end());
+    };
+    std::vector<int64_t> nblk((size_t)nb);
+    parallel_for(nb, 2048, threads, [&](int64_t b, int64_t e, int) {
+        std::vector<int32_t> tmp;
+        for (int64_t br = b; br < e; ++br) {
+            block_cols(br, tmp);
+            nblk[(size_t)br] = (int64_t)tmp.size();
+        }
+    });
+    std::vector<int32_t> brows((size_t)nb);
+    std::iota(brows.begin(), brows.end(), 0);
+    sort_rows(brows, nblk, sigma, threads);
+    const int64_t nsl = (nb + kWave - 1) / kWave;
+    std::vector<int64_t> slice_ptr((size_t)nsl + 1, 0);
+    int64_t real_blocks = 0;
+    for (int64_t s = 0; s < nsl; ++s) {
+        int64_t w = 0;
+        for (int64_t i = s * kWave; i < std::min(nb, (s + 1) * kWave); ++i) {
+            w = std::max(w, nblk[(size_t)brows[(size_t)i]]);
+            real_blocks += nblk[(size_t)brows[(size_t)i]];
+        }
+        slice_ptr[(size_t)s + 1] = slice_ptr[(size_t)s] + w * kWave;
+    }
+    const int64_t total = slice_ptr[(size_t)nsl];
+    const int BB = B * B;
+    if (total * BB >= ((int64_t)1 << 33)) fail(SPMV_ERR_UNSUPPORTED, "bsell: padded size too large");
+    HostBuf<int32_t> bcols(total);
+    HostBuf<T> vals(total * BB);
+    const T *av = (const T *)A.val;
+    parallel_for(nsl, 16, threads, [&](int64_t sb, int64_t se, int) {
+        std::vector<int32_t> bc;
+        for (int64_t s = sb; s < se; ++s) {
+            const int64_t base = slice_ptr[(size_t)s];
+            const int64_t w = (slice_ptr[(size_t)s + 1] - base) / kWave;
+            T *vs = vals.p + base * BB;
+            for (int64_t q = 0; q < w * BB * kWave; ++q) vs[q] = T(0);
+            for (int lane = 0; lane < kWave; ++lane) {
+                const int64_t i = s * kWave + lane;
+                bc.clear();
+                if (i < nb) {
+                    const int64_t br = brows[(size_t)i];
+                    block_cols(br, bc);
+                    for (int ri = 0; ri < B; ++ri) {
+                        const int64_t r = br * B + ri;
+                        size_t j = 0;
+                        for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
+                            const int32_t b = A.col[k] / B;
+                            while (bc[j] != b) ++j;   // columns ascend, so j only moves forward
+                            const int ci = A.col[k] - b * B;
+                            vs[((int64_t)j * BB + ri * B + ci) * kWave + lane] += av[k];
+                        }
+                    }
+                }
+                const int64_t L = (int64_t)bc.size();
+                for (int64_t j = 0; j < L; ++j) bcols[base + j * kWave + lane] = bc[(size_t)j];
+                const int32_t padc = L > 0 ? bc[(size_t)L - 1] : 0;
+                for (int64_t j = L; j < w; ++j) bcols[base + j * kWave + lane] = padc;
+            }
+        }
+    });
+    Part p;
+    p.kind = K_BSELL;
+    p.name = "bsell";
+    p.nrows = nb;
+    p.nnz = A.nnz;
+    p.stored = total * BB;
+    p.units = nsl;
+    p.block = B;
+    p.has_rows = sigma != 0;
+    p.remap = remap;
+    p.p0 = upload(plan, "bsell.slice_ptr", 8, nsl + 1, slice_ptr.data());
+    p.p1 = upload(plan, "bsell.bcols", 4, total, bcols.p);
+    p.p2 = upload(plan, "bsell.vals", (int)sizeof(T), total * BB, vals.p);
+    if (p.has_rows) p.p3 = upload(plan, "bsell.origin_brows", 4, nb, brows.data());
+    plan.parts.push_back(p);
+    (void)real_blocks;
+}
+
+// ---- heavy rows in column stripes --------------------------------------------------------------
+template <typename T>
+void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile,
+                  int lps, const std::vector<int64_t> &lens, int threads) {
+    const int64_t nh = (int64_t)hrows.size();
+    if (nh == 0) return;
+    if ((size_t)tile * sizeof(T) > 65536) fail(SPMV_ERR_UNSUPPORTED, "heavy: tile does not fit 64 KiB of LDS");
+    const int64_t ns = (A.ncols + tile - 1) / tile;
+    if (ns * nh >= ((int64_t)1 << 27)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many (row, stripe) segments");
+    std::vector<int32_t> seg_ptr((size_t)(ns * nh) + 1, 0);
+    int64_t total = 0;
+    for (int32_t r : hrows) total += lens[(size_t)r];
+    if (total >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many entries");
+    parallel_for(nh, 4, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t h = b; h < e; ++h) {
+            const int32_t r = hrows[(size_t)h];
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k)
+                seg_ptr[(size_t)((int64_t)(A.col[k] / tile) * nh + h) + 1] += 1;
+        }
+    });
+    for (int64_t i = 0; i < ns * nh; ++i) seg_ptr[(size_t)i + 1] += seg_ptr[(size_t)i];
+    HostBuf<uint16_t> lcol(total);
+    HostBuf<T> vals(total);
+    const T *av = (const T *)A.val;
+    parallel_for(nh, 4, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t h = b; h < e; ++h) {
+            const int32_t r = hrows[(size_t)h];
+            int64_t cur_s = -1, dst = 0;
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {   // columns ascend
+                const int64_t s = A.col[k] / tile;
+                if (s != cur_s) {
+                    cur_s = s;
+                    dst = seg_ptr[(size_t)(s * nh + h)];
+                }
+                lcol[dst] = (uint16_t)(A.col[k] - s * tile);
+                vals[dst] = av[k];
+                ++dst;
+            }
+        }
+    });
+    Part p;
+    p.kind = K_STRIPE;
+    p.name = "heavy";
+    p.nrows = nh;
+    p.nnz = total;
+    p.stored = total;
+    p.units = ns;
+    p.lanes = lps;
+    p.tile = tile;
+    p.has_rows = true;
+    p.p0 = upload(plan, "heavy.seg_ptr", 4, ns * nh + 1, seg_ptr.data());
+    p.p1 = upload(plan, "heavy.lcols", 2, total, lcol.p);
+    p.p2 = upload(plan, "heavy.vals", (int)sizeof(T), total, vals.p);
+    p.p3 = upload(plan, "heavy.rows", 4, nh, hrows.data());
+    plan.parts.push_back(p);
+}
+
+// Copy of A with ascending columns inside each row (stable: repeated columns keep their order).
+template <typename T>
+void sorted_copy(const HostCsr &A, OwnedCsr &out, int threads) {
+    out.row_ptr.assign(A.row_ptr, A.row_ptr + A.nrows + 1);
+    out.col.resize((size_t)A.nnz);
+    out.val.resize((size_t)A.nnz * sizeof(T));
+    const T *av = (const T *)A.val;
+    T *ov = (T *)out.val.data();
+    parallel_for(A.nrows, 1 << 12, threads, [&](int64_t b, int64_t e, int) {
+        std::vector<int32_t> idx;
+        for (int64_t r = b; r < e; ++r) {
+            const int64_t s = A.row_ptr[r], L = A.len(r);
+            idx.resize((size_t)L);
+            std::iota(idx.begin(), idx.end(), 0);
+            std::stable_sort(idx.begin(), idx.end(), [&](int32_t x, int32_t y) { return A.col[s + x] < A.col[s + y]; });
+            for (int64_t k = 0; k < L; ++k) {
+                out.col[(size_t)(s + k)] = A.col[s + idx[(size_t)k]];
+                ov[s + k] = av[s + idx[(size_t)k]];
+            }
+        }
+    });
+    out.view = A;
+    out.view.row_ptr = out.row_ptr.data();
+    out.view.col = out.col.data();
+    out.view.val = out.val.data();
+}
+
+template <typename T>
+std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const PlanSpec &spec,
+                                  const Allocator &mem, int threads) {
+    std::unique_ptr<Plan> plan(new Plan);
+    plan->dtype = A0.dtype;
+    plan->nrows = A0.nrows;
+    plan->ncols = A0.ncols;
+    plan->nnz = A0.nnz;
+    plan->spec = spec;
+    plan->mem = mem;
+    plan->census = cen;
+
+    OwnedCsr sorted, rem;
+    const HostCsr *cur = &A0;
+    if (!cen.cols_sorted) {
+        sorted_copy<T>(A0, sorted, threads);
+        cur = &sorted.view;
+    }
+    bool acc = false;
+    if (spec.dia) {
+        // offsets whose population reaches dia_fill (the census kept those >= 0.5)
+        std::vector<int32_t> offs = cen.diag_offsets;
+        if (spec.dia_fill > 0.5) {
+            // recount is not needed for the common case; thresholds above 0.5 filter by an exact pass
+            std::vector<int64_t> cnt(offs.size(), 0);
+            for (int64_t r = 0; r < cur->nrows; ++r)
+                for (int64_t k = cur->row_ptr[r]; k < cur->row_ptr[r + 1]; ++k) {
+                    auto it = std::lower_bound(offs.begin(), offs.end(), (int32_t)((int64_t)cur->col[k] - r));
+                    if (it != offs.end() && *it == (int32_t)((int64_t)cur->col[k] - r)) cnt[(size_t)(it - offs.begin())] += 1;
+                }
+            std::vector<int32_t> keep;
+            for (size_t d = 0; d < offs.size(); ++d) {
+                const int64_t off = offs[d];
+                const int64_t valid = std::min<int64_t>(cur->nrows, cur->ncols - off) - std::max<int64_t>(0, -off);
+                if (valid > 0 && (double)cnt[d] >= spec.dia_fill * (double)valid) keep.push_back(offs[d]);
+            }
+            offs.swap(keep);
+        }
+        if (offs.empty()) fail(SPMV_ERR_UNSUPPORTED, "dia: the matrix has no diagonal populated enough");
+        build_dia<T>(*plan, *cur, offs, rem, threads);
+        cur = &rem.view;
+        acc = true;
+        if (cur->nnz == 0) return plan;
+    }
+    const HostCsr &A = *cur;
+    std::vector<int64_t> lens((size_t)A.nrows);
+    parallel_for(A.nrows, 1 << 16, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t r = b; r < e; ++r) lens[(size_t)r] = A.len(r);
+    });
+
+    if (spec.light == L_BSELL) {
+        build_bsell<T>(*plan, A, spec.block, spec.sigma, spec.remap, threads);
+        return plan;
+    }
+
+    // ROW_DIV: heavy rows (longer than the threshold) against the rest.  After a DIA part wrote
+    // every y element, rows with nothing left are skipped.
+    std::vector<int32_t> heavy, light;
+    for (int64_t r = 0; r < A.nrows; ++r) {
+        const int64_t L = lens[(size_t)r];
+        if (spec.heavy > 0 && L > spec.heavy) heavy.push_back((int32_t)r);
+        else if (!(acc && L == 0)) light.push_back((int32_t)r);
+    }
+    // rows reduced through atomics are zeroed by the first launch
+    std::vector<int32_t> zero_rows;
+    const size_t zero_slot = plan->parts.size();
+    if (!acc) zero_rows = heavy;
+
+    switch (spec.light) {
+    case L_CSRV:
+        build_csrv<T>(*plan, A, light, spec.lpr, spec.chunk, spec.sigma, acc, spec.remap, "csrv", lens, zero_rows, threads);
+        break;
+    case L_SELL:
+        build_sell<T>(*plan, A, light, spec.sigma, acc, spec.remap, "sell", lens, threads);
+        break;
+    case L_BIN: {
+        // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront per
+        // row (cut into segments of `chunk`)
+        std::vector<int32_t> shorts, mids, longs;
+        for (int32_t r : light) {
+            const int64_t L = lens[(size_t)r];
+            if (L <= spec.smax) shorts.push_back(r);
+            else if (L <= 128) mids.push_back(r);
+            else longs.push_back(r);
+        }
+        build_sell<T>(*plan, A, shorts, spec.sigma, acc, spec.remap, "bin0.sell", lens, threads);
+        build_csrv<T>(*plan, A, mids, 8, 0, spec.sigma, acc, spec.remap, "bin1.csrv8", lens, zero_rows, threads);
+        build_csrv<T>(*plan, A, longs, 64, spec.chunk, 0, acc, spec.remap, "bin2.csrv64", lens, zero_rows, threads);
+        break;
+    }
+    default: fail(SPMV_ERR_INVALID_ARG, "unknown light design");
+    }
+    if (!heavy.empty()) build_stripe<T>(*plan, A, heavy, spec.tile, spec.hlps, lens, threads);
+
+    if (!zero_rows.empty()) {
+        std::sort(zero_rows.begin(), zero_rows.end());
+        Part z;
+        z.kind = K_ZERO;
+        z.name = "zero";
+        z.nrows = (int64_t)zero_rows.size();
+        z.units = z.nrows;
+        z.has_rows = true;
+        z.p0 = upload(*plan, "zero.rows", 4, z.nrows, zero_rows.data());
+        plan->parts.insert(plan->parts.begin() + (std::ptrdiff_t)zero_slot, z);
+    }
+    return plan;
+}
+
+}  // namespace
+
+std::unique_ptr<Plan> build_plan(const HostCsr &A, const Census &cen, const PlanSpec &spec,
+                                 const Allocator &mem, int threads) {
+    if (A.dtype == SPMV_F64) return build_typed<double>(A, cen, spec, mem, threads);
+    return build_typed<float>(A, cen, spec, mem, threads);
+}
+
+}  // namespace spmv

@@ -1,0 +1,170 @@
+// Internal types shared by the host format builder, the kernel launchers, the search and the
+// C ABI.  Nothing here is visible to users of include/spmv.h.
+#pragma once
+
+#include <atomic>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <functional>
+#include <memory>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "../../include/spmv.h"
+
+namespace spmv {
+
+// Lanes of a wavefront on CDNA4.  The paper's "warp" (32 lanes, Section IV-A) maps to this.
+constexpr int kWave = 64;
+
+struct Error {
+    spmv_status_t code;
+    std::string msg;
+};
+[[noreturn]] inline void fail(spmv_status_t code, const std::string &msg) { throw Error{code, msg}; }
+
+// ---- host-side threading -------------------------------------------------------------------
+// parallel_for splits [0, n) into chunks handed out dynamically to `threads` std::threads.
+void parallel_for(int64_t n, int64_t chunk, int threads,
+                  const std::function<void(int64_t, int64_t, int)> &body);
+int default_threads();
+
+// ---- the input matrix ----------------------------------------------------------------------
+struct HostCsr {
+    int64_t nrows = 0, ncols = 0, nnz = 0;
+    const int32_t *row_ptr = nullptr;
+    const int32_t *col = nullptr;
+    const void *val = nullptr;
+    spmv_dtype_t dtype = SPMV_F64;
+    size_t vsize() const { return dtype == SPMV_F64 ? 8 : 4; }
+    int64_t len(int64_t r) const { return (int64_t)row_ptr[r + 1] - row_ptr[r]; }
+};
+
+// Owned CSR storage (used when the builder has to derive a matrix: sorted columns, the
+// remainder after diagonal extraction).
+struct OwnedCsr {
+    std::vector<int32_t> row_ptr, col;
+    std::vector<char> val;
+    HostCsr view;
+};
+
+// ---- census (Section VI-B: the sparsity pattern prunes the candidate designs) --------------
+struct Census {
+    int64_t nrows = 0, ncols = 0, nnz = 0;
+    int64_t min_len = 0, max_len = 0, empty_rows = 0;
+    double mean_len = 0, var_len = 0;       // "irregular" when var_len > 100 (Section I)
+    // nnz held by rows longer than 2^k, k = 0..20 (tail mass, for the heavy-row threshold)
+    int64_t rows_over[21] = {0};
+    int64_t nnz_over[21] = {0};
+    // diagonals: offsets that are at least half populated, and the nnz they hold
+    std::vector<int32_t> diag_offsets;
+    int64_t diag_nnz = 0;
+    // aligned square blocks b x b, b = 2,3,4: number of non-empty blocks and fill = nnz/(b*b*blocks)
+    int64_t blocks[5] = {0};
+    double block_fill[5] = {0};
+    bool cols_sorted = true;
+};
+Census take_census(const HostCsr &A, int threads);
+
+// ---- plan specification --------------------------------------------------------------------
+enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3 };
+
+struct PlanSpec {
+    int dia = 0;             // extract well-populated diagonals into a DIA part first
+    double dia_fill = 0.5;   //   minimum population of a diagonal to be extracted
+    int64_t heavy = 0;       // ROW_DIV: rows longer than this go to the heavy part (0 = no split)
+    int tile = 8192;         //   COL_DIV width of the heavy part (columns per LDS tile of x)
+    int hlps = 16;           //   lanes per (row, tile) segment in the heavy kernel
+    int light = L_CSRV;      // design of the remaining rows
+    int lpr = 0;             // csrv: lanes per row (power of two <= 64; 0 = from the mean length)
+    int64_t chunk = 0;       // csrv: rows longer than this are cut into segments (0 = never)
+    int sigma = 0;           // sell/bsell: sort window in rows (0 = no sort, -1 = whole part)
+    int block = 3;           // bsell: block edge (2, 3 or 4)
+    int smax = 16;           // bin: rows up to this length go to the SELL bin
+    int remap = 0;           // 1 = give each XCD a contiguous range of workgroups
+};
+PlanSpec parse_spec(const std::string &s);
+std::string print_spec(const PlanSpec &p);
+std::string operator_chain(const PlanSpec &p);   // the design in the paper's operator names
+
+// ---- device layout -------------------------------------------------------------------------
+struct DevArray {
+    std::string name;
+    void *ptr = nullptr;
+    int elem_bytes = 0;
+    int64_t count = 0;
+    bool read_per_run = true;    // counts towards the algorithmic bytes of one run
+};
+
+enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE };
+
+// One kernel launch of spmv_run.  Pointers refer to entries of Plan::arrays.
+struct Part {
+    PartKind kind = K_ZERO;
+    std::string name;            // e.g. "sell", "csrv16", used as array-name prefix and in describe
+    int64_t nrows = 0;           // rows (or block rows) this part owns
+    int64_t nnz = 0;             // real non-zeros
+    int64_t stored = 0;          // stored entries including padding
+    int64_t units = 0;           // slices / segments / stripes: the launch's work items
+    bool accumulate = false;     // y += instead of y =
+    bool has_rows = false;       // an origin-row array is present (else row = arithmetic)
+    int lanes = 1;               // lanes per row / segment
+    int block = 1;               // bsell block edge
+    int ndiag = 0;
+    int tile = 0;
+    int remap = 0;
+    int64_t ld = 0;              // dia leading dimension
+    const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
+    int64_t y_passes = 1;        // how many times this part touches its rows of y (bytes model)
+};
+
+struct Allocator {
+    void *(*alloc)(size_t, void *) = nullptr;
+    void (*free)(void *, void *) = nullptr;
+    void *user = nullptr;
+    bool host_only = false;   // arrays live in host memory; the plan can be inspected, not run
+};
+
+struct CandidateLog {
+    std::string spec;
+    double build_ms = 0, run_us = -1;
+    std::string note;
+};
+
+struct Plan {
+    spmv_dtype_t dtype = SPMV_F64;
+    int64_t nrows = 0, ncols = 0, nnz = 0;
+    PlanSpec spec;
+    std::vector<DevArray> arrays;
+    std::vector<Part> parts;
+    Allocator mem;
+    Census census;
+    std::vector<CandidateLog> log;
+    std::string describe_cache;
+    ~Plan();
+    size_t vsize() const { return dtype == SPMV_F64 ? 8 : 4; }
+    int64_t bytes_plan() const;
+    int64_t bytes_csr() const;
+};
+
+// Host format builder: CSR + spec -> device layout (Sections IV, V-A, V-B).
+// Throws Error (SPMV_ERR_UNSUPPORTED when the spec cannot be applied to this matrix).
+std::unique_ptr<Plan> build_plan(const HostCsr &A, const Census &cen, const PlanSpec &spec,
+                                 const Allocator &mem, int threads);
+
+// Kernel launchers (kernels.hip).  Returns a hipError_t as int.
+int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
+                void *y, void *stream);
+const char *hip_error_text(int err);
+
+// Search (Section VI): enumerate pruned candidates, time them, keep the fastest.
+std::vector<PlanSpec> enumerate_candidates(const Census &cen, spmv_dtype_t dtype);
+std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spmv_options_t &opts,
+                                  const Allocator &mem, int threads);
+double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream);
+
+std::string describe_json(const Plan &plan);
+
+}  // namespace spmv

@@ -1,0 +1,235 @@
+// Search engine (Section VI).  The paper grows operator graphs at random, runs each parameter
+// point of a coarse grid on the GPU, interpolates with a learned cost model and stops by simulated
+// annealing within hours.  Here the candidate list is a bounded, deterministic enumeration pruned
+// by the census (Section VI-B: structure pruning by sparsity pattern, parameter pruning by a few
+// discrete values per operator); every candidate is built and timed on the device (the paper's
+// level-two search) and the fastest is kept, within a wall-clock budget.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+
+#include "internal.h"
+
+namespace spmv {
+
+static double now_ms() {
+    using namespace std::chrono;
+    return duration<double, std::milli>(steady_clock::now().time_since_epoch()).count();
+}
+
+std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) {
+    std::vector<PlanSpec> out;
+    auto push = [&](const PlanSpec &p) {
+        const std::string s = print_spec(p);
+        for (const PlanSpec &q : out)
+            if (print_spec(q) == s) return;
+        out.push_back(p);
+    };
+    if (c.nnz == 0 || c.nrows == 0) {
+        PlanSpec p;
+        p.light = L_CSRV;
+        p.lpr = 1;
+        push(p);
+        return out;
+    }
+    const int tile = dtype == SPMV_F64 ? 8192 : 16384;
+    // diagonals hold most of the matrix: DIA part, whatever is left goes to SELL
+    if (!c.diag_offsets.empty() && c.diag_nnz * 10 >= c.nnz * 8 && c.diag_offsets.size() <= 48) {
+        PlanSpec p;
+        p.dia = 1;
+        p.light = L_SELL;
+        p.sigma = 4096;
+        push(p);
+    }
+    // aligned dense blocks: the best-filled edge, largest first on ties
+    {
+        int best = 0;
+        for (int b = 4; b >= 2; --b)
+            if (c.block_fill[b] >= 0.85 && (best == 0 || c.block_fill[b] > c.block_fill[best] + 0.05)) best = b;
+        if (best) {
+            for (int remap = 1; remap >= 0; --remap) {
+                PlanSpec p;
+                p.light = L_BSELL;
+                p.block = best;
+                p.sigma = 4096;
+                p.remap = remap;
+                push(p);
+            }
+        }
+    }
+    const bool regular = c.max_len <= 2 * c.mean_len + 8;   // no long-row tail to balance
+    if (regular && c.max_len <= 96) {
+        // short, even rows: long-row reductions are pruned (Section VI-B)
+        for (int sigma : {4096, 0}) {
+            PlanSpec p;
+            p.light = L_SELL;
+            p.sigma = sigma;
+            push(p);
+        }
+    } else {
+        // irregular: BIN by length; optionally split off the heavy tail into column stripes
+        const int64_t ns = (c.ncols + tile - 1) / tile;
+        int64_t hth = 2048;
+        while (hth < 16 * ns) hth <<= 1;          // >= ~16 entries per (row, stripe) segment
+        int k = 0;
+        while (((int64_t)1 << k) < hth) ++k;
+        const bool tail = k <= 20 && c.nnz_over[k] * 20 >= c.nnz && c.rows_over[k] * ns < ((int64_t)1 << 27);
+        for (int heavy = tail ? 1 : 0; heavy >= 0; --heavy) {
+            PlanSpec p;
+            p.light = L_BIN;
+            p.smax = 16;
+            p.sigma = 8192;
+            p.chunk = 8192;
+            if (heavy) {
+                p.heavy = hth;
+                p.tile = tile;
+                p.hlps = 16;
+            }
+            push(p);
+        }
+        if (c.max_len <= 1024) {
+            PlanSpec p;
+            p.light = L_SELL;
+            p.sigma = 8192;
+            push(p);
+        }
+    }
+    {   // baseline every matrix admits: CSR, lanes per row from the mean length
+        PlanSpec p;
+        p.light = L_CSRV;
+        p.chunk = c.max_len > 16384 ? 8192 : 0;
+        push(p);
+    }
+    return out;
+}
+
+double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+        fail(SPMV_ERR_HIP, "hipEventCreate failed");
+    auto run = [&]() {
+        for (const Part &p : plan.parts) {
+            const int err = launch_part(p, plan.dtype, plan.nrows, plan.ncols, x, y, stream);
+            if (err) {
+                (void)hipEventDestroy(e0);
+                (void)hipEventDestroy(e1);
+                fail(SPMV_ERR_HIP, std::string("kernel launch failed: ") + hip_error_text(err));
+            }
+        }
+    };
+    run();
+    run();
+    std::vector<double> samples;
+    for (int r = 0; r < repeats; ++r) {
+        // batch enough runs that a sample lasts about a millisecond
+        int m = 1;
+        if (!samples.empty() && samples.back() < 500.0) m = (int)std::min(64.0, 500.0 / std::max(samples.back(), 5.0)) + 1;
+        (void)hipEventRecord(e0, st);
+        for (int i = 0; i < m; ++i) run();
+        (void)hipEventRecord(e1, st);
+        if (hipEventSynchronize(e1) != hipSuccess) {
+            (void)hipEventDestroy(e0);
+            (void)hipEventDestroy(e1);
+            fail(SPMV_ERR_HIP, "a candidate kernel failed while being timed");
+        }
+        float ms = 0;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        samples.push_back((double)ms * 1000.0 / m);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    std::sort(samples.begin(), samples.end());
+    return samples[samples.size() / 2];
+}
+
+std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spmv_options_t &opts,
+                                  const Allocator &mem, int threads) {
+    const std::vector<PlanSpec> cands = enumerate_candidates(cen, A.dtype);
+    const double budget = opts.search_budget_ms == 0 ? 8000.0 : opts.search_budget_ms;
+    const int repeats = opts.search_repeats > 0 ? opts.search_repeats : 5;
+    std::vector<CandidateLog> log;
+    if (budget < 0) {   // no timing: first candidate that builds
+        for (const PlanSpec &s : cands) {
+            CandidateLog l;
+            l.spec = print_spec(s);
+            const double t0 = now_ms();
+            try {
+                auto plan = build_plan(A, cen, s, mem, threads);
+                l.build_ms = now_ms() - t0;
+                l.note = "taken without timing";
+                log.push_back(l);
+                plan->log = log;
+                return plan;
+            } catch (const Error &e) {
+                l.note = "rejected: " + e.msg;
+                log.push_back(l);
+            }
+        }
+        fail(SPMV_ERR_INTERNAL, "no candidate plan could be built");
+    }
+    // device scratch for timing: x = 0 (finite), y
+    const size_t v = A.vsize();
+    void *x = mem.alloc(std::max<size_t>((size_t)A.ncols * v, 16), mem.user);
+    void *y = mem.alloc(std::max<size_t>((size_t)A.nrows * v, 16), mem.user);
+    hipStream_t st = nullptr;
+    auto cleanup = [&]() {
+        if (st) (void)hipStreamDestroy(st);
+        if (x) mem.free(x, mem.user);
+        if (y) mem.free(y, mem.user);
+    };
+    if (!x || !y) {
+        cleanup();
+        fail(SPMV_ERR_ALLOC, "device allocation for the search failed");
+    }
+    if (hipMemset(x, 0, (size_t)A.ncols * v) != hipSuccess || hipStreamCreate(&st) != hipSuccess) {
+        cleanup();
+        fail(SPMV_ERR_HIP, "search set-up failed");
+    }
+    std::unique_ptr<Plan> best;
+    double best_us = 0;
+    const double start = now_ms();
+    try {
+        for (size_t i = 0; i < cands.size(); ++i) {
+            CandidateLog l;
+            l.spec = print_spec(cands[i]);
+            if (best && now_ms() - start > budget) {
+                l.note = "skipped: search budget used up";
+                log.push_back(l);
+                continue;
+            }
+            const double t0 = now_ms();
+            std::unique_ptr<Plan> plan;
+            try {
+                plan = build_plan(A, cen, cands[i], mem, threads);
+            } catch (const Error &e) {
+                if (e.code == SPMV_ERR_HIP) throw;
+                l.note = "rejected: " + e.msg;
+                log.push_back(l);
+                continue;
+            }
+            l.build_ms = now_ms() - t0;
+            l.run_us = time_plan(*plan, x, y, repeats, st);
+            if (opts.verbosity > 0)
+                std::fprintf(stderr, "[spmv search] %-70s build %8.1f ms  run %10.2f us\n", l.spec.c_str(), l.build_ms, l.run_us);
+            if (!best || l.run_us < best_us) {
+                best = std::move(plan);
+                best_us = l.run_us;
+            }
+            log.push_back(l);
+        }
+    } catch (...) {
+        cleanup();
+        throw;
+    }
+    cleanup();
+    if (!best) fail(SPMV_ERR_INTERNAL, "no candidate plan could be built");
+    for (CandidateLog &l : log)
+        if (l.spec == print_spec(best->spec) && l.run_us >= 0) l.note = "kept";
+    best->log = log;
+    return best;
+}
+
+}  // namespace spmv

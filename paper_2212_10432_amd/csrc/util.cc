@@ -1,0 +1,185 @@
+// Host threading helpers and the plan-spec grammar.
+#include <algorithm>
+#include <sstream>
+
+#include "internal.h"
+
+namespace spmv {
+
+int default_threads() {
+    unsigned n = std::thread::hardware_concurrency();
+    if (const char *e = std::getenv("OMP_NUM_THREADS")) {   // the box exports its CPU share here
+        int v = std::atoi(e);
+        if (v > 0) n = (unsigned)v;
+    }
+    if (n < 1) n = 1;
+    if (n > 64) n = 64;
+    return (int)n;
+}
+
+void parallel_for(int64_t n, int64_t chunk, int threads,
+                  const std::function<void(int64_t, int64_t, int)> &body) {
+    if (n <= 0) return;
+    if (chunk < 1) chunk = 1;
+    const int64_t nchunks = (n + chunk - 1) / chunk;
+    if (threads > nchunks) threads = (int)nchunks;
+    if (threads <= 1) {
+        body(0, n, 0);
+        return;
+    }
+    std::atomic<int64_t> next{0};
+    std::vector<Error> errors;
+    std::atomic<bool> failed{false};
+    std::vector<std::thread> pool;
+    std::vector<std::string> what((size_t)threads);
+    std::vector<int> codes((size_t)threads, 0);
+    for (int t = 0; t < threads; ++t) {
+        pool.emplace_back([&, t] {
+            try {
+                for (;;) {
+                    const int64_t c = next.fetch_add(1, std::memory_order_relaxed);
+                    if (c >= nchunks || failed.load(std::memory_order_relaxed)) break;
+                    const int64_t b = c * chunk;
+                    body(b, std::min(n, b + chunk), t);
+                }
+            } catch (const Error &e) {
+                codes[(size_t)t] = (int)e.code;
+                what[(size_t)t] = e.msg;
+                failed = true;
+            } catch (const std::exception &e) {
+                codes[(size_t)t] = (int)SPMV_ERR_INTERNAL;
+                what[(size_t)t] = e.what();
+                failed = true;
+            }
+        });
+    }
+    for (auto &th : pool) th.join();
+    for (int t = 0; t < threads; ++t)
+        if (codes[(size_t)t]) fail((spmv_status_t)codes[(size_t)t], what[(size_t)t]);
+}
+
+// ---- plan-spec strings: "key=value,key=value" ------------------------------------------------
+static const char *light_name(int l) {
+    switch (l) {
+    case L_CSRV: return "csrv";
+    case L_SELL: return "sell";
+    case L_BSELL: return "bsell";
+    case L_BIN: return "bin";
+    }
+    return "?";
+}
+
+static bool pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+PlanSpec parse_spec(const std::string &s) {
+    PlanSpec p;
+    std::stringstream ss(s);
+    std::string tok;
+    while (std::getline(ss, tok, ',')) {
+        if (tok.empty()) continue;
+        const size_t eq = tok.find('=');
+        if (eq == std::string::npos) fail(SPMV_ERR_INVALID_ARG, "plan spec: token without '=': " + tok);
+        const std::string k = tok.substr(0, eq), v = tok.substr(eq + 1);
+        auto num = [&]() -> double {
+            char *end = nullptr;
+            const double d = std::strtod(v.c_str(), &end);
+            if (v.empty() || *end) fail(SPMV_ERR_INVALID_ARG, "plan spec: bad number in " + tok);
+            return d;
+        };
+        if (k == "light") {
+            if (v == "csrv") p.light = L_CSRV;
+            else if (v == "sell") p.light = L_SELL;
+            else if (v == "bsell") p.light = L_BSELL;
+            else if (v == "bin") p.light = L_BIN;
+            else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown light design " + v);
+        } else if (k == "dia") p.dia = (int)num();
+        else if (k == "dia_fill") p.dia_fill = num();
+        else if (k == "heavy") p.heavy = (int64_t)num();
+        else if (k == "tile") p.tile = (int)num();
+        else if (k == "hlps") p.hlps = (int)num();
+        else if (k == "lpr") p.lpr = (int)num();
+        else if (k == "chunk") p.chunk = (int64_t)num();
+        else if (k == "sigma") p.sigma = (int)num();
+        else if (k == "block") p.block = (int)num();
+        else if (k == "smax") p.smax = (int)num();
+        else if (k == "remap") p.remap = (int)num();
+        else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown key " + k);
+    }
+    if (p.dia != 0 && p.dia != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia must be 0 or 1");
+    if (!(p.dia_fill > 0 && p.dia_fill <= 1)) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia_fill must be in (0,1]");
+    if (p.heavy < 0) fail(SPMV_ERR_INVALID_ARG, "plan spec: heavy must be >= 0");
+    if (p.tile < 64 || p.tile > 65536 || p.tile % 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: tile must be a multiple of 64 in [64, 65536]");
+    if (!pow2(p.hlps) || p.hlps < 4 || p.hlps > 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: hlps must be 4..64, power of two");
+    if (p.lpr != 0 && (!pow2(p.lpr) || p.lpr > 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: lpr must be 0 or a power of two <= 64");
+    if (p.chunk < 0 || (p.chunk > 0 && p.chunk < 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: chunk must be 0 or >= 64");
+    if (p.sigma < -1) fail(SPMV_ERR_INVALID_ARG, "plan spec: sigma must be >= -1");
+    if (p.block < 2 || p.block > 4) fail(SPMV_ERR_INVALID_ARG, "plan spec: block must be 2, 3 or 4");
+    if (p.smax < 0 || p.smax > 1024) fail(SPMV_ERR_INVALID_ARG, "plan spec: smax must be in [0, 1024]");
+    if (p.remap != 0 && p.remap != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: remap must be 0 or 1");
+    if (p.light == L_BSELL && (p.dia || p.heavy)) fail(SPMV_ERR_INVALID_ARG, "plan spec: bsell cannot be combined with dia or heavy");
+    return p;
+}
+
+std::string print_spec(const PlanSpec &p) {
+    std::ostringstream o;
+    if (p.dia) o << "dia=1,dia_fill=" << p.dia_fill << ",";
+    if (p.heavy) o << "heavy=" << p.heavy << ",tile=" << p.tile << ",hlps=" << p.hlps << ",";
+    o << "light=" << light_name(p.light);
+    switch (p.light) {
+    case L_CSRV: o << ",lpr=" << p.lpr << ",chunk=" << p.chunk << ",sigma=" << p.sigma; break;
+    case L_SELL: o << ",sigma=" << p.sigma; break;
+    case L_BSELL: o << ",block=" << p.block << ",sigma=" << p.sigma; break;
+    case L_BIN: o << ",smax=" << p.smax << ",sigma=" << p.sigma << ",chunk=" << p.chunk; break;
+    }
+    o << ",remap=" << p.remap;
+    return o.str();
+}
+
+// The same design as a chain of the paper's operators (Table II).  DIA_EXTRACT, HEAVY_SPLIT and
+// DENSE_BLOCK name the three strategies Section VII-F lists as not yet supported by the paper.
+std::string operator_chain(const PlanSpec &p) {
+    std::ostringstream o;
+    o << "COMPRESS";
+    if (p.dia) o << " -> DIA_EXTRACT(fill>=" << p.dia_fill << ")[BMT_ROW_BLOCK(1) -> THREAD_TOTAL_RED]";
+    if (p.heavy)
+        o << " -> ROW_DIV(len>" << p.heavy << ")[HEAVY_SPLIT: COL_DIV(" << p.tile
+          << ") -> BMTB_COL_BLOCK -> BMW_ROW_BLOCK -> BMT_COL_BLOCK(" << p.hlps
+          << " lanes) -> WARP_TOTAL_RED -> GMEM_ATOM_RED]";
+    auto sort = [&]() {
+        if (p.sigma == -1) o << " -> SORT";
+        else if (p.sigma > 0) o << " -> SORT_SUB(" << p.sigma << ")";
+    };
+    switch (p.light) {
+    case L_CSRV:
+        sort();
+        o << " -> BMW_ROW_BLOCK -> BMT_COL_BLOCK(" << (p.lpr ? std::to_string(p.lpr) : std::string("auto")) << " lanes)";
+        if (p.chunk) o << " -> BMW_COL_BLOCK(" << p.chunk << ")";
+        o << " -> WARP_TOTAL_RED";
+        if (p.chunk) o << " -> GMEM_ATOM_RED";
+        break;
+    case L_SELL:
+        sort();
+        o << " -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD -> THREAD_TOTAL_RED";
+        break;
+    case L_BSELL:
+        o << " -> DENSE_BLOCK(" << p.block << "x" << p.block << ")";
+        sort();
+        o << " -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD -> THREAD_TOTAL_RED";
+        break;
+    case L_BIN:
+        o << " -> BIN(len<=" << p.smax << " | <=128 | >128)";
+        sort();
+        o << " -> {BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD -> THREAD_TOTAL_RED"
+          << " | BMT_COL_BLOCK(8 lanes) -> WARP_TOTAL_RED"
+          << " | BMT_COL_BLOCK(64 lanes)";
+        if (p.chunk) o << " -> BMW_COL_BLOCK(" << p.chunk << ")";
+        o << " -> WARP_TOTAL_RED";
+        if (p.chunk) o << " -> GMEM_ATOM_RED";
+        o << "}";
+        break;
+    }
+    if (p.remap) o << " -> SET_RESOURCES(xcd_contiguous)";
+    return o.str();
+}
+
+}  // namespace spmv

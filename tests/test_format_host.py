@@ -1,0 +1,242 @@
+"""Host format builder (C++, through the C ABI in host-only mode) against the NumPy reference
+builders of oracle/format_ref.py: every format array bit for bit, the round trip
+decode(arrays) == input matrix, and the closed forms the synthetic families imply.
+No GPU is touched: the plans are built with host_only, which keeps the arrays in host memory."""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import inputs
+import paper_2212_10432_amd as lib
+from oracle import format_ref as ref
+
+TINY = {
+    "C1": lambda **kw: inputs.uniform(n=1000, k=10, **kw),
+    "C2": lambda **kw: inputs.laplace2d(g=37, **kw),
+    "C3": lambda **kw: inputs.powerlaw(n=5003, cap=3000, **kw),
+    "C4": lambda **kw: inputs.fem3(nb=701, window=60, **kw),
+    "C5": lambda **kw: inputs.hybrid(n=20011, n_heavy=5, heavy_len=5000, **kw),
+}
+
+SPECS = {
+    "C1": ["light=csrv", "light=csrv,lpr=4,sigma=128", "light=sell", "light=sell,sigma=256", "light=sell,sigma=-1",
+           "light=bin,smax=4,sigma=128"],
+    "C2": ["dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
+    "C3": ["light=csrv,chunk=512", "light=bin,smax=16,sigma=512,chunk=256",
+           "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,hlps=8,light=csrv,lpr=8",
+           "heavy=256,tile=512,light=sell,sigma=128"],
+    "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=sell,sigma=512",
+           "light=csrv,lpr=16"],
+    "C5": ["heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
+           "heavy=1000,tile=4096,hlps=32,light=csrv,lpr=2"],
+}
+
+
+def host_plan(m, spec, values=None):
+    v = m.values if values is None else values
+    return lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, v, force_plan=spec, host_only=True)
+
+
+def as_scipy(nrows, ncols, r, c, v):
+    A = sp.coo_matrix((v, (r, c)), shape=(nrows, ncols)).tocsr()
+    A.sum_duplicates()
+    A.eliminate_zeros()
+    A.sort_indices()
+    return A
+
+
+def same_matrix(A, B):
+    return (A.shape == B.shape and np.array_equal(A.indptr, B.indptr) and np.array_equal(A.indices, B.indices)
+            and np.array_equal(A.data, B.data))
+
+
+CASES = [(name, spec) for name in SPECS for spec in SPECS[name]]
+
+
+@pytest.mark.parametrize("name,spec", CASES)
+@pytest.mark.parametrize("dt", [np.float64, np.float32])
+def test_arrays_match_reference_and_decode_to_input(name, spec, dt):
+    m = TINY[name]()
+    vals = m.values.astype(dt)
+    P = host_plan(m, spec, vals)
+    got = P.arrays()
+    want = ref.ref_plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, vals, spec)
+    assert sorted(got) == sorted(want)
+    for k in want:
+        assert got[k].dtype == want[k].dtype, k
+        assert np.array_equal(got[k], want[k]), k
+    p = ref.parse_spec(spec)
+    A_in = as_scipy(m.nrows, m.ncols, np.repeat(np.arange(m.nrows), np.diff(m.row_ptr)), m.col_idx, vals)
+    for arrays in (got, want):
+        r, c, v = ref.decode(arrays, m.nrows, m.ncols, block=p["block"], tile=p["tile"])
+        assert r.size == 0 or (r.min() >= 0 and r.max() < m.nrows and c.min() >= 0 and c.max() < m.ncols)
+        assert same_matrix(as_scipy(m.nrows, m.ncols, r, c, v), A_in)
+    d = P.describe()
+    assert sum(part["nnz"] for part in d["parts"]) == m.nnz
+    b_plan, b_csr = P.bytes()
+    v = vals.itemsize
+    assert b_csr == m.nnz * (v + 4) + 4 * (m.nrows + 1) + v * m.ncols + v * m.nrows
+    P.destroy()
+
+
+def test_structural_invariants():
+    m = TINY["C3"]()
+    spec = "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512"
+    P = host_plan(m, spec)
+    a = P.arrays()
+    lens = np.diff(m.row_ptr)
+    # origin rows of all row-owning parts + heavy rows partition the row set
+    owned = np.concatenate([a["bin0.sell.origin_rows"], a["bin1.csrv8.seg_row"],
+                            np.unique(np.where(a["bin2.csrv64.seg_row"] < 0, ~a["bin2.csrv64.seg_row"], a["bin2.csrv64.seg_row"])),
+                            a["heavy.rows"]])
+    assert np.array_equal(np.sort(owned), np.arange(m.nrows))
+    # offsets are non-decreasing and end at the totals
+    for k in ("bin0.sell.slice_ptr", "bin1.csrv8.seg_ptr", "bin2.csrv64.seg_ptr", "heavy.seg_ptr"):
+        assert a[k][0] == 0 and np.all(np.diff(a[k]) >= 0)
+    assert a["bin0.sell.slice_ptr"][-1] == a["bin0.sell.cols"].size
+    assert a["heavy.seg_ptr"][-1] == a["heavy.vals"].size == lens[a["heavy.rows"]].sum()
+    assert np.all(lens[a["heavy.rows"]] > 1024)
+    # padding = sum over slices of (slice width - row length)
+    order = a["bin0.sell.origin_rows"]
+    pad = 0
+    for s in range(len(a["bin0.sell.slice_ptr"]) - 1):
+        L = lens[order[s * 64:(s + 1) * 64]]
+        pad += 64 * L.max() - L.sum()
+    assert a["bin0.sell.cols"].size - lens[order].sum() == pad
+    # rows reduced through atomics are exactly the zeroed rows
+    sr = a["bin2.csrv64.seg_row"]
+    atomic_rows = np.unique(~sr[sr < 0])
+    assert np.array_equal(a["zero.rows"], np.sort(np.concatenate([atomic_rows, a["heavy.rows"]])))
+    assert np.all(lens[atomic_rows] > 512)
+    # stable descending sort inside each window of 256 rows
+    for b in range(0, order.size, 256):
+        w = order[b:b + 256]
+        assert np.all(np.diff(lens[w]) <= 0)
+        for L in np.unique(lens[w]):
+            assert np.all(np.diff(w[lens[w] == L]) > 0)
+    P.destroy()
+
+
+def test_closed_form_uniform_rows_need_no_padding_and_no_permutation():
+    m = TINY["C1"]()
+    for spec in ("light=sell,sigma=-1", "light=sell,sigma=256"):
+        a = host_plan(m, spec).arrays()
+        assert np.array_equal(a["sell.origin_rows"], np.arange(m.nrows))        # stable sort = identity
+        assert a["sell.cols"].size == 64 * 10 * (-(-m.nrows // 64))
+    a = host_plan(m, "light=sell").arrays()
+    assert "sell.origin_rows" not in a                                           # row = 64*slice + lane
+    assert np.array_equal(a["sell.slice_ptr"], 640 * np.arange(-(-m.nrows // 64) + 1))
+
+
+def test_closed_form_laplacian_diagonals():
+    g = 37
+    m = TINY["C2"]()
+    P = host_plan(m, "dia=1,light=sell")
+    a = P.arrays()
+    assert np.array_equal(a["dia.offsets"], [-g, -1, 0, 1, g])
+    assert set(a) == {"dia.offsets", "dia.vals"}                                 # nothing left over
+    n = g * g
+    ld = a["dia.vals"].size // 5
+    dv = a["dia.vals"].reshape(5, ld)[:, :n]
+    # explicit zeros in valid slots: the +-1 diagonals skip the grid's row ends (2*(g-1) slots);
+    # the slots outside the matrix are zero too: 2*g + 2 of them
+    inside_zero = sum(int(np.sum(dv[d, max(0, -o):min(n, n - o)] == 0)) for d, o in enumerate([-g, -1, 0, 1, g]))
+    assert inside_zero == 2 * (g - 1)
+    assert int(np.sum(dv == 0)) == 2 * (g - 1) + 2 * g + 2 == 5 * n - m.nnz
+    P.destroy()
+
+
+def test_closed_form_fem_blocks_are_full():
+    m = TINY["C4"]()
+    P = host_plan(m, "light=bsell,block=3,sigma=256")
+    a, d = P.arrays(), P.describe()
+    nblocks = m.nnz // 9
+    assert d["census"]["block_fill"]["3"] == pytest.approx(1.0)
+    order = a["bsell.origin_brows"]
+    nblk = np.diff(m.row_ptr)[0::3] // 3
+    pad_blocks = a["bsell.bcols"].size - nblocks
+    want_pad = sum(64 * nblk[order[s:s + 64]].max() - nblk[order[s:s + 64]].sum() for s in range(0, order.size, 64))
+    assert pad_blocks == want_pad
+    assert int(np.count_nonzero(a["bsell.vals"])) == m.nnz
+    P.destroy()
+
+
+def test_closed_form_hybrid_heavy_split_selects_the_generated_rows():
+    m = TINY["C5"]()
+    for thr in (9, 64, 4999):
+        a = host_plan(m, f"heavy={thr},tile=2048,light=sell,sigma=1024").arrays()
+        assert np.array_equal(a["heavy.rows"], m.meta["heavy_rows"])
+        assert a["heavy.vals"].size == 5 * 5000
+        assert np.array_equal(a["zero.rows"], m.meta["heavy_rows"])
+
+
+def test_duplicates_and_unsorted_columns_are_accepted():
+    rng = np.random.default_rng(5)
+    nrows, ncols = 300, 300
+    lens = rng.integers(0, 12, nrows)
+    rp = np.zeros(nrows + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    r = np.repeat(np.arange(nrows), lens)
+    ci = np.clip(r + rng.integers(-3, 4, rp[-1]), 0, ncols - 1).astype(np.int32)   # banded, duplicates, unsorted
+    va = rng.integers(-3, 4, rp[-1]).astype(np.float64)
+    A_in = as_scipy(nrows, ncols, r, ci, va)
+    for spec in ("light=csrv", "light=sell,sigma=64", "dia=1,light=sell", "light=bsell,block=3", "light=bsell,block=2,sigma=32",
+                 "heavy=8,tile=64,hlps=4,light=sell"):
+        P = lib.Plan(nrows, ncols, rp, ci, va, force_plan=spec, host_only=True)
+        assert P.describe()["census"]["cols_sorted"] is False
+        p = ref.parse_spec(spec)
+        rr, cc, vv = ref.decode(P.arrays(), nrows, ncols, block=p["block"], tile=p["tile"])
+        assert same_matrix(as_scipy(nrows, ncols, rr, cc, vv), A_in), spec
+        P.destroy()
+
+
+def test_empty_and_degenerate_matrices():
+    z = np.zeros(0)
+    for nrows, ncols in ((0, 0), (5, 7), (1, 1)):
+        rp = np.zeros(nrows + 1, np.int32)
+        for spec in ("light=csrv", "light=sell", "light=bin", "heavy=4,light=sell"):
+            P = lib.Plan(nrows, ncols, rp, np.zeros(0, np.int32), z, force_plan=spec, host_only=True)
+            assert P.describe()["nnz"] == 0
+            P.destroy()
+    # search without timing picks a deterministic candidate
+    m = TINY["C3"]()
+    specs = {lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, search_budget_ms=-1, host_only=True).describe()["spec"]
+             for _ in range(2)}
+    assert len(specs) == 1
+
+
+def test_errors():
+    m = TINY["C1"]()
+    E = lib.SpmvError
+    with pytest.raises(E) as e:
+        lib.Plan(m.nrows, m.ncols, m.row_ptr[::-1].copy(), m.col_idx, m.values, host_only=True, force_plan="light=csrv")
+    assert e.value.status == lib.SPMV_ERR_BAD_CSR
+    bad = m.col_idx.copy(); bad[17] = m.ncols
+    with pytest.raises(E) as e:
+        lib.Plan(m.nrows, m.ncols, m.row_ptr, bad, m.values, host_only=True, force_plan="light=csrv")
+    assert e.value.status == lib.SPMV_ERR_BAD_CSR
+    with pytest.raises(E) as e:
+        lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan="light=csrv", nnz=m.nnz - 1)
+    assert e.value.status == lib.SPMV_ERR_BAD_CSR
+    for spec in ("light=nope", "lpr=3", "tile=100", "sigma=-2", "block=5", "foo=1", "light", "heavy=4,light=bsell"):
+        with pytest.raises(E) as e:
+            lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan=spec)
+        assert e.value.status == lib.SPMV_ERR_INVALID_ARG, spec
+    with pytest.raises(E) as e:      # 1000 rows are not a multiple of 3
+        lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan="light=bsell,block=3")
+    assert e.value.status == lib.SPMV_ERR_UNSUPPORTED
+    with pytest.raises(E) as e:      # no populated diagonal in a random matrix
+        lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan="dia=1,light=sell")
+    assert e.value.status == lib.SPMV_ERR_UNSUPPORTED
+    with pytest.raises(E) as e:      # a search that times candidates needs a device
+        lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True)
+    assert e.value.status == lib.SPMV_ERR_INVALID_ARG
+    with pytest.raises(E) as e:
+        lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values.astype(np.float16), host_only=True, force_plan="light=csrv")
+    assert e.value.status == lib.SPMV_ERR_UNSUPPORTED
+    P = host_plan(m, "light=csrv")
+    with pytest.raises(E) as e:      # a host-only plan cannot run
+        lib.spmv_run(P.handle, 0x1000, 0x2000, 0)
+    assert e.value.status == lib.SPMV_ERR_UNSUPPORTED
+    P.destroy()
+    lib.spmv_plan_destroy(None)      # NULL is OK

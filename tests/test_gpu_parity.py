@@ -1,0 +1,179 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bar (from the benchmark spec): bit-exact on integer-valued inputs; otherwise
+|y - y_ref|_i <= tau * (|A||x|)_i with tau = 1e-12 (fp64) / 1e-5 (fp32), y_ref accumulated wide.
+Plans that reduce through atomics may differ between runs in the last bits on real data (the
+summation order changes); on integer data every order is exact, so two runs must be identical.
+"""
+import numpy as np
+import pytest
+
+import inputs
+import oracle
+import paper_2212_10432_amd as lib
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+SPECS = {
+    "C1": ["light=csrv", "light=csrv,lpr=1", "light=csrv,lpr=64,sigma=128", "light=sell", "light=sell,sigma=256,remap=1",
+           "light=bin,smax=4,sigma=128"],
+    "C2": ["dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
+    "C3": ["light=csrv,chunk=512", "light=csrv,lpr=32", "light=bin,smax=16,sigma=512,chunk=256",
+           "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,hlps=8,light=csrv,lpr=8",
+           "heavy=256,tile=512,hlps=4,light=sell,sigma=128", "heavy=2048,tile=8192,hlps=64,light=bin,chunk=1024"],
+    "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=sell,sigma=512",
+           "light=csrv,lpr=16"],
+    "C5": ["heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
+           "heavy=1000,tile=4096,hlps=32,light=csrv,lpr=2", "heavy=100,tile=8192,light=bin,sigma=8192,remap=1"],
+}
+CASES = [(n, s) for n in SPECS for s in SPECS[n]]
+
+
+def gpu_spmv(m, vals, x, spec=None, runs=1, **kw):
+    """Returns (list of y as NumPy arrays, one per run; plan description)."""
+    dev = torch.device("cuda:0")
+    tdt = torch.float64 if vals.dtype == np.float64 else torch.float32
+    P = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, vals, force_plan=spec, **kw)
+    xd = torch.from_numpy(np.ascontiguousarray(x.astype(vals.dtype))).to(dev)
+    out = []
+    for _ in range(runs):
+        yd = torch.full((m.nrows,), float("nan"), dtype=tdt, device=dev)   # every element must be overwritten
+        P.run(xd, yd)
+        torch.cuda.synchronize()
+        out.append(yd.cpu().numpy())
+    d = P.describe()
+    P.destroy()
+    return out, d
+
+
+@pytest.mark.parametrize("name,spec", CASES)
+@pytest.mark.parametrize("dt", [np.float64, np.float32])
+def test_forced_plans_match_oracle(name, spec, dt):
+    print(f"case {name} {spec} {np.dtype(dt).name}", flush=True)
+    # real-valued: tolerance
+    m = inputs.SMALL[name]()
+    vals, x = m.values.astype(dt), inputs.vector(m.ncols).astype(dt)
+    (y1, y2), d = gpu_spmv(m, vals, x, spec, runs=2)
+    for y in (y1, y2):
+        ok, worst = oracle.check(y, m.row_ptr, m.col_idx, vals, x, threads=8)
+        assert ok, (name, spec, worst)
+    # integer-valued: bit-exact, run to run identical
+    mi = inputs.SMALL[name](integer=True)
+    vi, xi = mi.values.astype(dt), inputs.vector(mi.ncols, integer=True).astype(dt)
+    (y1, y2), _ = gpu_spmv(mi, vi, xi, spec, runs=2)
+    want = oracle.spmv(mi.row_ptr, mi.col_idx, vi, xi, threads=8)
+    assert np.array_equal(y1, want) and np.array_equal(y2, want)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_searched_plan_matches_oracle(name):
+    print(f"search {name}", flush=True)
+    m = inputs.SMALL[name](integer=True)
+    x = inputs.vector(m.ncols, integer=True)
+    (y,), d = gpu_spmv(m, m.values, x, None, search_budget_ms=1500)
+    assert np.array_equal(y, oracle.spmv(m.row_ptr, m.col_idx, m.values, x, threads=8))
+    timed = [c for c in d["search"] if c["run_us"] >= 0]
+    kept = [c for c in timed if c["note"] == "kept"]
+    assert len(kept) == 1 and kept[0]["spec"] == d["spec"]
+    assert all(kept[0]["run_us"] <= c["run_us"] for c in timed)
+
+
+def test_device_arrays_equal_host_only_arrays():
+    m = inputs.SMALL["C3"]()
+    spec = "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512"
+    Pd = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, force_plan=spec)
+    Ph = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, force_plan=spec, host_only=True)
+    a, b = Pd.arrays(), Ph.arrays()
+    assert sorted(a) == sorted(b)
+    for k in a:
+        assert np.array_equal(a[k], b[k]), k
+    Pd.destroy(); Ph.destroy()
+
+
+def test_edge_cases():
+    rng = np.random.default_rng(11)
+    dev = torch.device("cuda:0")
+    # empty matrix, matrix of empty rows, single entry
+    for nrows, ncols in ((0, 0), (5, 7), (130, 3)):
+        rp = np.zeros(nrows + 1, np.int32)
+        for spec in ("light=csrv", "light=sell", "light=bin", "heavy=4,light=sell", None):
+            P = lib.Plan(nrows, ncols, rp, np.zeros(0, np.int32), np.zeros(0), force_plan=spec, search_budget_ms=200)
+            x = torch.ones(max(ncols, 1), dtype=torch.float64, device=dev)[:ncols]
+            y = torch.full((max(nrows, 1),), float("nan"), dtype=torch.float64, device=dev)[:nrows]
+            P.run(x, y)
+            torch.cuda.synchronize()
+            assert torch.all(y == 0)
+            P.destroy()
+    # ragged: many empty rows, duplicates, unsorted columns, rectangular
+    nrows, ncols = 777, 1234
+    lens = rng.integers(0, 40, nrows)
+    lens[rng.random(nrows) < 0.4] = 0
+    lens[5] = 3000
+    rp = np.zeros(nrows + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    ci = rng.integers(0, ncols, rp[-1]).astype(np.int32)
+    va = rng.integers(-3, 4, rp[-1]).astype(np.float64)
+    x = rng.integers(-3, 4, ncols).astype(np.float64)
+    want = oracle.spmv(rp, ci, va, x)
+
+    class M:
+        pass
+    m = M()
+    m.nrows, m.ncols, m.row_ptr, m.col_idx = nrows, ncols, rp, ci
+    for spec in ("light=csrv", "light=csrv,lpr=64,chunk=256", "light=sell,sigma=64", "light=bin,sigma=32,chunk=512",
+                 "heavy=100,tile=256,hlps=8,light=sell,sigma=64", "heavy=100,tile=64,hlps=4,light=bin", None):
+        for dt in (np.float64, np.float32):
+            (y,), _ = gpu_spmv(m, va.astype(dt), x.astype(dt), spec, search_budget_ms=300)
+            assert np.array_equal(y.astype(np.float64), want), (spec, dt)
+    # banded with duplicates: DIA and block plans must add repeated positions
+    n = 600
+    lens = rng.integers(0, 12, n)
+    rp = np.zeros(n + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    r = np.repeat(np.arange(n), lens)
+    ci = np.clip(r + rng.integers(-3, 4, rp[-1]), 0, n - 1).astype(np.int32)
+    va = rng.integers(-3, 4, rp[-1]).astype(np.float64)
+    x = rng.integers(-3, 4, n).astype(np.float64)
+    want = oracle.spmv(rp, ci, va, x)
+    m.nrows = m.ncols = n
+    m.row_ptr, m.col_idx = rp, ci
+    for spec in ("dia=1,light=sell", "dia=1,light=csrv,lpr=2", "light=bsell,block=3", "light=bsell,block=2,sigma=32",
+                 "light=bsell,block=4,sigma=-1,remap=1"):
+        (y,), _ = gpu_spmv(m, va, x, spec)
+        assert np.array_equal(y, want), spec
+
+
+def test_run_argument_errors():
+    m = inputs.SMALL["C1"]()
+    P = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, force_plan="light=csrv")
+    x = torch.zeros(m.ncols, dtype=torch.float64, device="cuda:0")
+    with pytest.raises(lib.SpmvError) as e:
+        lib.spmv_run(P.handle, x.data_ptr(), x.data_ptr(), 0)        # aliasing
+    assert e.value.status == lib.SPMV_ERR_INVALID_ARG
+    with pytest.raises(lib.SpmvError):
+        lib.spmv_run(P.handle, 0, x.data_ptr(), 0)
+    with pytest.raises(lib.SpmvError):
+        P.run(x[:-1], x)
+    P.destroy()
+
+
+def test_row_permutation_invariance():
+    """P (A x) == (P A) x: permuting the rows of A permutes y, whatever plan is chosen."""
+    m = inputs.SMALL["C5"](integer=True)
+    x = inputs.vector(m.ncols, integer=True)
+    rng = np.random.default_rng(2)
+    perm = rng.permutation(m.nrows)
+    lens = np.diff(m.row_ptr)[perm]
+    rp = np.zeros(m.nrows + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    idx = np.concatenate([np.arange(m.row_ptr[r], m.row_ptr[r + 1]) for r in perm])
+
+    class M:
+        pass
+    pm = M()
+    pm.nrows, pm.ncols, pm.row_ptr, pm.col_idx = m.nrows, m.ncols, rp, m.col_idx[idx]
+    spec = "heavy=100,tile=8192,light=bin,sigma=8192"
+    (y,), _ = gpu_spmv(m, m.values, x, spec)
+    (yp,), _ = gpu_spmv(pm, m.values[idx], x, spec)
+    assert np.array_equal(yp, y[perm])
