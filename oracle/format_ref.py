@@ -8,10 +8,12 @@ be compared bit for bit, and decodes any plan's arrays back to (row, col, value)
 Operators follow Table II of the paper; the readings of what it leaves open are:
   SORT / SORT_SUB  stable, decreasing row length; windows of sigma rows from the part's first row
   *_PAD            pad every row of a 64-row slice to the slice's longest row with value 0 and the
-                   column of the row's last real entry (0 for an empty row)
+                   column of the row's last real entry (an empty row takes the first column of the
+                   slice's first row, 0 if that is empty too)
   BIN              three bins: length <= smax, <= 128, > 128
   ROW_DIV (heavy)  rows longer than the threshold
-  COL_DIV (heavy)  stripes of `tile` columns; segments ordered stripe-major, then heavy row
+  COL_DIV (heavy)  stripes of `tile` columns; SORT_BMTB inside a stripe: heavy rows by decreasing
+                   entries in that stripe (stable); slices of 64 rows padded with (value 0, column 0)
 Diagonal extraction, heavy-row split and dense blocks are the strategies Section VII-F names as
 missing from the paper; they are built from their textbook definitions.
 
@@ -28,8 +30,8 @@ WAVE = 64
 
 
 def parse_spec(spec: str) -> dict:
-    d = dict(dia=0, dia_fill=0.5, heavy=0, tile=8192, hlps=16, light="csrv", lpr=0, chunk=0,
-             sigma=0, block=3, smax=16, remap=0)
+    d = dict(dia=0, dia_fill=0.5, heavy=0, tile=8192, light="csrv", lpr=0, chunk=0,
+             sigma=0, block=3, smax=16, remap=0, xwin=0)
     for tok in spec.split(","):
         if not tok:
             continue
@@ -70,6 +72,8 @@ def ref_sell(rp, ci, va, rows, sigma, nrows_total, name):
     vals = np.zeros(slice_ptr[-1], dtype=va.dtype)
     for s in range(nsl):
         base, w = slice_ptr[s], (slice_ptr[s + 1] - slice_ptr[s]) // WAVE
+        e0 = _row_entries(rp, order[s * WAVE])
+        fallback = ci[e0.start] if e0.stop > e0.start else 0
         for lane in range(WAVE):
             i = s * WAVE + lane
             pos = base + lane + WAVE * np.arange(w)
@@ -78,7 +82,9 @@ def ref_sell(rp, ci, va, rows, sigma, nrows_total, name):
                 L = e.stop - e.start
                 cols[pos[:L]] = ci[e]
                 vals[pos[:L]] = va[e]
-                cols[pos[L:]] = ci[e.stop - 1] if L else 0
+                cols[pos[L:]] = ci[e.stop - 1] if L else fallback
+            else:
+                cols[pos] = fallback
     out = {name + ".slice_ptr": slice_ptr, name + ".cols": cols, name + ".vals": vals}
     if not ident:
         out[name + ".origin_rows"] = order
@@ -141,7 +147,18 @@ def ref_dia(nrows, ncols, rp, ci, va, offs):
     return {"dia.offsets": np.asarray(offs, dtype=np.int32), "dia.vals": dv.reshape(-1)}, (rem_rp, ci[~on], va[~on])
 
 
-def ref_bsell(nrows, ncols, rp, ci, va, B, sigma):
+def _block_value_pos(B, itemsize, q):
+    """Position, inside the 64*B*B-value record of one block, of value q = B*ri + ci of each lane:
+    the first NV*V values of a lane are packed in vectors of V = 16/itemsize (vector p of lane l at
+    V*(64*p + l)), the rest follow one per lane.  Returns (offset, lane stride)."""
+    BB, V = B * B, 16 // itemsize
+    NV = BB // V
+    if q < NV * V:
+        return (q // V) * WAVE * V + (q % V), V
+    return NV * V * WAVE + (q - NV * V) * WAVE, 1
+
+
+def ref_bsell(nrows, ncols, rp, ci, va, B, sigma, xwin=0):
     nb = nrows // B
     bcl = []
     for br in range(nb):
@@ -157,50 +174,74 @@ def ref_bsell(nrows, ncols, rp, ci, va, B, sigma):
     vals = np.zeros(slice_ptr[-1] * B * B, dtype=va.dtype)
     for s in range(nsl):
         base, w = slice_ptr[s], (slice_ptr[s + 1] - slice_ptr[s]) // WAVE
+        first = bcl[order[s * WAVE]]
+        fallback = first[0] if len(first) else 0
         for lane in range(WAVE):
             i = s * WAVE + lane
             if i >= nb:
+                bcols[base + lane + WAVE * np.arange(w)] = fallback
                 continue
             br = order[i]
             bc = bcl[br]
             L = len(bc)
             bcols[base + lane + WAVE * np.arange(L)] = bc
-            bcols[base + lane + WAVE * np.arange(L, w)] = bc[-1] if L else 0
+            bcols[base + lane + WAVE * np.arange(L, w)] = bc[-1] if L else fallback
             for ri in range(B):
                 e = _row_entries(rp, br * B + ri)
                 j = np.searchsorted(bc, ci[e] // B)
-                q = j * B * B + ri * B + (ci[e] % B)
-                np.add.at(vals, base * B * B + q * WAVE + lane, va[e])
+                for jj, cc, vv in zip(j, ci[e], va[e]):
+                    off, stride = _block_value_pos(B, va.dtype.itemsize, ri * B + int(cc) % B)
+                    vals[(base + jj * WAVE) * B * B + off + stride * lane] += vv
     out = {"bsell.slice_ptr": slice_ptr, "bsell.bcols": bcols, "bsell.vals": vals}
     if sigma != 0:
         out["bsell.origin_brows"] = order
+    if xwin:
+        G = 32                                   # slices per workgroup
+        win = []
+        for g in range(-(-nsl // G)):
+            seg = bcols[slice_ptr[g * G]:slice_ptr[min(nsl, (g + 1) * G)]]
+            lo, hi = (int(seg.min()), int(seg.max())) if seg.size else (0, -1)
+            win += [lo * B, (hi - lo + 1) * B]
+        out["bsell.xwin"] = np.array(win, dtype=np.int32)
     return out
 
 
 def ref_stripe(ncols, rp, ci, va, hrows, tile):
+    """Heavy rows cut into column stripes; inside a stripe the rows are ordered by decreasing number
+    of entries in that stripe (stable), sliced by 64 and padded per slice (value 0, local column 0)."""
     nh = len(hrows)
     if nh == 0:
         return {}
     ns = -(-ncols // tile)
-    segs = [[None] * nh for _ in range(ns)]
-    for h, r in enumerate(hrows):
-        e = _row_entries(rp, r)
-        c, v = ci[e], va[e]
-        s_of = c // tile
-        for s in np.unique(s_of):
-            m = s_of == s
-            segs[s][h] = ((c[m] - s * tile).astype(np.uint16), v[m])
-    seg_ptr, lcols, vals = [0], [], []
+    nsl = -(-nh // WAVE)
+    unit_ptr = [0]
+    lane_row = np.full(ns * nsl * WAVE, 0xFFFF, dtype=np.uint16)
+    lcols, vals = [], []
     for s in range(ns):
-        for h in range(nh):
-            if segs[s][h] is not None:
-                lcols.append(segs[s][h][0])
-                vals.append(segs[s][h][1])
-                seg_ptr.append(seg_ptr[-1] + len(segs[s][h][0]))
-            else:
-                seg_ptr.append(seg_ptr[-1])
-    return {"heavy.seg_ptr": np.array(seg_ptr, dtype=np.int32), "heavy.lcols": np.concatenate(lcols),
-            "heavy.vals": np.concatenate(vals).astype(va.dtype), "heavy.rows": np.asarray(hrows, dtype=np.int32)}
+        segs = []
+        for r in hrows:
+            e = _row_entries(rp, r)
+            c = ci[e]
+            m = (c >= s * tile) & (c < (s + 1) * tile)
+            segs.append(((c[m] - s * tile).astype(np.uint16), va[e][m]))
+        seglen = np.array([len(sg[0]) for sg in segs], dtype=np.int64)
+        order = np.argsort(-seglen, kind="stable")
+        lane_row[s * nsl * WAVE:s * nsl * WAVE + nh] = order
+        for g in range(nsl):
+            members = order[g * WAVE:(g + 1) * WAVE]
+            w = int(seglen[members].max())
+            lc = np.zeros((w, WAVE), dtype=np.uint16)
+            vv = np.zeros((w, WAVE), dtype=va.dtype)
+            for lane, h in enumerate(members):
+                L = seglen[h]
+                lc[:L, lane] = segs[h][0]
+                vv[:L, lane] = segs[h][1]
+            lcols.append(lc.reshape(-1))
+            vals.append(vv.reshape(-1))
+            unit_ptr.append(unit_ptr[-1] + w * WAVE)
+    return {"heavy.unit_ptr": np.array(unit_ptr, dtype=np.int32), "heavy.lcols": np.concatenate(lcols),
+            "heavy.vals": np.concatenate(vals).astype(va.dtype), "heavy.rows": np.asarray(hrows, dtype=np.int32),
+            "heavy.lane_row": lane_row}
 
 
 def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
@@ -217,7 +258,7 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
             return out
     lens = np.diff(rp).astype(np.int64)
     if p["light"] == "bsell":
-        out.update(ref_bsell(nrows, ncols, rp, ci, va, p["block"], p["sigma"]))
+        out.update(ref_bsell(nrows, ncols, rp, ci, va, p["block"], p["sigma"], p["xwin"]))
         return out
     allrows = np.arange(nrows, dtype=np.int32)
     heavy = allrows[lens > p["heavy"]] if p["heavy"] > 0 else allrows[:0]
@@ -279,8 +320,9 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
                     for j in range(w):
                         b = int(bc[base + j * WAVE + lane])
                         for q in range(BB):
+                            off, stride = _block_value_pos(block, vv.dtype.itemsize, q)
                             R.append([br * block + q // block]); C.append([b * block + q % block])
-                            V.append([vv[base * BB + (j * BB + q) * WAVE + lane]])
+                            V.append([vv[(base + j * WAVE) * BB + off + stride * lane]])
         elif "slice_ptr" in a:   # SELL
             sp, cc, vv = a["slice_ptr"], a["cols"], a["vals"]
             nsl = len(sp) - 1
@@ -300,13 +342,18 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
                     pos = base + lane + WAVE * np.arange(w)
                     R.append(np.full(w, r, dtype=np.int64)); C.append(cc[pos]); V.append(vv[pos])
         elif "lcols" in a:       # heavy stripes
-            sp, lc, vv, hr = a["seg_ptr"], a["lcols"], a["vals"], a["rows"]
-            nh = len(hr)
-            for g in range(len(sp) - 1):
-                s, h = divmod(g, nh)
-                e = slice(int(sp[g]), int(sp[g + 1]))
-                n = e.stop - e.start
-                R.append(np.full(n, int(hr[h]), dtype=np.int64)); C.append(lc[e].astype(np.int64) + s * tile); V.append(vv[e])
+            up, lc, vv, hr, lr = a["unit_ptr"], a["lcols"], a["vals"], a["rows"], a["lane_row"]
+            nsl = -(-len(hr) // WAVE)
+            for u in range(len(up) - 1):
+                s = u // nsl
+                base, w = int(up[u]), int(up[u + 1] - up[u]) // WAVE
+                for lane in range(WAVE):
+                    h = int(lr[u * WAVE + lane])
+                    pos = base + lane + WAVE * np.arange(w)
+                    if h == 0xFFFF:
+                        assert not np.any(vv[pos])
+                        continue
+                    R.append(np.full(w, int(hr[h]), dtype=np.int64)); C.append(lc[pos].astype(np.int64) + s * tile); V.append(vv[pos])
         else:                    # CSR segments
             sp, cc, vv = a["seg_ptr"], a["cols"], a["vals"]
             sr = a.get("seg_row")

@@ -11,7 +11,8 @@
 //   - SORT / SORT_SUB are stable: rows of equal length keep ascending original order; the windows
 //     of SORT_SUB start at the first row of the part and the last one may be short.
 //   - PAD fills a slice to the longest row of that slice with value 0 and the column of the row's
-//     last real entry (column 0 for an empty row), so padded gathers stay in bounds and local.
+//     last real entry (for an empty row: the first column of the slice's first row, 0 if that row
+//     is empty too), so padded gathers stay in bounds and inside the slice's window of x.
 //   - A row cut by *_COL_BLOCK into several segments reduces through atomics into a y element that
 //     an earlier launch set to zero.
 #include <hip/hip_runtime_api.h>
@@ -136,6 +137,9 @@ void build_sell(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int sig
         for (int64_t s = sb; s < se; ++s) {
             const int64_t base = slice_ptr[(size_t)s];
             const int64_t w = (slice_ptr[(size_t)s + 1] - base) / kWave;
+            // padding column of empty lanes: the first column of the slice's first row
+            const int32_t r0 = rows[(size_t)(s * kWave)];
+            const int32_t fallback = lens[(size_t)r0] > 0 ? A.col[A.row_ptr[r0]] : 0;
             for (int lane = 0; lane < kWave; ++lane) {
                 const int64_t i = s * kWave + lane;
                 int64_t L = 0, src = 0;
@@ -149,7 +153,7 @@ void build_sell(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int sig
                     cols[base + j * kWave + lane] = A.col[src + j];
                     vals[base + j * kWave + lane] = av[src + j];
                 }
-                const int32_t padc = L > 0 ? A.col[src + L - 1] : 0;
+                const int32_t padc = L > 0 ? A.col[src + L - 1] : fallback;
                 for (; j < w; ++j) {
                     cols[base + j * kWave + lane] = padc;
                     vals[base + j * kWave + lane] = T(0);
@@ -321,7 +325,7 @@ void build_dia(Plan &plan, const HostCsr &A, const std::vector<int32_t> &offs, O
 
 // ---- dense B x B blocks in SELL order ----------------------------------------------------------
 template <typename T>
-void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int threads) {
+void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int xwin, int threads) {
     if (A.nrows % B || A.ncols % B)
         fail(SPMV_ERR_UNSUPPORTED, "bsell: matrix dimensions are not multiples of the block edge");
     const int64_t nb = A.nrows / B;
@@ -358,6 +362,7 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
     }
     const int64_t total = slice_ptr[(size_t)nsl];
     const int BB = B * B;
+    const int V = 16 / (int)sizeof(T), NV = BB / V;   // values packed per 16-byte load, vectors per block
     if (total * BB >= ((int64_t)1 << 33)) fail(SPMV_ERR_UNSUPPORTED, "bsell: padded size too large");
     HostBuf<int32_t> bcols(total);
     HostBuf<T> vals(total * BB);
@@ -369,6 +374,9 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
             const int64_t w = (slice_ptr[(size_t)s + 1] - base) / kWave;
             T *vs = vals.p + base * BB;
             for (int64_t q = 0; q < w * BB * kWave; ++q) vs[q] = T(0);
+            int32_t fallback = 0;   // padding column of empty lanes: first block column of the slice's first row
+            block_cols(brows[(size_t)(s * kWave)], bc);
+            if (!bc.empty()) fallback = bc[0];
             for (int lane = 0; lane < kWave; ++lane) {
                 const int64_t i = s * kWave + lane;
                 bc.clear();
@@ -381,14 +389,17 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
                         for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
                             const int32_t b = A.col[k] / B;
                             while (bc[j] != b) ++j;   // columns ascend, so j only moves forward
-                            const int ci = A.col[k] - b * B;
-                            vs[((int64_t)j * BB + ri * B + ci) * kWave + lane] += av[k];
+                            const int q = ri * B + (A.col[k] - b * B);
+                            // record of block j: NV vectors of V values per lane, then the rest
+                            T *rec = vs + (int64_t)j * BB * kWave;
+                            if (q < NV * V) rec[((int64_t)(q / V) * kWave + lane) * V + (q % V)] += av[k];
+                            else rec[(int64_t)NV * V * kWave + (int64_t)(q - NV * V) * kWave + lane] += av[k];
                         }
                     }
                 }
                 const int64_t L = (int64_t)bc.size();
                 for (int64_t j = 0; j < L; ++j) bcols[base + j * kWave + lane] = bc[(size_t)j];
-                const int32_t padc = L > 0 ? bc[(size_t)L - 1] : 0;
+                const int32_t padc = L > 0 ? bc[(size_t)L - 1] : fallback;
                 for (int64_t j = L; j < w; ++j) bcols[base + j * kWave + lane] = padc;
             }
         }
@@ -403,6 +414,32 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
     p.block = B;
     p.has_rows = sigma != 0;
     p.remap = remap;
+    if (xwin) {
+        // x window of each group of 32 slices: [lo, lo + n) in scalar columns
+        const int64_t ng = (nsl + kXwinGroup - 1) / kXwinGroup;
+        std::vector<int32_t> win((size_t)(2 * ng), 0);
+        std::atomic<int64_t> widest{0};
+        parallel_for(ng, 4, threads, [&](int64_t gb, int64_t ge, int) {
+            for (int64_t g = gb; g < ge; ++g) {
+                const int64_t b0 = slice_ptr[(size_t)(g * kXwinGroup)];
+                const int64_t b1 = slice_ptr[(size_t)std::min(nsl, (g + 1) * kXwinGroup)];
+                int32_t lo = INT32_MAX, hi = -1;
+                for (int64_t i = b0; i < b1; ++i) {
+                    lo = std::min(lo, bcols[i]);
+                    hi = std::max(hi, bcols[i]);
+                }
+                if (hi < 0) lo = 0;
+                win[(size_t)(2 * g)] = lo * B;
+                win[(size_t)(2 * g + 1)] = (hi - lo + 1) * B;
+                int64_t n = (int64_t)(hi - lo + 1) * B, cur = widest.load();
+                while (n > cur && !widest.compare_exchange_weak(cur, n)) {}
+            }
+        });
+        if (widest.load() * (int64_t)sizeof(T) > kXwinMaxBytes)
+            fail(SPMV_ERR_UNSUPPORTED, "bsell: the x window of a workgroup does not fit the LDS");
+        p.lds_bytes = std::max<int64_t>(widest.load() * (int64_t)sizeof(T), 16);
+        p.p4 = upload(plan, "bsell.xwin", 4, 2 * ng, win.data());
+    }
     p.p0 = upload(plan, "bsell.slice_ptr", 8, nsl + 1, slice_ptr.data());
     p.p1 = upload(plan, "bsell.bcols", 4, total, bcols.p);
     p.p2 = upload(plan, "bsell.vals", (int)sizeof(T), total * BB, vals.p);
@@ -412,42 +449,76 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
 }
 
 // ---- heavy rows in column stripes --------------------------------------------------------------
+// COL_DIV into stripes of `tile` columns; inside a stripe SORT_BMTB orders the heavy rows by the
+// number of entries they have there (stable, decreasing), slices of 64 rows are padded to their
+// longest segment (value 0, local column 0) and stored lane-interleaved.
 template <typename T>
 void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile,
-                  int lps, const std::vector<int64_t> &lens, int threads) {
+                  const std::vector<int64_t> &lens, int threads) {
     const int64_t nh = (int64_t)hrows.size();
     if (nh == 0) return;
     if ((size_t)tile * sizeof(T) > 65536) fail(SPMV_ERR_UNSUPPORTED, "heavy: tile does not fit 64 KiB of LDS");
+    if (nh > 65535) fail(SPMV_ERR_UNSUPPORTED, "heavy: more than 65535 heavy rows");
     const int64_t ns = (A.ncols + tile - 1) / tile;
-    if (ns * nh >= ((int64_t)1 << 27)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many (row, stripe) segments");
-    std::vector<int32_t> seg_ptr((size_t)(ns * nh) + 1, 0);
+    const int64_t nsl = (nh + kWave - 1) / kWave;
+    if (ns * nsl * kWave >= ((int64_t)1 << 28)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many (row, stripe) segments");
     int64_t total = 0;
     for (int32_t r : hrows) total += lens[(size_t)r];
-    if (total >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many entries");
+    // seg_len[s * nh + h] and seg_off[s * nh + h]: the entries of heavy row h inside stripe s are
+    // A[row_ptr[r] + seg_off .. + seg_len)   (columns ascend inside a row)
+    std::vector<int32_t> seg_len((size_t)(ns * nh), 0), seg_off((size_t)(ns * nh), 0);
     parallel_for(nh, 4, threads, [&](int64_t b, int64_t e, int) {
         for (int64_t h = b; h < e; ++h) {
             const int32_t r = hrows[(size_t)h];
-            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k)
-                seg_ptr[(size_t)((int64_t)(A.col[k] / tile) * nh + h) + 1] += 1;
+            const int64_t beg = A.row_ptr[r];
+            for (int64_t k = beg; k < A.row_ptr[r + 1]; ++k) {
+                const size_t i = (size_t)((int64_t)(A.col[k] / tile) * nh + h);
+                if (seg_len[i]++ == 0) seg_off[i] = (int32_t)(k - beg);
+            }
         }
     });
-    for (int64_t i = 0; i < ns * nh; ++i) seg_ptr[(size_t)i + 1] += seg_ptr[(size_t)i];
-    HostBuf<uint16_t> lcol(total);
-    HostBuf<T> vals(total);
+    // per stripe: order of the heavy rows, slice widths
+    std::vector<uint16_t> lane_row((size_t)(ns * nsl * kWave), (uint16_t)0xFFFF);
+    std::vector<int64_t> unit_w((size_t)(ns * nsl), 0);
+    parallel_for(ns, 1, threads, [&](int64_t sb, int64_t se, int) {
+        std::vector<int32_t> order((size_t)nh);
+        for (int64_t s = sb; s < se; ++s) {
+            const int32_t *sl = seg_len.data() + s * nh;
+            std::iota(order.begin(), order.end(), 0);
+            std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return sl[a] > sl[b]; });
+            for (int64_t i = 0; i < nh; ++i) lane_row[(size_t)(s * nsl * kWave + i)] = (uint16_t)order[(size_t)i];
+            for (int64_t g = 0; g < nsl; ++g) unit_w[(size_t)(s * nsl + g)] = sl[order[(size_t)(g * kWave)]];
+        }
+    });
+    std::vector<int32_t> unit_ptr((size_t)(ns * nsl) + 1, 0);
+    int64_t padded = 0;
+    for (int64_t u = 0; u < ns * nsl; ++u) {
+        padded += unit_w[(size_t)u] * kWave;
+        if (padded >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many entries");
+        unit_ptr[(size_t)u + 1] = (int32_t)padded;
+    }
+    HostBuf<uint16_t> lcol(padded);
+    HostBuf<T> vals(padded);
     const T *av = (const T *)A.val;
-    parallel_for(nh, 4, threads, [&](int64_t b, int64_t e, int) {
-        for (int64_t h = b; h < e; ++h) {
-            const int32_t r = hrows[(size_t)h];
-            int64_t cur_s = -1, dst = 0;
-            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {   // columns ascend
-                const int64_t s = A.col[k] / tile;
-                if (s != cur_s) {
-                    cur_s = s;
-                    dst = seg_ptr[(size_t)(s * nh + h)];
+    parallel_for(ns * nsl, 8, threads, [&](int64_t ub, int64_t ue, int) {
+        for (int64_t u = ub; u < ue; ++u) {
+            const int64_t s = u / nsl, base = unit_ptr[(size_t)u], w = unit_w[(size_t)u];
+            for (int lane = 0; lane < kWave; ++lane) {
+                const uint16_t h = lane_row[(size_t)(u * kWave + lane)];
+                int64_t L = 0, src = 0;
+                if (h != 0xFFFF) {
+                    L = seg_len[(size_t)(s * nh + h)];
+                    src = (int64_t)A.row_ptr[hrows[h]] + seg_off[(size_t)(s * nh + h)];
                 }
-                lcol[dst] = (uint16_t)(A.col[k] - s * tile);
-                vals[dst] = av[k];
-                ++dst;
+                int64_t j = 0;
+                for (; j < L; ++j) {
+                    lcol[base + j * kWave + lane] = (uint16_t)(A.col[src + j] - s * tile);
+                    vals[base + j * kWave + lane] = av[src + j];
+                }
+                for (; j < w; ++j) {
+                    lcol[base + j * kWave + lane] = 0;
+                    vals[base + j * kWave + lane] = T(0);
+                }
             }
         }
     });
@@ -456,15 +527,16 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     p.name = "heavy";
     p.nrows = nh;
     p.nnz = total;
-    p.stored = total;
+    p.stored = padded;
     p.units = ns;
-    p.lanes = lps;
+    p.nslices = nsl;
     p.tile = tile;
     p.has_rows = true;
-    p.p0 = upload(plan, "heavy.seg_ptr", 4, ns * nh + 1, seg_ptr.data());
-    p.p1 = upload(plan, "heavy.lcols", 2, total, lcol.p);
-    p.p2 = upload(plan, "heavy.vals", (int)sizeof(T), total, vals.p);
+    p.p0 = upload(plan, "heavy.unit_ptr", 4, ns * nsl + 1, unit_ptr.data());
+    p.p1 = upload(plan, "heavy.lcols", 2, padded, lcol.p);
+    p.p2 = upload(plan, "heavy.vals", (int)sizeof(T), padded, vals.p);
     p.p3 = upload(plan, "heavy.rows", 4, nh, hrows.data());
+    p.p4 = upload(plan, "heavy.lane_row", 2, ns * nsl * kWave, lane_row.data());
     plan.parts.push_back(p);
 }
 
@@ -546,7 +618,7 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
     });
 
     if (spec.light == L_BSELL) {
-        build_bsell<T>(*plan, A, spec.block, spec.sigma, spec.remap, threads);
+        build_bsell<T>(*plan, A, spec.block, spec.sigma, spec.remap, spec.xwin, threads);
         return plan;
     }
 
@@ -587,7 +659,7 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
     }
     default: fail(SPMV_ERR_INVALID_ARG, "unknown light design");
     }
-    if (!heavy.empty()) build_stripe<T>(*plan, A, heavy, spec.tile, spec.hlps, lens, threads);
+    if (!heavy.empty()) build_stripe<T>(*plan, A, heavy, spec.tile, lens, threads);
 
     if (!zero_rows.empty()) {
         std::sort(zero_rows.begin(), zero_rows.end());

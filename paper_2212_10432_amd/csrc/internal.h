@@ -18,6 +18,9 @@ namespace spmv {
 
 // Lanes of a wavefront on CDNA4.  The paper's "warp" (32 lanes, Section IV-A) maps to this.
 constexpr int kWave = 64;
+// Blocked SELL with an LDS x window: slices per workgroup, and the LDS budget of a window.
+constexpr int kXwinGroup = 32;
+constexpr int64_t kXwinMaxBytes = 160 * 1024;
 
 struct Error {
     spmv_status_t code;
@@ -76,7 +79,6 @@ struct PlanSpec {
     double dia_fill = 0.5;   //   minimum population of a diagonal to be extracted
     int64_t heavy = 0;       // ROW_DIV: rows longer than this go to the heavy part (0 = no split)
     int tile = 8192;         //   COL_DIV width of the heavy part (columns per LDS tile of x)
-    int hlps = 16;           //   lanes per (row, tile) segment in the heavy kernel
     int light = L_CSRV;      // design of the remaining rows
     int lpr = 0;             // csrv: lanes per row (power of two <= 64; 0 = from the mean length)
     int64_t chunk = 0;       // csrv: rows longer than this are cut into segments (0 = never)
@@ -84,6 +86,7 @@ struct PlanSpec {
     int block = 3;           // bsell: block edge (2, 3 or 4)
     int smax = 16;           // bin: rows up to this length go to the SELL bin
     int remap = 0;           // 1 = give each XCD a contiguous range of workgroups
+    int xwin = 0;            // bsell: stage the x window of 32 slices in LDS when it fits
 };
 PlanSpec parse_spec(const std::string &s);
 std::string print_spec(const PlanSpec &p);
@@ -116,6 +119,8 @@ struct Part {
     int tile = 0;
     int remap = 0;
     int64_t ld = 0;              // dia leading dimension
+    int64_t nslices = 0;         // heavy part: slices of 64 heavy rows per stripe
+    int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
     const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
     int64_t y_passes = 1;        // how many times this part touches its rows of y (bytes model)
 };

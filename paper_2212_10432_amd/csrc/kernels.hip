@@ -15,6 +15,7 @@ namespace spmv {
 namespace {
 
 constexpr int kWG = 256;   // workgroup size of the streaming kernels: 4 wavefronts
+constexpr int kMaxLds = 160 * 1024;   // LDS of one CDNA4 compute unit
 
 template <typename T>
 __device__ __forceinline__ T ldnt(const T *p) {
@@ -159,9 +160,65 @@ __global__ __launch_bounds__(kWG) void k_csrv(const int32_t *__restrict__ seg_pt
 
 // ---- blocked SELL: dense B x B blocks, one lane per block row -------------------------------
 // The SELL design applied to block rows; one column index per block (the per-entry indices of a
-// block follow a periodic linear model, Section V-D), B accumulators per lane in registers.
-// Value (ri, ci) of block j of the block row held by `lane` sits at
-// B*B*slice_ptr[s] + 64*(B*B*j + B*ri + ci) + lane.
+// block follow a periodic linear model, Section V-D), B accumulators per lane in registers
+// (THREAD_TOTAL_RED).  The B*B values of block j of the block row held by `lane` form a record
+// of 64*B*B values starting at B*B*(slice_ptr[s] + 64*j); inside the record the first
+// NV*V values of a lane are packed for 16-byte loads (vector p of the lane at V*(64*p + lane)),
+// the remaining B*B - NV*V values follow one per lane (at V*NV*64 + 64*r + lane).
+template <typename T, int B>
+struct BlockLoad {
+    static constexpr int BB = B * B;
+    static constexpr int V = 16 / (int)sizeof(T);
+    static constexpr int NV = BB / V;
+    static constexpr int NR = BB % V;
+    typedef T VT __attribute__((ext_vector_type(V)));
+    // values of one block into av[q], q = B*ri + ci
+    static __device__ __forceinline__ void load(const T *rec, int lane, T *av) {
+        VT pv[NV];
+#pragma unroll
+        for (int p = 0; p < NV; ++p) pv[p] = ldnt(reinterpret_cast<const VT *>(rec) + p * 64 + lane);
+#pragma unroll
+        for (int p = 0; p < NV; ++p)
+#pragma unroll
+            for (int e = 0; e < V; ++e) av[p * V + e] = pv[p][e];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) av[NV * V + r] = ldnt(rec + NV * V * 64 + r * 64 + lane);
+    }
+};
+
+// One slice: the gathers of block j are issued before the loads of block j + 1, so waiting for
+// x leaves the next block's stream in flight.  XS = true gathers from the LDS copy of x.
+template <typename T, int B, bool XS>
+__device__ __forceinline__ void bsell_slice(const int32_t *__restrict__ c, const T *__restrict__ v,
+                                            int w, int lane, const T *__restrict__ xsrc,
+                                            int64_t xbase, T *acc) {
+    constexpr int BB = B * B;
+    if (w <= 0) return;
+    int64_t xc = (int64_t)ldnt(c) * B - xbase;
+    T av[BB];
+    BlockLoad<T, B>::load(v, lane, av);
+    for (int j = 0; j < w; ++j) {
+        T xv[B];
+#pragma unroll
+        for (int ci = 0; ci < B; ++ci) xv[ci] = xsrc[xc + ci];
+        int64_t xcn = xc;
+        T an[BB];
+#pragma unroll
+        for (int q = 0; q < BB; ++q) an[q] = av[q];
+        if (j + 1 < w) {   // uniform over the wavefront
+            xcn = (int64_t)ldnt(c + (j + 1) * 64) * B - xbase;
+            BlockLoad<T, B>::load(v + (int64_t)(j + 1) * 64 * BB, lane, an);
+        }
+#pragma unroll
+        for (int ri = 0; ri < B; ++ri)
+#pragma unroll
+            for (int ci = 0; ci < B; ++ci) acc[ri] += av[ri * B + ci] * xv[ci];
+#pragma unroll
+        for (int q = 0; q < BB; ++q) av[q] = an[q];
+        xc = xcn;
+    }
+}
+
 template <typename T, int B, bool ROWS>
 __global__ __launch_bounds__(kWG) void k_bsell(const int64_t *__restrict__ slice_ptr,
                                                const int32_t *__restrict__ bcols,
@@ -175,24 +232,10 @@ __global__ __launch_bounds__(kWG) void k_bsell(const int64_t *__restrict__ slice
     if (s >= nslices) return;
     const int64_t b = slice_ptr[s];
     const int w = (int)((slice_ptr[s + 1] - b) >> 6);
-    const int32_t *c = bcols + b + lane;
-    const T *v = vals + b * (B * B) + lane;
     T acc[B];
 #pragma unroll
     for (int ri = 0; ri < B; ++ri) acc[ri] = T(0);
-    for (int j = 0; j < w; ++j) {
-        const int64_t xc = (int64_t)ldnt(c + j * 64) * B;
-        T av[B * B];
-#pragma unroll
-        for (int q = 0; q < B * B; ++q) av[q] = ldnt(v + ((int64_t)j * (B * B) + q) * 64);
-        T xv[B];
-#pragma unroll
-        for (int ci = 0; ci < B; ++ci) xv[ci] = x[xc + ci];
-#pragma unroll
-        for (int ri = 0; ri < B; ++ri)
-#pragma unroll
-            for (int ci = 0; ci < B; ++ci) acc[ri] += av[ri * B + ci] * xv[ci];
-    }
+    bsell_slice<T, B, false>(bcols + b + lane, vals + b * (B * B), w, lane, x, 0, acc);
     const int64_t r = s * 64 + lane;
     if (r < nbrows_part) {
         const int64_t br = ROWS ? (int64_t)brows[r] : r;
@@ -201,19 +244,62 @@ __global__ __launch_bounds__(kWG) void k_bsell(const int64_t *__restrict__ slice
     }
 }
 
+// Blocked SELL with the x window of the workgroup staged in LDS.  A workgroup of 16 wavefronts
+// owns 32 consecutive slices (one SORT_SUB window of 2048 block rows when sigma = 2048); the
+// columns its blocks touch lie in [win[2g], win[2g] + win[2g+1]), copied once with coalesced
+// loads; all gathers then go to LDS and leave the vector-memory path to the matrix stream.
+// Wavefront w takes slices w and 31 - w: inside a sorted window that pairs the longest slice with
+// the shortest, so the 16 wavefronts finish together.
+constexpr int kXwinWaves = 16;
+constexpr int kXwinSlices = 2 * kXwinWaves;
+template <typename T, int B, bool ROWS>
+__global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
+    const int64_t *__restrict__ slice_ptr, const int32_t *__restrict__ bcols,
+    const T *__restrict__ vals, const int32_t *__restrict__ brows, const int32_t *__restrict__ win,
+    const T *__restrict__ x, T *__restrict__ y, int64_t nslices, int64_t nbrows_part, int remap) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    T *xs = reinterpret_cast<T *>(smem);
+    const int64_t blk = logical_block(blockIdx.x, gridDim.x, remap);
+    const int lo = win[2 * blk], n = win[2 * blk + 1];
+    for (int i = threadIdx.x; i < n; i += kXwinWaves * kWave) xs[i] = x[lo + i];
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        const int64_t s = blk * kXwinSlices + (half ? kXwinSlices - 1 - wave : wave);
+        if (s >= nslices) continue;
+        const int64_t b = slice_ptr[s];
+        const int w = (int)((slice_ptr[s + 1] - b) >> 6);
+        T acc[B];
+#pragma unroll
+        for (int ri = 0; ri < B; ++ri) acc[ri] = T(0);
+        bsell_slice<T, B, true>(bcols + b + lane, vals + b * (B * B), w, lane, xs, lo, acc);
+        const int64_t r = s * 64 + lane;
+        if (r < nbrows_part) {
+            const int64_t br = ROWS ? (int64_t)brows[r] : r;
+#pragma unroll
+            for (int ri = 0; ri < B; ++ri) y[br * B + ri] = acc[ri];
+        }
+    }
+}
+
 // ---- heavy rows, column stripes: x tile in LDS ----------------------------------------------
-// ROW_DIV (rows longer than a threshold) then COL_DIV (stripes of `tile` columns).  A workgroup
-// copies its stripe of x into LDS with coalesced loads, then walks the (row, stripe) segments:
-// LPS lanes per segment gather from LDS with 16-bit local columns, WARP_TOTAL_RED over the
-// group, GMEM_ATOM_RED into y (zeroed by k_zero_rows).  x is read once per row group instead of
-// once per non-zero cache line.
-template <typename T, int LPS>
-__global__ __launch_bounds__(512) void k_stripe(const int32_t *__restrict__ seg_ptr,
-                                                const uint16_t *__restrict__ lcol,
-                                                const T *__restrict__ vals,
-                                                const int32_t *__restrict__ hrows,
-                                                const T *__restrict__ x, T *__restrict__ y,
-                                                int nh, int tile, int64_t ncols, int rows_per_y) {
+// ROW_DIV (rows longer than a threshold), then COL_DIV (stripes of `tile` columns): one workgroup
+// (BMTB) owns a stripe and copies its piece of x into LDS with coalesced loads.  Inside the
+// stripe the heavy rows are sorted by the number of entries they have in it (SORT_BMTB) and cut
+// into slices of 64 (BMW_ROW_BLOCK), each padded to its longest row (BMW_PAD): a lane owns one
+// (row, stripe) segment, gathers x from LDS through 16-bit local columns and keeps its sum in a
+// register (THREAD_TOTAL_RED); one atomic per lane adds it to y (GMEM_ATOM_RED; y was zeroed by
+// k_zero_rows).  x is read from memory once per workgroup instead of once per non-zero line.
+// Entry j of lane `lane` of unit u = stripe * nsl + slice sits at unit_ptr[u] + 64*j + lane.
+template <typename T>
+__global__ __launch_bounds__(512) void k_hsell(const int32_t *__restrict__ unit_ptr,
+                                               const uint16_t *__restrict__ lcol,
+                                               const T *__restrict__ vals,
+                                               const int32_t *__restrict__ hrows,
+                                               const uint16_t *__restrict__ lane_row,
+                                               const T *__restrict__ x, T *__restrict__ y,
+                                               int nsl, int tile, int64_t ncols, int slices_per_y) {
     extern __shared__ __align__(16) unsigned char smem[];
     T *xs = reinterpret_cast<T *>(smem);
     const int s = blockIdx.x;
@@ -221,29 +307,32 @@ __global__ __launch_bounds__(512) void k_stripe(const int32_t *__restrict__ seg_
     const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
     for (int i = threadIdx.x; i < w; i += blockDim.x) xs[i] = x[c0 + i];
     __syncthreads();
-    const int ngroups = blockDim.x / LPS;
-    const int g = threadIdx.x / LPS, t = threadIdx.x % LPS;
-    const int32_t *sp = seg_ptr + (int64_t)s * nh;
-    const int hbeg = blockIdx.y * rows_per_y;
-    const int hend = (hbeg + rows_per_y < nh) ? hbeg + rows_per_y : nh;
-    for (int h0 = hbeg; h0 < hend; h0 += ngroups) {   // same trip count for every lane of the group
-        const int h = h0 + g;
-        int32_t b = 0, e = 0;
-        if (h < hend) {
-            b = sp[h];
-            e = sp[h + 1];
-        }
-        T a0 = T(0), a1 = T(0);
-        int32_t k = b + t;
-        for (; k + LPS < e; k += 2 * LPS) {
-            const uint16_t c0l = ldnt(lcol + k), c1l = ldnt(lcol + k + LPS);
-            const T v0 = ldnt(vals + k), v1 = ldnt(vals + k + LPS);
+    const int lane = threadIdx.x & 63;
+    const int nwaves = blockDim.x >> 6;
+    const int gbeg = blockIdx.y * slices_per_y;
+    const int gend = (gbeg + slices_per_y < nsl) ? gbeg + slices_per_y : nsl;
+    for (int g = gbeg + (threadIdx.x >> 6); g < gend; g += nwaves) {
+        const int64_t u = (int64_t)s * nsl + g;
+        const int32_t b = unit_ptr[u];
+        const int wd = (unit_ptr[u + 1] - b) >> 6;
+        if (wd == 0) continue;
+        const uint16_t *c = lcol + b + lane;
+        const T *v = vals + b + lane;
+        T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
+        int j = 0;
+        for (; j + 4 <= wd; j += 4) {
+            const uint16_t c0l = ldnt(c + (j + 0) * 64), c1l = ldnt(c + (j + 1) * 64);
+            const uint16_t c2l = ldnt(c + (j + 2) * 64), c3l = ldnt(c + (j + 3) * 64);
+            const T v0 = ldnt(v + (j + 0) * 64), v1 = ldnt(v + (j + 1) * 64);
+            const T v2 = ldnt(v + (j + 2) * 64), v3 = ldnt(v + (j + 3) * 64);
             a0 += v0 * xs[c0l];
             a1 += v1 * xs[c1l];
+            a2 += v2 * xs[c2l];
+            a3 += v3 * xs[c3l];
         }
-        for (; k < e; k += LPS) a0 += ldnt(vals + k) * xs[ldnt(lcol + k)];
-        const T acc = group_sum<LPS>(a0 + a1);
-        if (t == 0 && e > b) atomic_add(y + hrows[h], acc);
+        for (; j < wd; ++j) a0 += ldnt(v + j * 64) * xs[ldnt(c + j * 64)];
+        const uint16_t lr = lane_row[u * 64 + lane];
+        if (lr != 0xFFFFu) atomic_add(y + hrows[lr], (a0 + a1) + (a2 + a3));
     }
 }
 
@@ -300,6 +389,35 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     }
     case K_BSELL: {
         if (p.units == 0) return 0;
+        if (p.lds_bytes > 0) {   // x window in LDS: 32 slices per workgroup of 1024 threads
+            const unsigned grid = blocks(p.units, kXwinSlices);
+            const int threads = kXwinWaves * kWave;
+#define XWIN_GO(B, R)                                                                              \
+    {                                                                                              \
+        static std::atomic<int> lds_set{0};                                                        \
+        if (lds_set.load() < p.lds_bytes) {                                                        \
+            hipError_t e = hipFuncSetAttribute((const void *)k_bsell_xwin<T, B, R>,                \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,        \
+                                               (int)kMaxLds);                                      \
+            if (e != hipSuccess) return (int)e;                                                    \
+            lds_set.store((int)kMaxLds);                                                           \
+        }                                                                                          \
+        k_bsell_xwin<T, B, R><<<grid, threads, (size_t)p.lds_bytes, st>>>(                         \
+            (const int64_t *)p.p0, (const int32_t *)p.p1, (const T *)p.p2, (const int32_t *)p.p3,  \
+            (const int32_t *)p.p4, x, y, p.units, p.nrows, p.remap);                               \
+    }
+#define XWIN_B(B)                                                                                  \
+    case B:                                                                                        \
+        if (p.has_rows) XWIN_GO(B, true) else XWIN_GO(B, false)                                    \
+        break;
+            switch (p.block) {
+                XWIN_B(2) XWIN_B(3) XWIN_B(4)
+            default: return (int)hipErrorInvalidValue;
+            }
+#undef XWIN_B
+#undef XWIN_GO
+            break;
+        }
         const unsigned grid = blocks(p.units, kWG / kWave);
 #define BSELL_GO(B, R)                                                                             \
     k_bsell<T, B, R><<<grid, kWG, 0, st>>>((const int64_t *)p.p0, (const int32_t *)p.p1,          \
@@ -318,30 +436,21 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         break;
     }
     case K_STRIPE: {
-        if (p.units == 0 || p.nrows == 0) return 0;
-        const int nh = (int)p.nrows;
-        const int threads = 512;
-        const int ngroups = threads / p.lanes;
-        // enough workgroups to fill 256 CUs: split the heavy rows over blockIdx.y when there
-        // are few stripes
+        if (p.units == 0 || p.nslices == 0) return 0;
+        const int threads = 512, nwaves = threads / kWave;
+        // enough workgroups to fill 256 CUs: split the slices of a stripe over blockIdx.y when
+        // there are few stripes, but keep every wavefront of a workgroup busy
         int64_t ysplit = (1024 + p.units - 1) / p.units;
-        const int64_t max_split = (nh + ngroups - 1) / ngroups;
+        const int64_t max_split = (p.nslices + nwaves - 1) / nwaves;
         if (ysplit > max_split) ysplit = max_split;
         if (ysplit < 1) ysplit = 1;
-        const int rows_per_y = (int)((nh + ysplit - 1) / ysplit);
-        const dim3 grid((unsigned)p.units, (unsigned)((nh + rows_per_y - 1) / rows_per_y));
+        const int spy = (int)((p.nslices + ysplit - 1) / ysplit);
+        const dim3 grid((unsigned)p.units, (unsigned)((p.nslices + spy - 1) / spy));
         const size_t lds = (size_t)p.tile * sizeof(T);
-#define STRIPE_L(L)                                                                                \
-    case L:                                                                                        \
-        k_stripe<T, L><<<grid, threads, lds, st>>>((const int32_t *)p.p0, (const uint16_t *)p.p1,  \
-                                                   (const T *)p.p2, (const int32_t *)p.p3, x, y,   \
-                                                   nh, p.tile, ncols, rows_per_y);                 \
-        break;
-        switch (p.lanes) {
-            STRIPE_L(4) STRIPE_L(8) STRIPE_L(16) STRIPE_L(32) STRIPE_L(64)
-        default: return (int)hipErrorInvalidValue;
-        }
-#undef STRIPE_L
+        k_hsell<T><<<grid, threads, lds, st>>>((const int32_t *)p.p0, (const uint16_t *)p.p1,
+                                               (const T *)p.p2, (const int32_t *)p.p3,
+                                               (const uint16_t *)p.p4, x, y, (int)p.nslices, p.tile,
+                                               ncols, spy);
         break;
     }
     }

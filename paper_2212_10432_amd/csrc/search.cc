@@ -49,6 +49,15 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
         for (int b = 4; b >= 2; --b)
             if (c.block_fill[b] >= 0.85 && (best == 0 || c.block_fill[b] > c.block_fill[best] + 0.05)) best = b;
         if (best) {
+            {   // x window of 2048 block rows staged in LDS (rejected by the builder if too wide)
+                PlanSpec p;
+                p.light = L_BSELL;
+                p.block = best;
+                p.sigma = 64 * kXwinGroup;
+                p.remap = 1;
+                p.xwin = 1;
+                push(p);
+            }
             for (int remap = 1; remap >= 0; --remap) {
                 PlanSpec p;
                 p.light = L_BSELL;
@@ -85,7 +94,6 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             if (heavy) {
                 p.heavy = hth;
                 p.tile = tile;
-                p.hlps = 16;
             }
             push(p);
         }

@@ -96,26 +96,27 @@ PlanSpec parse_spec(const std::string &s) {
         else if (k == "dia_fill") p.dia_fill = num();
         else if (k == "heavy") p.heavy = (int64_t)num();
         else if (k == "tile") p.tile = (int)num();
-        else if (k == "hlps") p.hlps = (int)num();
         else if (k == "lpr") p.lpr = (int)num();
         else if (k == "chunk") p.chunk = (int64_t)num();
         else if (k == "sigma") p.sigma = (int)num();
         else if (k == "block") p.block = (int)num();
         else if (k == "smax") p.smax = (int)num();
         else if (k == "remap") p.remap = (int)num();
+        else if (k == "xwin") p.xwin = (int)num();
         else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown key " + k);
     }
     if (p.dia != 0 && p.dia != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia must be 0 or 1");
     if (!(p.dia_fill > 0 && p.dia_fill <= 1)) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia_fill must be in (0,1]");
     if (p.heavy < 0) fail(SPMV_ERR_INVALID_ARG, "plan spec: heavy must be >= 0");
     if (p.tile < 64 || p.tile > 65536 || p.tile % 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: tile must be a multiple of 64 in [64, 65536]");
-    if (!pow2(p.hlps) || p.hlps < 4 || p.hlps > 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: hlps must be 4..64, power of two");
     if (p.lpr != 0 && (!pow2(p.lpr) || p.lpr > 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: lpr must be 0 or a power of two <= 64");
     if (p.chunk < 0 || (p.chunk > 0 && p.chunk < 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: chunk must be 0 or >= 64");
     if (p.sigma < -1) fail(SPMV_ERR_INVALID_ARG, "plan spec: sigma must be >= -1");
     if (p.block < 2 || p.block > 4) fail(SPMV_ERR_INVALID_ARG, "plan spec: block must be 2, 3 or 4");
     if (p.smax < 0 || p.smax > 1024) fail(SPMV_ERR_INVALID_ARG, "plan spec: smax must be in [0, 1024]");
     if (p.remap != 0 && p.remap != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: remap must be 0 or 1");
+    if (p.xwin != 0 && p.xwin != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin must be 0 or 1");
+    if (p.xwin && p.light != L_BSELL) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin needs light=bsell");
     if (p.light == L_BSELL && (p.dia || p.heavy)) fail(SPMV_ERR_INVALID_ARG, "plan spec: bsell cannot be combined with dia or heavy");
     return p;
 }
@@ -123,12 +124,12 @@ PlanSpec parse_spec(const std::string &s) {
 std::string print_spec(const PlanSpec &p) {
     std::ostringstream o;
     if (p.dia) o << "dia=1,dia_fill=" << p.dia_fill << ",";
-    if (p.heavy) o << "heavy=" << p.heavy << ",tile=" << p.tile << ",hlps=" << p.hlps << ",";
+    if (p.heavy) o << "heavy=" << p.heavy << ",tile=" << p.tile << ",";
     o << "light=" << light_name(p.light);
     switch (p.light) {
     case L_CSRV: o << ",lpr=" << p.lpr << ",chunk=" << p.chunk << ",sigma=" << p.sigma; break;
     case L_SELL: o << ",sigma=" << p.sigma; break;
-    case L_BSELL: o << ",block=" << p.block << ",sigma=" << p.sigma; break;
+    case L_BSELL: o << ",block=" << p.block << ",sigma=" << p.sigma << ",xwin=" << p.xwin; break;
     case L_BIN: o << ",smax=" << p.smax << ",sigma=" << p.sigma << ",chunk=" << p.chunk; break;
     }
     o << ",remap=" << p.remap;
@@ -143,8 +144,8 @@ std::string operator_chain(const PlanSpec &p) {
     if (p.dia) o << " -> DIA_EXTRACT(fill>=" << p.dia_fill << ")[BMT_ROW_BLOCK(1) -> THREAD_TOTAL_RED]";
     if (p.heavy)
         o << " -> ROW_DIV(len>" << p.heavy << ")[HEAVY_SPLIT: COL_DIV(" << p.tile
-          << ") -> BMTB_COL_BLOCK -> BMW_ROW_BLOCK -> BMT_COL_BLOCK(" << p.hlps
-          << " lanes) -> WARP_TOTAL_RED -> GMEM_ATOM_RED]";
+          << ") -> BMTB_COL_BLOCK -> SORT_BMTB -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD"
+          << " -> THREAD_TOTAL_RED -> GMEM_ATOM_RED]";
     auto sort = [&]() {
         if (p.sigma == -1) o << " -> SORT";
         else if (p.sigma > 0) o << " -> SORT_SUB(" << p.sigma << ")";
@@ -164,6 +165,7 @@ std::string operator_chain(const PlanSpec &p) {
     case L_BSELL:
         o << " -> DENSE_BLOCK(" << p.block << "x" << p.block << ")";
         sort();
+        if (p.xwin) o << " -> BMTB_ROW_BLOCK(2048)[x window in LDS]";
         o << " -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD -> THREAD_TOTAL_RED";
         break;
     case L_BIN:

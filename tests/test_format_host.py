@@ -23,12 +23,12 @@ SPECS = {
            "light=bin,smax=4,sigma=128"],
     "C2": ["dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
     "C3": ["light=csrv,chunk=512", "light=bin,smax=16,sigma=512,chunk=256",
-           "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,hlps=8,light=csrv,lpr=8",
+           "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
            "heavy=256,tile=512,light=sell,sigma=128"],
-    "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=sell,sigma=512",
+    "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", "light=sell,sigma=512",
            "light=csrv,lpr=16"],
     "C5": ["heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
-           "heavy=1000,tile=4096,hlps=32,light=csrv,lpr=2"],
+           "heavy=1000,tile=4096,light=csrv,lpr=2"],
 }
 
 
@@ -91,10 +91,16 @@ def test_structural_invariants():
                             a["heavy.rows"]])
     assert np.array_equal(np.sort(owned), np.arange(m.nrows))
     # offsets are non-decreasing and end at the totals
-    for k in ("bin0.sell.slice_ptr", "bin1.csrv8.seg_ptr", "bin2.csrv64.seg_ptr", "heavy.seg_ptr"):
+    for k in ("bin0.sell.slice_ptr", "bin1.csrv8.seg_ptr", "bin2.csrv64.seg_ptr", "heavy.unit_ptr"):
         assert a[k][0] == 0 and np.all(np.diff(a[k]) >= 0)
     assert a["bin0.sell.slice_ptr"][-1] == a["bin0.sell.cols"].size
-    assert a["heavy.seg_ptr"][-1] == a["heavy.vals"].size == lens[a["heavy.rows"]].sum()
+    assert a["heavy.unit_ptr"][-1] == a["heavy.vals"].size >= lens[a["heavy.rows"]].sum()
+    assert np.count_nonzero(a["heavy.vals"]) == lens[a["heavy.rows"]].sum()
+    # SORT_BMTB: in every stripe the lanes hold each heavy row exactly once
+    nh = a["heavy.rows"].size
+    lr = a["heavy.lane_row"].reshape(-1, 64 * (-(-nh // 64)))
+    for row in lr:
+        assert np.array_equal(np.sort(row[row != 0xFFFF]), np.arange(nh))
     assert np.all(lens[a["heavy.rows"]] > 1024)
     # padding = sum over slices of (slice width - row length)
     order = a["bin0.sell.origin_rows"]
@@ -166,7 +172,7 @@ def test_closed_form_hybrid_heavy_split_selects_the_generated_rows():
     for thr in (9, 64, 4999):
         a = host_plan(m, f"heavy={thr},tile=2048,light=sell,sigma=1024").arrays()
         assert np.array_equal(a["heavy.rows"], m.meta["heavy_rows"])
-        assert a["heavy.vals"].size == 5 * 5000
+        assert np.count_nonzero(a["heavy.vals"]) == 5 * 5000
         assert np.array_equal(a["zero.rows"], m.meta["heavy_rows"])
 
 
@@ -180,8 +186,8 @@ def test_duplicates_and_unsorted_columns_are_accepted():
     ci = np.clip(r + rng.integers(-3, 4, rp[-1]), 0, ncols - 1).astype(np.int32)   # banded, duplicates, unsorted
     va = rng.integers(-3, 4, rp[-1]).astype(np.float64)
     A_in = as_scipy(nrows, ncols, r, ci, va)
-    for spec in ("light=csrv", "light=sell,sigma=64", "dia=1,light=sell", "light=bsell,block=3", "light=bsell,block=2,sigma=32",
-                 "heavy=8,tile=64,hlps=4,light=sell"):
+    for spec in ("light=csrv", "light=sell,sigma=64", "dia=1,light=sell", "light=bsell,block=3", "light=bsell,block=2,sigma=32,xwin=1",
+                 "heavy=8,tile=64,light=sell"):
         P = lib.Plan(nrows, ncols, rp, ci, va, force_plan=spec, host_only=True)
         assert P.describe()["census"]["cols_sorted"] is False
         p = ref.parse_spec(spec)

@@ -20,12 +20,12 @@ SPECS = {
            "light=bin,smax=4,sigma=128"],
     "C2": ["dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
     "C3": ["light=csrv,chunk=512", "light=csrv,lpr=32", "light=bin,smax=16,sigma=512,chunk=256",
-           "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,hlps=8,light=csrv,lpr=8",
-           "heavy=256,tile=512,hlps=4,light=sell,sigma=128", "heavy=2048,tile=8192,hlps=64,light=bin,chunk=1024"],
-    "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=sell,sigma=512",
+           "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
+           "heavy=256,tile=512,light=sell,sigma=128", "heavy=2048,tile=8192,light=bin,chunk=1024"],
+    "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", "light=sell,sigma=512",
            "light=csrv,lpr=16"],
     "C5": ["heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
-           "heavy=1000,tile=4096,hlps=32,light=csrv,lpr=2", "heavy=100,tile=8192,light=bin,sigma=8192,remap=1"],
+           "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=100,tile=8192,light=bin,sigma=8192,remap=1"],
 }
 CASES = [(n, s) for n in SPECS for s in SPECS[n]]
 
@@ -122,7 +122,7 @@ def test_edge_cases():
     m = M()
     m.nrows, m.ncols, m.row_ptr, m.col_idx = nrows, ncols, rp, ci
     for spec in ("light=csrv", "light=csrv,lpr=64,chunk=256", "light=sell,sigma=64", "light=bin,sigma=32,chunk=512",
-                 "heavy=100,tile=256,hlps=8,light=sell,sigma=64", "heavy=100,tile=64,hlps=4,light=bin", None):
+                 "heavy=100,tile=256,light=sell,sigma=64", "heavy=100,tile=64,light=bin", None):
         for dt in (np.float64, np.float32):
             (y,), _ = gpu_spmv(m, va.astype(dt), x.astype(dt), spec, search_budget_ms=300)
             assert np.array_equal(y.astype(np.float64), want), (spec, dt)
@@ -138,7 +138,7 @@ def test_edge_cases():
     want = oracle.spmv(rp, ci, va, x)
     m.nrows = m.ncols = n
     m.row_ptr, m.col_idx = rp, ci
-    for spec in ("dia=1,light=sell", "dia=1,light=csrv,lpr=2", "light=bsell,block=3", "light=bsell,block=2,sigma=32",
+    for spec in ("dia=1,light=sell", "dia=1,light=csrv,lpr=2", "light=bsell,block=3", "light=bsell,block=2,sigma=32,xwin=1",
                  "light=bsell,block=4,sigma=-1,remap=1"):
         (y,), _ = gpu_spmv(m, va, x, spec)
         assert np.array_equal(y, want), spec
