@@ -112,48 +112,82 @@ def main():
         del vals, x
     cache.clear()
 
-    stream = torch.cuda.current_stream()
+    # All launches go to one side stream.  A step is captured once into a HIP graph (kernel nodes
+    # only: the library enqueues nothing else) and replayed, so that the launch-bound matrices are
+    # not timed through the Python call overhead of this script.
+    stream = torch.cuda.Stream()
+    ncopies = max(it["copies"] for it in items)
 
-    def step(k):
+    def step(k, only=None):
         for it in items:
+            if only is not None and it is not only:
+                continue
             i = k % it["copies"]
             it["plans"][i].run(it["xs"][i], it["ys"][i], stream.cuda_stream)
 
-    for k in range(args.warmup):
-        step(k)
+    def capture(nsteps, only=None):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for k in range(nsteps):
+                step(k, only)
+        return g
+
+    with torch.cuda.stream(stream):
+        for k in range(max(args.warmup, 1)):
+            step(k)
     torch.cuda.synchronize()
     # the timed region: exactly --steps steps, bracketed by synchronisation
+    block = ncopies                                    # one graph = one rotation over the copies
+    g_all = capture(block)
+    g_all.replay()
+    torch.cuda.synchronize()
+    nblocks, rest = divmod(args.steps, block)
     t0 = time.perf_counter()
-    for k in range(args.steps):
-        step(k)
+    for _ in range(nblocks):
+        g_all.replay()
+    with torch.cuda.stream(stream):
+        for k in range(rest):
+            step(k)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # per-matrix and per-launch times with HIP events on the launch stream
+    # per-matrix times (graph of `reps` runs, HIP events on the launch stream) and per-launch times
     for it in items:
+        reps = max(20, it["copies"] * 2)
+        reps -= reps % it["copies"]
+        g = capture(reps, it)
+        g.replay()
+        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = max(args.steps, 20)
-        e0.record(stream)
-        for k in range(reps):
-            i = k % it["copies"]
-            it["plans"][i].run(it["xs"][i], it["ys"][i], stream.cuda_stream)
-        e1.record(stream)
-        e1.synchronize()
-        it["ms"] = e0.elapsed_time(e1) / reps
-        # warm (cache-resident) figure for rotated matrices
-        if it["copies"] > 1:
+        nrep = max(1, min(50, int(math.ceil(args.steps / reps))))
+        with torch.cuda.stream(stream):
             e0.record(stream)
-            for k in range(reps):
-                it["plans"][0].run(it["xs"][0], it["ys"][0], stream.cuda_stream)
+            for _ in range(nrep):
+                g.replay()
             e1.record(stream)
+        e1.synchronize()
+        it["ms"] = e0.elapsed_time(e1) / (reps * nrep)
+        # warm (cache-resident) figure for rotated matrices: the same copy every time
+        if it["copies"] > 1:
+            gw = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gw, stream=stream):
+                for k in range(reps):
+                    it["plans"][0].run(it["xs"][0], it["ys"][0], stream.cuda_stream)
+            gw.replay()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(stream):
+                e0.record(stream)
+                for _ in range(nrep):
+                    gw.replay()
+                e1.record(stream)
             e1.synchronize()
-            it["ms_warm"] = e0.elapsed_time(e1) / reps
+            it["ms_warm"] = e0.elapsed_time(e1) / (reps * nrep)
         per = np.zeros(len(it["launches"]))
-        nrep = 10
-        for k in range(nrep):
+        nt = 10
+        for k in range(nt):
             i = k % it["copies"]
             per += np.array(it["plans"][i].run_timed(it["xs"][i], it["ys"][i], stream.cuda_stream))
-        it["launch_ms"] = (per / nrep).tolist()
+        it["launch_ms"] = (per / nt).tolist()
 
     per_config = []
     tot_ms = sum(it["ms"] for it in items)

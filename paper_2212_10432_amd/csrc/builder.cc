@@ -171,7 +171,12 @@ void build_sell(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int sig
     p.accumulate = acc;
     p.has_rows = !ident;
     p.remap = remap;
-    p.p0 = upload(plan, name + ".slice_ptr", 8, nsl + 1, slice_ptr.data());
+    bool uniform = true;
+    for (int64_t s = 1; s < nsl && uniform; ++s)
+        uniform = slice_ptr[(size_t)s + 1] - slice_ptr[(size_t)s] == slice_ptr[1] - slice_ptr[0];
+    if (uniform) p.uniform_w = (int)((slice_ptr[1] - slice_ptr[0]) / kWave);
+    // with one width for all slices the kernel computes the offsets; the array is kept for inspection only
+    p.p0 = upload(plan, name + ".slice_ptr", 8, nsl + 1, slice_ptr.data(), !uniform);
     p.p1 = upload(plan, name + ".cols", 4, total, cols.p);
     p.p2 = upload(plan, name + ".vals", (int)sizeof(T), total, vals.p);
     if (p.has_rows) p.p3 = upload(plan, name + ".origin_rows", 4, n, rows.data());

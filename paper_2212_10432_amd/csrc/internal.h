@@ -120,6 +120,7 @@ struct Part {
     int remap = 0;
     int64_t ld = 0;              // dia leading dimension
     int64_t nslices = 0;         // heavy part: slices of 64 heavy rows per stripe
+    int uniform_w = -1;          // sell: width shared by every slice (-1: read slice_ptr)
     int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
     const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
     int64_t y_passes = 1;        // how many times this part touches its rows of y (bytes model)

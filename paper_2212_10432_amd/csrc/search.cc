@@ -78,21 +78,29 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             push(p);
         }
     } else {
-        // irregular: BIN by length; optionally split off the heavy tail into column stripes
+        // irregular: BIN by length; optionally split off the heavy tail into column stripes.
+        // A heavy row should keep at least a couple of entries per (row, stripe) segment.
         const int64_t ns = (c.ncols + tile - 1) / tile;
-        int64_t hth = 2048;
-        while (hth < 16 * ns) hth <<= 1;          // >= ~16 entries per (row, stripe) segment
-        int k = 0;
-        while (((int64_t)1 << k) < hth) ++k;
-        const bool tail = k <= 20 && c.nnz_over[k] * 20 >= c.nnz && c.rows_over[k] * ns < ((int64_t)1 << 27);
-        for (int heavy = tail ? 1 : 0; heavy >= 0; --heavy) {
+        int64_t hth = 1024;
+        while (hth < 2 * ns) hth <<= 1;
+        auto tail_ok = [&](int64_t th) {
+            int k = 0;
+            while (((int64_t)1 << k) < th) ++k;
+            return k <= 20 && c.nnz_over[k] * 20 >= c.nnz && c.rows_over[k] <= 65535 &&
+                   c.rows_over[k] * ns < ((int64_t)1 << 22);
+        };
+        // sorted windows repeat every sigma/256 workgroups; remap = 1 keeps whole windows on one
+        // XCD, so the long slices at the head of each window do not all land on the same XCDs
+        for (int64_t th : {hth, 4 * hth, (int64_t)0}) {
+            if (th && !tail_ok(th)) continue;
             PlanSpec p;
             p.light = L_BIN;
             p.smax = 16;
             p.sigma = 8192;
             p.chunk = 8192;
-            if (heavy) {
-                p.heavy = hth;
+            p.remap = 1;
+            if (th) {
+                p.heavy = th;
                 p.tile = tile;
             }
             push(p);
@@ -101,6 +109,7 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             PlanSpec p;
             p.light = L_SELL;
             p.sigma = 8192;
+            p.remap = 1;
             push(p);
         }
     }
