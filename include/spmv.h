@@ -91,8 +91,10 @@ spmv_status_t spmv_plan_create(spmv_plan_t **out, int64_t nrows, int64_t ncols, 
  *   x_dev  : DEVICE, ncols elements of the plan's dtype, finite; must not alias y_dev
  *   y_dev  : DEVICE, nrows elements, every element OVERWRITTEN
  *   stream : a hipStream_t (NULL = the default stream)
- * No allocation, no host synchronisation.  A plan is immutable; concurrent runs of one plan on
- * different streams are safe as long as their y buffers differ.
+ * No allocation, no host synchronisation.  A plan's format arrays are immutable.  Plans whose
+ * description reports "scratch_bytes" > 0 keep partial sums in a buffer of their own between two
+ * of their launches: runs of such a plan must not overlap (same stream, or ordered by events);
+ * other plans may run concurrently on different streams as long as their y buffers differ.
  */
 spmv_status_t spmv_run(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream);
 

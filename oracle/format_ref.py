@@ -31,7 +31,7 @@ WAVE = 64
 
 def parse_spec(spec: str) -> dict:
     d = dict(dia=0, dia_fill=0.5, heavy=0, tile=8192, light="csrv", lpr=0, chunk=0,
-             sigma=0, block=3, smax=16, remap=0, xwin=0)
+             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8)
     for tok in spec.split(","):
         if not tok:
             continue
@@ -244,6 +244,64 @@ def ref_stripe(ncols, rp, ci, va, hrows, tile):
             "heavy.lane_row": lane_row}
 
 
+def ref_xs(ncols, rp, ci, va, rows, K, sigma, nrows_total):
+    """XCD-striped SELL: K column stripes of W = ceil(ncols/K) (rounded up to 64) columns; stripe s
+    belongs to XCD s mod 8.  Per stripe and per window of sigma part positions, the rows with entries
+    in the stripe are sorted by that count (stable, decreasing), sliced by 64 and padded.  Units are
+    ordered XCD by XCD, then stripe, then window.  Lane l of unit u owns scratch slot 64*u + l; pslot
+    lists the slots of each row in stripe order, pptr delimits them."""
+    rows = np.asarray(rows, dtype=np.int32)
+    n = rows.size
+    if n == 0:
+        return {}
+    ident = n == nrows_total and np.array_equal(rows, np.arange(nrows_total))
+    W = -(-ncols // K)
+    W = max(WAVE, -(-W // WAVE) * WAVE)
+    win = n if sigma <= 0 else sigma
+    seg = np.zeros((n, K), dtype=np.int64)
+    for i, r in enumerate(rows):
+        e = _row_entries(rp, r)
+        np.add.at(seg[i], ci[e] // W, 1)
+    pptr = np.zeros(n + 1, dtype=np.int32)
+    np.cumsum((seg > 0).sum(axis=1), out=pptr[1:])
+    unit_ptr, cols, vals, xbase = [0], [], [], []
+    pslot = np.full(int(pptr[-1]), -1, dtype=np.int32)
+    for k in range(8):
+        xbase.append(len(unit_ptr) - 1)
+        for s in range(k, K, 8):
+            for w0 in range(0, n, win):
+                part = np.array([i for i in range(w0, min(n, w0 + win)) if seg[i, s] > 0], dtype=np.int64)
+                part = part[np.argsort(-seg[part, s], kind="stable")] if part.size else part
+                for q in range(0, part.size, WAVE):
+                    members = part[q:q + WAVE]
+                    w = int(seg[members[0], s])
+                    cc = np.zeros((w, WAVE), dtype=np.int32)
+                    vv = np.zeros((w, WAVE), dtype=va.dtype)
+                    fallback = None
+                    u = len(unit_ptr) - 1
+                    for lane, i in enumerate(members):
+                        e = _row_entries(rp, rows[i])
+                        c, v = ci[e], va[e]
+                        m = (c // W) == s
+                        L = int(m.sum())
+                        cc[:L, lane] = c[m]
+                        vv[:L, lane] = v[m]
+                        cc[L:, lane] = c[m][-1]
+                        if lane == 0:
+                            fallback = c[m][0]
+                        pslot[pptr[i] + int((seg[i, :s] > 0).sum())] = u * WAVE + lane
+                    cc[:, len(members):] = fallback
+                    cols.append(cc.reshape(-1)); vals.append(vv.reshape(-1))
+                    unit_ptr.append(unit_ptr[-1] + w * WAVE)
+    xbase.append(len(unit_ptr) - 1)
+    cat = lambda parts, dt: np.concatenate(parts).astype(dt) if parts else np.zeros(0, dtype=dt)
+    out = {"xs.unit_ptr": np.array(unit_ptr, dtype=np.int64), "xs.cols": cat(cols, np.int32), "xs.vals": cat(vals, va.dtype),
+           "xs.pslot": pslot, "xs.xbase": np.array(xbase, dtype=np.int64), "xs.pptr": pptr}
+    if not ident:
+        out["xs.rows"] = rows
+    return out
+
+
 def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
     """All format arrays of the plan `spec` for a CSR matrix with ascending columns in each row."""
     p = parse_spec(spec)
@@ -267,12 +325,14 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
     if acc:
         is_light &= lens > 0
     light = allrows[is_light]
-    zero_rows = [] if acc else [int(r) for r in heavy]
+    zero_rows = []      # rows reduced through atomics (segments of a cut row); heavy rows have their own reduce launch
     if p["light"] == "csrv":
         lpr = p["lpr"]
         out.update(ref_csrv(rp, ci, va, light, lpr, p["chunk"], p["sigma"], acc, nrows, "csrv", zero_rows))
     elif p["light"] == "sell":
         out.update(ref_sell(rp, ci, va, light, p["sigma"], nrows, "sell"))
+    elif p["light"] == "xs":
+        out.update(ref_xs(ncols, rp, ci, va, light, p["k"], p["sigma"], nrows))
     elif p["light"] == "bin":
         L = lens[light]
         out.update(ref_sell(rp, ci, va, light[L <= p["smax"]], p["sigma"], nrows, "bin0.sell"))
@@ -296,6 +356,22 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
     for pre in prefixes:
         a = {k.rsplit(".", 1)[1]: v for k, v in arrays.items() if k.rsplit(".", 1)[0] == pre}
         if pre == "zero":
+            continue
+        if pre == "xs":
+            up, cc, vv, ps, pp = a["unit_ptr"], a["cols"], a["vals"], a["pslot"], a["pptr"]
+            rws = a.get("rows", np.arange(len(pp) - 1))
+            owner = np.full((len(up) - 1) * WAVE, -1, dtype=np.int64)      # slot -> part position
+            owner[ps] = np.repeat(np.arange(len(pp) - 1), np.diff(pp))
+            assert np.unique(ps).size == ps.size
+            for u in range(len(up) - 1):
+                base, w = int(up[u]), int(up[u + 1] - up[u]) // WAVE
+                for lane in range(WAVE):
+                    pos = base + lane + WAVE * np.arange(w)
+                    i = owner[u * WAVE + lane]
+                    if i < 0:
+                        assert not np.any(vv[pos])
+                        continue
+                    R.append(np.full(w, int(rws[i]), dtype=np.int64)); C.append(cc[pos]); V.append(vv[pos])
             continue
         if pre == "dia":
             offs, dv = a["offsets"], a["vals"]

@@ -87,7 +87,9 @@ std::string describe_json(const Plan &plan) {
         o << (i ? ", " : "") << "{\"name\": \"" << a.name << "\", \"elem_bytes\": " << a.elem_bytes
           << ", \"count\": " << a.count << "}";
     }
-    o << "], \"search\": [";
+    int64_t scratch_bytes = 0;
+    for (const DevArray &a : plan.scratch) scratch_bytes += a.count * a.elem_bytes;
+    o << "], \"scratch_bytes\": " << scratch_bytes << ", \"search\": [";
     for (size_t i = 0; i < plan.log.size(); ++i) {
         const CandidateLog &l = plan.log[i];
         o << (i ? ", " : "") << "{\"spec\": \"" << json_escape(l.spec) << "\", \"build_ms\": " << l.build_ms

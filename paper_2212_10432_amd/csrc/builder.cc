@@ -27,6 +27,8 @@ namespace spmv {
 Plan::~Plan() {
     for (DevArray &a : arrays)
         if (a.ptr) mem.free(a.ptr, mem.user);
+    for (DevArray &a : scratch)
+        if (a.ptr) mem.free(a.ptr, mem.user);
 }
 
 int64_t Plan::bytes_csr() const {
@@ -39,9 +41,10 @@ int64_t Plan::bytes_plan() const {
     int64_t b = v * ncols;
     for (const DevArray &a : arrays)
         if (a.read_per_run) b += a.count * a.elem_bytes;
+    for (const DevArray &a : scratch) b += 2 * a.count * a.elem_bytes;   // written, then read back
     for (const Part &p : parts) {
         const int64_t rows = (p.kind == K_BSELL) ? p.nrows * p.block : p.nrows;
-        if (p.kind == K_STRIPE) continue;   // its atomics land on rows counted by the zero part
+        if (p.kind == K_STRIPE || p.kind == K_XS) continue;   // write scratch only; y belongs to their reduce launch
         b += rows * v * (p.accumulate ? 2 : 1) * p.y_passes;
     }
     return b;
@@ -458,12 +461,12 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
 // number of entries they have there (stable, decreasing), slices of 64 rows are padded to their
 // longest segment (value 0, local column 0) and stored lane-interleaved.
 template <typename T>
-void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile,
+void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile, bool acc,
                   const std::vector<int64_t> &lens, int threads) {
     const int64_t nh = (int64_t)hrows.size();
     if (nh == 0) return;
     if ((size_t)tile * sizeof(T) > 65536) fail(SPMV_ERR_UNSUPPORTED, "heavy: tile does not fit 64 KiB of LDS");
-    if (nh > 65535) fail(SPMV_ERR_UNSUPPORTED, "heavy: more than 65535 heavy rows");
+    if (nh > 8192) fail(SPMV_ERR_UNSUPPORTED, "heavy: more than 8192 heavy rows (their accumulators live in LDS)");
     const int64_t ns = (A.ncols + tile - 1) / tile;
     const int64_t nsl = (nh + kWave - 1) / kWave;
     if (ns * nsl * kWave >= ((int64_t)1 << 28)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many (row, stripe) segments");
@@ -527,6 +530,19 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
             }
         }
     });
+    // workgroups: a few consecutive stripes each, about two workgroups per compute unit
+    const int64_t per_group = std::max<int64_t>(1, ns / 512);
+    const int64_t ngroups = (ns + per_group - 1) / per_group;
+    void *scratch = plan.mem.alloc((size_t)(ngroups * nh) * sizeof(T), plan.mem.user);
+    if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the heavy part's scratch failed");
+    {
+        DevArray a;
+        a.name = "heavy.scratch";
+        a.ptr = scratch;
+        a.elem_bytes = (int)sizeof(T);
+        a.count = ngroups * nh;
+        plan.scratch.push_back(a);
+    }
     Part p;
     p.kind = K_STRIPE;
     p.name = "heavy";
@@ -535,6 +551,9 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     p.stored = padded;
     p.units = ns;
     p.nslices = nsl;
+    p.ngroups = ngroups;
+    p.per_group = per_group;
+    p.scratch = scratch;
     p.tile = tile;
     p.has_rows = true;
     p.p0 = upload(plan, "heavy.unit_ptr", 4, ns * nsl + 1, unit_ptr.data());
@@ -543,6 +562,186 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     p.p3 = upload(plan, "heavy.rows", 4, nh, hrows.data());
     p.p4 = upload(plan, "heavy.lane_row", 2, ns * nsl * kWave, lane_row.data());
     plan.parts.push_back(p);
+    Part r;   // sums the workgroups' partial sums into y (overwrites, or adds after a DIA part)
+    r.kind = K_REDUCE_WIDE;
+    r.name = "heavy.reduce";
+    r.nrows = nh;
+    r.units = nh;
+    r.ngroups = ngroups;
+    r.scratch = scratch;
+    r.accumulate = acc;
+    r.has_rows = true;
+    r.p3 = p.p3;
+    plan.parts.push_back(r);
+}
+
+// ---- XCD-striped SELL ----------------------------------------------------------------------------
+// COL_DIV into K stripes of W = ceil(ncols / K) columns (rounded up to 64).  Per stripe: the rows
+// of the part that have entries in it, in windows of sigma part positions, sorted by that count
+// (stable, decreasing), cut into slices of 64 and padded per slice.  Units (slices) are laid out
+// XCD by XCD (XCD k owns stripes k, k + 8, ...), stripe by stripe, window by window.  Lane l of unit
+// u owns scratch slot 64*u + l; pslot lists the slots of every row (stripe order), pptr delimits them.
+template <typename T>
+void build_xs(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, int K, int sigma, bool acc,
+              const std::vector<int64_t> &lens, int threads) {
+    const int64_t n = (int64_t)rows.size();
+    if (n == 0) return;
+    const bool ident = is_identity(rows, A.nrows);
+    int64_t W = (A.ncols + K - 1) / K;
+    W = std::max<int64_t>(kWave, (W + kWave - 1) / kWave * kWave);
+    const int64_t win = sigma <= 0 ? n : (int64_t)sigma;
+    const int64_t nwin = (n + win - 1) / win;
+    // segment lengths, row-major: seg[i * K + s]
+    HostBuf<int32_t> seg(n * K);
+    std::vector<int32_t> pptr((size_t)n + 1, 0);
+    int64_t real = 0;
+    for (int32_t r : rows) real += lens[(size_t)r];
+    parallel_for(n, 1 << 12, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            int32_t *sg = seg.p + i * K;
+            for (int s = 0; s < K; ++s) sg[s] = 0;
+            const int32_t r = rows[(size_t)i];
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) sg[A.col[k] / W] += 1;
+            int32_t cnt = 0;
+            for (int s = 0; s < K; ++s) cnt += sg[s] > 0;
+            pptr[(size_t)i + 1] = cnt;
+        }
+    });
+    for (int64_t i = 0; i < n; ++i) pptr[(size_t)i + 1] += pptr[(size_t)i];
+    const int64_t nslots = pptr[(size_t)n];
+    // participants per (stripe, window), in memory order: XCD, phase (stripe = 8*phase + xcd), window
+    std::vector<int> stripe_order;
+    for (int k = 0; k < 8; ++k)
+        for (int s = k; s < K; s += 8) stripe_order.push_back(s);
+    const int64_t ncell = (int64_t)K * nwin;            // cell c = position in stripe_order * nwin + window
+    std::vector<int64_t> cell_units((size_t)ncell + 1, 0);
+    parallel_for(ncell, 4, threads, [&](int64_t cb, int64_t ce, int) {
+        for (int64_t c = cb; c < ce; ++c) {
+            const int s = stripe_order[(size_t)(c / nwin)];
+            const int64_t w0 = (c % nwin) * win, w1 = std::min(n, w0 + win);
+            int64_t cnt = 0;
+            for (int64_t i = w0; i < w1; ++i) cnt += seg[i * K + s] > 0;
+            cell_units[(size_t)c + 1] = (cnt + kWave - 1) / kWave;
+        }
+    });
+    for (int64_t c = 0; c < ncell; ++c) cell_units[(size_t)c + 1] += cell_units[(size_t)c];
+    const int64_t nunits = cell_units[(size_t)ncell];
+    std::vector<int64_t> xbase(9, 0);
+    {
+        size_t pos = 0;
+        for (int k = 0; k < 8; ++k) {
+            xbase[(size_t)k] = cell_units[pos * (size_t)nwin];
+            for (int s = k; s < K; s += 8) ++pos;
+        }
+        xbase[8] = nunits;
+    }
+    // sort each cell, record the lanes' part positions and the unit widths
+    HostBuf<int32_t> lane_i(nunits * kWave);
+    std::vector<int64_t> unit_ptr((size_t)nunits + 1, 0);
+    parallel_for(ncell, 1, threads, [&](int64_t cb, int64_t ce, int) {
+        std::vector<int32_t> part;
+        for (int64_t c = cb; c < ce; ++c) {
+            const int s = stripe_order[(size_t)(c / nwin)];
+            const int64_t w0 = (c % nwin) * win, w1 = std::min(n, w0 + win);
+            part.clear();
+            for (int64_t i = w0; i < w1; ++i)
+                if (seg[i * K + s] > 0) part.push_back((int32_t)i);
+            std::stable_sort(part.begin(), part.end(), [&](int32_t a, int32_t b) {
+                return seg[(int64_t)a * K + s] > seg[(int64_t)b * K + s];
+            });
+            const int64_t u0 = cell_units[(size_t)c];
+            const int64_t cnt = (int64_t)part.size();
+            for (int64_t q = 0; q < (cnt + kWave - 1) / kWave * kWave; ++q)
+                lane_i[u0 * kWave + q] = q < cnt ? part[(size_t)q] : -1;
+            for (int64_t u = u0; u < cell_units[(size_t)c + 1]; ++u)
+                unit_ptr[(size_t)u + 1] = (int64_t)seg[(int64_t)part[(size_t)((u - u0) * kWave)] * K + s] * kWave;
+        }
+    });
+    for (int64_t u = 0; u < nunits; ++u) unit_ptr[(size_t)u + 1] += unit_ptr[(size_t)u];
+    const int64_t total = unit_ptr[(size_t)nunits];
+    if (total >= ((int64_t)1 << 33)) fail(SPMV_ERR_UNSUPPORTED, "xs: padded size too large");
+    // stripe of every unit (needed to find the segment inside the row)
+    std::vector<int32_t> unit_stripe((size_t)nunits);
+    for (int64_t c = 0; c < ncell; ++c)
+        for (int64_t u = cell_units[(size_t)c]; u < cell_units[(size_t)c + 1]; ++u)
+            unit_stripe[(size_t)u] = stripe_order[(size_t)(c / nwin)];
+    HostBuf<int32_t> cols(total), pslot(nslots);
+    HostBuf<T> vals(total);
+    const T *av = (const T *)A.val;
+    parallel_for(nunits, 64, threads, [&](int64_t ub, int64_t ue, int) {
+        for (int64_t u = ub; u < ue; ++u) {
+            const int s = unit_stripe[(size_t)u];
+            const int64_t base = unit_ptr[(size_t)u], w = (unit_ptr[(size_t)u + 1] - base) / kWave;
+            int32_t fallback = 0;
+            for (int lane = 0; lane < kWave; ++lane) {
+                const int32_t i = lane_i[u * kWave + lane];
+                int64_t L = 0, src = 0;
+                if (i >= 0) {
+                    const int32_t *sg = seg.p + (int64_t)i * K;
+                    int64_t off = 0;
+                    int32_t rank = 0;
+                    for (int t = 0; t < s; ++t) {
+                        off += sg[t];
+                        rank += sg[t] > 0;
+                    }
+                    L = sg[s];
+                    src = (int64_t)A.row_ptr[rows[(size_t)i]] + off;
+                    pslot[pptr[(size_t)i] + rank] = (int32_t)(u * kWave + lane);
+                    if (lane == 0) fallback = A.col[src];
+                }
+                int64_t j = 0;
+                for (; j < L; ++j) {
+                    cols[base + j * kWave + lane] = A.col[src + j];
+                    vals[base + j * kWave + lane] = av[src + j];
+                }
+                const int32_t padc = L > 0 ? A.col[src + L - 1] : fallback;
+                for (; j < w; ++j) {
+                    cols[base + j * kWave + lane] = padc;
+                    vals[base + j * kWave + lane] = T(0);
+                }
+            }
+        }
+    });
+    if (nunits * kWave >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "xs: too many segments");
+    void *scratch = plan.mem.alloc((size_t)std::max<int64_t>(nunits * kWave, 1) * sizeof(T), plan.mem.user);
+    if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the striped part's scratch failed");
+    {
+        DevArray a;
+        a.name = "xs.scratch";
+        a.ptr = scratch;
+        a.elem_bytes = (int)sizeof(T);
+        a.count = nunits * kWave;
+        plan.scratch.push_back(a);
+    }
+    int64_t per_xcd = 0;
+    for (int k = 0; k < 8; ++k) per_xcd = std::max(per_xcd, xbase[(size_t)k + 1] - xbase[(size_t)k]);
+    Part p;
+    p.kind = K_XS;
+    p.name = "xs";
+    p.nrows = n;
+    p.nnz = real;
+    p.stored = total;
+    p.units = nunits;
+    p.ngroups = (per_xcd + 3) / 4;   // workgroups per XCD, four slices each
+    p.scratch = scratch;
+    p.has_rows = !ident;
+    p.p0 = upload(plan, "xs.unit_ptr", 8, nunits + 1, unit_ptr.data());
+    p.p1 = upload(plan, "xs.cols", 4, total, cols.p);
+    p.p2 = upload(plan, "xs.vals", (int)sizeof(T), total, vals.p);
+    p.p4 = upload(plan, "xs.xbase", 8, 9, xbase.data());
+    plan.parts.push_back(p);
+    Part r;
+    r.kind = K_REDUCE_ROWS;
+    r.name = "xs.reduce";
+    r.nrows = n;
+    r.units = n;
+    r.scratch = scratch;
+    r.accumulate = acc;
+    r.has_rows = !ident;
+    r.p0 = upload(plan, "xs.pptr", 4, n + 1, pptr.data());
+    r.p1 = upload(plan, "xs.pslot", 4, nslots, pslot.p);
+    if (!ident) r.p3 = upload(plan, "xs.rows", 4, n, rows.data());
+    plan.parts.push_back(r);
 }
 
 // Copy of A with ascending columns inside each row (stable: repeated columns keep their order).
@@ -638,7 +837,7 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
     // rows reduced through atomics are zeroed by the first launch
     std::vector<int32_t> zero_rows;
     const size_t zero_slot = plan->parts.size();
-    if (!acc) zero_rows = heavy;
+    // (heavy rows are written by their own reduce launch and need no zeroing)
 
     switch (spec.light) {
     case L_CSRV:
@@ -646,6 +845,9 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         break;
     case L_SELL:
         build_sell<T>(*plan, A, light, spec.sigma, acc, spec.remap, "sell", lens, threads);
+        break;
+    case L_XS:
+        build_xs<T>(*plan, A, light, spec.k, spec.sigma, acc, lens, threads);
         break;
     case L_BIN: {
         // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront per
@@ -664,7 +866,7 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
     }
     default: fail(SPMV_ERR_INVALID_ARG, "unknown light design");
     }
-    if (!heavy.empty()) build_stripe<T>(*plan, A, heavy, spec.tile, lens, threads);
+    if (!heavy.empty()) build_stripe<T>(*plan, A, heavy, spec.tile, acc, lens, threads);
 
     if (!zero_rows.empty()) {
         std::sort(zero_rows.begin(), zero_rows.end());

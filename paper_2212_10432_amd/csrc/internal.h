@@ -72,7 +72,7 @@ struct Census {
 Census take_census(const HostCsr &A, int threads);
 
 // ---- plan specification --------------------------------------------------------------------
-enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3 };
+enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4 };
 
 struct PlanSpec {
     int dia = 0;             // extract well-populated diagonals into a DIA part first
@@ -86,6 +86,7 @@ struct PlanSpec {
     int block = 3;           // bsell: block edge (2, 3 or 4)
     int smax = 16;           // bin: rows up to this length go to the SELL bin
     int remap = 0;           // 1 = give each XCD a contiguous range of workgroups
+    int k = 8;               // xs: column stripes (8 or 16: one or two per XCD)
     int xwin = 0;            // bsell: stage the x window of 32 slices in LDS when it fits
 };
 PlanSpec parse_spec(const std::string &s);
@@ -101,7 +102,7 @@ struct DevArray {
     bool read_per_run = true;    // counts towards the algorithmic bytes of one run
 };
 
-enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE };
+enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS };
 
 // One kernel launch of spmv_run.  Pointers refer to entries of Plan::arrays.
 struct Part {
@@ -120,6 +121,9 @@ struct Part {
     int remap = 0;
     int64_t ld = 0;              // dia leading dimension
     int64_t nslices = 0;         // heavy part: slices of 64 heavy rows per stripe
+    int64_t ngroups = 0;         // heavy part: workgroups (= partial-sum rows in scratch)
+    int64_t per_group = 0;       // heavy part: stripes per workgroup
+    void *scratch = nullptr;     // partial sums written by one launch and read by the next
     int uniform_w = -1;          // sell: width shared by every slice (-1: read slice_ptr)
     int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
     const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
@@ -143,7 +147,8 @@ struct Plan {
     spmv_dtype_t dtype = SPMV_F64;
     int64_t nrows = 0, ncols = 0, nnz = 0;
     PlanSpec spec;
-    std::vector<DevArray> arrays;
+    std::vector<DevArray> arrays;    // format arrays (inspectable)
+    std::vector<DevArray> scratch;   // partial-sum buffers: written and read back in every run
     std::vector<Part> parts;
     Allocator mem;
     Census census;

@@ -45,6 +45,48 @@ __device__ __forceinline__ T group_sum(T v) {
     return v;
 }
 
+// Sum of one lane of a SELL slice: entries at c[64*j], v[64*j], j < w (w is uniform over the
+// wavefront).  Four independent loads and gathers are in flight per step; the last 1-3 entries
+// are issued together as well instead of one dependent load-gather chain per entry.
+template <typename T, typename CI>
+__device__ __forceinline__ T sell_lane_sum(const CI *__restrict__ c, const T *__restrict__ v, int w,
+                                           const T *__restrict__ xsrc) {
+    T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
+    int j = 0;
+    for (; j + 4 <= w; j += 4) {
+        const CI c0 = ldnt(c + (j + 0) * 64), c1 = ldnt(c + (j + 1) * 64);
+        const CI c2 = ldnt(c + (j + 2) * 64), c3 = ldnt(c + (j + 3) * 64);
+        const T v0 = ldnt(v + (j + 0) * 64), v1 = ldnt(v + (j + 1) * 64);
+        const T v2 = ldnt(v + (j + 2) * 64), v3 = ldnt(v + (j + 3) * 64);
+        a0 += v0 * xsrc[c0];
+        a1 += v1 * xsrc[c1];
+        a2 += v2 * xsrc[c2];
+        a3 += v3 * xsrc[c3];
+    }
+    switch (w - j) {
+    case 3: {
+        const CI c0 = ldnt(c + (j + 0) * 64), c1 = ldnt(c + (j + 1) * 64), c2 = ldnt(c + (j + 2) * 64);
+        const T v0 = ldnt(v + (j + 0) * 64), v1 = ldnt(v + (j + 1) * 64), v2 = ldnt(v + (j + 2) * 64);
+        a0 += v0 * xsrc[c0];
+        a1 += v1 * xsrc[c1];
+        a2 += v2 * xsrc[c2];
+        break;
+    }
+    case 2: {
+        const CI c0 = ldnt(c + (j + 0) * 64), c1 = ldnt(c + (j + 1) * 64);
+        const T v0 = ldnt(v + (j + 0) * 64), v1 = ldnt(v + (j + 1) * 64);
+        a0 += v0 * xsrc[c0];
+        a1 += v1 * xsrc[c1];
+        break;
+    }
+    case 1:
+        a0 += ldnt(v + j * 64) * xsrc[ldnt(c + j * 64)];
+        break;
+    default: break;
+    }
+    return (a0 + a1) + (a2 + a3);
+}
+
 // ---- y[rows[i]] = 0 : rows that are later accumulated with atomics --------------------------
 template <typename T>
 __global__ __launch_bounds__(kWG) void k_zero_rows(const int32_t *__restrict__ rows, int64_t n,
@@ -94,27 +136,65 @@ __global__ __launch_bounds__(kWG) void k_sell(const int64_t *__restrict__ slice_
     // every slice equally wide: the offset array follows a linear model and is not read (Section V-D)
     const int64_t b = uniform_w >= 0 ? s * 64 * (int64_t)uniform_w : slice_ptr[s];
     const int w = uniform_w >= 0 ? uniform_w : (int)((slice_ptr[s + 1] - b) >> 6);
-    const int32_t *c = cols + b + lane;
-    const T *v = vals + b + lane;
-    T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
-    int j = 0;
-    for (; j + 4 <= w; j += 4) {
-        const int32_t c0 = ldnt(c + (j + 0) * 64), c1 = ldnt(c + (j + 1) * 64);
-        const int32_t c2 = ldnt(c + (j + 2) * 64), c3 = ldnt(c + (j + 3) * 64);
-        const T v0 = ldnt(v + (j + 0) * 64), v1 = ldnt(v + (j + 1) * 64);
-        const T v2 = ldnt(v + (j + 2) * 64), v3 = ldnt(v + (j + 3) * 64);
-        a0 += v0 * x[c0];
-        a1 += v1 * x[c1];
-        a2 += v2 * x[c2];
-        a3 += v3 * x[c3];
-    }
-    for (; j < w; ++j) a0 += ldnt(v + j * 64) * x[ldnt(c + j * 64)];
-    const T acc = (a0 + a1) + (a2 + a3);
+    const T acc = sell_lane_sum<T, int32_t>(cols + b + lane, vals + b + lane, w, x);
     const int64_t r = s * 64 + lane;
     if (r < nrows_part) {
         const int64_t row = ROWS ? (int64_t)rows[r] : r;
         y[row] = ACC ? y[row] + acc : acc;
     }
+}
+
+// ---- XCD-striped SELL -----------------------------------------------------------------------
+// COL_DIV into K = 8*P column stripes, stripe s being worked on by XCD s mod 8 only (workgroup
+// ids are dealt round-robin to the 8 XCDs, so workgroup b serves XCD b & 7).  The piece of x a
+// stripe touches is ncols/K elements; sized to fit the 4 MB L2 of one XCD, the gathers of random
+// columns hit that L2 instead of each pulling a 128-byte line across the fabric.  Inside a stripe
+// the rows that have entries there are sorted by that count in windows (SORT_SUB) and stored as
+// SELL slices (BMW_ROW_BLOCK(64) + BMT_ROW_BLOCK(1) + BMW_PAD + THREAD_TOTAL_RED).  A lane's sum is
+// one of the partial sums of its row; lane l of unit u stores it to scratch[64*u + l] (one
+// contiguous 512-byte store per wavefront: scattered 8-byte stores cost a 64-byte write each) and
+// k_reduce_rows gathers the partial sums of every row.  The units (slices) of XCD k are
+// contiguous: [xbase[k], xbase[k+1]), phase by phase, so all XCDs move from their first stripe to
+// their second together.
+template <typename T>
+__global__ __launch_bounds__(kWG) void k_xs(const int64_t *__restrict__ unit_ptr,
+                                            const int32_t *__restrict__ cols,
+                                            const T *__restrict__ vals,
+                                            const int64_t *__restrict__ xbase,
+                                            const T *__restrict__ x, T *__restrict__ partial) {
+    const int k = blockIdx.x & 7;
+    const int64_t u = xbase[k] + (int64_t)(blockIdx.x >> 3) * (kWG / kWave) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (u >= xbase[k + 1]) return;
+    const int64_t b = unit_ptr[u];
+    const int w = (int)((unit_ptr[u + 1] - b) >> 6);
+    const T acc = sell_lane_sum<T, int32_t>(cols + b + lane, vals + b + lane, w, x);
+    partial[u * 64 + lane] = acc;   // lanes without a row hold only padding and store 0
+}
+
+// y[rows[i]] (+)= sum of the partial sums of row i: scratch[pslot[q]], pptr[i] <= q < pptr[i+1].
+// With remap on, an XCD reduces a contiguous range of rows, so a scratch line (16 partial sums of
+// neighbouring rows of one window) is fetched into one L2 only.
+template <typename T, bool ROWS, bool ACC>
+__global__ __launch_bounds__(kWG) void k_reduce_rows(const int32_t *__restrict__ pptr,
+                                                     const int32_t *__restrict__ pslot,
+                                                     const T *__restrict__ partial,
+                                                     const int32_t *__restrict__ rows,
+                                                     T *__restrict__ y, int64_t n, int remap) {
+    const int64_t blk = logical_block(blockIdx.x, gridDim.x, remap);
+    const int64_t i = blk * kWG + threadIdx.x;
+    if (i >= n) return;
+    const int32_t b = pptr[i], e = pptr[i + 1];
+    T a0 = T(0), a1 = T(0);
+    int32_t q = b;
+    for (; q + 1 < e; q += 2) {
+        const int32_t s0 = ldnt(pslot + q), s1 = ldnt(pslot + q + 1);
+        a0 += partial[s0];
+        a1 += partial[s1];
+    }
+    if (q < e) a0 += partial[ldnt(pslot + q)];
+    const int64_t r = ROWS ? (int64_t)rows[i] : i;
+    y[r] = ACC ? y[r] + (a0 + a1) : (a0 + a1);
 }
 
 // ---- CSR segments: LPR lanes per row segment ------------------------------------------------
@@ -291,54 +371,81 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
 
 // ---- heavy rows, column stripes: x tile in LDS ----------------------------------------------
 // ROW_DIV (rows longer than a threshold), then COL_DIV (stripes of `tile` columns): one workgroup
-// (BMTB) owns a stripe and copies its piece of x into LDS with coalesced loads.  Inside the
-// stripe the heavy rows are sorted by the number of entries they have in it (SORT_BMTB) and cut
-// into slices of 64 (BMW_ROW_BLOCK), each padded to its longest row (BMW_PAD): a lane owns one
-// (row, stripe) segment, gathers x from LDS through 16-bit local columns and keeps its sum in a
-// register (THREAD_TOTAL_RED); one atomic per lane adds it to y (GMEM_ATOM_RED; y was zeroed by
-// k_zero_rows).  x is read from memory once per workgroup instead of once per non-zero line.
+// (BMTB) owns a few consecutive stripes and copies each stripe's piece of x into LDS with coalesced
+// loads.  Inside a stripe the heavy rows are sorted by the number of entries they have in it
+// (SORT_BMTB) and cut into slices of 64 (BMW_ROW_BLOCK), each padded to its longest row (BMW_PAD):
+// a lane owns one (row, stripe) segment, gathers x from LDS through 16-bit local columns and keeps
+// its sum in a register (THREAD_TOTAL_RED).  The sums of a workgroup meet in an LDS accumulator per
+// heavy row (the shared-memory reduction by row of SHMEM_OFFSET_RED, the "offset" being the lane's
+// row id); a row occurs once per stripe, so no two lanes touch an accumulator between barriers.
+// The workgroup then writes its nh partial sums to scratch and k_reduce_wide adds them up: global
+// atomics (GMEM_ATOM_RED) would be several times slower here, since hundreds of workgroups would
+// hit the same few thousand y elements.
 // Entry j of lane `lane` of unit u = stripe * nsl + slice sits at unit_ptr[u] + 64*j + lane.
+constexpr int kHeavyWG = 512;
 template <typename T>
-__global__ __launch_bounds__(512) void k_hsell(const int32_t *__restrict__ unit_ptr,
-                                               const uint16_t *__restrict__ lcol,
-                                               const T *__restrict__ vals,
-                                               const int32_t *__restrict__ hrows,
-                                               const uint16_t *__restrict__ lane_row,
-                                               const T *__restrict__ x, T *__restrict__ y,
-                                               int nsl, int tile, int64_t ncols, int slices_per_y) {
+__global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ unit_ptr,
+                                                    const uint16_t *__restrict__ lcol,
+                                                    const T *__restrict__ vals,
+                                                    const uint16_t *__restrict__ lane_row,
+                                                    const T *__restrict__ x, T *__restrict__ partial,
+                                                    int nsl, int nh, int tile, int64_t ncols, int ns,
+                                                    int stripes_per_wg) {
     extern __shared__ __align__(16) unsigned char smem[];
     T *xs = reinterpret_cast<T *>(smem);
-    const int s = blockIdx.x;
-    const int64_t c0 = (int64_t)s * tile;
-    const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
-    for (int i = threadIdx.x; i < w; i += blockDim.x) xs[i] = x[c0 + i];
-    __syncthreads();
+    T *ys = xs + tile;
+    for (int i = threadIdx.x; i < nh; i += kHeavyWG) ys[i] = T(0);
     const int lane = threadIdx.x & 63;
-    const int nwaves = blockDim.x >> 6;
-    const int gbeg = blockIdx.y * slices_per_y;
-    const int gend = (gbeg + slices_per_y < nsl) ? gbeg + slices_per_y : nsl;
-    for (int g = gbeg + (threadIdx.x >> 6); g < gend; g += nwaves) {
-        const int64_t u = (int64_t)s * nsl + g;
-        const int32_t b = unit_ptr[u];
-        const int wd = (unit_ptr[u + 1] - b) >> 6;
-        if (wd == 0) continue;
-        const uint16_t *c = lcol + b + lane;
-        const T *v = vals + b + lane;
-        T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
-        int j = 0;
-        for (; j + 4 <= wd; j += 4) {
-            const uint16_t c0l = ldnt(c + (j + 0) * 64), c1l = ldnt(c + (j + 1) * 64);
-            const uint16_t c2l = ldnt(c + (j + 2) * 64), c3l = ldnt(c + (j + 3) * 64);
-            const T v0 = ldnt(v + (j + 0) * 64), v1 = ldnt(v + (j + 1) * 64);
-            const T v2 = ldnt(v + (j + 2) * 64), v3 = ldnt(v + (j + 3) * 64);
-            a0 += v0 * xs[c0l];
-            a1 += v1 * xs[c1l];
-            a2 += v2 * xs[c2l];
-            a3 += v3 * xs[c3l];
+    const int s0 = blockIdx.x * stripes_per_wg;
+    const int s1 = (s0 + stripes_per_wg < ns) ? s0 + stripes_per_wg : ns;
+    for (int s = s0; s < s1; ++s) {
+        __syncthreads();   // the previous stripe's gathers are done (first pass: ys is zeroed)
+        const int64_t c0 = (int64_t)s * tile;
+        const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
+        for (int i = threadIdx.x; i < w; i += kHeavyWG) xs[i] = x[c0 + i];
+        __syncthreads();
+        for (int g = threadIdx.x >> 6; g < nsl; g += kHeavyWG / kWave) {
+            const int64_t u = (int64_t)s * nsl + g;
+            const int32_t b = unit_ptr[u];
+            const int wd = (unit_ptr[u + 1] - b) >> 6;
+            if (wd == 0) continue;
+            const T acc = sell_lane_sum<T, uint16_t>(lcol + b + lane, vals + b + lane, wd, xs);
+            const uint16_t lr = lane_row[u * 64 + lane];
+            if (lr != 0xFFFFu) ys[lr] += acc;
         }
-        for (; j < wd; ++j) a0 += ldnt(v + j * 64) * xs[ldnt(c + j * 64)];
-        const uint16_t lr = lane_row[u * 64 + lane];
-        if (lr != 0xFFFFu) atomic_add(y + hrows[lr], (a0 + a1) + (a2 + a3));
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nh; i += kHeavyWG) partial[(int64_t)blockIdx.x * nh + i] = ys[i];
+}
+
+// y[rows[i]] (+)= sum over g < np of partial[g * n + i]: many partials (one per workgroup of the
+// heavy kernel), few rows.  16 wavefronts split the partials, LDS combines them.
+constexpr int kReduceWaves = 16;
+template <typename T, bool ACC>
+__global__ __launch_bounds__(kReduceWaves * kWave) void k_reduce_wide(const T *__restrict__ partial,
+                                                                      int np, int64_t n,
+                                                                      const int32_t *__restrict__ rows,
+                                                                      T *__restrict__ y) {
+    __shared__ T red[kReduceWaves][kWave];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * kWave + lane;
+    T a0 = T(0), a1 = T(0);
+    if (i < n) {
+        int g = wave;
+        for (; g + kReduceWaves < np; g += 2 * kReduceWaves) {
+            a0 += partial[(int64_t)g * n + i];
+            a1 += partial[(int64_t)(g + kReduceWaves) * n + i];
+        }
+        for (; g < np; g += kReduceWaves) a0 += partial[(int64_t)g * n + i];
+    }
+    red[wave][lane] = a0 + a1;
+    __syncthreads();
+    if (wave == 0 && i < n) {
+        T acc = T(0);
+#pragma unroll
+        for (int k = 0; k < kReduceWaves; ++k) acc += red[k][lane];
+        const int64_t r = rows[i];
+        y[r] = ACC ? y[r] + acc : acc;
     }
 }
 
@@ -443,20 +550,45 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     }
     case K_STRIPE: {
         if (p.units == 0 || p.nslices == 0) return 0;
-        const int threads = 512, nwaves = threads / kWave;
-        // enough workgroups to fill 256 CUs: split the slices of a stripe over blockIdx.y when
-        // there are few stripes, but keep every wavefront of a workgroup busy
-        int64_t ysplit = (1024 + p.units - 1) / p.units;
-        const int64_t max_split = (p.nslices + nwaves - 1) / nwaves;
-        if (ysplit > max_split) ysplit = max_split;
-        if (ysplit < 1) ysplit = 1;
-        const int spy = (int)((p.nslices + ysplit - 1) / ysplit);
-        const dim3 grid((unsigned)p.units, (unsigned)((p.nslices + spy - 1) / spy));
-        const size_t lds = (size_t)p.tile * sizeof(T);
-        k_hsell<T><<<grid, threads, lds, st>>>((const int32_t *)p.p0, (const uint16_t *)p.p1,
-                                               (const T *)p.p2, (const int32_t *)p.p3,
-                                               (const uint16_t *)p.p4, x, y, (int)p.nslices, p.tile,
-                                               ncols, spy);
+        const size_t lds = ((size_t)p.tile + (size_t)p.nrows) * sizeof(T);
+        static std::atomic<int> lds_set{0};
+        if (lds > 65536 && !lds_set.load()) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_hsell<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
+            if (e != hipSuccess) return (int)e;
+            lds_set.store(1);
+        }
+        k_hsell<T><<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(
+            (const int32_t *)p.p0, (const uint16_t *)p.p1, (const T *)p.p2, (const uint16_t *)p.p4, x,
+            (T *)p.scratch, (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group);
+        break;
+    }
+    case K_XS: {
+        if (p.units == 0) return 0;
+        k_xs<T><<<(unsigned)(8 * p.ngroups), kWG, 0, st>>>((const int64_t *)p.p0, (const int32_t *)p.p1,
+                                                          (const T *)p.p2, (const int64_t *)p.p4, x,
+                                                          (T *)p.scratch);
+        break;
+    }
+    case K_REDUCE_ROWS: {
+        if (p.nrows == 0) return 0;
+        const unsigned grid = blocks(p.nrows, kWG);
+#define RR_GO(R, A)                                                                               \
+    k_reduce_rows<T, R, A><<<grid, kWG, 0, st>>>((const int32_t *)p.p0, (const int32_t *)p.p1,    \
+                                                  (const T *)p.scratch, (const int32_t *)p.p3, y, \
+                                                  p.nrows, 1)
+        if (p.has_rows) { if (p.accumulate) RR_GO(true, true); else RR_GO(true, false); }
+        else            { if (p.accumulate) RR_GO(false, true); else RR_GO(false, false); }
+#undef RR_GO
+        break;
+    }
+    case K_REDUCE_WIDE: {
+        if (p.nrows == 0) return 0;
+        if (p.accumulate)
+            k_reduce_wide<T, true><<<blocks(p.nrows, kWave), kReduceWaves * kWave, 0, st>>>(
+                (const T *)p.scratch, (int)p.ngroups, p.nrows, (const int32_t *)p.p3, y);
+        else
+            k_reduce_wide<T, false><<<blocks(p.nrows, kWave), kReduceWaves * kWave, 0, st>>>(
+                (const T *)p.scratch, (int)p.ngroups, p.nrows, (const int32_t *)p.p3, y);
         break;
     }
     }

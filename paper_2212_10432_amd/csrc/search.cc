@@ -86,13 +86,17 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
         auto tail_ok = [&](int64_t th) {
             int k = 0;
             while (((int64_t)1 << k) < th) ++k;
-            return k <= 20 && c.nnz_over[k] * 20 >= c.nnz && c.rows_over[k] <= 65535 &&
+            return k <= 20 && c.nnz_over[k] * 20 >= c.nnz && c.rows_over[k] <= 8192 &&
                    c.rows_over[k] * ns < ((int64_t)1 << 22);
         };
         // sorted windows repeat every sigma/256 workgroups; remap = 1 keeps whole windows on one
         // XCD, so the long slices at the head of each window do not all land on the same XCDs
-        for (int64_t th : {hth, 4 * hth, (int64_t)0}) {
-            if (th && !tail_ok(th)) continue;
+        // x larger than one L2: stripe the columns so that every XCD gathers from its own piece
+        const int64_t xbytes = c.ncols * (dtype == SPMV_F64 ? 8 : 4);
+        int k0 = (int)(8 * ((xbytes + (32 << 20) - 1) / (32 << 20)));
+        if (k0 > 32) k0 = 32;
+        const bool striping = xbytes > (4 << 20);
+        auto bin_plan = [&](int64_t th) {
             PlanSpec p;
             p.light = L_BIN;
             p.smax = 16;
@@ -103,8 +107,32 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
                 p.heavy = th;
                 p.tile = tile;
             }
-            push(p);
+            return p;
+        };
+        auto xs_plan = [&](int64_t th, int k, int tl) {
+            PlanSpec p = bin_plan(th);
+            p.light = L_XS;
+            p.k = k;
+            p.sigma = 65536;
+            p.chunk = 0;
+            p.remap = 0;
+            if (th) p.tile = tl;
+            return p;
+        };
+        const int64_t th0 = tail_ok(hth) ? hth : (tail_ok(4 * hth) ? 4 * hth : 0);
+        if (striping) {
+            // the stripe of x an XCD gathers from should be about half its 4 MB L2 or less
+            const int k1 = 2 * k0 <= 32 ? 2 * k0 : k0;
+            push(xs_plan(th0, k1, tile / 2));
+            push(xs_plan(th0, k1, tile));
+            if (k1 != k0) push(xs_plan(th0, k0, tile / 2));
+            if (th0 && tail_ok(2 * th0)) push(xs_plan(2 * th0, k1, tile / 2));
+            if (th0 && tail_ok(4 * th0)) push(xs_plan(4 * th0, k1, tile / 2));
+            if (2 * k1 <= 32) push(xs_plan(th0, 2 * k1, tile / 2));
         }
+        push(bin_plan(th0));
+        if (th0 && tail_ok(4 * th0)) push(bin_plan(4 * th0));
+        if (th0) push(bin_plan(0));
         if (c.max_len <= 1024) {
             PlanSpec p;
             p.light = L_SELL;

@@ -65,6 +65,7 @@ static const char *light_name(int l) {
     case L_SELL: return "sell";
     case L_BSELL: return "bsell";
     case L_BIN: return "bin";
+    case L_XS: return "xs";
     }
     return "?";
 }
@@ -91,6 +92,7 @@ PlanSpec parse_spec(const std::string &s) {
             else if (v == "sell") p.light = L_SELL;
             else if (v == "bsell") p.light = L_BSELL;
             else if (v == "bin") p.light = L_BIN;
+            else if (v == "xs") p.light = L_XS;
             else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown light design " + v);
         } else if (k == "dia") p.dia = (int)num();
         else if (k == "dia_fill") p.dia_fill = num();
@@ -103,6 +105,7 @@ PlanSpec parse_spec(const std::string &s) {
         else if (k == "smax") p.smax = (int)num();
         else if (k == "remap") p.remap = (int)num();
         else if (k == "xwin") p.xwin = (int)num();
+        else if (k == "k") p.k = (int)num();
         else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown key " + k);
     }
     if (p.dia != 0 && p.dia != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia must be 0 or 1");
@@ -115,6 +118,7 @@ PlanSpec parse_spec(const std::string &s) {
     if (p.block < 2 || p.block > 4) fail(SPMV_ERR_INVALID_ARG, "plan spec: block must be 2, 3 or 4");
     if (p.smax < 0 || p.smax > 1024) fail(SPMV_ERR_INVALID_ARG, "plan spec: smax must be in [0, 1024]");
     if (p.remap != 0 && p.remap != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: remap must be 0 or 1");
+    if (p.k != 8 && p.k != 16 && p.k != 24 && p.k != 32) fail(SPMV_ERR_INVALID_ARG, "plan spec: k must be 8, 16, 24 or 32");
     if (p.xwin != 0 && p.xwin != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin must be 0 or 1");
     if (p.xwin && p.light != L_BSELL) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin needs light=bsell");
     if (p.light == L_BSELL && (p.dia || p.heavy)) fail(SPMV_ERR_INVALID_ARG, "plan spec: bsell cannot be combined with dia or heavy");
@@ -131,6 +135,7 @@ std::string print_spec(const PlanSpec &p) {
     case L_SELL: o << ",sigma=" << p.sigma; break;
     case L_BSELL: o << ",block=" << p.block << ",sigma=" << p.sigma << ",xwin=" << p.xwin; break;
     case L_BIN: o << ",smax=" << p.smax << ",sigma=" << p.sigma << ",chunk=" << p.chunk; break;
+    case L_XS: o << ",k=" << p.k << ",sigma=" << p.sigma; break;
     }
     o << ",remap=" << p.remap;
     return o.str();
@@ -167,6 +172,11 @@ std::string operator_chain(const PlanSpec &p) {
         sort();
         if (p.xwin) o << " -> BMTB_ROW_BLOCK(2048)[x window in LDS]";
         o << " -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD -> THREAD_TOTAL_RED";
+        break;
+    case L_XS:
+        o << " -> COL_DIV(" << p.k << " stripes, stripe s on XCD s mod 8)";
+        sort();
+        o << " -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD -> THREAD_TOTAL_RED -> SCRATCH_ROW_RED";
         break;
     case L_BIN:
         o << " -> BIN(len<=" << p.smax << " | <=128 | >128)";
