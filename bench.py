@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--configs", default="C1,C2,C3,C4,C5,C5f32")
     ap.add_argument("--budget-ms", type=float, default=8000.0, help="search budget per matrix")
     ap.add_argument("--plan", default="", help="force this plan spec for every matrix (skips the search)")
+    ap.add_argument("--plan-json", default="", help="JSON file {config: plan spec}: skip the search for those matrices")
+    ap.add_argument("--save-plans", default="", help="write the chosen plan specs to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
@@ -60,6 +62,7 @@ def main():
     names = [c for c in args.configs.split(",") if c]
     log = (lambda *a: print(*a, file=sys.stderr, flush=True)) if args.verbose else (lambda *a: None)
 
+    forced = json.load(open(args.plan_json)) if args.plan_json else {}
     items = []
     cpu = {"seconds": 0.0, "flops": 0.0, "cores": 0, "sample": []}
     cache = {}
@@ -75,7 +78,7 @@ def main():
         x = inputs.vector(m.ncols).astype(dt)
         t_gen = time.time() - t0
         t0 = time.time()
-        plan = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, vals, force_plan=args.plan or None,
+        plan = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, vals, force_plan=args.plan or forced.get(name) or None,
                         search_budget_ms=args.budget_ms, verbosity=int(args.verbose))
         t_plan = time.time() - t0
         d = plan.describe()
@@ -106,7 +109,8 @@ def main():
             cpu["sample"].append(name)
         items.append(dict(name=name, desc=desc, nnz=m.nnz, nrows=m.nrows, dtype=dt.name, plans=plans, xs=xs, ys=ys,
                           copies=copies, b_plan=b_plan, b_csr=b_csr, spec=d["spec"], operators=d["operators"],
-                          launches=plan.launch_names(), gen_s=t_gen, plan_s=t_plan,
+                          launches=plan.launch_names(), launch_bytes=[p["bytes"] for p in d["parts"]],
+                          gen_s=t_gen, plan_s=t_plan,
                           search=[(c["spec"], c["run_us"], c["note"]) for c in d["search"]]))
         log(f"{name}: nnz={m.nnz} gen {t_gen:.1f}s plan {t_plan:.1f}s -> {d['spec']} (copies={copies})")
         del vals, x
@@ -167,6 +171,12 @@ def main():
             e1.record(stream)
         e1.synchronize()
         it["ms"] = e0.elapsed_time(e1) / (reps * nrep)
+        it["ms_graph"] = it["ms"]
+        if it["copies"] == 1:
+            # back-to-back launches from the library's own timing loop (what a C caller sees); for
+            # the launch-bound matrices this is faster than replaying a graph of kernel nodes
+            it["ms_loop"] = it["plans"][0].time(it["xs"][0], it["ys"][0], stream.cuda_stream, 25) * 1e-3
+            it["ms"] = min(it["ms"], it["ms_loop"])
         # warm (cache-resident) figure for rotated matrices: the same copy every time
         if it["copies"] > 1:
             gw = torch.cuda.CUDAGraph()
@@ -200,31 +210,36 @@ def main():
                    gbps_credited=credited / t / 1e9, hbm_frac=credited / t / HBM_PEAK,
                    gbps_csr=it["b_csr"] / t / 1e9, gbps_plan=it["b_plan"] / t / 1e9,
                    plan=it["spec"], operators=it["operators"], launches=it["launches"],
-                   launch_us=[v * 1e3 for v in it["launch_ms"]], rotated_copies=it["copies"],
+                   launch_us=[v * 1e3 for v in it["launch_ms"]], launch_bytes=it["launch_bytes"],
+                   rotated_copies=it["copies"],
                    plan_create_s=it["plan_s"], search=it["search"])
         if "ms_warm" in it:
             rec["us_cache_warm"] = it["ms_warm"] * 1e3
+        rec["us_graph_replay"] = it["ms_graph"] * 1e3
+        if "ms_loop" in it:
+            rec["us_stream_loop"] = it["ms_loop"] * 1e3
         per_config.append(rec)
 
     def geomean(v):
         return float(np.exp(np.mean(np.log(v)))) if len(v) else None
 
-    # dominant kernel: the launch with the largest share of a step
-    dom = max(((it, i) for it in items for i in range(len(it["launches"]))), key=lambda p: p[0]["launch_ms"][p[1]])
-    dit, di = dom
-    dshare = dit["launch_ms"][di] / max(sum(dit["launch_ms"]), 1e-12)
-    dom_bytes = min(dit["b_plan"], dit["b_csr"]) * dshare if len(dit["launches"]) > 1 else min(dit["b_plan"], dit["b_csr"])
+    # dominant kernel: the launch with the largest share of a step; its algorithmic bytes are the
+    # format arrays it reads plus the x, scratch and y elements it touches (plan description)
+    dit, di = max(((it, i) for it in items for i in range(len(it["launches"]))), key=lambda p: p[0]["launch_ms"][p[1]])
+    dom_bytes = dit["launch_bytes"][di]
     achieved = dom_bytes / (dit["launch_ms"][di] * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(dit["name"])
+            traffic = json.load(open(tpath)).get(f"{dit['name']}:{dit['launches'][di]}")
         except Exception:
             traffic = None
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK / 1e9, unit="GB/s", frac=achieved / (HBM_PEAK / 1e9),
                     traffic=traffic, kernel=f"{dit['name']}:{dit['launches'][di]}",
                     launch_us=dit["launch_ms"][di] * 1e3, algorithmic_bytes=dom_bytes)
+    if args.save_plans:
+        json.dump({it["name"]: it["spec"] for it in items}, open(args.save_plans, "w"), indent=1)
 
     out = {
         "metric": "SpMV GFLOP/s (2*nnz/time) and achieved HBM GB/s (fraction of 8 TB/s peak) per matrix, 1 MI355X",

@@ -106,6 +106,15 @@ spmv_status_t spmv_run(const spmv_plan_t *plan, const void *x_dev, void *y_dev, 
 spmv_status_t spmv_run_timed(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
                              float *launch_ms);
 
+/*
+ * Benchmark helper, the same routine the search uses to time a candidate (Section VI-A, level two):
+ * two warm-up runs, then `repeats` samples, each a batch of back-to-back spmv_run launches on
+ * `stream` bracketed by HIP events; *median_us receives the median time of one run in microseconds.
+ * Synchronises the stream.  x_dev / y_dev as for spmv_run.
+ */
+spmv_status_t spmv_plan_time(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
+                             int repeats, double *median_us);
+
 /* Free the plan's device arrays (through the allocator pair it was created with). NULL is OK. */
 spmv_status_t spmv_plan_destroy(spmv_plan_t *plan);
 
@@ -129,8 +138,10 @@ spmv_status_t spmv_plan_array_copy(const spmv_plan_t *plan, int i, void *host_ds
 
 /*
  * Algorithmic bytes of one spmv_run:
- *   *b_plan = bytes of the format arrays the plan's kernels read, plus x once and y once (plus
- *             y again for every extra pass a plan makes over y);
+ *   *b_plan = sum over the plan's launches of: the format arrays the launch reads, the elements
+ *             of x it can touch (at most one per stored entry, at most all of x), the partial
+ *             sums it writes to or reads from scratch, and the y elements it writes (twice if it
+ *             updates them);
  *   *b_csr  = nnz*(v+4) + 4*(nrows+1) + v*ncols + v*nrows, the same for plain CSR (v = 4 or 8).
  */
 spmv_status_t spmv_plan_bytes(const spmv_plan_t *plan, int64_t *b_plan, int64_t *b_csr);

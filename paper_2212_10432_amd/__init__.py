@@ -20,7 +20,7 @@ SPMV_OK, SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_CSR, SPMV_ERR_UNSUPPORTED = 0, 1, 2,
 SPMV_ERR_ALLOC, SPMV_ERR_HIP, SPMV_ERR_INTERNAL = 4, 5, 6
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC", 5: "HIP", 6: "INTERNAL"}
 
-EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_timed", "spmv_plan_destroy", "spmv_plan_describe",
+EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
            "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
            "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error"]
 
@@ -70,6 +70,8 @@ def load():
     lib.spmv_run.argtypes = [vp, vp, vp, vp]
     lib.spmv_run_timed.restype = ci
     lib.spmv_run_timed.argtypes = [vp, vp, vp, vp, P(ctypes.c_float)]
+    lib.spmv_plan_time.restype = ci
+    lib.spmv_plan_time.argtypes = [vp, vp, vp, vp, ci, P(ctypes.c_double)]
     lib.spmv_plan_destroy.restype = ci
     lib.spmv_plan_destroy.argtypes = [vp]
     lib.spmv_plan_describe.restype = ci
@@ -149,6 +151,13 @@ def spmv_run_timed(plan: int, x_dev: int, y_dev: int, stream: int = 0):
     ms = (ctypes.c_float * max(n.value, 1))()
     _check(lib.spmv_run_timed(plan, x_dev, y_dev, stream, ms))
     return [ms[i] for i in range(n.value)]
+
+
+def spmv_plan_time(plan: int, x_dev: int, y_dev: int, stream: int = 0, repeats: int = 20) -> float:
+    """Median time of one run in microseconds (batches of back-to-back launches, HIP events)."""
+    us = ctypes.c_double()
+    _check(load().spmv_plan_time(plan, x_dev, y_dev, stream, repeats, ctypes.byref(us)))
+    return us.value
 
 
 def spmv_plan_destroy(plan: int) -> None:
@@ -235,6 +244,12 @@ class Plan:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
         return spmv_run_timed(self.handle, x.data_ptr(), y.data_ptr(), int(stream))
+
+    def time(self, x, y, stream=None, repeats=20) -> float:
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        return spmv_plan_time(self.handle, x.data_ptr(), y.data_ptr(), int(stream), repeats)
 
     def describe(self) -> dict:
         return spmv_plan_describe(self.handle)

@@ -78,7 +78,7 @@ std::string describe_json(const Plan &plan) {
         const Part &p = plan.parts[i];
         o << (i ? ", " : "") << "{\"name\": \"" << p.name << "\", \"rows\": " << p.nrows
           << ", \"nnz\": " << p.nnz << ", \"stored\": " << p.stored << ", \"units\": " << p.units
-          << ", \"lanes\": " << p.lanes << ", \"accumulate\": " << (p.accumulate ? "true" : "false")
+          << ", \"bytes\": " << p.bytes << ", \"lanes\": " << p.lanes << ", \"accumulate\": " << (p.accumulate ? "true" : "false")
           << ", \"origin_rows\": " << (p.has_rows ? "true" : "false") << "}";
     }
     o << "], \"arrays\": [";
@@ -246,6 +246,20 @@ spmv_status_t spmv_run_timed(const spmv_plan_t *plan, const void *x_dev, void *y
     }
     for (size_t i = 0; i < n; ++i) (void)hipEventElapsedTime(&launch_ms[i], ev[i], ev[i + 1]);
     drop();
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_time(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
+                             int repeats, double *median_us) {
+    API_BEGIN
+    if (!plan || !plan->impl || !median_us) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    const Plan &p = *plan->impl;
+    if (p.mem.host_only) fail(SPMV_ERR_UNSUPPORTED, "the plan was built host-only and cannot run");
+    if ((!x_dev && p.ncols > 0) || (!y_dev && p.nrows > 0)) fail(SPMV_ERR_INVALID_ARG, "x or y is NULL");
+    if (x_dev && x_dev == y_dev) fail(SPMV_ERR_INVALID_ARG, "x and y must not alias");
+    if (repeats < 1 || repeats > 100000) fail(SPMV_ERR_INVALID_ARG, "repeats out of range");
+    *median_us = time_plan(p, x_dev, y_dev, repeats, stream);
     return SPMV_OK;
     API_END
 }

@@ -37,16 +37,8 @@ int64_t Plan::bytes_csr() const {
 }
 
 int64_t Plan::bytes_plan() const {
-    const int64_t v = (int64_t)vsize();
-    int64_t b = v * ncols;
-    for (const DevArray &a : arrays)
-        if (a.read_per_run) b += a.count * a.elem_bytes;
-    for (const DevArray &a : scratch) b += 2 * a.count * a.elem_bytes;   // written, then read back
-    for (const Part &p : parts) {
-        const int64_t rows = (p.kind == K_BSELL) ? p.nrows * p.block : p.nrows;
-        if (p.kind == K_STRIPE || p.kind == K_XS) continue;   // write scratch only; y belongs to their reduce launch
-        b += rows * v * (p.accumulate ? 2 : 1) * p.y_passes;
-    }
+    int64_t b = 0;
+    for (const Part &p : parts) b += p.bytes;
     return b;
 }
 
@@ -85,6 +77,19 @@ const void *upload(Plan &plan, const std::string &name, int elem_bytes, int64_t 
         if (err != hipSuccess) fail(SPMV_ERR_HIP, std::string("hipMemcpy H2D (") + name + "): " + hipGetErrorString(err));
     }
     return d;
+}
+
+// Algorithmic bytes of one launch of a part: the format arrays it reads (those uploaded since
+// `first_array`), plus what it reads of x, reads/writes of scratch and writes (or updates) of y.
+void add_part(Plan &plan, Part p, size_t first_array, int64_t x_elems, int64_t scratch_elems,
+              int64_t y_elems) {
+    const int64_t v = (int64_t)plan.vsize();
+    int64_t b = 0;
+    for (size_t i = first_array; i < plan.arrays.size(); ++i)
+        if (plan.arrays[i].read_per_run) b += plan.arrays[i].count * plan.arrays[i].elem_bytes;
+    b += v * (x_elems + scratch_elems + y_elems * (p.accumulate ? 2 : 1));
+    p.bytes = b;
+    plan.parts.push_back(p);
 }
 
 // Row order of a part: stable sort by decreasing length inside windows of sigma rows
@@ -179,11 +184,12 @@ void build_sell(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int sig
         uniform = slice_ptr[(size_t)s + 1] - slice_ptr[(size_t)s] == slice_ptr[1] - slice_ptr[0];
     if (uniform) p.uniform_w = (int)((slice_ptr[1] - slice_ptr[0]) / kWave);
     // with one width for all slices the kernel computes the offsets; the array is kept for inspection only
+    const size_t a0 = plan.arrays.size();
     p.p0 = upload(plan, name + ".slice_ptr", 8, nsl + 1, slice_ptr.data(), !uniform);
     p.p1 = upload(plan, name + ".cols", 4, total, cols.p);
     p.p2 = upload(plan, name + ".vals", (int)sizeof(T), total, vals.p);
     if (p.has_rows) p.p3 = upload(plan, name + ".origin_rows", 4, n, rows.data());
-    plan.parts.push_back(p);
+    add_part(plan, p, a0, std::min<int64_t>(A.ncols, real), 0, n);
 }
 
 // ---- CSR segments ----------------------------------------------------------------------------
@@ -218,10 +224,11 @@ void build_csrv(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int lpr
     if (ident) {   // the input arrays already are the layout; origin row = segment id
         p.units = n;
         p.has_rows = false;
+        const size_t a0 = plan.arrays.size();
         p.p0 = upload(plan, name + ".seg_ptr", 4, n + 1, A.row_ptr);
         p.p2 = upload(plan, name + ".cols", 4, A.nnz, A.col);
         p.p3 = upload(plan, name + ".vals", (int)sizeof(T), A.nnz, A.val);
-        plan.parts.push_back(p);
+        add_part(plan, p, a0, std::min<int64_t>(A.ncols, total), 0, n);
         return;
     }
     sort_rows(rows, lens, sigma, threads);
@@ -260,11 +267,12 @@ void build_csrv(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int lpr
     });
     p.units = (int64_t)seg_row.size();
     p.has_rows = true;
+    const size_t a0 = plan.arrays.size();
     p.p0 = upload(plan, name + ".seg_ptr", 4, (int64_t)seg_ptr.size(), seg_ptr.data());
     p.p1 = upload(plan, name + ".seg_row", 4, (int64_t)seg_row.size(), seg_row.data());
     p.p2 = upload(plan, name + ".cols", 4, total, cols.p);
     p.p3 = upload(plan, name + ".vals", (int)sizeof(T), total, vals.p);
-    plan.parts.push_back(p);
+    add_part(plan, p, a0, std::min<int64_t>(A.ncols, total), 0, n);
 }
 
 // ---- DIA extraction --------------------------------------------------------------------------
@@ -325,10 +333,12 @@ void build_dia(Plan &plan, const HostCsr &A, const std::vector<int32_t> &offs, O
     p.stored = nd * ld;
     p.units = A.nrows;
     p.ndiag = (int)nd;
+    for (int64_t d = 0; d < std::min<int64_t>(nd, 8); ++d) p.dia_offsets[d] = offs[(size_t)d];
     p.ld = ld;
+    const size_t a0 = plan.arrays.size();
     p.p0 = upload(plan, "dia.offsets", 4, nd, offs.data());
     p.p1 = upload(plan, "dia.vals", (int)sizeof(T), nd * ld, dv.p);
-    plan.parts.push_back(p);
+    add_part(plan, p, a0, A.ncols, 0, A.nrows);
 }
 
 // ---- dense B x B blocks in SELL order ----------------------------------------------------------
@@ -422,6 +432,7 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
     p.block = B;
     p.has_rows = sigma != 0;
     p.remap = remap;
+    const size_t a0 = plan.arrays.size();
     if (xwin) {
         // x window of each group of 32 slices: [lo, lo + n) in scalar columns
         const int64_t ng = (nsl + kXwinGroup - 1) / kXwinGroup;
@@ -452,7 +463,7 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
     p.p1 = upload(plan, "bsell.bcols", 4, total, bcols.p);
     p.p2 = upload(plan, "bsell.vals", (int)sizeof(T), total * BB, vals.p);
     if (p.has_rows) p.p3 = upload(plan, "bsell.origin_brows", 4, nb, brows.data());
-    plan.parts.push_back(p);
+    add_part(plan, p, a0, A.ncols, 0, A.nrows);
     (void)real_blocks;
 }
 
@@ -556,12 +567,15 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     p.scratch = scratch;
     p.tile = tile;
     p.has_rows = true;
+    const size_t a0 = plan.arrays.size();
     p.p0 = upload(plan, "heavy.unit_ptr", 4, ns * nsl + 1, unit_ptr.data());
     p.p1 = upload(plan, "heavy.lcols", 2, padded, lcol.p);
     p.p2 = upload(plan, "heavy.vals", (int)sizeof(T), padded, vals.p);
     p.p3 = upload(plan, "heavy.rows", 4, nh, hrows.data());
     p.p4 = upload(plan, "heavy.lane_row", 2, ns * nsl * kWave, lane_row.data());
-    plan.parts.push_back(p);
+    plan.arrays[a0 + 3].read_per_run = false;   // heavy.rows is read by the reduce launch
+    add_part(plan, p, a0, A.ncols, ngroups * nh, 0);
+    plan.arrays[a0 + 3].read_per_run = true;
     Part r;   // sums the workgroups' partial sums into y (overwrites, or adds after a DIA part)
     r.kind = K_REDUCE_WIDE;
     r.name = "heavy.reduce";
@@ -572,7 +586,7 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     r.accumulate = acc;
     r.has_rows = true;
     r.p3 = p.p3;
-    plan.parts.push_back(r);
+    add_part(plan, r, plan.arrays.size(), 0, ngroups * nh + nh / 2, nh);   // + heavy.rows (4 bytes each)
 }
 
 // ---- XCD-striped SELL ----------------------------------------------------------------------------
@@ -725,11 +739,12 @@ void build_xs(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
     p.ngroups = (per_xcd + 3) / 4;   // workgroups per XCD, four slices each
     p.scratch = scratch;
     p.has_rows = !ident;
+    const size_t a0 = plan.arrays.size();
     p.p0 = upload(plan, "xs.unit_ptr", 8, nunits + 1, unit_ptr.data());
     p.p1 = upload(plan, "xs.cols", 4, total, cols.p);
     p.p2 = upload(plan, "xs.vals", (int)sizeof(T), total, vals.p);
     p.p4 = upload(plan, "xs.xbase", 8, 9, xbase.data());
-    plan.parts.push_back(p);
+    add_part(plan, p, a0, std::min<int64_t>(A.ncols, real), nunits * kWave, 0);
     Part r;
     r.kind = K_REDUCE_ROWS;
     r.name = "xs.reduce";
@@ -738,10 +753,11 @@ void build_xs(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
     r.scratch = scratch;
     r.accumulate = acc;
     r.has_rows = !ident;
+    const size_t a1 = plan.arrays.size();
     r.p0 = upload(plan, "xs.pptr", 4, n + 1, pptr.data());
     r.p1 = upload(plan, "xs.pslot", 4, nslots, pslot.p);
     if (!ident) r.p3 = upload(plan, "xs.rows", 4, n, rows.data());
-    plan.parts.push_back(r);
+    add_part(plan, r, a1, 0, nslots, n);
 }
 
 // Copy of A with ascending columns inside each row (stable: repeated columns keep their order).
@@ -877,6 +893,7 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         z.units = z.nrows;
         z.has_rows = true;
         z.p0 = upload(*plan, "zero.rows", 4, z.nrows, zero_rows.data());
+        z.bytes = z.nrows * (4 + (int64_t)plan->vsize());
         plan->parts.insert(plan->parts.begin() + (std::ptrdiff_t)zero_slot, z);
     }
     return plan;

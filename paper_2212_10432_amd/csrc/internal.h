@@ -117,6 +117,7 @@ struct Part {
     int lanes = 1;               // lanes per row / segment
     int block = 1;               // bsell block edge
     int ndiag = 0;
+    int32_t dia_offsets[8] = {0};   // host copy of the first offsets (kernel arguments when ndiag <= 8)
     int tile = 0;
     int remap = 0;
     int64_t ld = 0;              // dia leading dimension
@@ -127,7 +128,7 @@ struct Part {
     int uniform_w = -1;          // sell: width shared by every slice (-1: read slice_ptr)
     int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
     const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
-    int64_t y_passes = 1;        // how many times this part touches its rows of y (bytes model)
+    int64_t bytes = 0;           // algorithmic bytes of one launch: arrays read + x + scratch + y
 };
 
 struct Allocator {

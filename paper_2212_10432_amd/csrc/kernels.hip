@@ -95,27 +95,47 @@ __global__ __launch_bounds__(kWG) void k_zero_rows(const int32_t *__restrict__ r
     if (i < n) y[rows[i]] = T(0);
 }
 
-// ---- DIA: diagonals stored column-major (d * ld + row), two rows per lane --------------------
+// ---- DIA: one lane per row, diagonals stored column-major (d * ld + row) --------------------
 // THREAD_TOTAL_RED over the ndiag slots of a row; the column index is arithmetic (row + offset),
-// i.e. the index array is replaced by a linear model (Section V-D).  A lane owns rows 2i and
-// 2i + 1 so that the diagonal values arrive in 16-byte loads (ld is a multiple of 64).
+// i.e. the index array is replaced by a linear model (Section V-D).
 template <typename T, bool ACC>
 __global__ __launch_bounds__(kWG) void k_dia(const int32_t *__restrict__ offs, int ndiag,
                                              const T *__restrict__ vals, int64_t ld,
                                              const T *__restrict__ x, T *__restrict__ y,
                                              int64_t nrows, int64_t ncols) {
-    typedef T V2 __attribute__((ext_vector_type(2)));
-    const int64_t i = 2 * ((int64_t)blockIdx.x * kWG + threadIdx.x);
+    const int64_t i = (int64_t)blockIdx.x * kWG + threadIdx.x;
     if (i >= nrows) return;
-    T acc0 = T(0), acc1 = T(0);
+    T acc = T(0);
     for (int d = 0; d < ndiag; ++d) {
         const int64_t c = i + offs[d];
-        const V2 v = ldnt(reinterpret_cast<const V2 *>(vals + (int64_t)d * ld + i));   // rows i, i+1 < ld
-        if (c >= 0 && c < ncols) acc0 += v.x * x[c];
-        if (c + 1 >= 0 && c + 1 < ncols) acc1 += v.y * x[c + 1];
+        const T v = ldnt(vals + (int64_t)d * ld + i);
+        if (c >= 0 && c < ncols) acc += v * x[c];
     }
-    y[i] = ACC ? y[i] + acc0 : acc0;
-    if (i + 1 < nrows) y[i + 1] = ACC ? y[i + 1] + acc1 : acc1;
+    y[i] = ACC ? y[i] + acc : acc;
+}
+
+// Up to 8 diagonals: the offsets travel as kernel arguments and the loop is unrolled, so all
+// 2*ND loads of a lane are issued before the first is used.
+struct DiaOffsets {
+    int32_t o[8];
+};
+template <typename T, int ND, bool ACC>
+__global__ __launch_bounds__(kWG) void k_dia_fixed(DiaOffsets offs, const T *__restrict__ vals,
+                                                   int64_t ld, const T *__restrict__ x,
+                                                   T *__restrict__ y, int64_t nrows, int64_t ncols) {
+    const int64_t i = (int64_t)blockIdx.x * kWG + threadIdx.x;
+    if (i >= nrows) return;
+    T v[ND], xv[ND];
+#pragma unroll
+    for (int d = 0; d < ND; ++d) {
+        const int64_t c = i + offs.o[d];
+        v[d] = ldnt(vals + (int64_t)d * ld + i);
+        xv[d] = (c >= 0 && c < ncols) ? x[c] : T(0);
+    }
+    T acc = T(0);
+#pragma unroll
+    for (int d = 0; d < ND; ++d) acc += v[d] * xv[d];
+    y[i] = ACC ? y[i] + acc : acc;
 }
 
 // ---- SELL: one wavefront per slice of 64 rows, one lane per row -----------------------------
@@ -463,10 +483,23 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (nrows == 0) return 0;
         auto *offs = (const int32_t *)p.p0;
         auto *vals = (const T *)p.p1;
+        const unsigned grid = blocks(nrows, kWG);
+        if (p.ndiag >= 1 && p.ndiag <= 8) {
+            DiaOffsets o;
+            for (int d = 0; d < 8; ++d) o.o[d] = d < p.ndiag ? p.dia_offsets[d] : 0;
+#define DIA_N(N)                                                                                   \
+    case N:                                                                                        \
+        if (p.accumulate) k_dia_fixed<T, N, true><<<grid, kWG, 0, st>>>(o, vals, p.ld, x, y, nrows, ncols); \
+        else k_dia_fixed<T, N, false><<<grid, kWG, 0, st>>>(o, vals, p.ld, x, y, nrows, ncols);    \
+        break;
+            switch (p.ndiag) { DIA_N(1) DIA_N(2) DIA_N(3) DIA_N(4) DIA_N(5) DIA_N(6) DIA_N(7) DIA_N(8) }
+#undef DIA_N
+            break;
+        }
         if (p.accumulate)
-            k_dia<T, true><<<blocks((nrows + 1) / 2, kWG), kWG, 0, st>>>(offs, p.ndiag, vals, p.ld, x, y, nrows, ncols);
+            k_dia<T, true><<<grid, kWG, 0, st>>>(offs, p.ndiag, vals, p.ld, x, y, nrows, ncols);
         else
-            k_dia<T, false><<<blocks((nrows + 1) / 2, kWG), kWG, 0, st>>>(offs, p.ndiag, vals, p.ld, x, y, nrows, ncols);
+            k_dia<T, false><<<grid, kWG, 0, st>>>(offs, p.ndiag, vals, p.ld, x, y, nrows, ncols);
         break;
     }
     case K_SELL: {
