@@ -31,7 +31,7 @@ WAVE = 64
 
 def parse_spec(spec: str) -> dict:
     d = dict(dia=0, dia_fill=0.5, heavy=0, tile=8192, light="csrv", lpr=0, chunk=0,
-             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8)
+             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8, r=8)
     for tok in spec.split(","):
         if not tok:
             continue
@@ -302,6 +302,44 @@ def ref_xs(ncols, rp, ci, va, rows, K, sigma, nrows_total):
     return out
 
 
+def ref_nnzb(rp, ci, va, rows, R, acc, zero_rows):
+    """nnz-balanced tiles: the entries of the part's non-empty rows form one stream; lane l of tile i
+    holds the R consecutive entries from 64*R*i + R*l, stored at 64*R*i + 64*t + l (t < R); bit t of
+    bits[64*i + l] marks an entry that starts a row; tile_row[i] counts the row starts before tile i.
+    Rows open at a tile border, and empty rows, are zeroed by an earlier launch."""
+    lens = np.diff(rp).astype(np.int64)
+    keep = [int(r) for r in rows if lens[r] > 0]
+    if not acc:
+        zero_rows += [int(r) for r in rows if lens[r] == 0]
+    if not keep:
+        return {}
+    stream_c = np.concatenate([ci[_row_entries(rp, r)] for r in keep])
+    stream_v = np.concatenate([va[_row_entries(rp, r)] for r in keep])
+    starts = np.concatenate([[0], np.cumsum(lens[keep])])[:-1]
+    total = stream_c.size
+    tsz = WAVE * R
+    ntiles = -(-total // tsz)
+    g = np.arange(ntiles * tsz)
+    dst = (g // tsz) * tsz + ((g % tsz) % R) * WAVE + (g % tsz) // R
+    cols = np.zeros(ntiles * tsz, dtype=np.int32)
+    vals = np.zeros(ntiles * tsz, dtype=va.dtype)
+    cols[dst[:total]] = stream_c
+    vals[dst[:total]] = stream_v
+    bits = np.zeros(ntiles * WAVE, dtype=np.uint8 if R <= 8 else np.uint16)
+    for st in starts:
+        bits[(st // tsz) * WAVE + (st % tsz) // R] |= 1 << ((st % tsz) % R)
+    tile_row = np.zeros(ntiles + 1, dtype=np.int32)
+    np.cumsum(np.bincount(starts // tsz, minlength=ntiles), out=tile_row[1:])
+    if not acc:
+        owner = np.repeat(np.arange(len(keep)), lens[keep])          # stream position -> row index
+        for t in range(ntiles):
+            zero_rows.append(keep[owner[min(total, (t + 1) * tsz) - 1]])
+            if starts[owner[t * tsz]] != t * tsz:
+                zero_rows.append(keep[owner[t * tsz]])
+    return {"nnzb.cols": cols, "nnzb.vals": vals, "nnzb.bits": bits, "nnzb.tile_row": tile_row,
+            "nnzb.rows": np.array(keep, dtype=np.int32)}
+
+
 def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
     """All format arrays of the plan `spec` for a CSR matrix with ascending columns in each row."""
     p = parse_spec(spec)
@@ -331,6 +369,8 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
         out.update(ref_csrv(rp, ci, va, light, lpr, p["chunk"], p["sigma"], acc, nrows, "csrv", zero_rows))
     elif p["light"] == "sell":
         out.update(ref_sell(rp, ci, va, light, p["sigma"], nrows, "sell"))
+    elif p["light"] == "nnzb":
+        out.update(ref_nnzb(rp, ci, va, light, p["r"], acc, zero_rows))
     elif p["light"] == "xs":
         out.update(ref_xs(ncols, rp, ci, va, light, p["k"], p["sigma"], nrows))
     elif p["light"] == "bin":
@@ -342,7 +382,7 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
         raise ValueError(p["light"])
     out.update(ref_stripe(ncols, rp, ci, va, heavy, p["tile"]))
     if zero_rows:
-        out["zero.rows"] = np.array(sorted(zero_rows), dtype=np.int32)
+        out["zero.rows"] = np.array(sorted(set(zero_rows)), dtype=np.int32)
     return out
 
 
@@ -356,6 +396,16 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
     for pre in prefixes:
         a = {k.rsplit(".", 1)[1]: v for k, v in arrays.items() if k.rsplit(".", 1)[0] == pre}
         if pre == "zero":
+            continue
+        if pre == "nnzb":
+            cc, vv, bb, rws = a["cols"], a["vals"], a["bits"], a["rows"]
+            R_ = cc.size // bb.size
+            tsz = WAVE * R_
+            g = np.arange(cc.size)
+            src = (g // tsz) * tsz + ((g % tsz) % R_) * WAVE + (g % tsz) // R_      # stream order -> storage
+            mark = ((bb[(g // tsz) * WAVE + (g % tsz) // R_].astype(np.int64) >> ((g % tsz) % R_)) & 1).astype(np.int64)
+            rowidx = np.cumsum(mark) - 1
+            R.append(rws[rowidx].astype(np.int64)); C.append(cc[src]); V.append(vv[src])
             continue
         if pre == "xs":
             up, cc, vv, ps, pp = a["unit_ptr"], a["cols"], a["vals"], a["pslot"], a["pptr"]

@@ -190,7 +190,7 @@ def spmv_plan_array_copy(plan: int, i: int, value_dtype=np.float64) -> np.ndarra
     if name.endswith("vals"):
         dt = np.dtype(value_dtype)
     else:
-        dt = {2: np.dtype(np.uint16), 4: np.dtype(np.int32), 8: np.dtype(np.int64)}[eb]
+        dt = {1: np.dtype(np.uint8), 2: np.dtype(np.uint16), 4: np.dtype(np.int32), 8: np.dtype(np.int64)}[eb]
     assert dt.itemsize == eb, (name, dt, eb)
     out = np.empty(cnt, dtype=dt)
     _check(load().spmv_plan_array_copy(plan, i, out.ctypes.data))

@@ -589,6 +589,99 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     add_part(plan, r, plan.arrays.size(), 0, ngroups * nh + nh / 2, nh);   // + heavy.rows (4 bytes each)
 }
 
+// ---- nnz-balanced tiles ----------------------------------------------------------------------------
+// The non-empty rows of the part, in order, form one stream of entries; tile i holds entries
+// [64*R*i, 64*R*(i+1)), lane l of the tile the R consecutive entries from 64*R*i + R*l, stored
+// transposed (entry t of lane l at 64*R*i + 64*t + l).  The stream's tail is padded with
+// (value 0, column 0).  bits[64*i + l] marks the entries of the lane that start a row.  Rows open
+// at a tile border are accumulated with atomics and therefore zeroed first; empty rows too.
+template <typename T>
+void build_nnzb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows_in, int R, bool acc,
+                const std::vector<int64_t> &lens, std::vector<int32_t> &zero_rows, int threads) {
+    std::vector<int32_t> rows;
+    rows.reserve(rows_in.size());
+    for (int32_t r : rows_in) {
+        if (lens[(size_t)r] > 0) rows.push_back(r);
+        else if (!acc) zero_rows.push_back(r);
+    }
+    const int64_t n = (int64_t)rows.size();
+    if (n == 0) return;
+    std::vector<int64_t> start((size_t)n + 1, 0);   // position of each row's first entry in the stream
+    for (int64_t i = 0; i < n; ++i) start[(size_t)i + 1] = start[(size_t)i] + lens[(size_t)rows[(size_t)i]];
+    const int64_t total = start[(size_t)n];
+    const int64_t tile_sz = (int64_t)kWave * R;
+    const int64_t ntiles = (total + tile_sz - 1) / tile_sz;
+    if (ntiles * tile_sz >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "nnzb: too many entries");
+    HostBuf<int32_t> cols(ntiles * tile_sz);
+    HostBuf<T> vals(ntiles * tile_sz);
+    std::vector<uint16_t> bits((size_t)(ntiles * kWave), 0);
+    std::vector<int32_t> tile_row((size_t)ntiles + 1, 0);
+    const T *av = (const T *)A.val;
+    // entries: parallel over rows; marks: one per row
+    parallel_for(n, 1024, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t r = rows[(size_t)i];
+            const int64_t src = A.row_ptr[r], L = lens[(size_t)r];
+            for (int64_t k = 0; k < L; ++k) {
+                const int64_t g = start[(size_t)i] + k;          // position in the stream
+                const int64_t tile = g / tile_sz, in = g % tile_sz;
+                const int64_t dst = tile * tile_sz + (in % R) * kWave + in / R;
+                cols[dst] = A.col[src + k];
+                vals[dst] = av[src + k];
+            }
+        }
+    });
+    for (int64_t g = total; g < ntiles * tile_sz; ++g) {
+        const int64_t tile = g / tile_sz, in = g % tile_sz;
+        const int64_t dst = tile * tile_sz + (in % R) * kWave + in / R;
+        cols[dst] = 0;
+        vals[dst] = T(0);
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t g = start[(size_t)i];
+        const int64_t tile = g / tile_sz, in = g % tile_sz;
+        bits[(size_t)(tile * kWave + in / R)] |= (uint16_t)(1u << (in % R));
+        tile_row[(size_t)tile + 1] += 1;
+    }
+    for (int64_t t = 0; t < ntiles; ++t) tile_row[(size_t)t + 1] += tile_row[(size_t)t];
+    // rows open at a tile border: the row holding a tile's last entry, and the row holding its
+    // first entry when that entry does not start a row
+    if (!acc) {
+        for (int64_t t = 0; t < ntiles; ++t) {
+            const int64_t last = std::min(total, (t + 1) * tile_sz) - 1;
+            const int64_t i_last = (int64_t)(std::upper_bound(start.begin(), start.end(), last) - start.begin()) - 1;
+            zero_rows.push_back(rows[(size_t)i_last]);
+            const int64_t first = t * tile_sz;
+            const int64_t i_first = (int64_t)(std::upper_bound(start.begin(), start.end(), first) - start.begin()) - 1;
+            if (start[(size_t)i_first] != first) zero_rows.push_back(rows[(size_t)i_first]);
+        }
+        std::sort(zero_rows.begin(), zero_rows.end());
+        zero_rows.erase(std::unique(zero_rows.begin(), zero_rows.end()), zero_rows.end());
+    }
+    Part p;
+    p.kind = K_NNZB;
+    p.name = "nnzb";
+    p.nrows = n;
+    p.nnz = total;
+    p.stored = ntiles * tile_sz;
+    p.units = ntiles;
+    p.lanes = R;
+    p.accumulate = acc;
+    p.has_rows = true;
+    const size_t a0 = plan.arrays.size();
+    p.p0 = upload(plan, "nnzb.cols", 4, ntiles * tile_sz, cols.p);
+    p.p1 = upload(plan, "nnzb.vals", (int)sizeof(T), ntiles * tile_sz, vals.p);
+    if (R <= 8) {
+        std::vector<uint8_t> b8(bits.begin(), bits.end());
+        p.p2 = upload(plan, "nnzb.bits", 1, ntiles * kWave, b8.data());
+    } else {
+        p.p2 = upload(plan, "nnzb.bits", 2, ntiles * kWave, bits.data());
+    }
+    p.p3 = upload(plan, "nnzb.tile_row", 4, ntiles + 1, tile_row.data());
+    p.p4 = upload(plan, "nnzb.rows", 4, n, rows.data());
+    add_part(plan, p, a0, std::min<int64_t>(A.ncols, total), 0, n);
+}
+
 // ---- XCD-striped SELL ----------------------------------------------------------------------------
 // COL_DIV into K stripes of W = ceil(ncols / K) columns (rounded up to 64).  Per stripe: the rows
 // of the part that have entries in it, in windows of sigma part positions, sorted by that count
@@ -864,6 +957,9 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         break;
     case L_XS:
         build_xs<T>(*plan, A, light, spec.k, spec.sigma, acc, lens, threads);
+        break;
+    case L_NNZB:
+        build_nnzb<T>(*plan, A, light, spec.r, acc, lens, zero_rows, threads);
         break;
     case L_BIN: {
         // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront per

@@ -72,7 +72,7 @@ struct Census {
 Census take_census(const HostCsr &A, int threads);
 
 // ---- plan specification --------------------------------------------------------------------
-enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4 };
+enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZB = 5 };
 
 struct PlanSpec {
     int dia = 0;             // extract well-populated diagonals into a DIA part first
@@ -86,6 +86,7 @@ struct PlanSpec {
     int block = 3;           // bsell: block edge (2, 3 or 4)
     int smax = 16;           // bin: rows up to this length go to the SELL bin
     int remap = 0;           // 1 = give each XCD a contiguous range of workgroups
+    int r = 8;               // nnzb: consecutive non-zeros per lane (4, 8 or 16)
     int k = 8;               // xs: column stripes (8 or 16: one or two per XCD)
     int xwin = 0;            // bsell: stage the x window of 32 slices in LDS when it fits
 };
@@ -102,7 +103,7 @@ struct DevArray {
     bool read_per_run = true;    // counts towards the algorithmic bytes of one run
 };
 
-enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS };
+enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB };
 
 // One kernel launch of spmv_run.  Pointers refer to entries of Plan::arrays.
 struct Part {

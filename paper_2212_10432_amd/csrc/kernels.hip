@@ -264,6 +264,107 @@ __global__ __launch_bounds__(kWG) void k_csrv(const int32_t *__restrict__ seg_pt
     }
 }
 
+// ---- nnz-balanced segmented kernel ----------------------------------------------------------
+// BMT_NNZ_BLOCK(R): every lane owns R consecutive non-zeros of the part's CSR stream, whatever
+// rows they belong to (perfect balance, no padding except the stream's tail).  A wavefront's tile
+// of 64*R entries is stored transposed (entry t of lane l at 64*R*tile + 64*t + l) so that loads
+// stay contiguous.  THREAD_BITMAP_RED: bit t of the lane's bitmap marks an entry that starts a
+// row; the lane adds its entries up serially and closes a row at each mark.  Rows that lie inside
+// one lane are stored directly.  WARP_SEG_RED: the open pieces (the lane's sum before its first
+// mark, after its last mark, or everything if it has no mark) are combined by a segmented scan
+// over the 64 lanes.  A row that starts in the wavefront and ends in it is stored by the lane that
+// sees its end; what enters the wavefront from an earlier tile and what is still open at its end
+// is added atomically (GMEM_ATOM_RED) to y elements zeroed by an earlier launch.
+// tile_row[i] = number of row starts before tile i = index (into rows[]) of the first row that
+// starts in it.
+template <typename T, int R, typename BM, bool ACC>
+__global__ __launch_bounds__(kWG) void k_nnzb(const int32_t *__restrict__ cols,
+                                              const T *__restrict__ vals,
+                                              const BM *__restrict__ bits,
+                                              const int32_t *__restrict__ tile_row,
+                                              const int32_t *__restrict__ rows,
+                                              const T *__restrict__ x, T *__restrict__ y,
+                                              int64_t ntiles) {
+    const int64_t tile = (int64_t)blockIdx.x * (kWG / kWave) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (tile >= ntiles) return;
+    const int64_t base = tile * 64 * R + lane;
+    int32_t c[R];
+    T v[R], xv[R];
+#pragma unroll
+    for (int t = 0; t < R; ++t) {
+        c[t] = ldnt(cols + base + t * 64);
+        v[t] = ldnt(vals + base + t * 64);
+    }
+    const uint32_t bm = (uint32_t)ldnt(bits + tile * 64 + lane);
+#pragma unroll
+    for (int t = 0; t < R; ++t) xv[t] = x[c[t]];
+    // index of the first row starting in this lane: row starts in earlier lanes of the tile
+    const int nstart = __popc(bm);
+    int pre = nstart;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(pre, o, kWave);
+        if (lane >= o) pre += up;
+    }
+    int32_t row = tile_row[tile] + (pre - nstart);   // row of the lane's first mark
+    // serial pass over the lane's entries
+    T acc = T(0), head = T(0);
+    bool seen = false;
+#pragma unroll
+    for (int t = 0; t < R; ++t) {
+        if ((bm >> t) & 1u) {
+            if (seen) {
+                const int32_t r = rows[row];   // a row that starts and ends inside this lane
+                y[r] = ACC ? y[r] + acc : acc;
+                ++row;
+            } else {
+                head = acc;           // belongs to a row that started earlier
+                seen = true;
+            }
+            acc = T(0);
+        }
+        acc += v[t] * xv[t];
+    }
+    // now: seen ? (head = sum before the first mark, acc = sum after the last mark, `row` = row of
+    // the last mark) : (acc = sum of the whole lane, which lies inside one open row)
+    // segmented scan: carry entering lane k = seen_{k-1} ? tail_{k-1} : carry_{k-1} + all_{k-1}
+    T val = acc;
+    int flag = seen ? 1 : 0;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const T uv = __shfl_up(val, o, kWave);
+        const int uf = __shfl_up(flag, o, kWave);
+        if (lane >= o) {
+            if (!flag) val += uv;
+            flag |= uf;
+        }
+    }
+    // val/flag are inclusive; the carry entering this lane is the inclusive result of lane - 1
+    T carry = __shfl_up(val, 1, kWave);
+    int started = __shfl_up(flag, 1, kWave);   // a row start exists in an earlier lane of the tile
+    if (lane == 0) {
+        carry = T(0);
+        started = 0;
+    }
+    if (seen) {
+        // close the row that ends at this lane's first mark (unless nothing precedes the mark)
+        const int32_t first_row = tile_row[tile] + (pre - nstart);
+        const bool empty = (lane == 0) && (bm & 1u);
+        if (!empty) {
+            const T total = carry + head;
+            const int32_t r = rows[first_row - 1];
+            if (started) y[r] = ACC ? y[r] + total : total;
+            else atomic_add(y + r, total);
+        }
+    }
+    if (lane == 63) {
+        // what is still open at the end of the tile: the row of the last mark at or before it
+        const int32_t last_row = tile_row[tile + 1] - 1;
+        atomic_add(y + rows[last_row], val);
+    }
+}
+
 // ---- blocked SELL: dense B x B blocks, one lane per block row -------------------------------
 // The SELL design applied to block rows; one column index per block (the per-entry indices of a
 // block follow a periodic linear model, Section V-D), B accumulators per lane in registers
@@ -612,6 +713,27 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (p.has_rows) { if (p.accumulate) RR_GO(true, true); else RR_GO(true, false); }
         else            { if (p.accumulate) RR_GO(false, true); else RR_GO(false, false); }
 #undef RR_GO
+        break;
+    }
+    case K_NNZB: {
+        if (p.units == 0) return 0;
+        const unsigned grid = blocks(p.units, kWG / kWave);
+#define NNZB_GO(RR, BM)                                                                            \
+    if (p.accumulate)                                                                              \
+        k_nnzb<T, RR, BM, true><<<grid, kWG, 0, st>>>((const int32_t *)p.p0, (const T *)p.p1,     \
+                                                       (const BM *)p.p2, (const int32_t *)p.p3,    \
+                                                       (const int32_t *)p.p4, x, y, p.units);      \
+    else                                                                                           \
+        k_nnzb<T, RR, BM, false><<<grid, kWG, 0, st>>>((const int32_t *)p.p0, (const T *)p.p1,    \
+                                                        (const BM *)p.p2, (const int32_t *)p.p3,   \
+                                                        (const int32_t *)p.p4, x, y, p.units)
+        switch (p.lanes) {
+        case 4: NNZB_GO(4, uint8_t); break;
+        case 8: NNZB_GO(8, uint8_t); break;
+        case 16: NNZB_GO(16, uint16_t); break;
+        default: return (int)hipErrorInvalidValue;
+        }
+#undef NNZB_GO
         break;
     }
     case K_REDUCE_WIDE: {

@@ -131,6 +131,15 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             if (2 * k1 <= 32) push(xs_plan(th0, 2 * k1, tile / 2));
         }
         push(bin_plan(th0));
+        {   // nnz-balanced segmented tiles for everything but the heavy tail
+            PlanSpec p = bin_plan(th0);
+            p.light = L_NNZB;
+            p.r = 8;
+            p.sigma = 0;
+            p.chunk = 0;
+            p.remap = 0;
+            push(p);
+        }
         if (th0 && tail_ok(4 * th0)) push(bin_plan(4 * th0));
         if (th0) push(bin_plan(0));
         if (c.max_len <= 1024) {

@@ -66,6 +66,7 @@ static const char *light_name(int l) {
     case L_BSELL: return "bsell";
     case L_BIN: return "bin";
     case L_XS: return "xs";
+    case L_NNZB: return "nnzb";
     }
     return "?";
 }
@@ -93,6 +94,7 @@ PlanSpec parse_spec(const std::string &s) {
             else if (v == "bsell") p.light = L_BSELL;
             else if (v == "bin") p.light = L_BIN;
             else if (v == "xs") p.light = L_XS;
+            else if (v == "nnzb") p.light = L_NNZB;
             else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown light design " + v);
         } else if (k == "dia") p.dia = (int)num();
         else if (k == "dia_fill") p.dia_fill = num();
@@ -106,6 +108,7 @@ PlanSpec parse_spec(const std::string &s) {
         else if (k == "remap") p.remap = (int)num();
         else if (k == "xwin") p.xwin = (int)num();
         else if (k == "k") p.k = (int)num();
+        else if (k == "r") p.r = (int)num();
         else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown key " + k);
     }
     if (p.dia != 0 && p.dia != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia must be 0 or 1");
@@ -119,6 +122,7 @@ PlanSpec parse_spec(const std::string &s) {
     if (p.smax < 0 || p.smax > 1024) fail(SPMV_ERR_INVALID_ARG, "plan spec: smax must be in [0, 1024]");
     if (p.remap != 0 && p.remap != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: remap must be 0 or 1");
     if (p.k != 8 && p.k != 16 && p.k != 24 && p.k != 32) fail(SPMV_ERR_INVALID_ARG, "plan spec: k must be 8, 16, 24 or 32");
+    if (p.r != 4 && p.r != 8 && p.r != 16) fail(SPMV_ERR_INVALID_ARG, "plan spec: r must be 4, 8 or 16");
     if (p.xwin != 0 && p.xwin != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin must be 0 or 1");
     if (p.xwin && p.light != L_BSELL) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin needs light=bsell");
     if (p.light == L_BSELL && (p.dia || p.heavy)) fail(SPMV_ERR_INVALID_ARG, "plan spec: bsell cannot be combined with dia or heavy");
@@ -136,6 +140,7 @@ std::string print_spec(const PlanSpec &p) {
     case L_BSELL: o << ",block=" << p.block << ",sigma=" << p.sigma << ",xwin=" << p.xwin; break;
     case L_BIN: o << ",smax=" << p.smax << ",sigma=" << p.sigma << ",chunk=" << p.chunk; break;
     case L_XS: o << ",k=" << p.k << ",sigma=" << p.sigma; break;
+    case L_NNZB: o << ",r=" << p.r; break;
     }
     o << ",remap=" << p.remap;
     return o.str();
@@ -172,6 +177,10 @@ std::string operator_chain(const PlanSpec &p) {
         sort();
         if (p.xwin) o << " -> BMTB_ROW_BLOCK(2048)[x window in LDS]";
         o << " -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD -> THREAD_TOTAL_RED";
+        break;
+    case L_NNZB:
+        o << " -> BMW_NNZ_BLOCK(" << 64 * p.r << ") -> BMT_NNZ_BLOCK(" << p.r
+          << ") -> THREAD_BITMAP_RED -> WARP_SEG_RED -> GMEM_ATOM_RED(tile borders)";
         break;
     case L_XS:
         o << " -> COL_DIV(" << p.k << " stripes, stripe s on XCD s mod 8)";
