@@ -340,6 +340,79 @@ def ref_nnzb(rp, ci, va, rows, R, acc, zero_rows):
             "nnzb.rows": np.array(keep, dtype=np.int32)}
 
 
+def ref_xnb(ncols, rp, ci, va, rows, K, R, nrows_total):
+    """XCD-striped nnz-balanced tiles.  K stripes of W = ceil(ncols/K) (rounded up to 64) columns, XCD k
+    owning stripes k, k+8, ...; the streams are laid out XCD by XCD.  Inside a stripe the (row, stripe)
+    segments follow each other in part order; the stream is padded to whole tiles of 64*R entries with
+    (value 0, first column of the stripe) and stored transposed per tile.  Segments are numbered in
+    stream order.  mask[w*K + s] bit b: row 64w+b has entries in stripe s; pbase[w*K + s]: number of
+    the first segment of stripe s at or after row 64w."""
+    rows = np.asarray(rows, dtype=np.int32)
+    n = rows.size
+    if n == 0:
+        return {}
+    ident = n == nrows_total and np.array_equal(rows, np.arange(nrows_total))
+    W = -(-ncols // K)
+    W = max(WAVE, -(-W // WAVE) * WAVE)
+    tsz = WAVE * R
+    nw = -(-n // WAVE)
+    mask = np.zeros(K * nw, dtype=np.uint64)
+    pbase = np.zeros(K * nw, dtype=np.int32)
+    cols, vals, marks, xbase = [], [], [], []
+    ntiles = nsegs = 0
+    for k in range(8):
+        xbase.append(ntiles)
+        for s in range(k, K, 8):
+            sc, sv, sm = [], [], []
+            q = nsegs
+            for i, r in enumerate(rows):
+                if i % WAVE == 0:
+                    pbase[(i // WAVE) * K + s] = q
+                e = _row_entries(rp, r)
+                m = (ci[e] // W) == s
+                L = int(m.sum())
+                if L:
+                    sc.append(ci[e][m]); sv.append(va[e][m])
+                    sm.append(np.concatenate([[1], np.zeros(L - 1, dtype=np.int64)]))
+                    mask[(i // WAVE) * K + s] |= np.uint64(1) << np.uint64(i % WAVE)
+                    q += 1
+            nsegs = q
+            if not sc:
+                continue
+            sc, sv, sm = np.concatenate(sc), np.concatenate(sv), np.concatenate(sm)
+            pad = -sc.size % tsz
+            cols.append(np.concatenate([sc, np.full(pad, min(s * W, ncols - 1), dtype=np.int32)]))
+            vals.append(np.concatenate([sv, np.zeros(pad, dtype=va.dtype)]))
+            marks.append(np.concatenate([sm, np.zeros(pad, dtype=np.int64)]))
+            ntiles += (sc.size + pad) // tsz
+    xbase.append(ntiles)
+    if ntiles:
+        cols, vals, marks = np.concatenate(cols), np.concatenate(vals), np.concatenate(marks)
+    else:
+        cols, vals, marks = np.zeros(0, np.int32), np.zeros(0, va.dtype), np.zeros(0, np.int64)
+    g = np.arange(ntiles * tsz)
+    dst = (g // tsz) * tsz + ((g % tsz) % R) * WAVE + (g % tsz) // R
+    tc = np.zeros(ntiles * tsz, dtype=np.int32); tv = np.zeros(ntiles * tsz, dtype=va.dtype)
+    tc[dst] = cols; tv[dst] = vals
+    bits = np.zeros(ntiles * WAVE, dtype=np.uint8 if R <= 8 else np.uint16)
+    pos = np.flatnonzero(marks)
+    np.bitwise_or.at(bits, (pos // tsz) * WAVE + (pos % tsz) // R, (1 << ((pos % tsz) % R)).astype(bits.dtype))
+    tile_row = np.zeros(ntiles + 1, dtype=np.int32)
+    np.cumsum(np.bincount(pos // tsz, minlength=ntiles), out=tile_row[1:])
+    out = {"xnb.cols": tc, "xnb.vals": tv.astype(va.dtype), "xnb.bits": bits, "xnb.tile_row": tile_row,
+           "xnb.xbase": np.array(xbase, dtype=np.int64), "xnb.mask": mask, "xnb.pbase": pbase}
+    opens = set()
+    for t in range(ntiles):
+        if not marks[t * tsz]:
+            opens.add(int(tile_row[t]) - 1)
+        opens.add(int(tile_row[t + 1]) - 1)
+    if opens:
+        out["xnb.open_slots"] = np.array(sorted(opens), dtype=np.int32)
+    if not ident:
+        out["xnb.rows"] = rows
+    return out
+
+
 def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
     """All format arrays of the plan `spec` for a CSR matrix with ascending columns in each row."""
     p = parse_spec(spec)
@@ -371,6 +444,8 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
         out.update(ref_sell(rp, ci, va, light, p["sigma"], nrows, "sell"))
     elif p["light"] == "nnzb":
         out.update(ref_nnzb(rp, ci, va, light, p["r"], acc, zero_rows))
+    elif p["light"] == "xnb":
+        out.update(ref_xnb(ncols, rp, ci, va, light, p["k"], p["r"], nrows))
     elif p["light"] == "xs":
         out.update(ref_xs(ncols, rp, ci, va, light, p["k"], p["sigma"], nrows))
     elif p["light"] == "bin":
@@ -396,6 +471,32 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
     for pre in prefixes:
         a = {k.rsplit(".", 1)[1]: v for k, v in arrays.items() if k.rsplit(".", 1)[0] == pre}
         if pre == "zero":
+            continue
+        if pre == "xnb":
+            cc, vv, bb, mk, pb = a["cols"], a["vals"], a["bits"], a["mask"], a["pbase"]
+            if cc.size == 0:
+                continue
+            R_ = cc.size // bb.size
+            tsz = WAVE * R_
+            nseg = int(a["tile_row"][-1])
+            seg_row = np.full(nseg, -1, dtype=np.int64)     # segment number -> part position
+            # table index: idx = w*K + s  ->  w = idx // K
+            nrows_part = len(a["rows"]) if "rows" in a else nrows
+            nw = -(-nrows_part // WAVE)
+            for idx in range(mk.size):
+                m, q, w = int(mk[idx]), int(pb[idx]), idx // (mk.size // nw)
+                b = 0
+                while m:
+                    if m & 1:
+                        seg_row[q] = w * WAVE + b; q += 1
+                    m >>= 1; b += 1
+            assert np.all(seg_row >= 0)
+            rws = a.get("rows", np.arange(nrows_part))
+            g = np.arange(cc.size)
+            src = (g // tsz) * tsz + ((g % tsz) % R_) * WAVE + (g % tsz) // R_
+            mark = ((bb[(g // tsz) * WAVE + (g % tsz) // R_].astype(np.int64) >> ((g % tsz) % R_)) & 1).astype(np.int64)
+            segidx = np.cumsum(mark) - 1
+            R.append(np.asarray(rws)[seg_row[segidx]].astype(np.int64)); C.append(cc[src]); V.append(vv[src])
             continue
         if pre == "nnzb":
             cc, vv, bb, rws = a["cols"], a["vals"], a["bits"], a["rows"]

@@ -189,6 +189,8 @@ def spmv_plan_array_copy(plan: int, i: int, value_dtype=np.float64) -> np.ndarra
     name, eb, cnt = spmv_plan_array_info(plan, i)
     if name.endswith("vals"):
         dt = np.dtype(value_dtype)
+    elif name.endswith("mask"):
+        dt = np.dtype(np.uint64)
     else:
         dt = {1: np.dtype(np.uint8), 2: np.dtype(np.uint16), 4: np.dtype(np.int32), 8: np.dtype(np.int64)}[eb]
     assert dt.itemsize == eb, (name, dt, eb)

@@ -682,6 +682,211 @@ void build_nnzb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows_i
     add_part(plan, p, a0, std::min<int64_t>(A.ncols, total), 0, n);
 }
 
+// ---- XCD-striped nnz-balanced tiles ------------------------------------------------------------------
+// COL_DIV into K stripes of W columns as for the striped SELL.  The (row, stripe) segments of a
+// stripe follow each other in part order as one stream, cut into tiles of 64*R entries (transposed
+// as in build_nnzb); a stripe's stream is padded to a whole tile with (value 0, the stripe's first
+// column).  Streams are laid out XCD by XCD.  Segments are numbered in stream order; segment q sums
+// into scratch[q].  For the reduce launch, mask[w*K + s] has bit b set when row 64w+b of the part has
+// entries in stripe s, and pbase[w*K + s] is the number of the first such segment.
+template <typename T>
+void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, int K, int R, bool acc,
+               const std::vector<int64_t> &lens, int threads) {
+    const int64_t n = (int64_t)rows.size();
+    if (n == 0) return;
+    const bool ident = is_identity(rows, A.nrows);
+    int64_t W = (A.ncols + K - 1) / K;
+    W = std::max<int64_t>(kWave, (W + kWave - 1) / kWave * kWave);
+    const int64_t tsz = (int64_t)kWave * R;
+    const int64_t nw = (n + kWave - 1) / kWave;
+    const int64_t chunk = 1 << 16;                    // rows per work item, a multiple of 64
+    const int64_t nchunks = (n + chunk - 1) / chunk;
+    int64_t real = 0;
+    for (int32_t r : rows) real += lens[(size_t)r];
+    // pass A: entries and segments per (chunk, stripe)
+    std::vector<int64_t> cnt_e((size_t)(nchunks * K), 0), cnt_q((size_t)(nchunks * K), 0);
+    parallel_for(nchunks, 1, threads, [&](int64_t cb, int64_t ce, int) {
+        for (int64_t c = cb; c < ce; ++c)
+            for (int64_t i = c * chunk; i < std::min(n, (c + 1) * chunk); ++i) {
+                const int32_t r = rows[(size_t)i];
+                int64_t prev = -1;
+                for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
+                    const int64_t s = A.col[k] / W;
+                    cnt_e[(size_t)(c * K + s)] += 1;
+                    if (s != prev) cnt_q[(size_t)(c * K + s)] += 1;
+                    prev = s;
+                }
+            }
+    });
+    // stream layout: XCD k owns stripes k, k+8, ...; every stripe starts on a tile boundary
+    std::vector<int64_t> stream_base((size_t)K, 0), seg_base((size_t)K, 0), stripe_len((size_t)K, 0), xbase(9, 0);
+    int64_t ntiles = 0, nsegs = 0;
+    for (int k = 0; k < 8; ++k) {
+        xbase[(size_t)k] = ntiles;
+        for (int s = k; s < K; s += 8) {
+            int64_t le = 0, lq = 0;
+            for (int64_t c = 0; c < nchunks; ++c) {
+                le += cnt_e[(size_t)(c * K + s)];
+                lq += cnt_q[(size_t)(c * K + s)];
+            }
+            stream_base[(size_t)s] = ntiles * tsz;
+            seg_base[(size_t)s] = nsegs;
+            stripe_len[(size_t)s] = le;
+            ntiles += (le + tsz - 1) / tsz;
+            nsegs += lq;
+        }
+    }
+    xbase[8] = ntiles;
+    if (ntiles * tsz >= ((int64_t)1 << 31) || nsegs >= ((int64_t)1 << 31))
+        fail(SPMV_ERR_UNSUPPORTED, "xnb: too many entries");
+    // turn the per-chunk counts into starting positions
+    for (int s = 0; s < K; ++s) {
+        int64_t e = stream_base[(size_t)s], q = seg_base[(size_t)s];
+        for (int64_t c = 0; c < nchunks; ++c) {
+            const int64_t de = cnt_e[(size_t)(c * K + s)], dq = cnt_q[(size_t)(c * K + s)];
+            cnt_e[(size_t)(c * K + s)] = e;
+            cnt_q[(size_t)(c * K + s)] = q;
+            e += de;
+            q += dq;
+        }
+    }
+    HostBuf<int32_t> cols(ntiles * tsz);
+    HostBuf<T> vals(ntiles * tsz);
+    HostBuf<uint8_t> mark(ntiles * tsz);
+    std::memset(mark.p, 0, (size_t)(ntiles * tsz));
+    std::vector<uint64_t> mask((size_t)(K * nw), 0);
+    std::vector<int32_t> pbase((size_t)(K * nw), 0);
+    const T *av = (const T *)A.val;
+    auto transposed = [&](int64_t g) {
+        const int64_t tile = g / tsz, in = g % tsz;
+        return tile * tsz + (in % R) * kWave + in / R;
+    };
+    // pass B: place the entries, mark the segment starts, fill the reduce tables
+    parallel_for(nchunks, 1, threads, [&](int64_t cb, int64_t ce, int) {
+        std::vector<int64_t> run_e((size_t)K), run_q((size_t)K);
+        for (int64_t c = cb; c < ce; ++c) {
+            for (int s = 0; s < K; ++s) {
+                run_e[(size_t)s] = cnt_e[(size_t)(c * K + s)];
+                run_q[(size_t)s] = cnt_q[(size_t)(c * K + s)];
+            }
+            for (int64_t i = c * chunk; i < std::min(n, (c + 1) * chunk); ++i) {
+                if ((i & 63) == 0)
+                    for (int s = 0; s < K; ++s) pbase[(size_t)((i >> 6) * K + s)] = (int32_t)run_q[(size_t)s];
+                const int32_t r = rows[(size_t)i];
+                int64_t prev = -1;
+                for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
+                    const int64_t s = A.col[k] / W;
+                    const int64_t g = run_e[(size_t)s]++;
+                    const int64_t dst = transposed(g);
+                    cols[dst] = A.col[k];
+                    vals[dst] = av[k];
+                    if (s != prev) {
+                        mark[g] = 1;
+                        mask[(size_t)((i >> 6) * K + s)] |= 1ull << (i & 63);
+                        run_q[(size_t)s] += 1;
+                    }
+                    prev = s;
+                }
+            }
+        }
+    });
+    for (int s = 0; s < K; ++s) {   // pad every stripe's last tile
+        const int64_t b = stream_base[(size_t)s] + stripe_len[(size_t)s];
+        const int64_t e = stream_base[(size_t)s] + (stripe_len[(size_t)s] + tsz - 1) / tsz * tsz;
+        const int32_t padc = (int32_t)std::min<int64_t>((int64_t)s * W, A.ncols - 1);
+        for (int64_t g = b; g < e; ++g) {
+            cols[transposed(g)] = padc < 0 ? 0 : padc;
+            vals[transposed(g)] = T(0);
+        }
+    }
+    // lane bitmaps, segment starts per tile, scratch slots open at a tile border
+    std::vector<uint16_t> bits((size_t)(ntiles * kWave), 0);
+    std::vector<int32_t> tile_row((size_t)ntiles + 1, 0);
+    parallel_for(ntiles, 256, threads, [&](int64_t tb, int64_t te, int) {
+        for (int64_t t = tb; t < te; ++t) {
+            int32_t cnt = 0;
+            for (int lane = 0; lane < kWave; ++lane) {
+                uint16_t bm = 0;
+                for (int q = 0; q < R; ++q)
+                    if (mark[t * tsz + (int64_t)lane * R + q]) bm |= (uint16_t)(1u << q);
+                bits[(size_t)(t * kWave + lane)] = bm;
+                cnt += __builtin_popcount(bm);
+            }
+            tile_row[(size_t)t + 1] = cnt;
+        }
+    });
+    for (int64_t t = 0; t < ntiles; ++t) tile_row[(size_t)t + 1] += tile_row[(size_t)t];
+    std::vector<int32_t> open_slots;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        if (!mark[t * tsz]) open_slots.push_back(tile_row[(size_t)t] - 1);
+        open_slots.push_back(tile_row[(size_t)t + 1] - 1);
+    }
+    std::sort(open_slots.begin(), open_slots.end());
+    open_slots.erase(std::unique(open_slots.begin(), open_slots.end()), open_slots.end());
+
+    void *scratch = plan.mem.alloc((size_t)std::max<int64_t>(nsegs, 1) * sizeof(T), plan.mem.user);
+    if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the striped part's scratch failed");
+    {
+        DevArray a;
+        a.name = "xnb.scratch";
+        a.ptr = scratch;
+        a.elem_bytes = (int)sizeof(T);
+        a.count = nsegs;
+        plan.scratch.push_back(a);
+    }
+    if (!open_slots.empty()) {
+        Part z;
+        z.kind = K_ZERO_SCRATCH;
+        z.name = "xnb.zero";
+        z.nrows = (int64_t)open_slots.size();
+        z.units = z.nrows;
+        z.scratch = scratch;
+        const size_t a0 = plan.arrays.size();
+        z.p0 = upload(plan, "xnb.open_slots", 4, z.nrows, open_slots.data());
+        add_part(plan, z, a0, 0, z.nrows, 0);
+    }
+    int64_t per_xcd = 0;
+    for (int k = 0; k < 8; ++k) per_xcd = std::max(per_xcd, xbase[(size_t)k + 1] - xbase[(size_t)k]);
+    Part p;
+    p.kind = K_XNB;
+    p.name = "xnb";
+    p.nrows = n;
+    p.nnz = real;
+    p.stored = ntiles * tsz;
+    p.units = ntiles;
+    p.ngroups = (per_xcd + 3) / 4;
+    p.lanes = R;
+    p.scratch = scratch;
+    p.has_rows = !ident;
+    const size_t a1 = plan.arrays.size();
+    p.p0 = upload(plan, "xnb.cols", 4, ntiles * tsz, cols.p);
+    p.p1 = upload(plan, "xnb.vals", (int)sizeof(T), ntiles * tsz, vals.p);
+    if (R <= 8) {
+        std::vector<uint8_t> b8(bits.begin(), bits.end());
+        p.p2 = upload(plan, "xnb.bits", 1, ntiles * kWave, b8.data());
+    } else {
+        p.p2 = upload(plan, "xnb.bits", 2, ntiles * kWave, bits.data());
+    }
+    p.p3 = upload(plan, "xnb.tile_row", 4, ntiles + 1, tile_row.data());
+    p.p4 = upload(plan, "xnb.xbase", 8, 9, xbase.data());
+    add_part(plan, p, a1, std::min<int64_t>(A.ncols, real), nsegs, 0);
+    Part r;
+    r.kind = K_REDUCE_BITMAP;
+    r.name = "xnb.reduce";
+    r.nrows = n;
+    r.units = n;
+    r.nslices = nw;
+    r.lanes = K;
+    r.scratch = scratch;
+    r.accumulate = acc;
+    r.has_rows = !ident;
+    const size_t a2 = plan.arrays.size();
+    r.p0 = upload(plan, "xnb.mask", 8, K * nw, mask.data());
+    r.p1 = upload(plan, "xnb.pbase", 4, K * nw, pbase.data());
+    if (!ident) r.p3 = upload(plan, "xnb.rows", 4, n, rows.data());
+    add_part(plan, r, a2, 0, nsegs, n);
+}
+
 // ---- XCD-striped SELL ----------------------------------------------------------------------------
 // COL_DIV into K stripes of W = ceil(ncols / K) columns (rounded up to 64).  Per stripe: the rows
 // of the part that have entries in it, in windows of sigma part positions, sorted by that count
@@ -960,6 +1165,9 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         break;
     case L_NNZB:
         build_nnzb<T>(*plan, A, light, spec.r, acc, lens, zero_rows, threads);
+        break;
+    case L_XNB:
+        build_xnb<T>(*plan, A, light, spec.k, spec.r, acc, lens, threads);
         break;
     case L_BIN: {
         // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront per

@@ -277,17 +277,17 @@ __global__ __launch_bounds__(kWG) void k_csrv(const int32_t *__restrict__ seg_pt
 // is added atomically (GMEM_ATOM_RED) to y elements zeroed by an earlier launch.
 // tile_row[i] = number of row starts before tile i = index (into rows[]) of the first row that
 // starts in it.
-template <typename T, int R, typename BM, bool ACC>
-__global__ __launch_bounds__(kWG) void k_nnzb(const int32_t *__restrict__ cols,
-                                              const T *__restrict__ vals,
-                                              const BM *__restrict__ bits,
-                                              const int32_t *__restrict__ tile_row,
-                                              const int32_t *__restrict__ rows,
-                                              const T *__restrict__ x, T *__restrict__ y,
-                                              int64_t ntiles) {
-    const int64_t tile = (int64_t)blockIdx.x * (kWG / kWave) + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (tile >= ntiles) return;
+// One tile of the nnz-balanced stream.  ROWS: row r of the stream is y element rows[r]; otherwise
+// the stream's rows are consecutive elements of `y` (the scratch slots of a striped part).
+// STAGE (only with !ROWS): the sums of the rows that start and end inside the tile are consecutive
+// elements of `y`; they are collected in the wavefront's LDS buffer `stage` and written out as
+// contiguous runs instead of one scattered 8-byte store each.
+template <typename T, int R, typename BM, bool ACC, bool ROWS, bool STAGE>
+__device__ __forceinline__ void nnzb_tile(int64_t tile, int lane, const int32_t *__restrict__ cols,
+                                          const T *__restrict__ vals, const BM *__restrict__ bits,
+                                          const int32_t *__restrict__ tile_row,
+                                          const int32_t *__restrict__ rows,
+                                          const T *__restrict__ x, T *__restrict__ y, T *stage) {
     const int64_t base = tile * 64 * R + lane;
     int32_t c[R];
     T v[R], xv[R];
@@ -307,7 +307,9 @@ __global__ __launch_bounds__(kWG) void k_nnzb(const int32_t *__restrict__ cols,
         const int up = __shfl_up(pre, o, kWave);
         if (lane >= o) pre += up;
     }
-    int32_t row = tile_row[tile] + (pre - nstart);   // row of the lane's first mark
+    const int32_t tile_first = tile_row[tile];
+    const int32_t first_row = tile_first + (pre - nstart);   // row of the lane's first mark
+    int32_t row = first_row;
     // serial pass over the lane's entries
     T acc = T(0), head = T(0);
     bool seen = false;
@@ -315,8 +317,12 @@ __global__ __launch_bounds__(kWG) void k_nnzb(const int32_t *__restrict__ cols,
     for (int t = 0; t < R; ++t) {
         if ((bm >> t) & 1u) {
             if (seen) {
-                const int32_t r = rows[row];   // a row that starts and ends inside this lane
-                y[r] = ACC ? y[r] + acc : acc;
+                if (STAGE) {
+                    stage[row - tile_first] = acc;   // a row inside this lane
+                } else {
+                    const int64_t r = ROWS ? (int64_t)rows[row] : (int64_t)row;
+                    y[r] = ACC ? y[r] + acc : acc;
+                }
                 ++row;
             } else {
                 head = acc;           // belongs to a row that started earlier
@@ -326,8 +332,8 @@ __global__ __launch_bounds__(kWG) void k_nnzb(const int32_t *__restrict__ cols,
         }
         acc += v[t] * xv[t];
     }
-    // now: seen ? (head = sum before the first mark, acc = sum after the last mark, `row` = row of
-    // the last mark) : (acc = sum of the whole lane, which lies inside one open row)
+    // now: seen ? (head = sum before the first mark, acc = sum after the last mark) : (acc = sum of
+    // the whole lane, which lies inside one open row)
     // segmented scan: carry entering lane k = seen_{k-1} ? tail_{k-1} : carry_{k-1} + all_{k-1}
     T val = acc;
     int flag = seen ? 1 : 0;
@@ -349,19 +355,109 @@ __global__ __launch_bounds__(kWG) void k_nnzb(const int32_t *__restrict__ cols,
     }
     if (seen) {
         // close the row that ends at this lane's first mark (unless nothing precedes the mark)
-        const int32_t first_row = tile_row[tile] + (pre - nstart);
         const bool empty = (lane == 0) && (bm & 1u);
         if (!empty) {
             const T total = carry + head;
-            const int32_t r = rows[first_row - 1];
-            if (started) y[r] = ACC ? y[r] + total : total;
-            else atomic_add(y + r, total);
+            const int64_t r = ROWS ? (int64_t)rows[first_row - 1] : (int64_t)(first_row - 1);
+            if (started) {
+                if (STAGE) stage[first_row - 1 - tile_first] = total;
+                else y[r] = ACC ? y[r] + total : total;
+            } else {
+                atomic_add(y + r, total);
+            }
         }
     }
     if (lane == 63) {
         // what is still open at the end of the tile: the row of the last mark at or before it
         const int32_t last_row = tile_row[tile + 1] - 1;
-        atomic_add(y + rows[last_row], val);
+        const int64_t r = ROWS ? (int64_t)rows[last_row] : (int64_t)last_row;
+        atomic_add(y + r, val);
+    }
+    if (STAGE) {
+        // rows tile_first .. tile_row[tile+1]-2 started and ended in this tile; each was staged once
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        const int ndone = tile_row[tile + 1] - 1 - tile_first;
+        for (int j = lane; j < ndone; j += kWave) y[(int64_t)tile_first + j] = stage[j];
+    }
+}
+
+template <typename T, int R, typename BM, bool ACC>
+__global__ __launch_bounds__(kWG) void k_nnzb(const int32_t *__restrict__ cols,
+                                              const T *__restrict__ vals,
+                                              const BM *__restrict__ bits,
+                                              const int32_t *__restrict__ tile_row,
+                                              const int32_t *__restrict__ rows,
+                                              const T *__restrict__ x, T *__restrict__ y,
+                                              int64_t ntiles) {
+    const int64_t tile = (int64_t)blockIdx.x * (kWG / kWave) + (threadIdx.x >> 6);
+    if (tile >= ntiles) return;
+    nnzb_tile<T, R, BM, ACC, true, false>(tile, threadIdx.x & 63, cols, vals, bits, tile_row, rows, x, y, nullptr);
+}
+
+// ---- XCD-striped nnz-balanced tiles -----------------------------------------------------------
+// COL_DIV into K = 8*P stripes as in k_xs (stripe s only on XCD s mod 8, so that the stripe of x
+// stays in that XCD's L2), but inside a stripe the (row, stripe) segments simply follow each other
+// in row order as one nnz-balanced stream (BMT_NNZ_BLOCK + THREAD_BITMAP_RED + WARP_SEG_RED): no
+// sorting, no padding, and the partial sum of segment number q (counted stripe by stripe, in row
+// order) lands in scratch[q].  k_reduce_bitmap then finds the partial sums of a row by arithmetic.
+// Tiles never straddle stripes; the tiles of XCD k are [xbase[k], xbase[k+1]).
+template <typename T, int R, typename BM>
+__global__ __launch_bounds__(kWG) void k_xnb(const int32_t *__restrict__ cols,
+                                             const T *__restrict__ vals,
+                                             const BM *__restrict__ bits,
+                                             const int32_t *__restrict__ tile_row,
+                                             const int64_t *__restrict__ xbase,
+                                             const T *__restrict__ x, T *__restrict__ partial) {
+    __shared__ T stage[kWG / kWave][kWave * R];
+    const int k = blockIdx.x & 7;
+    const int wave = threadIdx.x >> 6;
+    const int64_t tile = xbase[k] + (int64_t)(blockIdx.x >> 3) * (kWG / kWave) + wave;
+    if (tile >= xbase[k + 1]) return;
+    nnzb_tile<T, R, BM, false, false, true>(tile, threadIdx.x & 63, cols, vals, bits, tile_row, nullptr, x,
+                                            partial, stage[wave]);
+}
+
+// y[rows[i]] (+)= sum over the stripes s in which row i has entries of
+// scratch[pbase[w*K + s] + (number of rows below i in its group w = i/64 that have entries in s)].
+// mask[w*K + s] holds one bit per row of group w.  The 64 lanes read consecutive scratch elements.
+template <typename T, bool ROWS, bool ACC>
+__global__ __launch_bounds__(kWG) void k_reduce_bitmap(const uint64_t *__restrict__ mask,
+                                                       const int32_t *__restrict__ pbase,
+                                                       const T *__restrict__ partial,
+                                                       const int32_t *__restrict__ rows,
+                                                       T *__restrict__ y, int64_t n, int K, int64_t nw) {
+    // an XCD reduces a contiguous range of rows: neighbouring row groups share scratch lines
+    const int64_t blk = logical_block(blockIdx.x, gridDim.x, 1);
+    const int64_t w = __builtin_amdgcn_readfirstlane((int)(blk * (kWG / kWave) + (threadIdx.x >> 6)));
+    const int lane = threadIdx.x & 63;
+    if (w >= nw) return;
+    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    // lane q < K fetches the table entries of stripe q (one coalesced load each); they are then
+    // broadcast stripe by stripe, so a row group costs one table round trip plus the gathers
+    uint64_t my_m = 0;
+    int32_t my_pb = 0;
+    if (lane < K) {
+        my_m = mask[w * K + lane];
+        my_pb = pbase[w * K + lane];
+    }
+    T acc = T(0);
+    for (int s0 = 0; s0 < K; s0 += 8) {   // K is a multiple of 8
+        T part[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)my_m, s0 + q);
+            const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(my_m >> 32), s0 + q);
+            const uint64_t m = ((uint64_t)hi << 32) | lo;
+            const int32_t pb = __builtin_amdgcn_readlane(my_pb, s0 + q);
+            part[q] = ((m >> lane) & 1ull) ? partial[pb + __popcll(m & below)] : T(0);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc += part[q];
+    }
+    const int64_t i = w * kWave + lane;
+    if (i < n) {
+        const int64_t r = ROWS ? (int64_t)rows[i] : i;
+        y[r] = ACC ? y[r] + acc : acc;
     }
 }
 
@@ -734,6 +830,38 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         default: return (int)hipErrorInvalidValue;
         }
 #undef NNZB_GO
+        break;
+    }
+    case K_XNB: {
+        if (p.units == 0) return 0;
+#define XNB_GO(RR, BM)                                                                             \
+    k_xnb<T, RR, BM><<<(unsigned)(8 * p.ngroups), kWG, 0, st>>>(                                   \
+        (const int32_t *)p.p0, (const T *)p.p1, (const BM *)p.p2, (const int32_t *)p.p3,           \
+        (const int64_t *)p.p4, x, (T *)p.scratch)
+        switch (p.lanes) {
+        case 4: XNB_GO(4, uint8_t); break;
+        case 8: XNB_GO(8, uint8_t); break;
+        case 16: XNB_GO(16, uint16_t); break;
+        default: return (int)hipErrorInvalidValue;
+        }
+#undef XNB_GO
+        break;
+    }
+    case K_ZERO_SCRATCH: {
+        if (p.nrows == 0) return 0;
+        k_zero_rows<T><<<blocks(p.nrows, kWG), kWG, 0, st>>>((const int32_t *)p.p0, p.nrows, (T *)p.scratch);
+        break;
+    }
+    case K_REDUCE_BITMAP: {
+        if (p.nrows == 0) return 0;
+        const unsigned grid = blocks(p.nslices * kWave, kWG);
+#define RB_GO(Rw, A)                                                                               \
+    k_reduce_bitmap<T, Rw, A><<<grid, kWG, 0, st>>>((const uint64_t *)p.p0, (const int32_t *)p.p1, \
+                                                    (const T *)p.scratch, (const int32_t *)p.p3, y, \
+                                                    p.nrows, p.lanes, p.nslices)
+        if (p.has_rows) { if (p.accumulate) RB_GO(true, true); else RB_GO(true, false); }
+        else            { if (p.accumulate) RB_GO(false, true); else RB_GO(false, false); }
+#undef RB_GO
         break;
     }
     case K_REDUCE_WIDE: {

@@ -120,15 +120,23 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             return p;
         };
         const int64_t th0 = tail_ok(hth) ? hth : (tail_ok(4 * hth) ? 4 * hth : 0);
+        auto xnb_plan = [&](int64_t th, int k, int tl) {
+            PlanSpec p = xs_plan(th, k, tl);
+            p.light = L_XNB;
+            p.sigma = 0;
+            p.r = 16;
+            return p;
+        };
         if (striping) {
             // the stripe of x an XCD gathers from should be about half its 4 MB L2 or less
             const int k1 = 2 * k0 <= 32 ? 2 * k0 : k0;
+            push(xnb_plan(th0, k1, tile / 2));
+            if (k1 != k0) push(xnb_plan(th0, k0, tile / 2));
+            if (2 * k1 <= 32) push(xnb_plan(th0, 2 * k1, tile / 2));
+            push(xnb_plan(th0, k1, tile));
+            if (th0 && tail_ok(2 * th0)) push(xnb_plan(2 * th0, k1, tile / 2));
+            if (th0 && tail_ok(4 * th0)) push(xnb_plan(4 * th0, k1, tile / 2));
             push(xs_plan(th0, k1, tile / 2));
-            push(xs_plan(th0, k1, tile));
-            if (k1 != k0) push(xs_plan(th0, k0, tile / 2));
-            if (th0 && tail_ok(2 * th0)) push(xs_plan(2 * th0, k1, tile / 2));
-            if (th0 && tail_ok(4 * th0)) push(xs_plan(4 * th0, k1, tile / 2));
-            if (2 * k1 <= 32) push(xs_plan(th0, 2 * k1, tile / 2));
         }
         push(bin_plan(th0));
         {   // nnz-balanced segmented tiles for everything but the heavy tail

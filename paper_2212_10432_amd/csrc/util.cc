@@ -67,6 +67,7 @@ static const char *light_name(int l) {
     case L_BIN: return "bin";
     case L_XS: return "xs";
     case L_NNZB: return "nnzb";
+    case L_XNB: return "xnb";
     }
     return "?";
 }
@@ -95,6 +96,7 @@ PlanSpec parse_spec(const std::string &s) {
             else if (v == "bin") p.light = L_BIN;
             else if (v == "xs") p.light = L_XS;
             else if (v == "nnzb") p.light = L_NNZB;
+            else if (v == "xnb") p.light = L_XNB;
             else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown light design " + v);
         } else if (k == "dia") p.dia = (int)num();
         else if (k == "dia_fill") p.dia_fill = num();
@@ -141,6 +143,7 @@ std::string print_spec(const PlanSpec &p) {
     case L_BIN: o << ",smax=" << p.smax << ",sigma=" << p.sigma << ",chunk=" << p.chunk; break;
     case L_XS: o << ",k=" << p.k << ",sigma=" << p.sigma; break;
     case L_NNZB: o << ",r=" << p.r; break;
+    case L_XNB: o << ",k=" << p.k << ",r=" << p.r; break;
     }
     o << ",remap=" << p.remap;
     return o.str();
@@ -181,6 +184,10 @@ std::string operator_chain(const PlanSpec &p) {
     case L_NNZB:
         o << " -> BMW_NNZ_BLOCK(" << 64 * p.r << ") -> BMT_NNZ_BLOCK(" << p.r
           << ") -> THREAD_BITMAP_RED -> WARP_SEG_RED -> GMEM_ATOM_RED(tile borders)";
+        break;
+    case L_XNB:
+        o << " -> COL_DIV(" << p.k << " stripes, stripe s on XCD s mod 8) -> BMW_NNZ_BLOCK(" << 64 * p.r
+          << ") -> BMT_NNZ_BLOCK(" << p.r << ") -> THREAD_BITMAP_RED -> WARP_SEG_RED -> SCRATCH_ROW_RED(bitmap)";
         break;
     case L_XS:
         o << " -> COL_DIV(" << p.k << " stripes, stripe s on XCD s mod 8)";
