@@ -345,8 +345,8 @@ def ref_xnb(ncols, rp, ci, va, rows, K, R, nrows_total):
     owning stripes k, k+8, ...; the streams are laid out XCD by XCD.  Inside a stripe the (row, stripe)
     segments follow each other in part order; the stream is padded to whole tiles of 64*R entries with
     (value 0, first column of the stripe) and stored transposed per tile.  Segments are numbered in
-    stream order.  mask[w*K + s] bit b: row 64w+b has entries in stripe s; pbase[w*K + s]: number of
-    the first segment of stripe s at or after row 64w."""
+    stream order.  seg_row[q]: part position of segment q's row modulo 1024; bbase[b*K + s]: number of
+    the first segment of stripe s at or after part position 1024*b (row nblk: end of the stripe)."""
     rows = np.asarray(rows, dtype=np.int32)
     n = rows.size
     if n == 0:
@@ -355,9 +355,10 @@ def ref_xnb(ncols, rp, ci, va, rows, K, R, nrows_total):
     W = -(-ncols // K)
     W = max(WAVE, -(-W // WAVE) * WAVE)
     tsz = WAVE * R
-    nw = -(-n // WAVE)
-    mask = np.zeros(K * nw, dtype=np.uint64)
-    pbase = np.zeros(K * nw, dtype=np.int32)
+    BLK = 1024
+    nblk = -(-n // BLK)
+    bbase = np.zeros((nblk + 1) * K, dtype=np.int32)
+    seg_row = []
     cols, vals, marks, xbase = [], [], [], []
     ntiles = nsegs = 0
     for k in range(8):
@@ -366,16 +367,17 @@ def ref_xnb(ncols, rp, ci, va, rows, K, R, nrows_total):
             sc, sv, sm = [], [], []
             q = nsegs
             for i, r in enumerate(rows):
-                if i % WAVE == 0:
-                    pbase[(i // WAVE) * K + s] = q
+                if i % BLK == 0:
+                    bbase[(i // BLK) * K + s] = q
                 e = _row_entries(rp, r)
                 m = (ci[e] // W) == s
                 L = int(m.sum())
                 if L:
                     sc.append(ci[e][m]); sv.append(va[e][m])
                     sm.append(np.concatenate([[1], np.zeros(L - 1, dtype=np.int64)]))
-                    mask[(i // WAVE) * K + s] |= np.uint64(1) << np.uint64(i % WAVE)
+                    seg_row.append(i % BLK)
                     q += 1
+            bbase[nblk * K + s] = q
             nsegs = q
             if not sc:
                 continue
@@ -400,7 +402,8 @@ def ref_xnb(ncols, rp, ci, va, rows, K, R, nrows_total):
     tile_row = np.zeros(ntiles + 1, dtype=np.int32)
     np.cumsum(np.bincount(pos // tsz, minlength=ntiles), out=tile_row[1:])
     out = {"xnb.cols": tc, "xnb.vals": tv.astype(va.dtype), "xnb.bits": bits, "xnb.tile_row": tile_row,
-           "xnb.xbase": np.array(xbase, dtype=np.int64), "xnb.mask": mask, "xnb.pbase": pbase}
+           "xnb.xbase": np.array(xbase, dtype=np.int64), "xnb.seg_row": np.array(seg_row, dtype=np.uint16),
+           "xnb.bbase": bbase}
     opens = set()
     for t in range(ntiles):
         if not marks[t * tsz]:
@@ -473,23 +476,20 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
         if pre == "zero":
             continue
         if pre == "xnb":
-            cc, vv, bb, mk, pb = a["cols"], a["vals"], a["bits"], a["mask"], a["pbase"]
+            cc, vv, bb, sr, bbs = a["cols"], a["vals"], a["bits"], a["seg_row"], a["bbase"]
             if cc.size == 0:
                 continue
             R_ = cc.size // bb.size
             tsz = WAVE * R_
             nseg = int(a["tile_row"][-1])
-            seg_row = np.full(nseg, -1, dtype=np.int64)     # segment number -> part position
-            # table index: idx = w*K + s  ->  w = idx // K
             nrows_part = len(a["rows"]) if "rows" in a else nrows
-            nw = -(-nrows_part // WAVE)
-            for idx in range(mk.size):
-                m, q, w = int(mk[idx]), int(pb[idx]), idx // (mk.size // nw)
-                b = 0
-                while m:
-                    if m & 1:
-                        seg_row[q] = w * WAVE + b; q += 1
-                    m >>= 1; b += 1
+            nblk = -(-nrows_part // 1024)
+            K_ = bbs.size // (nblk + 1)
+            seg_row = np.full(nseg, -1, dtype=np.int64)     # segment number -> part position
+            for blk in range(nblk):
+                for s_ in range(K_):
+                    q0, q1 = int(bbs[blk * K_ + s_]), int(bbs[(blk + 1) * K_ + s_])
+                    seg_row[q0:q1] = blk * 1024 + sr[q0:q1].astype(np.int64)
             assert np.all(seg_row >= 0)
             rws = a.get("rows", np.arange(nrows_part))
             g = np.arange(cc.size)

@@ -698,8 +698,7 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
     int64_t W = (A.ncols + K - 1) / K;
     W = std::max<int64_t>(kWave, (W + kWave - 1) / kWave * kWave);
     const int64_t tsz = (int64_t)kWave * R;
-    const int64_t nw = (n + kWave - 1) / kWave;
-    const int64_t chunk = 1 << 16;                    // rows per work item, a multiple of 64
+    const int64_t chunk = 1 << 16;                    // rows per work item, a multiple of 1024
     const int64_t nchunks = (n + chunk - 1) / chunk;
     int64_t real = 0;
     for (int32_t r : rows) real += lens[(size_t)r];
@@ -719,7 +718,7 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
             }
     });
     // stream layout: XCD k owns stripes k, k+8, ...; every stripe starts on a tile boundary
-    std::vector<int64_t> stream_base((size_t)K, 0), seg_base((size_t)K, 0), stripe_len((size_t)K, 0), xbase(9, 0);
+    std::vector<int64_t> stream_base((size_t)K, 0), seg_base((size_t)K, 0), seg_cnt((size_t)K, 0), stripe_len((size_t)K, 0), xbase(9, 0);
     int64_t ntiles = 0, nsegs = 0;
     for (int k = 0; k < 8; ++k) {
         xbase[(size_t)k] = ntiles;
@@ -732,6 +731,7 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
             stream_base[(size_t)s] = ntiles * tsz;
             seg_base[(size_t)s] = nsegs;
             stripe_len[(size_t)s] = le;
+            seg_cnt[(size_t)s] = lq;
             ntiles += (le + tsz - 1) / tsz;
             nsegs += lq;
         }
@@ -754,8 +754,9 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
     HostBuf<T> vals(ntiles * tsz);
     HostBuf<uint8_t> mark(ntiles * tsz);
     std::memset(mark.p, 0, (size_t)(ntiles * tsz));
-    std::vector<uint64_t> mask((size_t)(K * nw), 0);
-    std::vector<int32_t> pbase((size_t)(K * nw), 0);
+    const int64_t nblk = (n + kReduceBlockRows - 1) / kReduceBlockRows;
+    std::vector<uint16_t> seg_row((size_t)std::max<int64_t>(nsegs, 1), 0);
+    std::vector<int32_t> bbase((size_t)((nblk + 1) * K), 0);
     const T *av = (const T *)A.val;
     auto transposed = [&](int64_t g) {
         const int64_t tile = g / tsz, in = g % tsz;
@@ -770,8 +771,9 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
                 run_q[(size_t)s] = cnt_q[(size_t)(c * K + s)];
             }
             for (int64_t i = c * chunk; i < std::min(n, (c + 1) * chunk); ++i) {
-                if ((i & 63) == 0)
-                    for (int s = 0; s < K; ++s) pbase[(size_t)((i >> 6) * K + s)] = (int32_t)run_q[(size_t)s];
+                if (i % kReduceBlockRows == 0)
+                    for (int s = 0; s < K; ++s)
+                        bbase[(size_t)((i / kReduceBlockRows) * K + s)] = (int32_t)run_q[(size_t)s];
                 const int32_t r = rows[(size_t)i];
                 int64_t prev = -1;
                 for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
@@ -782,7 +784,7 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
                     vals[dst] = av[k];
                     if (s != prev) {
                         mark[g] = 1;
-                        mask[(size_t)((i >> 6) * K + s)] |= 1ull << (i & 63);
+                        seg_row[(size_t)run_q[(size_t)s]] = (uint16_t)(i % kReduceBlockRows);
                         run_q[(size_t)s] += 1;
                     }
                     prev = s;
@@ -790,6 +792,8 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
             }
         }
     });
+    for (int s = 0; s < K; ++s)   // end of every stripe's segments
+        bbase[(size_t)(nblk * K + s)] = (int32_t)(seg_base[(size_t)s] + seg_cnt[(size_t)s]);
     for (int s = 0; s < K; ++s) {   // pad every stripe's last tile
         const int64_t b = stream_base[(size_t)s] + stripe_len[(size_t)s];
         const int64_t e = stream_base[(size_t)s] + (stripe_len[(size_t)s] + tsz - 1) / tsz * tsz;
@@ -871,18 +875,17 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
     p.p4 = upload(plan, "xnb.xbase", 8, 9, xbase.data());
     add_part(plan, p, a1, std::min<int64_t>(A.ncols, real), nsegs, 0);
     Part r;
-    r.kind = K_REDUCE_BITMAP;
+    r.kind = K_REDUCE_LDS;
     r.name = "xnb.reduce";
     r.nrows = n;
     r.units = n;
-    r.nslices = nw;
     r.lanes = K;
     r.scratch = scratch;
     r.accumulate = acc;
     r.has_rows = !ident;
     const size_t a2 = plan.arrays.size();
-    r.p0 = upload(plan, "xnb.mask", 8, K * nw, mask.data());
-    r.p1 = upload(plan, "xnb.pbase", 4, K * nw, pbase.data());
+    r.p0 = upload(plan, "xnb.seg_row", 2, nsegs, seg_row.data());
+    r.p1 = upload(plan, "xnb.bbase", 4, (nblk + 1) * K, bbase.data());
     if (!ident) r.p3 = upload(plan, "xnb.rows", 4, n, rows.data());
     add_part(plan, r, a2, 0, nsegs, n);
 }

@@ -21,6 +21,8 @@ constexpr int kWave = 64;
 // Blocked SELL with an LDS x window: slices per workgroup, and the LDS budget of a window.
 constexpr int kXwinGroup = 32;
 constexpr int64_t kXwinMaxBytes = 160 * 1024;
+// Rows per workgroup of the striped parts' reduce launch (their sums live in LDS).
+constexpr int kReduceBlockRows = 1024;
 
 struct Error {
     spmv_status_t code;
@@ -103,7 +105,7 @@ struct DevArray {
     bool read_per_run = true;    // counts towards the algorithmic bytes of one run
 };
 
-enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_BITMAP };
+enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS };
 
 // One kernel launch of spmv_run.  Pointers refer to entries of Plan::arrays.
 struct Part {

@@ -417,47 +417,53 @@ __global__ __launch_bounds__(kWG) void k_xnb(const int32_t *__restrict__ cols,
                                             partial, stage[wave]);
 }
 
-// y[rows[i]] (+)= sum over the stripes s in which row i has entries of
-// scratch[pbase[w*K + s] + (number of rows below i in its group w = i/64 that have entries in s)].
-// mask[w*K + s] holds one bit per row of group w.  The 64 lanes read consecutive scratch elements.
+// Row reduce of the striped nnz-balanced part.  A workgroup owns kRedRows consecutive rows of the
+// part.  In every stripe the segments of those rows are consecutive scratch slots
+// [bbase[blk*K + s], bbase[(blk+1)*K + s]); seg_row[q] is the row (within the block) segment q
+// belongs to.  The slots are read with contiguous loads and added into one LDS accumulator per row
+// (SHMEM_OFFSET_RED: a shared-memory reduction by row offset); then y is written contiguously.
+constexpr int kRedRows = 1024;
 template <typename T, bool ROWS, bool ACC>
-__global__ __launch_bounds__(kWG) void k_reduce_bitmap(const uint64_t *__restrict__ mask,
-                                                       const int32_t *__restrict__ pbase,
-                                                       const T *__restrict__ partial,
-                                                       const int32_t *__restrict__ rows,
-                                                       T *__restrict__ y, int64_t n, int K, int64_t nw) {
-    // an XCD reduces a contiguous range of rows: neighbouring row groups share scratch lines
-    const int64_t blk = logical_block(blockIdx.x, gridDim.x, 1);
-    const int64_t w = __builtin_amdgcn_readfirstlane((int)(blk * (kWG / kWave) + (threadIdx.x >> 6)));
-    const int lane = threadIdx.x & 63;
-    if (w >= nw) return;
-    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-    // lane q < K fetches the table entries of stripe q (one coalesced load each); they are then
-    // broadcast stripe by stripe, so a row group costs one table round trip plus the gathers
-    uint64_t my_m = 0;
-    int32_t my_pb = 0;
-    if (lane < K) {
-        my_m = mask[w * K + lane];
-        my_pb = pbase[w * K + lane];
-    }
-    T acc = T(0);
-    for (int s0 = 0; s0 < K; s0 += 8) {   // K is a multiple of 8
-        T part[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)my_m, s0 + q);
-            const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(my_m >> 32), s0 + q);
-            const uint64_t m = ((uint64_t)hi << 32) | lo;
-            const int32_t pb = __builtin_amdgcn_readlane(my_pb, s0 + q);
-            part[q] = ((m >> lane) & 1ull) ? partial[pb + __popcll(m & below)] : T(0);
+__global__ __launch_bounds__(kWG) void k_reduce_lds(const uint16_t *__restrict__ seg_row,
+                                                    const int32_t *__restrict__ bbase,
+                                                    const T *__restrict__ partial,
+                                                    const int32_t *__restrict__ rows,
+                                                    T *__restrict__ y, int64_t n, int K) {
+    __shared__ T acc[kRedRows];
+    for (int t = threadIdx.x; t < kRedRows; t += kWG) acc[t] = T(0);
+    __syncthreads();
+    const int64_t blk = blockIdx.x;
+    const int32_t *b0 = bbase + blk * K, *b1 = b0 + K;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // every wavefront walks its own stripes (two at a time, so their loads overlap)
+    for (int s0 = 2 * wave; s0 < K; s0 += 2 * (kWG / kWave)) {   // K is a multiple of 8
+        int32_t q0 = b0[s0] + lane, q1 = b0[s0 + 1] + lane;
+        const int32_t e0 = b1[s0], e1 = b1[s0 + 1];
+        while (__any(q0 < e0 || q1 < e1)) {
+            T v0 = T(0), v1 = T(0);
+            uint16_t r0 = 0, r1 = 0;
+            const bool a0 = q0 < e0, a1 = q1 < e1;
+            if (a0) {
+                v0 = ldnt(partial + q0);
+                r0 = ldnt(seg_row + q0);
+            }
+            if (a1) {
+                v1 = ldnt(partial + q1);
+                r1 = ldnt(seg_row + q1);
+            }
+            if (a0) atomic_add(&acc[r0], v0);
+            if (a1) atomic_add(&acc[r1], v1);
+            q0 += kWave;
+            q1 += kWave;
         }
-#pragma unroll
-        for (int q = 0; q < 8; ++q) acc += part[q];
     }
-    const int64_t i = w * kWave + lane;
-    if (i < n) {
-        const int64_t r = ROWS ? (int64_t)rows[i] : i;
-        y[r] = ACC ? y[r] + acc : acc;
+    __syncthreads();
+    for (int t = threadIdx.x; t < kRedRows; t += kWG) {
+        const int64_t i = blk * kRedRows + t;
+        if (i < n) {
+            const int64_t r = ROWS ? (int64_t)rows[i] : i;
+            y[r] = ACC ? y[r] + acc[t] : acc[t];
+        }
     }
 }
 
@@ -852,16 +858,16 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         k_zero_rows<T><<<blocks(p.nrows, kWG), kWG, 0, st>>>((const int32_t *)p.p0, p.nrows, (T *)p.scratch);
         break;
     }
-    case K_REDUCE_BITMAP: {
+    case K_REDUCE_LDS: {
         if (p.nrows == 0) return 0;
-        const unsigned grid = blocks(p.nslices * kWave, kWG);
-#define RB_GO(Rw, A)                                                                               \
-    k_reduce_bitmap<T, Rw, A><<<grid, kWG, 0, st>>>((const uint64_t *)p.p0, (const int32_t *)p.p1, \
-                                                    (const T *)p.scratch, (const int32_t *)p.p3, y, \
-                                                    p.nrows, p.lanes, p.nslices)
-        if (p.has_rows) { if (p.accumulate) RB_GO(true, true); else RB_GO(true, false); }
-        else            { if (p.accumulate) RB_GO(false, true); else RB_GO(false, false); }
-#undef RB_GO
+        const unsigned grid = blocks(p.nrows, kRedRows);
+#define RL_GO(Rw, A)                                                                               \
+    k_reduce_lds<T, Rw, A><<<grid, kWG, 0, st>>>((const uint16_t *)p.p0, (const int32_t *)p.p1,    \
+                                                 (const T *)p.scratch, (const int32_t *)p.p3, y,   \
+                                                 p.nrows, p.lanes)
+        if (p.has_rows) { if (p.accumulate) RL_GO(true, true); else RL_GO(true, false); }
+        else            { if (p.accumulate) RL_GO(false, true); else RL_GO(false, false); }
+#undef RL_GO
         break;
     }
     case K_REDUCE_WIDE: {
