@@ -429,8 +429,9 @@ __global__ __launch_bounds__(kWG) void k_reduce_lds(const uint16_t *__restrict__
                                                     const T *__restrict__ partial,
                                                     const int32_t *__restrict__ rows,
                                                     T *__restrict__ y, int64_t n, int K) {
-    __shared__ T acc[kRedRows];
-    for (int t = threadIdx.x; t < kRedRows; t += kWG) acc[t] = T(0);
+    // the accumulators are double for both value types: LDS adds of doubles are the faster ones here
+    __shared__ double acc[kRedRows];
+    for (int t = threadIdx.x; t < kRedRows; t += kWG) acc[t] = 0.0;
     __syncthreads();
     const int64_t blk = blockIdx.x;
     const int32_t *b0 = bbase + blk * K, *b1 = b0 + K;
@@ -451,8 +452,8 @@ __global__ __launch_bounds__(kWG) void k_reduce_lds(const uint16_t *__restrict__
                 v1 = ldnt(partial + q1);
                 r1 = ldnt(seg_row + q1);
             }
-            if (a0) atomic_add(&acc[r0], v0);
-            if (a1) atomic_add(&acc[r1], v1);
+            if (a0) atomic_add(&acc[r0], (double)v0);
+            if (a1) atomic_add(&acc[r1], (double)v1);
             q0 += kWave;
             q1 += kWave;
         }
@@ -462,7 +463,7 @@ __global__ __launch_bounds__(kWG) void k_reduce_lds(const uint16_t *__restrict__
         const int64_t i = blk * kRedRows + t;
         if (i < n) {
             const int64_t r = ROWS ? (int64_t)rows[i] : i;
-            y[r] = ACC ? y[r] + acc[t] : acc[t];
+            y[r] = ACC ? y[r] + (T)acc[t] : (T)acc[t];
         }
     }
 }
