@@ -60,6 +60,7 @@ static std::string json_escape(const std::string &s) {
 
 std::string describe_json(const Plan &plan) {
     std::ostringstream o;
+    o.precision(12);
     const Census &c = plan.census;
     o << "{\"spec\": \"" << json_escape(print_spec(plan.spec)) << "\", ";
     o << "\"operators\": \"" << json_escape(operator_chain(plan.spec)) << "\", ";

@@ -177,3 +177,60 @@ def test_row_permutation_invariance():
     (y,), _ = gpu_spmv(m, m.values, x, spec)
     (yp,), _ = gpu_spmv(pm, m.values[idx], x, spec)
     assert np.array_equal(yp, y[perm])
+
+
+def test_timing_and_launch_introspection():
+    """spmv_run_timed / spmv_plan_time / launch names and per-launch bytes agree with the plan."""
+    m = inputs.SMALL["C3"]()
+    x = inputs.vector(m.ncols)
+    P = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, force_plan="heavy=1024,tile=2048,light=xnb,k=8,r=8")
+    d = P.describe()
+    names = P.launch_names()
+    assert names == [p["name"] for p in d["parts"]] == ["xnb.zero", "xnb", "xnb.reduce", "heavy", "heavy.reduce"]
+    assert d["scratch_bytes"] > 0 and all(p["bytes"] > 0 for p in d["parts"])
+    b_plan, b_csr = P.bytes()
+    assert b_plan == sum(p["bytes"] for p in d["parts"])
+    xd = torch.from_numpy(x).to("cuda:0")
+    yd = torch.full((m.nrows,), float("nan"), dtype=torch.float64, device="cuda:0")
+    ms = P.run_timed(xd, yd)
+    assert len(ms) == len(names) and all(t >= 0 for t in ms)
+    ok, worst = oracle.check(yd.cpu().numpy(), m.row_ptr, m.col_idx, m.values, x)
+    assert ok, worst
+    us = P.time(xd, yd, repeats=5)
+    assert 0 < us < 1e5
+    # a plan with scratch gives the same result on repeated runs into the same y (integer data: exact)
+    mi = inputs.SMALL["C3"](integer=True)
+    xi = inputs.vector(mi.ncols, integer=True)
+    Pi = lib.Plan(mi.nrows, mi.ncols, mi.row_ptr, mi.col_idx, mi.values, force_plan="heavy=1024,tile=2048,light=xnb,k=8,r=8")
+    xid = torch.from_numpy(xi).to("cuda:0")
+    want = oracle.spmv(mi.row_ptr, mi.col_idx, mi.values, xi)
+    for _ in range(3):
+        Pi.run(xid, yd)
+    torch.cuda.synchronize()
+    assert np.array_equal(yd.cpu().numpy(), want)
+    P.destroy(); Pi.destroy()
+
+
+def test_graph_replay_matches_eager():
+    """spmv_run enqueues kernels only, so a captured HIP graph of runs replays to the same result."""
+    m = inputs.SMALL["C5"](integer=True)
+    x = inputs.vector(m.ncols, integer=True)
+    want = oracle.spmv(m.row_ptr, m.col_idx, m.values, x)
+    P = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, search_budget_ms=500)
+    xd = torch.from_numpy(x).to("cuda:0")
+    yd = torch.zeros(m.nrows, dtype=torch.float64, device="cuda:0")
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        P.run(xd, yd, s.cuda_stream)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        for _ in range(3):
+            P.run(xd, yd, s.cuda_stream)
+    for _ in range(3):
+        yd.fill_(-1.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(yd.cpu().numpy(), want)
+    P.destroy()
