@@ -445,6 +445,13 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
         out.update(ref_csrv(rp, ci, va, light, lpr, p["chunk"], p["sigma"], acc, nrows, "csrv", zero_rows))
     elif p["light"] == "sell":
         out.update(ref_sell(rp, ci, va, light, p["sigma"], nrows, "sell"))
+    elif p["light"] == "coo":
+        if light.size:
+            out["coo.rows"] = np.repeat(light, lens[light]).astype(np.int32)
+            out["coo.cols"] = np.concatenate([ci[_row_entries(rp, r)] for r in light]).astype(np.int32)
+            out["coo.vals"] = np.concatenate([va[_row_entries(rp, r)] for r in light]).astype(va.dtype)
+            if not acc:
+                zero_rows += [int(r) for r in light]
     elif p["light"] == "nnzb":
         out.update(ref_nnzb(rp, ci, va, light, p["r"], acc, zero_rows))
     elif p["light"] == "xnb":
@@ -474,6 +481,9 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
     for pre in prefixes:
         a = {k.rsplit(".", 1)[1]: v for k, v in arrays.items() if k.rsplit(".", 1)[0] == pre}
         if pre == "zero":
+            continue
+        if pre == "coo":
+            R.append(a["rows"].astype(np.int64)); C.append(a["cols"]); V.append(a["vals"])
             continue
         if pre == "xnb":
             cc, vv, bb, sr, bbs = a["cols"], a["vals"], a["bits"], a["seg_row"], a["bbase"]

@@ -116,8 +116,10 @@ def _dtype_code(dt) -> int:
 
 def spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, *, force_plan=None,
                      search_budget_ms=0.0, search_repeats=0, host_threads=0, verbosity=0,
-                     host_only=False, nnz=None) -> int:
-    """Returns an opaque plan handle (int).  row_ptr / col_idx / values are host NumPy arrays."""
+                     host_only=False, nnz=None, allocator=None) -> int:
+    """Returns an opaque plan handle (int).  row_ptr / col_idx / values are host NumPy arrays.
+    allocator = (alloc(nbytes) -> device address or 0, free(address)): Python callables the library
+    uses for every device array of the plan (kept alive until spmv_plan_destroy)."""
     lib = load()
     row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int32)
     col_idx = np.ascontiguousarray(col_idx, dtype=np.int32)
@@ -132,10 +134,20 @@ def spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, *, force_plan=None,
     opts.host_threads = int(host_threads)
     opts.verbosity = int(verbosity)
     opts.host_only = int(bool(host_only))
+    keep = None
+    if allocator is not None:
+        alloc_py, free_py = allocator
+        keep = (_ALLOC_FN(lambda nbytes, user: alloc_py(nbytes) or None), _FREE_FN(lambda ptr, user: free_py(ptr)))
+        opts.dev_alloc, opts.dev_free = keep
     handle = ctypes.c_void_p()
     _check(lib.spmv_plan_create(ctypes.byref(handle), nrows, ncols, nnz, row_ptr.ctypes.data,
                                 col_idx.ctypes.data, values.ctypes.data, code, ctypes.byref(opts)))
+    if keep is not None:
+        _callbacks[handle.value] = keep      # the plan calls dev_free when it is destroyed
     return handle.value
+
+
+_callbacks = {}
 
 
 def spmv_run(plan: int, x_dev: int, y_dev: int, stream: int = 0) -> None:
@@ -162,6 +174,7 @@ def spmv_plan_time(plan: int, x_dev: int, y_dev: int, stream: int = 0, repeats: 
 
 def spmv_plan_destroy(plan: int) -> None:
     _check(load().spmv_plan_destroy(plan))
+    _callbacks.pop(plan, None)
 
 
 def spmv_plan_describe(plan: int) -> dict:

@@ -589,6 +589,45 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     add_part(plan, r, plan.arrays.size(), 0, ngroups * nh + nh / 2, nh);   // + heavy.rows (4 bytes each)
 }
 
+// ---- COO -----------------------------------------------------------------------------------------
+// One (row, column, value) triple per stored entry of the part's rows, in row order.  Every row of
+// the part is zeroed first: all sums go through atomics.
+template <typename T>
+void build_coo(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, bool acc,
+               const std::vector<int64_t> &lens, std::vector<int32_t> &zero_rows, int threads) {
+    const int64_t n = (int64_t)rows.size();
+    if (n == 0) return;
+    std::vector<int64_t> start((size_t)n + 1, 0);
+    for (int64_t i = 0; i < n; ++i) start[(size_t)i + 1] = start[(size_t)i] + lens[(size_t)rows[(size_t)i]];
+    const int64_t total = start[(size_t)n];
+    if (!acc) zero_rows.insert(zero_rows.end(), rows.begin(), rows.end());
+    HostBuf<int32_t> er(total), ec(total);
+    HostBuf<T> ev(total);
+    const T *av = (const T *)A.val;
+    parallel_for(n, 1024, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t r = rows[(size_t)i];
+            const int64_t src = A.row_ptr[r], L = lens[(size_t)r], dst = start[(size_t)i];
+            for (int64_t k = 0; k < L; ++k) er[dst + k] = r;
+            std::memcpy(ec.p + dst, A.col + src, (size_t)L * 4);
+            std::memcpy(ev.p + dst, av + src, (size_t)L * sizeof(T));
+        }
+    });
+    Part p;
+    p.kind = K_COO;
+    p.name = "coo";
+    p.nrows = n;
+    p.nnz = total;
+    p.stored = total;
+    p.units = total;
+    p.has_rows = true;
+    const size_t a0 = plan.arrays.size();
+    p.p0 = upload(plan, "coo.rows", 4, total, er.p);
+    p.p1 = upload(plan, "coo.cols", 4, total, ec.p);
+    p.p2 = upload(plan, "coo.vals", (int)sizeof(T), total, ev.p);
+    add_part(plan, p, a0, std::min<int64_t>(A.ncols, total), 0, 2 * total);   // one read-modify-write of y per entry
+}
+
 // ---- nnz-balanced tiles ----------------------------------------------------------------------------
 // The non-empty rows of the part, in order, form one stream of entries; tile i holds entries
 // [64*R*i, 64*R*(i+1)), lane l of the tile the R consecutive entries from 64*R*i + R*l, stored
@@ -1171,6 +1210,9 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         break;
     case L_XNB:
         build_xnb<T>(*plan, A, light, spec.k, spec.r, acc, lens, threads);
+        break;
+    case L_COO:
+        build_coo<T>(*plan, A, light, acc, lens, zero_rows, threads);
         break;
     case L_BIN: {
         // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront per

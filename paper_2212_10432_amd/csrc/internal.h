@@ -74,7 +74,7 @@ struct Census {
 Census take_census(const HostCsr &A, int threads);
 
 // ---- plan specification --------------------------------------------------------------------
-enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZB = 5, L_XNB = 6 };
+enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZB = 5, L_XNB = 6, L_COO = 7 };
 
 struct PlanSpec {
     int dia = 0;             // extract well-populated diagonals into a DIA part first
@@ -105,7 +105,7 @@ struct DevArray {
     bool read_per_run = true;    // counts towards the algorithmic bytes of one run
 };
 
-enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS };
+enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS, K_COO };
 
 // One kernel launch of spmv_run.  Pointers refer to entries of Plan::arrays.
 struct Part {

@@ -264,6 +264,19 @@ __global__ __launch_bounds__(kWG) void k_csrv(const int32_t *__restrict__ seg_pt
     }
 }
 
+// ---- COO: one lane per stored entry ---------------------------------------------------------
+// BMT_NNZ_BLOCK(1) + GMEM_ATOM_RED: every product is added atomically into a y element zeroed by
+// an earlier launch.  The root format the paper starts from (Section I); kept as the fallback that
+// needs no structure at all.
+template <typename T>
+__global__ __launch_bounds__(kWG) void k_coo(const int32_t *__restrict__ rows,
+                                             const int32_t *__restrict__ cols,
+                                             const T *__restrict__ vals, const T *__restrict__ x,
+                                             T *__restrict__ y, int64_t nnz) {
+    const int64_t k = (int64_t)blockIdx.x * kWG + threadIdx.x;
+    if (k < nnz) atomic_add(y + ldnt(rows + k), ldnt(vals + k) * x[ldnt(cols + k)]);
+}
+
 // ---- nnz-balanced segmented kernel ----------------------------------------------------------
 // BMT_NNZ_BLOCK(R): every lane owns R consecutive non-zeros of the part's CSR stream, whatever
 // rows they belong to (perfect balance, no padding except the stream's tail).  A wavefront's tile
@@ -869,6 +882,12 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (p.has_rows) { if (p.accumulate) RL_GO(true, true); else RL_GO(true, false); }
         else            { if (p.accumulate) RL_GO(false, true); else RL_GO(false, false); }
 #undef RL_GO
+        break;
+    }
+    case K_COO: {
+        if (p.units == 0) return 0;
+        k_coo<T><<<blocks(p.units, kWG), kWG, 0, st>>>((const int32_t *)p.p0, (const int32_t *)p.p1,
+                                                       (const T *)p.p2, x, y, p.units);
         break;
     }
     case K_REDUCE_WIDE: {

@@ -68,6 +68,7 @@ static const char *light_name(int l) {
     case L_XS: return "xs";
     case L_NNZB: return "nnzb";
     case L_XNB: return "xnb";
+    case L_COO: return "coo";
     }
     return "?";
 }
@@ -97,6 +98,7 @@ PlanSpec parse_spec(const std::string &s) {
             else if (v == "xs") p.light = L_XS;
             else if (v == "nnzb") p.light = L_NNZB;
             else if (v == "xnb") p.light = L_XNB;
+            else if (v == "coo") p.light = L_COO;
             else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown light design " + v);
         } else if (k == "dia") p.dia = (int)num();
         else if (k == "dia_fill") p.dia_fill = num();
@@ -184,6 +186,9 @@ std::string operator_chain(const PlanSpec &p) {
     case L_NNZB:
         o << " -> BMW_NNZ_BLOCK(" << 64 * p.r << ") -> BMT_NNZ_BLOCK(" << p.r
           << ") -> THREAD_BITMAP_RED -> WARP_SEG_RED -> GMEM_ATOM_RED(tile borders)";
+        break;
+    case L_COO:
+        o << " -> BMT_NNZ_BLOCK(1) -> GMEM_ATOM_RED";
         break;
     case L_XNB:
         o << " -> COL_DIV(" << p.k << " stripes, stripe s on XCD s mod 8) -> BMW_NNZ_BLOCK(" << 64 * p.r

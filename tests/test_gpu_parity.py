@@ -16,15 +16,15 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 SPECS = {
-    "C1": ["light=xnb,k=8,r=4", "light=nnzb,r=4", "light=xs,k=8,sigma=256", "light=xs,k=32,sigma=0", "light=csrv", "light=csrv,lpr=1", "light=csrv,lpr=64,sigma=128", "light=sell", "light=sell,sigma=256,remap=1",
+    "C1": ["light=coo", "light=xnb,k=8,r=4", "light=nnzb,r=4", "light=xs,k=8,sigma=256", "light=xs,k=32,sigma=0", "light=csrv", "light=csrv,lpr=1", "light=csrv,lpr=64,sigma=128", "light=sell", "light=sell,sigma=256,remap=1",
            "light=bin,smax=4,sigma=128"],
-    "C2": ["dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "light=xs,k=24,sigma=4096", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
+    "C2": ["dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "light=xs,k=24,sigma=4096", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
     "C3": ["light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=8192", "light=csrv,chunk=512", "light=csrv,lpr=32", "light=bin,smax=16,sigma=512,chunk=256",
            "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
            "heavy=256,tile=512,light=sell,sigma=128", "heavy=2048,tile=8192,light=bin,chunk=1024"],
     "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", "light=sell,sigma=512",
            "light=csrv,lpr=16"],
-    "C5": ["heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
+    "C5": ["heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
            "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=100,tile=8192,light=bin,sigma=8192,remap=1"],
 }
 CASES = [(n, s) for n in SPECS for s in SPECS[n]]
@@ -97,7 +97,7 @@ def test_edge_cases():
     # empty matrix, matrix of empty rows, single entry
     for nrows, ncols in ((0, 0), (5, 7), (130, 3)):
         rp = np.zeros(nrows + 1, np.int32)
-        for spec in ("light=csrv", "light=sell", "light=bin", "heavy=4,light=sell", "light=xs", "light=nnzb", "light=xnb", None):
+        for spec in ("light=csrv", "light=sell", "light=bin", "heavy=4,light=sell", "light=xs", "light=nnzb", "light=xnb", "light=coo", None):
             P = lib.Plan(nrows, ncols, rp, np.zeros(0, np.int32), np.zeros(0), force_plan=spec, search_budget_ms=200)
             x = torch.ones(max(ncols, 1), dtype=torch.float64, device=dev)[:ncols]
             y = torch.full((max(nrows, 1),), float("nan"), dtype=torch.float64, device=dev)[:nrows]
@@ -122,7 +122,7 @@ def test_edge_cases():
     m = M()
     m.nrows, m.ncols, m.row_ptr, m.col_idx = nrows, ncols, rp, ci
     for spec in ("light=csrv", "light=csrv,lpr=64,chunk=256", "light=sell,sigma=64", "light=bin,sigma=32,chunk=512",
-                 "heavy=100,tile=256,light=sell,sigma=64", "heavy=100,tile=64,light=bin", "heavy=100,tile=64,light=xs,k=8,sigma=64", "light=xs,k=16", "light=nnzb,r=4", "heavy=100,tile=64,light=nnzb,r=16", "light=xnb,k=8,r=4", "heavy=100,tile=64,light=xnb,k=16,r=8", None):
+                 "heavy=100,tile=256,light=sell,sigma=64", "heavy=100,tile=64,light=bin", "heavy=100,tile=64,light=xs,k=8,sigma=64", "light=xs,k=16", "light=nnzb,r=4", "heavy=100,tile=64,light=nnzb,r=16", "light=xnb,k=8,r=4", "heavy=100,tile=64,light=xnb,k=16,r=8", "light=coo", None):
         for dt in (np.float64, np.float32):
             (y,), _ = gpu_spmv(m, va.astype(dt), x.astype(dt), spec, search_budget_ms=300)
             assert np.array_equal(y.astype(np.float64), want), (spec, dt)
@@ -234,3 +234,52 @@ def test_graph_replay_matches_eager():
         torch.cuda.synchronize()
         assert np.array_equal(yd.cpu().numpy(), want)
     P.destroy()
+
+
+def test_caller_supplied_allocator_and_allocation_failure():
+    """dev_alloc / dev_free: every device array of a plan comes from the caller's allocator (here backed
+    by torch tensors) and goes back through it; a failing allocator yields SPMV_ERR_ALLOC with nothing
+    left allocated."""
+    m = inputs.SMALL["C5"](integer=True)
+    x = inputs.vector(m.ncols, integer=True)
+    want = oracle.spmv(m.row_ptr, m.col_idx, m.values, x)
+    live, stats = {}, {"allocs": 0, "frees": 0, "fail_at": None}
+
+    def alloc(nbytes):
+        stats["allocs"] += 1
+        if stats["fail_at"] is not None and stats["allocs"] >= stats["fail_at"]:
+            return 0
+        t = torch.empty(max(int(nbytes), 1), dtype=torch.uint8, device="cuda:0")
+        live[t.data_ptr()] = t
+        return t.data_ptr()
+
+    def free(ptr):
+        stats["frees"] += 1
+        del live[ptr]
+
+    spec = "heavy=64,tile=2048,light=xnb,k=8,r=8"
+    P = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, force_plan=spec, allocator=(alloc, free))
+    n_arrays = lib.spmv_plan_array_count(P.handle)
+    assert len(live) >= n_arrays and stats["frees"] == 0
+    xd = torch.from_numpy(x).to("cuda:0")
+    yd = torch.empty(m.nrows, dtype=torch.float64, device="cuda:0")
+    P.run(xd, yd)
+    torch.cuda.synchronize()
+    assert np.array_equal(yd.cpu().numpy(), want)
+    P.destroy()
+    assert not live and stats["frees"] == stats["allocs"]
+    # the search allocates and frees candidate after candidate through the same pair
+    P = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, search_budget_ms=300, allocator=(alloc, free))
+    P.run(xd, yd)
+    torch.cuda.synchronize()
+    assert np.array_equal(yd.cpu().numpy(), want)
+    P.destroy()
+    assert not live
+    # failure on the n-th allocation: error code, message, and everything handed back
+    for fail_at in (1, 3, 6):
+        stats.update(allocs=0, frees=0, fail_at=fail_at)
+        with pytest.raises(lib.SpmvError) as e:
+            lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, force_plan=spec, allocator=(alloc, free))
+        assert e.value.status == lib.SPMV_ERR_ALLOC and "allocation" in e.value.message
+        assert not live and stats["frees"] == fail_at - 1
+    stats["fail_at"] = None
