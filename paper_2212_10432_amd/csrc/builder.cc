@@ -224,8 +224,12 @@ void build_csrv(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int lpr
     if (ident) {   // the input arrays already are the layout; origin row = segment id
         p.units = n;
         p.has_rows = false;
+        // one length for all rows: the kernel computes the offsets, the array is kept for inspection only
+        bool uniform = A.nnz < ((int64_t)1 << 31);
+        for (int64_t i = 1; i < n && uniform; ++i) uniform = lens[(size_t)i] == lens[0];
+        if (uniform) p.uniform_w = (int)lens[0];
         const size_t a0 = plan.arrays.size();
-        p.p0 = upload(plan, name + ".seg_ptr", 4, n + 1, A.row_ptr);
+        p.p0 = upload(plan, name + ".seg_ptr", 4, n + 1, A.row_ptr, !uniform);
         p.p2 = upload(plan, name + ".cols", 4, A.nnz, A.col);
         p.p3 = upload(plan, name + ".vals", (int)sizeof(T), A.nnz, A.val);
         add_part(plan, p, a0, std::min<int64_t>(A.ncols, total), 0, n);

@@ -128,7 +128,7 @@ struct Part {
     int64_t ngroups = 0;         // heavy part: workgroups (= partial-sum rows in scratch)
     int64_t per_group = 0;       // heavy part: stripes per workgroup
     void *scratch = nullptr;     // partial sums written by one launch and read by the next
-    int uniform_w = -1;          // sell: width shared by every slice (-1: read slice_ptr)
+    int uniform_w = -1;          // sell / csrv: width shared by every slice / row (-1: read the offsets)
     int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
     const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
     int64_t bytes = 0;           // algorithmic bytes of one launch: arrays read + x + scratch + y

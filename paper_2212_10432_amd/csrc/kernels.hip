@@ -227,15 +227,20 @@ __global__ __launch_bounds__(kWG) void k_csrv(const int32_t *__restrict__ seg_pt
                                               const int32_t *__restrict__ cols,
                                               const T *__restrict__ vals,
                                               const T *__restrict__ x, T *__restrict__ y,
-                                              int64_t nseg, int remap) {
+                                              int64_t nseg, int remap, int uniform_len) {
     const int64_t blk = logical_block(blockIdx.x, gridDim.x, remap);
     const int64_t g = (blk * kWG + threadIdx.x) / LPR;
     const int t = threadIdx.x % LPR;
     const bool live = g < nseg;
     int32_t b = 0, e = 0;
     if (live) {
-        b = seg_ptr[g];
-        e = seg_ptr[g + 1];
+        if (uniform_len >= 0) {   // every segment equally long: the offsets follow a linear model
+            b = (int32_t)g * uniform_len;
+            e = b + uniform_len;
+        } else {
+            b = seg_ptr[g];
+            e = seg_ptr[g + 1];
+        }
     }
     T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
     int32_t k = b + t;
@@ -249,7 +254,22 @@ __global__ __launch_bounds__(kWG) void k_csrv(const int32_t *__restrict__ seg_pt
         a2 += v2 * x[c2];
         a3 += v3 * x[c3];
     }
-    for (; k < e; k += LPR) a0 += ldnt(vals + k) * x[ldnt(cols + k)];
+    // the lane's last 1-3 entries are loaded together, not one dependent chain after the other
+    const int left = k < e ? (e - k + LPR - 1) / LPR : 0;
+    if (left == 3) {
+        const int32_t c0 = ldnt(cols + k), c1 = ldnt(cols + k + LPR), c2 = ldnt(cols + k + 2 * LPR);
+        const T v0 = ldnt(vals + k), v1 = ldnt(vals + k + LPR), v2 = ldnt(vals + k + 2 * LPR);
+        a0 += v0 * x[c0];
+        a1 += v1 * x[c1];
+        a2 += v2 * x[c2];
+    } else if (left == 2) {
+        const int32_t c0 = ldnt(cols + k), c1 = ldnt(cols + k + LPR);
+        const T v0 = ldnt(vals + k), v1 = ldnt(vals + k + LPR);
+        a0 += v0 * x[c0];
+        a1 += v1 * x[c1];
+    } else if (left == 1) {
+        a0 += ldnt(vals + k) * x[ldnt(cols + k)];
+    }
     const T acc = group_sum<LPR>((a0 + a1) + (a2 + a3));
     if (live && t == 0) {
         if (ROWS) {
@@ -736,7 +756,7 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
 #define CSRV_GO(L, R, A)                                                                           \
     k_csrv<T, L, R, A><<<blocks(p.units * L, kWG), kWG, 0, st>>>(                                  \
         (const int32_t *)p.p0, (const int32_t *)p.p1, (const int32_t *)p.p2, (const T *)p.p3, x,   \
-        y, p.units, p.remap)
+        y, p.units, p.remap, p.uniform_w)
 #define CSRV_L(L)                                                                                  \
     case L:                                                                                        \
         if (p.has_rows) { if (p.accumulate) CSRV_GO(L, true, true); else CSRV_GO(L, true, false); } \
