@@ -31,7 +31,7 @@ WAVE = 64
 
 def parse_spec(spec: str) -> dict:
     d = dict(dia=0, dia_fill=0.5, heavy=0, tile=8192, light="csrv", lpr=0, chunk=0,
-             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8, r=8)
+             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8, r=8, w=0, rb=16384)
     for tok in spec.split(","):
         if not tok:
             continue
@@ -416,6 +416,74 @@ def ref_xnb(ncols, rp, ci, va, rows, K, R, nrows_total):
     return out
 
 
+def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
+    """Two passes with x windows in LDS.  Windows of W columns (0: 64 KiB worth of values), blocks of
+    RB part positions.  Entry (part position i, column c) is in run (s, b) = (c // W, i // RB); runs
+    are stored window by window, block by block inside a window, by part position and row order
+    inside a run, each padded to a multiple of 16 entries with (value 0, local column 0, local row
+    0).  items: (window, first entry, end entry) pieces of a window's entries, m = ceil(len / chunk)
+    pieces of ceil16(ceil(len / m)) entries; chunk 0 means max(4096, ceil16(ceil(total / 1024))).
+    glist: for block b the 16-entry groups of runs (0, b), (1, b), ...; gptr: its offsets per block."""
+    rows = np.asarray(rows, dtype=np.int32)
+    n = rows.size
+    if n == 0:
+        return {}
+    ident = n == nrows_total and np.array_equal(rows, np.arange(nrows_total))
+    if W == 0:
+        W = 65536 // va.dtype.itemsize
+    G = 16
+    S = max(1, -(-ncols // W))
+    B = -(-n // RB)
+    lens = (rp[rows + 1] - rp[rows]).astype(np.int64)
+    pos_of_entry = np.repeat(np.arange(n, dtype=np.int64), lens)           # part position i
+    src = np.concatenate([np.arange(rp[r], rp[r + 1], dtype=np.int64) for r in rows]) if lens.sum() else np.zeros(0, np.int64)
+    c = ci[src].astype(np.int64)
+    run = (c // W) * B + pos_of_entry // RB
+    order = np.argsort(run, kind="stable")                                   # keeps (i, row order) inside a run
+    cnt = np.bincount(run, minlength=S * B).astype(np.int64)
+    padded = -(-cnt // G) * G
+    start = np.concatenate([[0], np.cumsum(padded)])
+    tot = int(start[-1])
+    vals = np.zeros(tot, dtype=va.dtype)
+    lcol = np.zeros(tot, dtype=np.uint16)
+    lrow = np.zeros(tot, dtype=np.uint16)
+    run_sorted = run[order]
+    first = np.concatenate([[0], np.cumsum(cnt)])[run_sorted]              # unpadded start of the entry's run
+    dst = start[run_sorted] + (np.arange(order.size) - first)
+    vals[dst] = va[src[order]]
+    lcol[dst] = (c[order] % W).astype(np.uint16)
+    lrow[dst] = (pos_of_entry[order] % RB).astype(np.uint16)
+    ceil16 = lambda v: -(-v // G) * G
+    chunk = ceil16(chunk) if chunk > 0 else max(4096, ceil16(-(-tot // 1024)))
+    items = []
+    for s_ in range(S):
+        b0, e0 = int(start[s_ * B]), int(start[(s_ + 1) * B])
+        if e0 == b0:
+            continue
+        m = -(-(e0 - b0) // chunk)
+        per = ceil16(-(-(e0 - b0) // m))
+        for cpos in range(b0, e0, per):
+            items += [s_, cpos, min(e0, cpos + per)]
+    gptr = np.zeros(B + 1, dtype=np.int32)
+    glist = []
+    for b in range(B):
+        ngroups = 0
+        for s_ in range(S):
+            j = s_ * B + b
+            glist.append(np.arange(start[j] // G, start[j + 1] // G, dtype=np.int32))
+            ngroups += glist[-1].size
+        gptr[b + 1] = gptr[b] + ngroups
+    out = {"xl.vals": vals, "xl.lcol": lcol, "xl.gptr": gptr,
+           "xl.glist": np.concatenate(glist).astype(np.int32) if glist else np.zeros(0, np.int32), "xl.lrow": lrow}
+    if items:
+        out["xl.items"] = np.array(items, dtype=np.int32)
+    else:
+        del out["xl.vals"], out["xl.lcol"]
+    if not ident:
+        out["xl.rows"] = rows
+    return out
+
+
 def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
     """All format arrays of the plan `spec` for a CSR matrix with ascending columns in each row."""
     p = parse_spec(spec)
@@ -456,6 +524,8 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
         out.update(ref_nnzb(rp, ci, va, light, p["r"], acc, zero_rows))
     elif p["light"] == "xnb":
         out.update(ref_xnb(ncols, rp, ci, va, light, p["k"], p["r"], nrows))
+    elif p["light"] == "xl":
+        out.update(ref_xl(ncols, rp, ci, va, light, p["w"], p["rb"], p["chunk"], nrows))
     elif p["light"] == "xs":
         out.update(ref_xs(ncols, rp, ci, va, light, p["k"], p["sigma"], nrows))
     elif p["light"] == "bin":
@@ -473,7 +543,7 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
 
 # ---- decoding: plan arrays -> (row, col, value) triples --------------------------------------
 
-def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 8192):
+def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 8192, xl_w: int = 0, xl_rb: int = 16384):
     """Every stored entry of every part as COO triples (padding included: it carries value 0).
     The part kind is recognised from the array names."""
     R, C, V = [], [], []
@@ -484,6 +554,23 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
             continue
         if pre == "coo":
             R.append(a["rows"].astype(np.int64)); C.append(a["cols"]); V.append(a["vals"])
+            continue
+        if pre == "xl":
+            if "vals" not in a:
+                continue
+            vv, lc, lr, it, gp, gl = a["vals"], a["lcol"], a["lrow"], a["items"], a["gptr"], a["glist"]
+            W_ = xl_w if xl_w else 65536 // vv.dtype.itemsize
+            win = np.full(vv.size, -1, dtype=np.int64)        # entry -> window, from the items
+            for s_, b0, e0 in it.reshape(-1, 3):
+                win[b0:e0] = s_
+            blk = np.full(vv.size // 16, -1, dtype=np.int64)   # group -> row block, from the group list
+            blk[gl] = np.repeat(np.arange(gp.size - 1), np.diff(gp))
+            assert np.all(win >= 0) and np.all(blk >= 0) and np.unique(gl).size == gl.size
+            posn = np.repeat(blk, 16) * xl_rb + lr.astype(np.int64)
+            rws = np.asarray(a["rows"]) if "rows" in a else np.arange(nrows)
+            assert not np.any(vv[posn >= rws.size])
+            keep = posn < rws.size
+            R.append(rws[posn[keep]].astype(np.int64)); C.append(win[keep] * W_ + lc[keep].astype(np.int64)); V.append(vv[keep])
             continue
         if pre == "xnb":
             cc, vv, bb, sr, bbs = a["cols"], a["vals"], a["bits"], a["seg_row"], a["bbase"]

@@ -933,6 +933,146 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
     add_part(plan, r, a2, 0, nsegs, n);
 }
 
+// ---- two passes with x windows in LDS --------------------------------------------------------------
+// COL_DIV into windows of W columns (an LDS-sized piece of x), ROW_DIV of the part into blocks of RB
+// rows (an LDS-sized piece of y).  Entry (part position i, column c) belongs to run (s, b) =
+// (c / W, i / RB); runs are stored window by window, inside a window block by block, inside a run
+// by part position and then in row order; every run is padded to a multiple of 16 entries with
+// (value 0, local column 0, local row 0).  Entry g holds vals[g], lcol[g] = c - s*W and
+// lrow[g] = i - b*RB; its product goes to scratch[g].  The multiply launch works through items
+// (s, first entry, end entry): a window's entries cut into pieces of about `chunk` entries.  The
+// reduce launch of block b adds the 16-entry groups glist[gptr[b]] .. glist[gptr[b+1] - 1]: the
+// groups of runs (0, b), (1, b), ... in that order.
+template <typename T>
+void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, int w_spec, int RB,
+              int64_t chunk_spec, bool acc, const std::vector<int64_t> &lens, int threads) {
+    const int64_t n = (int64_t)rows.size();
+    if (n == 0) return;
+    const bool ident = is_identity(rows, A.nrows);
+    const int64_t W = w_spec > 0 ? w_spec : (int64_t)(65536 / sizeof(T));
+    if (W * (int64_t)sizeof(T) > kXlMaxLds) fail(SPMV_ERR_UNSUPPORTED, "xl: the x window does not fit in LDS");
+    if ((int64_t)RB * 8 > kXlMaxLds) fail(SPMV_ERR_UNSUPPORTED, "xl: the row block does not fit in LDS");
+    const int64_t S = std::max<int64_t>(1, (A.ncols + W - 1) / W);
+    const int64_t B = (n + RB - 1) / RB;
+    if (S * B > ((int64_t)1 << 26)) fail(SPMV_ERR_UNSUPPORTED, "xl: too many (window, row block) runs");
+    const int64_t G = kXlGroup;
+    int64_t real = 0;
+    for (int32_t r : rows) real += lens[(size_t)r];
+    // entries per run
+    std::vector<int64_t> start((size_t)(S * B) + 1, 0);
+    parallel_for(B, 1, threads, [&](int64_t bb, int64_t be, int) {
+        for (int64_t b = bb; b < be; ++b)
+            for (int64_t i = b * RB; i < std::min(n, (b + 1) * RB); ++i) {
+                const int32_t r = rows[(size_t)i];
+                for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k)
+                    start[(size_t)((A.col[k] / W) * B + b) + 1] += 1;
+            }
+    });
+    for (int64_t j = 0; j < S * B; ++j)
+        start[(size_t)j + 1] = start[(size_t)j] + (start[(size_t)j + 1] + G - 1) / G * G;
+    const int64_t tot = start[(size_t)(S * B)];
+    if (tot >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "xl: too many entries");
+    HostBuf<T> vals(tot);
+    HostBuf<uint16_t> lcol(tot), lrow(tot);
+    const T *av = (const T *)A.val;
+    parallel_for(B, 1, threads, [&](int64_t bb, int64_t be, int) {
+        std::vector<int64_t> cur((size_t)S);
+        for (int64_t b = bb; b < be; ++b) {
+            for (int64_t s = 0; s < S; ++s) cur[(size_t)s] = start[(size_t)(s * B + b)];
+            for (int64_t i = b * RB; i < std::min(n, (b + 1) * RB); ++i) {
+                const int32_t r = rows[(size_t)i];
+                for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
+                    const int64_t s = A.col[k] / W;
+                    const int64_t g = cur[(size_t)s]++;
+                    vals[g] = av[k];
+                    lcol[g] = (uint16_t)(A.col[k] - s * W);
+                    lrow[g] = (uint16_t)(i - b * RB);
+                }
+            }
+            for (int64_t s = 0; s < S; ++s)
+                for (int64_t g = cur[(size_t)s]; g < start[(size_t)(s * B + b) + 1]; ++g) {
+                    vals[g] = T(0);
+                    lcol[g] = 0;
+                    lrow[g] = 0;
+                }
+        }
+    });
+    // items of the multiply launch
+    int64_t chunk = chunk_spec > 0 ? (chunk_spec + G - 1) / G * G
+                                   : std::max<int64_t>(4096, ((tot + 1023) / 1024 + G - 1) / G * G);
+    std::vector<int32_t> items;
+    for (int64_t s = 0; s < S; ++s) {
+        const int64_t b0 = start[(size_t)(s * B)], e0 = start[(size_t)((s + 1) * B)];
+        if (e0 == b0) continue;
+        const int64_t m = (e0 - b0 + chunk - 1) / chunk;
+        const int64_t per = ((e0 - b0 + m - 1) / m + G - 1) / G * G;
+        for (int64_t c = b0; c < e0; c += per) {
+            items.push_back((int32_t)s);
+            items.push_back((int32_t)c);
+            items.push_back((int32_t)std::min(e0, c + per));
+        }
+    }
+    const int64_t nitems = (int64_t)items.size() / 3;
+    // group list of the reduce launch
+    std::vector<int32_t> gptr((size_t)B + 1, 0);
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t c = 0;
+        for (int64_t s = 0; s < S; ++s) c += (start[(size_t)(s * B + b) + 1] - start[(size_t)(s * B + b)]) / G;
+        gptr[(size_t)b + 1] = (int32_t)(gptr[(size_t)b] + c);
+    }
+    HostBuf<int32_t> glist(tot / G);
+    parallel_for(B, 1, threads, [&](int64_t bb, int64_t be, int) {
+        for (int64_t b = bb; b < be; ++b) {
+            int64_t o = gptr[(size_t)b];
+            for (int64_t s = 0; s < S; ++s)
+                for (int64_t g = start[(size_t)(s * B + b)] / G; g < start[(size_t)(s * B + b) + 1] / G; ++g)
+                    glist[o++] = (int32_t)g;
+        }
+    });
+
+    void *scratch = plan.mem.alloc((size_t)std::max<int64_t>(tot, 1) * sizeof(T), plan.mem.user);
+    if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the xl part's scratch failed");
+    {
+        DevArray a;
+        a.name = "xl.scratch";
+        a.ptr = scratch;
+        a.elem_bytes = (int)sizeof(T);
+        a.count = tot;
+        plan.scratch.push_back(a);
+    }
+    if (nitems > 0) {
+        Part p;
+        p.kind = K_XL_MUL;
+        p.name = "xl";
+        p.nrows = n;
+        p.nnz = real;
+        p.stored = tot;
+        p.units = nitems;
+        p.tile = (int)W;
+        p.scratch = scratch;
+        const size_t a1 = plan.arrays.size();
+        p.p0 = upload(plan, "xl.items", 4, 3 * nitems, items.data());
+        p.p1 = upload(plan, "xl.vals", (int)sizeof(T), tot, vals.p);
+        p.p2 = upload(plan, "xl.lcol", 2, tot, lcol.p);
+        add_part(plan, p, a1, std::min<int64_t>(A.ncols, real), tot, 0);
+    }
+    Part r;
+    r.kind = K_XL_REDUCE;
+    r.name = "xl.reduce";
+    r.nrows = n;
+    r.units = B;
+    r.tile = RB;
+    r.scratch = scratch;
+    r.accumulate = acc;
+    r.has_rows = !ident;
+    const size_t a2 = plan.arrays.size();
+    r.p0 = upload(plan, "xl.gptr", 4, B + 1, gptr.data());
+    r.p1 = upload(plan, "xl.glist", 4, tot / G, glist.p);
+    r.p2 = upload(plan, "xl.lrow", 2, tot, lrow.p);
+    if (!ident) r.p3 = upload(plan, "xl.rows", 4, n, rows.data());
+    add_part(plan, r, a2, 0, tot, n);
+}
+
 // ---- XCD-striped SELL ----------------------------------------------------------------------------
 // COL_DIV into K stripes of W = ceil(ncols / K) columns (rounded up to 64).  Per stripe: the rows
 // of the part that have entries in it, in windows of sigma part positions, sorted by that count
@@ -1217,6 +1357,9 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         break;
     case L_COO:
         build_coo<T>(*plan, A, light, acc, lens, zero_rows, threads);
+        break;
+    case L_XL:
+        build_xl<T>(*plan, A, light, spec.w, spec.rb, spec.chunk, acc, lens, threads);
         break;
     case L_BIN: {
         // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront per

@@ -23,6 +23,10 @@ constexpr int kXwinGroup = 32;
 constexpr int64_t kXwinMaxBytes = 160 * 1024;
 // Rows per workgroup of the striped parts' reduce launch (their sums live in LDS).
 constexpr int kReduceBlockRows = 1024;
+// Two-pass part with x windows in LDS: entries per group (the unit of padding and of the reduce
+// launch's group list), and the LDS budget of an x window or of a block's accumulators.
+constexpr int kXlGroup = 16;
+constexpr int64_t kXlMaxLds = 128 * 1024;
 
 struct Error {
     spmv_status_t code;
@@ -74,7 +78,7 @@ struct Census {
 Census take_census(const HostCsr &A, int threads);
 
 // ---- plan specification --------------------------------------------------------------------
-enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZB = 5, L_XNB = 6, L_COO = 7 };
+enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZB = 5, L_XNB = 6, L_COO = 7, L_XL = 8 };
 
 struct PlanSpec {
     int dia = 0;             // extract well-populated diagonals into a DIA part first
@@ -84,6 +88,7 @@ struct PlanSpec {
     int light = L_CSRV;      // design of the remaining rows
     int lpr = 0;             // csrv: lanes per row (power of two <= 64; 0 = from the mean length)
     int64_t chunk = 0;       // csrv: rows longer than this are cut into segments (0 = never)
+                             // xl: entries per workgroup of the multiply launch (0 = chosen by the builder)
     int sigma = 0;           // sell/bsell: sort window in rows (0 = no sort, -1 = whole part)
     int block = 3;           // bsell: block edge (2, 3 or 4)
     int smax = 16;           // bin: rows up to this length go to the SELL bin
@@ -91,6 +96,8 @@ struct PlanSpec {
     int r = 8;               // nnzb: consecutive non-zeros per lane (4, 8 or 16)
     int k = 8;               // xs: column stripes (8 or 16: one or two per XCD)
     int xwin = 0;            // bsell: stage the x window of 32 slices in LDS when it fits
+    int w = 0;               // xl: columns per LDS x window (0 = 64 KiB worth)
+    int rb = 16384;          // xl: rows per block of the reduce launch (their sums live in LDS)
 };
 PlanSpec parse_spec(const std::string &s);
 std::string print_spec(const PlanSpec &p);
@@ -105,7 +112,7 @@ struct DevArray {
     bool read_per_run = true;    // counts towards the algorithmic bytes of one run
 };
 
-enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS, K_COO };
+enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS, K_COO, K_XL_MUL, K_XL_REDUCE };
 
 // One kernel launch of spmv_run.  Pointers refer to entries of Plan::arrays.
 struct Part {

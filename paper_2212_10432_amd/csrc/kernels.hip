@@ -706,6 +706,132 @@ __global__ __launch_bounds__(kReduceWaves * kWave) void k_reduce_wide(const T *_
     }
 }
 
+// ---- two passes with x windows in LDS ---------------------------------------------------------
+// For rows too short and too scattered for any tile of x to be reused from a cache: COL_DIV cuts
+// the columns into windows small enough for LDS, and the part's entries are stored window by
+// window (inside a window by row block, then by row).  The first launch stages a window of x in
+// LDS and writes one product per stored entry to scratch, at the entry's own index; everything it
+// touches in memory is streamed.  The second launch owns one block of rows per workgroup, keeps a
+// double accumulator per row in LDS and adds the block's products, which it finds through a list
+// of 16-entry groups (SHMEM_OFFSET_RED).  Runs of one (window, row block) pair are padded to whole
+// groups with (value 0, local column 0, local row 0).
+typedef double xl_d2 __attribute__((ext_vector_type(2)));
+typedef float xl_f4 __attribute__((ext_vector_type(4)));
+typedef unsigned short xl_u2 __attribute__((ext_vector_type(2)));
+typedef unsigned short xl_u4 __attribute__((ext_vector_type(4)));
+template <typename T> struct XlVec;
+template <> struct XlVec<double> { typedef xl_d2 V; typedef xl_u2 I; static constexpr int N = 2; };
+template <> struct XlVec<float> { typedef xl_f4 V; typedef xl_u4 I; static constexpr int N = 4; };
+
+constexpr int kXlWG = 1024;
+// item i = (window, first entry, end entry); both entry numbers are multiples of 16
+template <typename T, int U>
+__global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ item,
+                                                  const T *__restrict__ vals,
+                                                  const uint16_t *__restrict__ lcol,
+                                                  const T *__restrict__ x, T *__restrict__ prod, int W,
+                                                  int64_t ncols) {
+    typedef typename XlVec<T>::V V;
+    typedef typename XlVec<T>::I I;
+    constexpr int N = XlVec<T>::N;
+    extern __shared__ __align__(16) unsigned char smem[];
+    T *xs = reinterpret_cast<T *>(smem);
+    const int s = item[3 * blockIdx.x];
+    const int64_t b = item[3 * blockIdx.x + 1], e = item[3 * blockIdx.x + 2];
+    const int64_t c0 = (int64_t)s * W;
+    const int w = (int)((ncols - c0) < (int64_t)W ? (ncols - c0) : (int64_t)W);
+    for (int i = threadIdx.x; i < w; i += kXlWG) xs[i] = x[c0 + i];
+    __syncthreads();
+    const V *vv = reinterpret_cast<const V *>(vals + b);
+    const I *cc = reinterpret_cast<const I *>(lcol + b);
+    V *pp = reinterpret_cast<V *>(prod + b);
+    const int64_t nv = (e - b) / N;
+    int64_t i = threadIdx.x;
+    for (; i + (int64_t)(U - 1) * kXlWG < nv; i += (int64_t)U * kXlWG) {
+        V v[U];
+        I c[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            v[u] = ldnt(vv + i + u * kXlWG);
+            c[u] = ldnt(cc + i + u * kXlWG);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            V r;
+#pragma unroll
+            for (int k = 0; k < N; ++k) r[k] = v[u][k] * xs[c[u][k]];
+            __builtin_nontemporal_store(r, pp + i + u * kXlWG);
+        }
+    }
+    for (; i < nv; i += kXlWG) {
+        const V v = ldnt(vv + i);
+        const I c = ldnt(cc + i);
+        V r;
+#pragma unroll
+        for (int k = 0; k < N; ++k) r[k] = v[k] * xs[c[k]];
+        __builtin_nontemporal_store(r, pp + i);
+    }
+}
+
+// Block blk adds the groups glist[gptr[blk]] .. glist[gptr[blk + 1] - 1].  A lane reads 16 bytes of
+// products, so 16 / N lanes share a group and one load instruction of a wavefront covers 64 * N
+// entries; a wavefront takes 64 list entries at a time and fetches the next 64 while it adds.
+template <typename T, bool ROWS, bool ACC>
+__global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__ gptr,
+                                                     const int32_t *__restrict__ glist,
+                                                     const T *__restrict__ prod,
+                                                     const uint16_t *__restrict__ lrow,
+                                                     const int32_t *__restrict__ rows,
+                                                     T *__restrict__ y, int RB, int64_t n) {
+    typedef typename XlVec<T>::V V;
+    typedef typename XlVec<T>::I I;
+    constexpr int N = XlVec<T>::N, LPG = kXlGroup / N, GPI = kWave / LPG, IT = kWave / GPI;
+    extern __shared__ __align__(16) unsigned char smem[];
+    double *acc = reinterpret_cast<double *>(smem);
+    for (int i = threadIdx.x; i < RB; i += kXlWG) acc[i] = 0.0;
+    __syncthreads();
+    const int64_t blk = blockIdx.x;
+    const int32_t g0 = gptr[blk], g1 = gptr[blk + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane / LPG, l = lane % LPG;
+    const V *pv = reinterpret_cast<const V *>(prod);
+    const I *pr = reinterpret_cast<const I *>(lrow);
+    int32_t base = g0 + wave * kWave;
+    int32_t mine = (base + lane < g1) ? ldnt(glist + base + lane) : -1;
+    while (base < g1) {   // uniform over the wavefront
+        const int32_t nbase = base + (kXlWG / kWave) * kWave;
+        const int32_t next = (nbase + lane < g1) ? ldnt(glist + nbase + lane) : -1;
+        V v[IT];
+        I r[IT];
+        bool ok[IT];
+#pragma unroll
+        for (int u = 0; u < IT; ++u) {
+            const int32_t gid = __shfl(mine, u * GPI + sub, kWave);
+            ok[u] = gid >= 0;
+            if (ok[u]) {
+                const int64_t q = (int64_t)gid * LPG + l;
+                v[u] = ldnt(pv + q);
+                r[u] = ldnt(pr + q);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < IT; ++u)
+            if (ok[u]) {
+#pragma unroll
+                for (int k = 0; k < N; ++k) atomic_add(&acc[r[u][k]], (double)v[u][k]);
+            }
+        base = nbase;
+        mine = next;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < RB; i += kXlWG) {
+        const int64_t pos = blk * RB + i;
+        if (pos < n) {
+            const int64_t row = ROWS ? (int64_t)rows[pos] : pos;
+            y[row] = ACC ? y[row] + (T)acc[i] : (T)acc[i];
+        }
+    }
+}
+
 // -------------------------------------------------------------------------------------------
 template <typename T>
 int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, hipStream_t st) {
@@ -908,6 +1034,43 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (p.units == 0) return 0;
         k_coo<T><<<blocks(p.units, kWG), kWG, 0, st>>>((const int32_t *)p.p0, (const int32_t *)p.p1,
                                                        (const T *)p.p2, x, y, p.units);
+        break;
+    }
+    case K_XL_MUL: {
+        if (p.units == 0) return 0;
+        constexpr int U = sizeof(T) == 8 ? 4 : 2;
+        const size_t lds = (size_t)p.tile * sizeof(T);
+        static std::atomic<int> lds_set{0};
+        if (lds > 65536 && !lds_set.load()) {
+            hipError_t e = hipFuncSetAttribute((const void *)k_xl_mul<T, U>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
+            if (e != hipSuccess) return (int)e;
+            lds_set.store(1);
+        }
+        k_xl_mul<T, U><<<(unsigned)p.units, kXlWG, lds, st>>>((const int32_t *)p.p0, (const T *)p.p1,
+                                                             (const uint16_t *)p.p2, x, (T *)p.scratch,
+                                                             p.tile, ncols);
+        break;
+    }
+    case K_XL_REDUCE: {
+        if (p.units == 0) return 0;
+        const size_t lds = (size_t)p.tile * sizeof(double);
+#define XLR_GO(Rw, A)                                                                              \
+    {                                                                                              \
+        static std::atomic<int> lds_set{0};                                                        \
+        if (lds > 65536 && !lds_set.load()) {                                                      \
+            hipError_t e = hipFuncSetAttribute((const void *)k_xl_reduce<T, Rw, A>,                \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,        \
+                                               (int)kMaxLds);                                      \
+            if (e != hipSuccess) return (int)e;                                                    \
+            lds_set.store(1);                                                                      \
+        }                                                                                          \
+        k_xl_reduce<T, Rw, A><<<(unsigned)p.units, kXlWG, lds, st>>>(                              \
+            (const int32_t *)p.p0, (const int32_t *)p.p1, (const T *)p.scratch,                    \
+            (const uint16_t *)p.p2, (const int32_t *)p.p3, y, p.tile, p.nrows);                    \
+    }
+        if (p.has_rows) { if (p.accumulate) XLR_GO(true, true) else XLR_GO(true, false) }
+        else            { if (p.accumulate) XLR_GO(false, true) else XLR_GO(false, false) }
+#undef XLR_GO
         break;
     }
     case K_REDUCE_WIDE: {

@@ -127,7 +127,18 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             p.r = 16;
             return p;
         };
+        auto xl_plan = [&](int64_t th, int tl, int rb) {
+            PlanSpec p = xs_plan(th, 8, tl);
+            p.light = L_XL;
+            p.sigma = 0;
+            p.w = 0;
+            p.rb = rb;
+            return p;
+        };
         if (striping) {
+            // x far larger than the L2s: windows of x in LDS, products through scratch
+            push(xl_plan(th0, tile / 2, 16384));
+            push(xl_plan(th0, tile / 2, 8192));
             // the stripe of x an XCD gathers from should be about half its 4 MB L2 or less
             const int k1 = 2 * k0 <= 32 ? 2 * k0 : k0;
             push(xnb_plan(th0, k1, tile / 2));

@@ -69,6 +69,7 @@ static const char *light_name(int l) {
     case L_NNZB: return "nnzb";
     case L_XNB: return "xnb";
     case L_COO: return "coo";
+    case L_XL: return "xl";
     }
     return "?";
 }
@@ -99,6 +100,7 @@ PlanSpec parse_spec(const std::string &s) {
             else if (v == "nnzb") p.light = L_NNZB;
             else if (v == "xnb") p.light = L_XNB;
             else if (v == "coo") p.light = L_COO;
+            else if (v == "xl") p.light = L_XL;
             else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown light design " + v);
         } else if (k == "dia") p.dia = (int)num();
         else if (k == "dia_fill") p.dia_fill = num();
@@ -113,6 +115,8 @@ PlanSpec parse_spec(const std::string &s) {
         else if (k == "xwin") p.xwin = (int)num();
         else if (k == "k") p.k = (int)num();
         else if (k == "r") p.r = (int)num();
+        else if (k == "w") p.w = (int)num();
+        else if (k == "rb") p.rb = (int)num();
         else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown key " + k);
     }
     if (p.dia != 0 && p.dia != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia must be 0 or 1");
@@ -127,6 +131,8 @@ PlanSpec parse_spec(const std::string &s) {
     if (p.remap != 0 && p.remap != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: remap must be 0 or 1");
     if (p.k != 8 && p.k != 16 && p.k != 24 && p.k != 32) fail(SPMV_ERR_INVALID_ARG, "plan spec: k must be 8, 16, 24 or 32");
     if (p.r != 4 && p.r != 8 && p.r != 16) fail(SPMV_ERR_INVALID_ARG, "plan spec: r must be 4, 8 or 16");
+    if (p.w != 0 && (p.w < 64 || p.w > 32768 || p.w % 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: w must be 0 or a multiple of 64 in [64, 32768]");
+    if (p.rb < 64 || p.rb > 16384 || p.rb % 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: rb must be a multiple of 64 in [64, 16384]");
     if (p.xwin != 0 && p.xwin != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin must be 0 or 1");
     if (p.xwin && p.light != L_BSELL) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin needs light=bsell");
     if (p.light == L_BSELL && (p.dia || p.heavy)) fail(SPMV_ERR_INVALID_ARG, "plan spec: bsell cannot be combined with dia or heavy");
@@ -146,6 +152,7 @@ std::string print_spec(const PlanSpec &p) {
     case L_XS: o << ",k=" << p.k << ",sigma=" << p.sigma; break;
     case L_NNZB: o << ",r=" << p.r; break;
     case L_XNB: o << ",k=" << p.k << ",r=" << p.r; break;
+    case L_XL: o << ",w=" << p.w << ",rb=" << p.rb << ",chunk=" << p.chunk; break;
     }
     o << ",remap=" << p.remap;
     return o.str();
@@ -193,6 +200,11 @@ std::string operator_chain(const PlanSpec &p) {
     case L_XNB:
         o << " -> COL_DIV(" << p.k << " stripes, stripe s on XCD s mod 8) -> BMW_NNZ_BLOCK(" << 64 * p.r
           << ") -> BMT_NNZ_BLOCK(" << p.r << ") -> THREAD_BITMAP_RED -> WARP_SEG_RED -> SCRATCH_ROW_RED(bitmap)";
+        break;
+    case L_XL:
+        o << " -> COL_DIV(" << (p.w ? std::to_string(p.w) : std::string("64 KiB of")) << " columns, x window in LDS) -> BMTB_NNZ_BLOCK("
+          << (p.chunk ? std::to_string(p.chunk) : std::string("auto")) << ") -> BMT_NNZ_BLOCK(" << "16 bytes) -> SCRATCH_PRODUCTS"
+          << " -> ROW_DIV(" << p.rb << " rows) -> SHMEM_OFFSET_RED";
         break;
     case L_XS:
         o << " -> COL_DIV(" << p.k << " stripes, stripe s on XCD s mod 8)";
