@@ -422,7 +422,7 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
     are stored window by window, block by block inside a window, by part position and row order
     inside a run, each padded to a multiple of 16 entries with (value 0, local column 0, local row
     0).  items: (window, first entry, end entry) pieces of a window's entries, m = ceil(len / chunk)
-    pieces of ceil16(ceil(len / m)) entries; chunk 0 means max(4096, ceil16(ceil(total / 1024))).
+    pieces of ceil16(ceil(len / m)) entries; chunk 0 means 32768.
     glist: for block b the 16-entry groups of runs (0, b), (1, b), ...; gptr: its offsets per block."""
     rows = np.asarray(rows, dtype=np.int32)
     n = rows.size
@@ -454,7 +454,7 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
     lcol[dst] = (c[order] % W).astype(np.uint16)
     lrow[dst] = (pos_of_entry[order] % RB).astype(np.uint16)
     ceil16 = lambda v: -(-v // G) * G
-    chunk = ceil16(chunk) if chunk > 0 else max(4096, ceil16(-(-tot // 1024)))
+    chunk = ceil16(chunk) if chunk > 0 else 32768
     items = []
     for s_ in range(S):
         b0, e0 = int(start[s_ * B]), int(start[(s_ + 1) * B])

@@ -940,7 +940,8 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
 // by part position and then in row order; every run is padded to a multiple of 16 entries with
 // (value 0, local column 0, local row 0).  Entry g holds vals[g], lcol[g] = c - s*W and
 // lrow[g] = i - b*RB; its product goes to scratch[g].  The multiply launch works through items
-// (s, first entry, end entry): a window's entries cut into pieces of about `chunk` entries.  The
+// (s, first entry, end entry): a window's entries cut into equal pieces of at most `chunk` entries
+// (32768 unless the spec says otherwise).  The
 // reduce launch of block b adds the 16-entry groups glist[gptr[b]] .. glist[gptr[b+1] - 1]: the
 // groups of runs (0, b), (1, b), ... in that order.
 template <typename T>
@@ -998,8 +999,7 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
         }
     });
     // items of the multiply launch
-    int64_t chunk = chunk_spec > 0 ? (chunk_spec + G - 1) / G * G
-                                   : std::max<int64_t>(4096, ((tot + 1023) / 1024 + G - 1) / G * G);
+    const int64_t chunk = chunk_spec > 0 ? (chunk_spec + G - 1) / G * G : 32768;
     std::vector<int32_t> items;
     for (int64_t s = 0; s < S; ++s) {
         const int64_t b0 = start[(size_t)(s * B)], e0 = start[(size_t)((s + 1) * B)];

@@ -88,7 +88,7 @@ struct PlanSpec {
     int light = L_CSRV;      // design of the remaining rows
     int lpr = 0;             // csrv: lanes per row (power of two <= 64; 0 = from the mean length)
     int64_t chunk = 0;       // csrv: rows longer than this are cut into segments (0 = never)
-                             // xl: entries per workgroup of the multiply launch (0 = chosen by the builder)
+                             // xl: most entries per workgroup of the multiply launch (0 = 32768)
     int sigma = 0;           // sell/bsell: sort window in rows (0 = no sort, -1 = whole part)
     int block = 3;           // bsell: block edge (2, 3 or 4)
     int smax = 16;           // bin: rows up to this length go to the SELL bin

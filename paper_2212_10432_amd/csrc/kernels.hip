@@ -661,14 +661,36 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
         const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
         for (int i = threadIdx.x; i < w; i += kHeavyWG) xs[i] = x[c0 + i];
         __syncthreads();
-        for (int g = threadIdx.x >> 6; g < nsl; g += kHeavyWG / kWave) {
+        // the offsets and the row ids of the next slice are fetched while this one is summed:
+        // with many short slices per stripe the chain of dependent loads is what costs
+        int g = threadIdx.x >> 6;
+        int32_t b = 0, e = 0;
+        uint16_t lr = 0xFFFFu;
+        if (g < nsl) {
             const int64_t u = (int64_t)s * nsl + g;
-            const int32_t b = unit_ptr[u];
-            const int wd = (unit_ptr[u + 1] - b) >> 6;
-            if (wd == 0) continue;
-            const T acc = sell_lane_sum<T, uint16_t>(lcol + b + lane, vals + b + lane, wd, xs);
-            const uint16_t lr = lane_row[u * 64 + lane];
-            if (lr != 0xFFFFu) ys[lr] += acc;
+            b = unit_ptr[u];
+            e = unit_ptr[u + 1];
+            lr = lane_row[u * 64 + lane];
+        }
+        while (g < nsl) {   // uniform over the wavefront
+            const int gn = g + kHeavyWG / kWave;
+            int32_t bn = 0, en = 0;
+            uint16_t lrn = 0xFFFFu;
+            if (gn < nsl) {
+                const int64_t un = (int64_t)s * nsl + gn;
+                bn = unit_ptr[un];
+                en = unit_ptr[un + 1];
+                lrn = lane_row[un * 64 + lane];
+            }
+            const int wd = (e - b) >> 6;
+            if (wd != 0) {
+                const T acc = sell_lane_sum<T, uint16_t>(lcol + b + lane, vals + b + lane, wd, xs);
+                if (lr != 0xFFFFu) ys[lr] += acc;
+            }
+            g = gn;
+            b = bn;
+            e = en;
+            lr = lrn;
         }
     }
     __syncthreads();
@@ -686,16 +708,17 @@ __global__ __launch_bounds__(kReduceWaves * kWave) void k_reduce_wide(const T *_
     __shared__ T red[kReduceWaves][kWave];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * kWave + lane;
-    T a0 = T(0), a1 = T(0);
+    // eight independent loads per step: the launch has few workgroups and lives on latency
+    T a[8] = {T(0), T(0), T(0), T(0), T(0), T(0), T(0), T(0)};
     if (i < n) {
         int g = wave;
-        for (; g + kReduceWaves < np; g += 2 * kReduceWaves) {
-            a0 += partial[(int64_t)g * n + i];
-            a1 += partial[(int64_t)(g + kReduceWaves) * n + i];
+        for (; g + 7 * kReduceWaves < np; g += 8 * kReduceWaves) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] += partial[(int64_t)(g + u * kReduceWaves) * n + i];
         }
-        for (; g < np; g += kReduceWaves) a0 += partial[(int64_t)g * n + i];
+        for (; g < np; g += kReduceWaves) a[0] += partial[(int64_t)g * n + i];
     }
-    red[wave][lane] = a0 + a1;
+    red[wave][lane] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     __syncthreads();
     if (wave == 0 && i < n) {
         T acc = T(0);

@@ -138,15 +138,15 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
         if (striping) {
             // x far larger than the L2s: windows of x in LDS, products through scratch
             push(xl_plan(th0, tile / 2, 16384));
+            if (th0) push(xl_plan(th0, tile, 16384));
             push(xl_plan(th0, tile / 2, 8192));
-            // the stripe of x an XCD gathers from should be about half its 4 MB L2 or less
+            if (th0 && tail_ok(2 * th0)) push(xl_plan(2 * th0, tile / 2, 16384));
+            // x in the L2s instead: the stripe of x an XCD gathers from should be about half its
+            // 4 MB L2 or less
             const int k1 = 2 * k0 <= 32 ? 2 * k0 : k0;
             push(xnb_plan(th0, k1, tile / 2));
             if (k1 != k0) push(xnb_plan(th0, k0, tile / 2));
-            if (2 * k1 <= 32) push(xnb_plan(th0, 2 * k1, tile / 2));
             push(xnb_plan(th0, k1, tile));
-            if (th0 && tail_ok(2 * th0)) push(xnb_plan(2 * th0, k1, tile / 2));
-            if (th0 && tail_ok(4 * th0)) push(xnb_plan(4 * th0, k1, tile / 2));
             push(xs_plan(th0, k1, tile / 2));
         }
         push(bin_plan(th0));
