@@ -48,11 +48,46 @@ __device__ __forceinline__ T group_sum(T v) {
 // Sum of one lane of a SELL slice: entries at c[64*j], v[64*j], j < w (w is uniform over the
 // wavefront).  Four independent loads and gathers are in flight per step; the last 1-3 entries
 // are issued together as well instead of one dependent load-gather chain per entry.
-template <typename T, typename CI>
+// WIDE adds front loops with sixteen and eight entries in flight (long slices of narrow entries).
+template <typename T, typename CI, bool WIDE = false>
 __device__ __forceinline__ T sell_lane_sum(const CI *__restrict__ c, const T *__restrict__ v, int w,
                                            const T *__restrict__ xsrc) {
     T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
     int j = 0;
+    if (WIDE) {
+        for (; j + 16 <= w; j += 16) {
+            CI cc[16];
+            T vv[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                cc[u] = ldnt(c + (j + u) * 64);
+                vv[u] = ldnt(v + (j + u) * 64);
+            }
+#pragma unroll
+            for (int u = 0; u < 16; u += 4) {
+                a0 += vv[u + 0] * xsrc[cc[u + 0]];
+                a1 += vv[u + 1] * xsrc[cc[u + 1]];
+                a2 += vv[u + 2] * xsrc[cc[u + 2]];
+                a3 += vv[u + 3] * xsrc[cc[u + 3]];
+            }
+        }
+        for (; j + 8 <= w; j += 8) {
+            CI cc[8];
+            T vv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                cc[u] = ldnt(c + (j + u) * 64);
+                vv[u] = ldnt(v + (j + u) * 64);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; u += 4) {
+                a0 += vv[u + 0] * xsrc[cc[u + 0]];
+                a1 += vv[u + 1] * xsrc[cc[u + 1]];
+                a2 += vv[u + 2] * xsrc[cc[u + 2]];
+                a3 += vv[u + 3] * xsrc[cc[u + 3]];
+            }
+        }
+    }
     for (; j + 4 <= w; j += 4) {
         const CI c0 = ldnt(c + (j + 0) * 64), c1 = ldnt(c + (j + 1) * 64);
         const CI c2 = ldnt(c + (j + 2) * 64), c3 = ldnt(c + (j + 3) * 64);
@@ -684,7 +719,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
             }
             const int wd = (e - b) >> 6;
             if (wd != 0) {
-                const T acc = sell_lane_sum<T, uint16_t>(lcol + b + lane, vals + b + lane, wd, xs);
+                const T acc = sell_lane_sum<T, uint16_t, true>(lcol + b + lane, vals + b + lane, wd, xs);
                 if (lr != 0xFFFFu) ys[lr] += acc;
             }
             g = gn;
