@@ -178,6 +178,116 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
     return out;
 }
 
+// Level-two candidates: the given plan with one numeric parameter halved or doubled.  Illegal
+// combinations are left to parse-time checks here and to the builder (which rejects them).
+static std::vector<PlanSpec> neighbours(const PlanSpec &b, spmv_dtype_t dtype) {
+    std::vector<PlanSpec> out;
+    auto add = [&](PlanSpec p) { out.push_back(p); };
+    const int vsize = dtype == SPMV_F64 ? 8 : 4;
+    if (b.heavy > 0) {
+        PlanSpec p = b;
+        p.heavy = b.heavy * 2;
+        add(p);
+        if (b.heavy >= 128) {
+            p.heavy = b.heavy / 2;
+            add(p);
+        }
+        if (b.tile * 2 * vsize <= 65536) {
+            p = b;
+            p.tile = b.tile * 2;
+            add(p);
+        }
+        if (b.tile >= 1024) {
+            p = b;
+            p.tile = b.tile / 2;
+            add(p);
+        }
+    }
+    switch (b.light) {
+    case L_XL: {
+        const int w = b.w ? b.w : 65536 / vsize;
+        PlanSpec p = b;
+        if ((int64_t)w * 2 * vsize <= kXlMaxLds) {
+            p.w = w * 2;
+            add(p);
+        }
+        p = b;
+        p.w = w / 2;
+        if (p.w >= 1024) add(p);
+        p = b;
+        p.rb = b.rb / 2;
+        if (p.rb >= 1024) add(p);
+        p = b;
+        p.rb = b.rb * 2;
+        if ((int64_t)p.rb * 8 <= kXlMaxLds) add(p);
+        const int64_t ch = b.chunk ? b.chunk : 32768;
+        p = b;
+        p.chunk = ch * 2;
+        add(p);
+        p = b;
+        p.chunk = ch / 2;
+        if (p.chunk >= 4096) add(p);
+        break;
+    }
+    case L_XNB:
+    case L_XS: {
+        PlanSpec p = b;
+        if (b.k + 8 <= 32) {
+            p.k = b.k + 8;
+            add(p);
+        }
+        if (b.k - 8 >= 8) {
+            p = b;
+            p.k = b.k - 8;
+            add(p);
+        }
+        if (b.light == L_XNB && b.r == 16) {
+            p = b;
+            p.r = 8;
+            add(p);
+        }
+        break;
+    }
+    case L_SELL:
+    case L_BSELL:
+    case L_BIN: {
+        if (b.sigma > 0) {
+            PlanSpec p = b;
+            p.sigma = b.sigma * 2;
+            add(p);
+            if (b.sigma >= 128 && !(b.light == L_BSELL && b.xwin)) {
+                p.sigma = b.sigma / 2;
+                add(p);
+            }
+        }
+        if (b.light == L_BIN) {
+            PlanSpec p = b;
+            p.smax = b.smax * 2;
+            if (p.smax <= 1024) add(p);
+            p.smax = b.smax / 2;
+            if (p.smax >= 2) add(p);
+        }
+        break;
+    }
+    case L_CSRV: {
+        if (b.lpr > 0) {
+            PlanSpec p = b;
+            if (b.lpr < 64) {
+                p.lpr = b.lpr * 2;
+                add(p);
+            }
+            if (b.lpr > 1) {
+                p.lpr = b.lpr / 2;
+                add(p);
+            }
+        }
+        break;
+    }
+    default: break;
+    }
+    return out;
+}
+
 double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t e0, e1;
@@ -264,34 +374,51 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
     std::unique_ptr<Plan> best;
     double best_us = 0;
     const double start = now_ms();
-    try {
-        for (size_t i = 0; i < cands.size(); ++i) {
-            CandidateLog l;
-            l.spec = print_spec(cands[i]);
-            if (best && now_ms() - start > budget) {
-                l.note = "skipped: search budget used up";
-                log.push_back(l);
-                continue;
-            }
-            const double t0 = now_ms();
-            std::unique_ptr<Plan> plan;
-            try {
-                plan = build_plan(A, cen, cands[i], mem, threads);
-            } catch (const Error &e) {
-                if (e.code == SPMV_ERR_HIP) throw;
-                l.note = "rejected: " + e.msg;
-                log.push_back(l);
-                continue;
-            }
-            l.build_ms = now_ms() - t0;
-            l.run_us = time_plan(*plan, x, y, repeats, st);
-            if (opts.verbosity > 0)
-                std::fprintf(stderr, "[spmv search] %-70s build %8.1f ms  run %10.2f us\n", l.spec.c_str(), l.build_ms, l.run_us);
-            if (!best || l.run_us < best_us) {
-                best = std::move(plan);
-                best_us = l.run_us;
-            }
+    // build, time and log one candidate; keeps it when it is the fastest so far
+    auto evaluate = [&](const PlanSpec &spec, const char *tag) {
+        CandidateLog l;
+        l.spec = print_spec(spec);
+        for (const CandidateLog &seen : log)
+            if (seen.spec == l.spec) return false;   // tried already
+        if (best && now_ms() - start > budget) {
+            l.note = "skipped: search budget used up";
             log.push_back(l);
+            return false;
+        }
+        const double t0 = now_ms();
+        std::unique_ptr<Plan> plan;
+        try {
+            plan = build_plan(A, cen, spec, mem, threads);
+        } catch (const Error &e) {
+            if (e.code == SPMV_ERR_HIP) throw;
+            l.note = "rejected: " + e.msg;
+            log.push_back(l);
+            return false;
+        }
+        l.build_ms = now_ms() - t0;
+        l.run_us = time_plan(*plan, x, y, repeats, st);
+        if (opts.verbosity > 0)
+            std::fprintf(stderr, "[spmv search] %-6s %-70s build %8.1f ms  run %10.2f us\n", tag, l.spec.c_str(), l.build_ms, l.run_us);
+        bool better = false;
+        if (!best || l.run_us < best_us) {
+            best = std::move(plan);
+            best_us = l.run_us;
+            better = true;
+        }
+        log.push_back(l);
+        return better;
+    };
+    try {
+        // level one: the pruned list of designs, each with its default parameters
+        for (const PlanSpec &c : cands) evaluate(c, "design");
+        // level two (Section VI-A: parameters of the kept design on a finer grid): halve and double
+        // every numeric parameter of the best plan, move to the best neighbour, repeat while that
+        // gains more than one percent and the budget lasts
+        for (int round = 0; best && round < 3 && now_ms() - start <= budget; ++round) {
+            const PlanSpec base = best->spec;
+            const double before = best_us;
+            for (const PlanSpec &n : neighbours(base, A.dtype)) evaluate(n, "tune");
+            if (best_us > 0.99 * before) break;
         }
     } catch (...) {
         cleanup();
