@@ -150,6 +150,28 @@ spmv_status_t spmv_plan_bytes(const spmv_plan_t *plan, int64_t *b_plan, int64_t 
 spmv_status_t spmv_plan_launch_count(const spmv_plan_t *plan, int *n);
 spmv_status_t spmv_plan_launch_name(const spmv_plan_t *plan, int i, const char **name);
 
+/* ---- Matrix Market input ------------------------------------------------------------------ */
+
+/*
+ * Read a Matrix Market coordinate file, the input of the paper's tool (Section III "Overview";
+ * artifact description), into CSR arrays ready for spmv_plan_create.
+ *   path   : HOST, NUL-terminated file name
+ *   dtype  : type of the values array to produce; "integer" files are converted, "pattern" files
+ *            give the value 1 for every entry
+ *   *nrows, *ncols, *nnz : sizes; nnz counts the entries after a symmetric or skew-symmetric file
+ *            has been expanded to both triangles
+ *   *row_ptr (nrows+1), *col_idx (nnz), *values (nnz of dtype) : HOST arrays allocated by the
+ *            library and OWNED BY THE CALLER, to be released with spmv_mm_free.  Rows ascend,
+ *            columns ascend inside a row, repeated positions are kept (in file order; they add).
+ * Errors: unreadable file, malformed banner / size line / entry -> SPMV_ERR_INVALID_ARG; an entry
+ * outside the matrix -> SPMV_ERR_BAD_CSR; dense ("array") files, complex or hermitian matrices,
+ * sizes >= 2^31 -> SPMV_ERR_UNSUPPORTED.  On failure the three pointers are NULL.
+ */
+spmv_status_t spmv_mm_read(const char *path, spmv_dtype_t dtype, int64_t *nrows, int64_t *ncols,
+                           int64_t *nnz, int32_t **row_ptr, int32_t **col_idx, void **values);
+/* Release the arrays of spmv_mm_read (NULLs are fine). */
+spmv_status_t spmv_mm_free(int32_t *row_ptr, int32_t *col_idx, void *values);
+
 /* Message of the last failure on the calling thread ("" if none). */
 const char *spmv_last_error(void);
 

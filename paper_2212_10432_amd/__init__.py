@@ -22,7 +22,7 @@ _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC"
 
 EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
            "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
-           "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error"]
+           "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error", "spmv_mm_read", "spmv_mm_free"]
 
 
 class SpmvError(RuntimeError):
@@ -90,6 +90,10 @@ def load():
     lib.spmv_plan_launch_name.argtypes = [vp, ci, P(ctypes.c_char_p)]
     lib.spmv_last_error.restype = ctypes.c_char_p
     lib.spmv_last_error.argtypes = []
+    lib.spmv_mm_read.restype = ci
+    lib.spmv_mm_read.argtypes = [ctypes.c_char_p, ci, P(i64), P(i64), P(i64), P(vp), P(vp), P(vp)]
+    lib.spmv_mm_free.restype = ci
+    lib.spmv_mm_free.argtypes = [vp, vp, vp]
     _lib = lib
     return lib
 
@@ -184,6 +188,35 @@ def spmv_plan_describe(plan: int) -> dict:
     buf = ctypes.create_string_buffer(need.value)
     _check(lib.spmv_plan_describe(plan, buf, need.value, None))
     return json.loads(buf.value.decode())
+
+
+def spmv_mm_free(row_ptr: int, col_idx: int, values: int) -> None:
+    """Release the three arrays spmv_mm_read allocated (addresses as integers; 0 is fine)."""
+    _check(load().spmv_mm_free(row_ptr or None, col_idx or None, values or None))
+
+
+def spmv_mm_read(path: str, dtype=np.float64):
+    """Matrix Market coordinate file -> (nrows, ncols, row_ptr, col_idx, values) as NumPy arrays
+    (copies; the library's own arrays are released before returning)."""
+    lib = load()
+    code = _dtype_code(dtype)
+    nrows, ncols, nnz = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rp, ci, va = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+    _check(lib.spmv_mm_read(os.fsencode(path), code, ctypes.byref(nrows), ctypes.byref(ncols), ctypes.byref(nnz),
+                            ctypes.byref(rp), ctypes.byref(ci), ctypes.byref(va)))
+    try:
+        n, z = nrows.value, nnz.value
+        row_ptr = np.ctypeslib.as_array(ctypes.cast(rp, ctypes.POINTER(ctypes.c_int32)), shape=(n + 1,)).copy()
+        if z:
+            col_idx = np.ctypeslib.as_array(ctypes.cast(ci, ctypes.POINTER(ctypes.c_int32)), shape=(z,)).copy()
+            ct = ctypes.c_double if code == SPMV_F64 else ctypes.c_float
+            values = np.ctypeslib.as_array(ctypes.cast(va, ctypes.POINTER(ct)), shape=(z,)).copy()
+        else:
+            col_idx = np.zeros(0, np.int32)
+            values = np.zeros(0, np.dtype(dtype))
+    finally:
+        spmv_mm_free(rp.value, ci.value, va.value)
+    return n, ncols.value, row_ptr, col_idx, values
 
 
 def spmv_plan_array_count(plan: int) -> int:

@@ -128,6 +128,34 @@ extern "C" {
 
 const char *spmv_last_error(void) { return g_last_error.c_str(); }
 
+spmv_status_t spmv_mm_read(const char *path, spmv_dtype_t dtype, int64_t *nrows, int64_t *ncols,
+                           int64_t *nnz, int32_t **row_ptr, int32_t **col_idx, void **values) {
+    if (row_ptr) *row_ptr = nullptr;
+    if (col_idx) *col_idx = nullptr;
+    if (values) *values = nullptr;
+    API_BEGIN
+    if (!path || !nrows || !ncols || !nnz || !row_ptr || !col_idx || !values)
+        fail(SPMV_ERR_INVALID_ARG, "spmv_mm_read: NULL argument");
+    if (dtype != SPMV_F32 && dtype != SPMV_F64) fail(SPMV_ERR_UNSUPPORTED, "unknown dtype");
+    MmCsr m;
+    read_matrix_market(path, dtype, m);
+    *nrows = m.nrows;
+    *ncols = m.ncols;
+    *nnz = m.nnz;
+    *row_ptr = m.row_ptr;
+    *col_idx = m.col;
+    *values = m.val;
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_mm_free(int32_t *row_ptr, int32_t *col_idx, void *values) {
+    std::free(row_ptr);
+    std::free(col_idx);
+    std::free(values);
+    return SPMV_OK;
+}
+
 spmv_status_t spmv_plan_create(spmv_plan_t **out, int64_t nrows, int64_t ncols, int64_t nnz,
                                const int32_t *row_ptr, const int32_t *col_idx, const void *values,
                                spmv_dtype_t dtype, const spmv_options_t *opts) {

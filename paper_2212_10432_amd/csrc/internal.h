@@ -8,6 +8,7 @@
 #include <cstring>
 #include <functional>
 #include <memory>
+#include <sstream>
 #include <string>
 #include <thread>
 #include <vector>
@@ -188,5 +189,13 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
 double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream);
 
 std::string describe_json(const Plan &plan);
+
+// Matrix Market coordinate file -> CSR in malloc'ed arrays (mmio.cc).  Throws Error.
+struct MmCsr {
+    int64_t nrows = 0, ncols = 0, nnz = 0;
+    int32_t *row_ptr = nullptr, *col = nullptr;
+    void *val = nullptr;
+};
+void read_matrix_market(const char *path, spmv_dtype_t dtype, MmCsr &out);
 
 }  // namespace spmv
