@@ -283,3 +283,25 @@ def test_caller_supplied_allocator_and_allocation_failure():
         assert e.value.status == lib.SPMV_ERR_ALLOC and "allocation" in e.value.message
         assert not live and stats["frees"] == fail_at - 1
     stats["fail_at"] = None
+
+
+def test_matrix_market_file_to_gpu_result(tmp_path):
+    """The path a user of the paper's tool takes: a Matrix Market file in, y out."""
+    m = inputs.hybrid(n=20011, n_heavy=5, heavy_len=5000, integer=True)
+    path = str(tmp_path / "h.mtx")
+    rows = np.repeat(np.arange(m.nrows), np.diff(m.row_ptr))
+    with open(path, "w") as f:
+        f.write("%%MatrixMarket matrix coordinate integer general\n")
+        f.write(f"{m.nrows} {m.ncols} {m.nnz}\n")
+        for r, c, v in zip(rows, m.col_idx, m.values):
+            f.write(f"{r + 1} {c + 1} {int(v)}\n")
+    nrows, ncols, rp, ci, va = lib.spmv_mm_read(path, np.float64)
+    assert np.array_equal(rp, m.row_ptr) and np.array_equal(ci, m.col_idx) and np.array_equal(va, m.values)
+
+    class M:
+        pass
+    mm = M()
+    mm.nrows, mm.ncols, mm.row_ptr, mm.col_idx = nrows, ncols, rp, ci
+    x = inputs.vector(ncols, integer=True)
+    (y,), d = gpu_spmv(mm, va, x, None, search_budget_ms=500)
+    assert np.array_equal(y, oracle.spmv(rp, ci, va, x))
