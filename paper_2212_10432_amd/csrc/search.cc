@@ -77,6 +77,20 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             p.sigma = sigma;
             push(p);
         }
+        // x larger than one L2: if the columns are scattered, SELL pays a cache line per entry;
+        // windows of x in LDS (or stripes of x per L2) do not
+        const int64_t xb = c.ncols * (dtype == SPMV_F64 ? 8 : 4);
+        if (xb > (4 << 20)) {
+            PlanSpec p;
+            p.light = L_XL;
+            push(p);
+            int k = (int)(8 * ((xb + (16 << 20) - 1) / (16 << 20)));
+            p = PlanSpec();
+            p.light = L_XNB;
+            p.k = k > 32 ? 32 : k;
+            p.r = 16;
+            push(p);
+        }
     } else {
         // irregular: BIN by length; optionally split off the heavy tail into column stripes.
         // A heavy row should keep at least a couple of entries per (row, stripe) segment.
