@@ -783,7 +783,7 @@ template <> struct XlVec<float> { typedef xl_f4 V; typedef xl_u4 I; static const
 
 constexpr int kXlWG = 1024;
 // item i = (window, first entry, end entry); both entry numbers are multiples of 16
-template <typename T, int U>
+template <typename T>
 __global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ item,
                                                   const T *__restrict__ vals,
                                                   const uint16_t *__restrict__ lcol,
@@ -804,24 +804,9 @@ __global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ it
     const I *cc = reinterpret_cast<const I *>(lcol + b);
     V *pp = reinterpret_cast<V *>(prod + b);
     const int64_t nv = (e - b) / N;
-    int64_t i = threadIdx.x;
-    for (; i + (int64_t)(U - 1) * kXlWG < nv; i += (int64_t)U * kXlWG) {
-        V v[U];
-        I c[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            v[u] = ldnt(vv + i + u * kXlWG);
-            c[u] = ldnt(cc + i + u * kXlWG);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            V r;
-#pragma unroll
-            for (int k = 0; k < N; ++k) r[k] = v[u][k] * xs[c[u][k]];
-            __builtin_nontemporal_store(r, pp + i + u * kXlWG);
-        }
-    }
-    for (; i < nv; i += kXlWG) {
+    // one 16-byte load of values per lane and step: two workgroups of 16 wavefronts per CU keep
+    // enough of them in flight (unrolling this loop was measured to be no faster)
+    for (int64_t i = threadIdx.x; i < nv; i += kXlWG) {
         const V v = ldnt(vv + i);
         const I c = ldnt(cc + i);
         V r;
@@ -1096,17 +1081,16 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     }
     case K_XL_MUL: {
         if (p.units == 0) return 0;
-        constexpr int U = sizeof(T) == 8 ? 4 : 2;
         const size_t lds = (size_t)p.tile * sizeof(T);
         static std::atomic<int> lds_set{0};
         if (lds > 65536 && !lds_set.load()) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_xl_mul<T, U>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
+            hipError_t e = hipFuncSetAttribute((const void *)k_xl_mul<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
             if (e != hipSuccess) return (int)e;
             lds_set.store(1);
         }
-        k_xl_mul<T, U><<<(unsigned)p.units, kXlWG, lds, st>>>((const int32_t *)p.p0, (const T *)p.p1,
-                                                             (const uint16_t *)p.p2, x, (T *)p.scratch,
-                                                             p.tile, ncols);
+        k_xl_mul<T><<<(unsigned)p.units, kXlWG, lds, st>>>((const int32_t *)p.p0, (const T *)p.p1,
+                                                          (const uint16_t *)p.p2, x, (T *)p.scratch,
+                                                          p.tile, ncols);
         break;
     }
     case K_XL_REDUCE: {
