@@ -31,7 +31,7 @@ WAVE = 64
 
 def parse_spec(spec: str) -> dict:
     d = dict(dia=0, dia_fill=0.5, heavy=0, tile=8192, light="csrv", lpr=0, chunk=0,
-             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8, r=8, w=0, rb=16384)
+             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8, r=8, w=0, rb=16384, hd=0)
     for tok in spec.split(","):
         if not tok:
             continue
@@ -206,9 +206,16 @@ def ref_bsell(nrows, ncols, rp, ci, va, B, sigma, xwin=0):
     return out
 
 
-def ref_stripe(ncols, rp, ci, va, hrows, tile):
+def ref_stripe(ncols, rp, ci, va, hrows, tile, delta=0):
     """Heavy rows cut into column stripes; inside a stripe the rows are ordered by decreasing number
-    of entries in that stripe (stable), sliced by 64 and padded per slice (value 0, local column 0)."""
+    of entries in that stripe (stable), sliced by 64 and padded per slice (value 0, local column 0).
+
+    delta=1: 8-bit column differences.  A segment (row, stripe) with local columns c_0 <= c_1 <= ...
+    is stored as the byte sequence d_0 = 0, d_k = c_k - c_(k-1), where a gap g > 255 is first bridged
+    by (g - 1) // 255 entries (255, value 0).  Rows are ordered by the stored length (entries +
+    bridges), a slice is padded with (0, 0) to its longest segment rounded up to a multiple of 4.
+    lane_meta = c_0 << 16 | heavy row (0xFFFF: none).  dcols packs entries 4q..4q+3 of a lane into
+    one little-endian 32-bit word at unit_ptr[u] / 4 + 64 q + lane."""
     nh = len(hrows)
     if nh == 0:
         return {}
@@ -216,6 +223,7 @@ def ref_stripe(ncols, rp, ci, va, hrows, tile):
     nsl = -(-nh // WAVE)
     unit_ptr = [0]
     lane_row = np.full(ns * nsl * WAVE, 0xFFFF, dtype=np.uint16)
+    lane_meta = np.full(ns * nsl * WAVE, 0xFFFF, dtype=np.uint32)
     lcols, vals = [], []
     for s in range(ns):
         segs = []
@@ -223,25 +231,46 @@ def ref_stripe(ncols, rp, ci, va, hrows, tile):
             e = _row_entries(rp, r)
             c = ci[e]
             m = (c >= s * tile) & (c < (s + 1) * tile)
-            segs.append(((c[m] - s * tile).astype(np.uint16), va[e][m]))
+            lc, vv = (c[m] - s * tile).astype(np.int64), va[e][m]
+            if delta:
+                d, v2 = [], []
+                for k in range(lc.size):
+                    gap = int(lc[k] - lc[k - 1]) if k else 0
+                    while gap > 255:
+                        d.append(255); v2.append(0.0); gap -= 255
+                    d.append(gap); v2.append(vv[k])
+                segs.append((np.array(d, dtype=np.uint8), np.array(v2, dtype=va.dtype), int(lc[0]) if lc.size else 0))
+            else:
+                segs.append((lc.astype(np.uint16), vv, 0))
         seglen = np.array([len(sg[0]) for sg in segs], dtype=np.int64)
         order = np.argsort(-seglen, kind="stable")
         lane_row[s * nsl * WAVE:s * nsl * WAVE + nh] = order
         for g in range(nsl):
             members = order[g * WAVE:(g + 1) * WAVE]
             w = int(seglen[members].max())
-            lc = np.zeros((w, WAVE), dtype=np.uint16)
+            if delta:
+                w = -(-w // 4) * 4
+            lc = np.zeros((w, WAVE), dtype=np.uint8 if delta else np.uint16)
             vv = np.zeros((w, WAVE), dtype=va.dtype)
             for lane, h in enumerate(members):
                 L = seglen[h]
                 lc[:L, lane] = segs[h][0]
                 vv[:L, lane] = segs[h][1]
+                lane_meta[(s * nsl + g) * WAVE + lane] = (segs[h][2] << 16) | int(h)
+            if delta:   # (w, 64) -> words: [w/4][lane][4]
+                lc = lc.reshape(w // 4, 4, WAVE).transpose(0, 2, 1)
             lcols.append(lc.reshape(-1))
             vals.append(vv.reshape(-1))
             unit_ptr.append(unit_ptr[-1] + w * WAVE)
-    return {"heavy.unit_ptr": np.array(unit_ptr, dtype=np.int32), "heavy.lcols": np.concatenate(lcols),
-            "heavy.vals": np.concatenate(vals).astype(va.dtype), "heavy.rows": np.asarray(hrows, dtype=np.int32),
-            "heavy.lane_row": lane_row}
+    out = {"heavy.unit_ptr": np.array(unit_ptr, dtype=np.int32),
+           "heavy.vals": np.concatenate(vals).astype(va.dtype), "heavy.rows": np.asarray(hrows, dtype=np.int32)}
+    if delta:
+        out["heavy.dcols"] = np.ascontiguousarray(np.concatenate(lcols)).view("<u4")
+        out["heavy.lane_meta"] = lane_meta
+    else:
+        out["heavy.lcols"] = np.concatenate(lcols)
+        out["heavy.lane_row"] = lane_row
+    return out
 
 
 def ref_xs(ncols, rp, ci, va, rows, K, sigma, nrows_total):
@@ -535,7 +564,7 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
         out.update(ref_csrv(rp, ci, va, light[L > max(128, p["smax"])], 64, p["chunk"], 0, acc, nrows, "bin2.csrv64", zero_rows))
     else:
         raise ValueError(p["light"])
-    out.update(ref_stripe(ncols, rp, ci, va, heavy, p["tile"]))
+    out.update(ref_stripe(ncols, rp, ci, va, heavy, p["tile"], p["hd"]))
     if zero_rows:
         out["zero.rows"] = np.array(sorted(set(zero_rows)), dtype=np.int32)
     return out
@@ -665,6 +694,22 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
                         r = int(order[i])
                     pos = base + lane + WAVE * np.arange(w)
                     R.append(np.full(w, r, dtype=np.int64)); C.append(cc[pos]); V.append(vv[pos])
+        elif "dcols" in a:       # heavy stripes, 8-bit column differences
+            up, dw, vv, hr, lm = a["unit_ptr"], a["dcols"], a["vals"], a["rows"], a["lane_meta"]
+            db = np.ascontiguousarray(dw.astype("<u4")).view(np.uint8)       # byte 4*word + (entry % 4)
+            nsl = -(-len(hr) // WAVE)
+            for u in range(len(up) - 1):
+                s = u // nsl
+                base, w = int(up[u]), int(up[u + 1] - up[u]) // WAVE
+                j = np.arange(w)
+                for lane in range(WAVE):
+                    h, c0 = int(lm[u * WAVE + lane]) & 0xFFFF, int(lm[u * WAVE + lane]) >> 16
+                    pos = base + lane + WAVE * j
+                    d = db[base + (j // 4) * 4 * WAVE + lane * 4 + j % 4].astype(np.int64)
+                    if h == 0xFFFF:
+                        assert not np.any(vv[pos]) and not np.any(d)
+                        continue
+                    R.append(np.full(w, int(hr[h]), dtype=np.int64)); C.append(c0 + np.cumsum(d) + s * tile); V.append(vv[pos])
         elif "lcols" in a:       # heavy stripes
             up, lc, vv, hr, lr = a["unit_ptr"], a["lcols"], a["vals"], a["rows"], a["lane_row"]
             nsl = -(-len(hr) // WAVE)

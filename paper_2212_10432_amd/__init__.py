@@ -237,6 +237,8 @@ def spmv_plan_array_copy(plan: int, i: int, value_dtype=np.float64) -> np.ndarra
         dt = np.dtype(value_dtype)
     elif name.endswith("mask"):
         dt = np.dtype(np.uint64)
+    elif name.endswith("dcols") or name.endswith("lane_meta"):
+        dt = np.dtype(np.uint32)      # packed bytes / bit fields
     else:
         dt = {1: np.dtype(np.uint8), 2: np.dtype(np.uint16), 4: np.dtype(np.int32), 8: np.dtype(np.int64)}[eb]
     assert dt.itemsize == eb, (name, dt, eb)

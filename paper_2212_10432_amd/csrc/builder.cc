@@ -475,9 +475,18 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
 // COL_DIV into stripes of `tile` columns; inside a stripe SORT_BMTB orders the heavy rows by the
 // number of entries they have there (stable, decreasing), slices of 64 rows are padded to their
 // longest segment (value 0, local column 0) and stored lane-interleaved.
+//
+// delta = 1 (index compression): a lane's columns are stored as 8-bit differences to the previous
+// column of the same (row, stripe) segment.  lane_meta[u*64 + lane] = first local column << 16 |
+// heavy row (0xFFFF: none); the difference of the first entry is 0; a gap g > 255 is bridged by
+// (g - 1) / 255 entries (difference 255, value 0) in front of the real entry; padding is
+// (difference 0, value 0).  The rows of a stripe are ordered by the stored length of their segments
+// (entries + bridges), and a slice's width is rounded up to a multiple of 4: the differences of
+// entries 4q .. 4q+3 of a lane form one 32-bit word (entry 4q in the low byte) at word
+// unit_ptr[u] / 4 + 64*q + lane.
 template <typename T>
-void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile, bool acc,
-                  const std::vector<int64_t> &lens, int threads) {
+void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile, int delta,
+                  bool acc, const std::vector<int64_t> &lens, int threads) {
     const int64_t nh = (int64_t)hrows.size();
     if (nh == 0) return;
     if ((size_t)tile * sizeof(T) > 65536) fail(SPMV_ERR_UNSUPPORTED, "heavy: tile does not fit 64 KiB of LDS");
@@ -487,9 +496,12 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     if (ns * nsl * kWave >= ((int64_t)1 << 28)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many (row, stripe) segments");
     int64_t total = 0;
     for (int32_t r : hrows) total += lens[(size_t)r];
+    auto bridges = [](int64_t gap) { return gap > 255 ? (gap - 1) / 255 : (int64_t)0; };
     // seg_len[s * nh + h] and seg_off[s * nh + h]: the entries of heavy row h inside stripe s are
-    // A[row_ptr[r] + seg_off .. + seg_len)   (columns ascend inside a row)
+    // A[row_ptr[r] + seg_off .. + seg_len)   (columns ascend inside a row); enc_len: stored length
     std::vector<int32_t> seg_len((size_t)(ns * nh), 0), seg_off((size_t)(ns * nh), 0);
+    std::vector<int32_t> enc_len;
+    if (delta) enc_len.assign((size_t)(ns * nh), 0);
     parallel_for(nh, 4, threads, [&](int64_t b, int64_t e, int) {
         for (int64_t h = b; h < e; ++h) {
             const int32_t r = hrows[(size_t)h];
@@ -497,20 +509,27 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
             for (int64_t k = beg; k < A.row_ptr[r + 1]; ++k) {
                 const size_t i = (size_t)((int64_t)(A.col[k] / tile) * nh + h);
                 if (seg_len[i]++ == 0) seg_off[i] = (int32_t)(k - beg);
+                else if (delta) enc_len[i] += (int32_t)bridges((int64_t)A.col[k] - A.col[k - 1]);
+                if (delta) enc_len[i] += 1;
             }
         }
     });
+    const std::vector<int32_t> &key = delta ? enc_len : seg_len;
     // per stripe: order of the heavy rows, slice widths
     std::vector<uint16_t> lane_row((size_t)(ns * nsl * kWave), (uint16_t)0xFFFF);
     std::vector<int64_t> unit_w((size_t)(ns * nsl), 0);
     parallel_for(ns, 1, threads, [&](int64_t sb, int64_t se, int) {
         std::vector<int32_t> order((size_t)nh);
         for (int64_t s = sb; s < se; ++s) {
-            const int32_t *sl = seg_len.data() + s * nh;
+            const int32_t *sl = key.data() + s * nh;
             std::iota(order.begin(), order.end(), 0);
             std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return sl[a] > sl[b]; });
             for (int64_t i = 0; i < nh; ++i) lane_row[(size_t)(s * nsl * kWave + i)] = (uint16_t)order[(size_t)i];
-            for (int64_t g = 0; g < nsl; ++g) unit_w[(size_t)(s * nsl + g)] = sl[order[(size_t)(g * kWave)]];
+            for (int64_t g = 0; g < nsl; ++g) {
+                int64_t w = sl[order[(size_t)(g * kWave)]];
+                if (delta) w = (w + 3) / 4 * 4;
+                unit_w[(size_t)(s * nsl + g)] = w;
+            }
         }
     });
     std::vector<int32_t> unit_ptr((size_t)(ns * nsl) + 1, 0);
@@ -520,7 +539,10 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
         if (padded >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many entries");
         unit_ptr[(size_t)u + 1] = (int32_t)padded;
     }
-    HostBuf<uint16_t> lcol(padded);
+    HostBuf<uint16_t> lcol(delta ? 0 : padded);
+    HostBuf<uint8_t> dcol(delta ? padded : 0);
+    std::vector<uint32_t> lane_meta;
+    if (delta) lane_meta.assign((size_t)(ns * nsl * kWave), 0xFFFFu);
     HostBuf<T> vals(padded);
     const T *av = (const T *)A.val;
     parallel_for(ns * nsl, 8, threads, [&](int64_t ub, int64_t ue, int) {
@@ -534,14 +556,30 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
                     src = (int64_t)A.row_ptr[hrows[h]] + seg_off[(size_t)(s * nh + h)];
                 }
                 int64_t j = 0;
-                for (; j < L; ++j) {
-                    lcol[base + j * kWave + lane] = (uint16_t)(A.col[src + j] - s * tile);
-                    vals[base + j * kWave + lane] = av[src + j];
+                if (!delta) {
+                    for (; j < L; ++j) {
+                        lcol[base + j * kWave + lane] = (uint16_t)(A.col[src + j] - s * tile);
+                        vals[base + j * kWave + lane] = av[src + j];
+                    }
+                    for (; j < w; ++j) {
+                        lcol[base + j * kWave + lane] = 0;
+                        vals[base + j * kWave + lane] = T(0);
+                    }
+                    continue;
                 }
-                for (; j < w; ++j) {
-                    lcol[base + j * kWave + lane] = 0;
-                    vals[base + j * kWave + lane] = T(0);
+                // byte of entry j: word base/4 + 64*(j/4) + lane, byte j%4 (little endian)
+                auto put = [&](int64_t jj, uint8_t d, T v) {
+                    dcol[base + (jj / 4) * 4 * kWave + (int64_t)lane * 4 + jj % 4] = d;
+                    vals[base + jj * kWave + lane] = v;
+                };
+                const uint32_t col0 = L ? (uint32_t)(A.col[src] - s * tile) : 0u;
+                lane_meta[(size_t)(u * kWave + lane)] = (col0 << 16) | (uint32_t)h;
+                for (int64_t k = 0; k < L; ++k) {
+                    int64_t gap = k ? (int64_t)A.col[src + k] - A.col[src + k - 1] : 0;
+                    for (; gap > 255; gap -= 255) put(j++, 255, T(0));
+                    put(j++, (uint8_t)gap, av[src + k]);
                 }
+                for (; j < w; ++j) put(j, 0, T(0));
             }
         }
     });
@@ -570,13 +608,16 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     p.per_group = per_group;
     p.scratch = scratch;
     p.tile = tile;
+    p.delta = delta;
     p.has_rows = true;
     const size_t a0 = plan.arrays.size();
     p.p0 = upload(plan, "heavy.unit_ptr", 4, ns * nsl + 1, unit_ptr.data());
-    p.p1 = upload(plan, "heavy.lcols", 2, padded, lcol.p);
+    if (delta) p.p1 = upload(plan, "heavy.dcols", 4, padded / 4, dcol.p);
+    else p.p1 = upload(plan, "heavy.lcols", 2, padded, lcol.p);
     p.p2 = upload(plan, "heavy.vals", (int)sizeof(T), padded, vals.p);
     p.p3 = upload(plan, "heavy.rows", 4, nh, hrows.data());
-    p.p4 = upload(plan, "heavy.lane_row", 2, ns * nsl * kWave, lane_row.data());
+    if (delta) p.p4 = upload(plan, "heavy.lane_meta", 4, ns * nsl * kWave, lane_meta.data());
+    else p.p4 = upload(plan, "heavy.lane_row", 2, ns * nsl * kWave, lane_row.data());
     plan.arrays[a0 + 3].read_per_run = false;   // heavy.rows is read by the reduce launch
     add_part(plan, p, a0, A.ncols, ngroups * nh, 0);
     plan.arrays[a0 + 3].read_per_run = true;
@@ -1378,7 +1419,7 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
     }
     default: fail(SPMV_ERR_INVALID_ARG, "unknown light design");
     }
-    if (!heavy.empty()) build_stripe<T>(*plan, A, heavy, spec.tile, acc, lens, threads);
+    if (!heavy.empty()) build_stripe<T>(*plan, A, heavy, spec.tile, spec.hd, acc, lens, threads);
 
     if (!zero_rows.empty()) {
         std::sort(zero_rows.begin(), zero_rows.end());

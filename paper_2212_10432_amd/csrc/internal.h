@@ -86,6 +86,7 @@ struct PlanSpec {
     double dia_fill = 0.5;   //   minimum population of a diagonal to be extracted
     int64_t heavy = 0;       // ROW_DIV: rows longer than this go to the heavy part (0 = no split)
     int tile = 8192;         //   COL_DIV width of the heavy part (columns per LDS tile of x)
+    int hd = 0;              //   1 = the heavy part stores 8-bit column deltas instead of 16-bit columns
     int light = L_CSRV;      // design of the remaining rows
     int lpr = 0;             // csrv: lanes per row (power of two <= 64; 0 = from the mean length)
     int64_t chunk = 0;       // csrv: rows longer than this are cut into segments (0 = never)
@@ -137,6 +138,7 @@ struct Part {
     int64_t per_group = 0;       // heavy part: stripes per workgroup
     void *scratch = nullptr;     // partial sums written by one launch and read by the next
     int uniform_w = -1;          // sell / csrv: width shared by every slice / row (-1: read the offsets)
+    int delta = 0;               // heavy part: columns stored as 8-bit deltas
     int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
     const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
     int64_t bytes = 0;           // algorithmic bytes of one launch: arrays read + x + scratch + y

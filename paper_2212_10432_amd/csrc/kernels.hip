@@ -732,6 +732,76 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
     for (int i = threadIdx.x; i < nh; i += kHeavyWG) partial[(int64_t)blockIdx.x * nh + i] = ys[i];
 }
 
+// The same part with 8-bit column differences (index compression): a lane starts at the first
+// local column of its segment (upper half of lane_meta) and adds one byte per entry; four entries
+// share a 32-bit word.  Bridging entries (difference 255, value 0) and padding (0, 0) multiply an
+// in-range x element by zero.
+template <typename T, int NW>
+__device__ __forceinline__ void hdelta_step(const uint32_t *__restrict__ dw, const T *__restrict__ vv,
+                                            int j, uint32_t &c, const T *__restrict__ xs, T &a0, T &a1,
+                                            T &a2, T &a3) {
+    uint32_t w[NW];
+    T v[4 * NW];
+#pragma unroll
+    for (int q = 0; q < NW; ++q) w[q] = ldnt(dw + ((j >> 2) + q) * 64);
+#pragma unroll
+    for (int t = 0; t < 4 * NW; ++t) v[t] = ldnt(vv + (j + t) * 64);
+#pragma unroll
+    for (int q = 0; q < NW; ++q) {
+        c += w[q] & 255u;
+        a0 += v[4 * q + 0] * xs[c];
+        c += (w[q] >> 8) & 255u;
+        a1 += v[4 * q + 1] * xs[c];
+        c += (w[q] >> 16) & 255u;
+        a2 += v[4 * q + 2] * xs[c];
+        c += w[q] >> 24;
+        a3 += v[4 * q + 3] * xs[c];
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restrict__ unit_ptr,
+                                                          const uint32_t *__restrict__ dcols,
+                                                          const T *__restrict__ vals,
+                                                          const uint32_t *__restrict__ lane_meta,
+                                                          const T *__restrict__ x, T *__restrict__ partial,
+                                                          int nsl, int nh, int tile, int64_t ncols, int ns,
+                                                          int stripes_per_wg) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    T *xs = reinterpret_cast<T *>(smem);
+    T *ys = xs + tile;
+    for (int i = threadIdx.x; i < nh; i += kHeavyWG) ys[i] = T(0);
+    const int lane = threadIdx.x & 63;
+    const int s0 = blockIdx.x * stripes_per_wg;
+    const int s1 = (s0 + stripes_per_wg < ns) ? s0 + stripes_per_wg : ns;
+    for (int s = s0; s < s1; ++s) {
+        __syncthreads();   // the previous stripe's gathers are done (first pass: ys is zeroed)
+        const int64_t c0 = (int64_t)s * tile;
+        const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
+        for (int i = threadIdx.x; i < w; i += kHeavyWG) xs[i] = x[c0 + i];
+        __syncthreads();
+        for (int g = threadIdx.x >> 6; g < nsl; g += kHeavyWG / kWave) {
+            const int64_t u = (int64_t)s * nsl + g;
+            const int32_t b = unit_ptr[u];
+            const int wd = (unit_ptr[u + 1] - b) >> 6;   // a multiple of 4
+            if (wd == 0) continue;
+            const uint32_t meta = lane_meta[u * 64 + lane];
+            uint32_t c = meta >> 16;
+            const uint32_t *dw = dcols + (b >> 2) + lane;
+            const T *vv = vals + b + lane;
+            T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
+            int j = 0;
+            for (; j + 16 <= wd; j += 16) hdelta_step<T, 4>(dw, vv, j, c, xs, a0, a1, a2, a3);
+            for (; j + 8 <= wd; j += 8) hdelta_step<T, 2>(dw, vv, j, c, xs, a0, a1, a2, a3);
+            for (; j < wd; j += 4) hdelta_step<T, 1>(dw, vv, j, c, xs, a0, a1, a2, a3);
+            const uint32_t lr = meta & 0xFFFFu;
+            if (lr != 0xFFFFu) ys[lr] += (a0 + a1) + (a2 + a3);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < nh; i += kHeavyWG) partial[(int64_t)blockIdx.x * nh + i] = ys[i];
+}
+
 // y[rows[i]] (+)= sum over g < np of partial[g * n + i]: many partials (one per workgroup of the
 // heavy kernel), few rows.  16 wavefronts split the partials, LDS combines them.
 constexpr int kReduceWaves = 16;
@@ -995,6 +1065,18 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
             hipError_t e = hipFuncSetAttribute((const void *)k_hsell<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
             if (e != hipSuccess) return (int)e;
             lds_set.store(1);
+        }
+        if (p.delta) {
+            static std::atomic<int> lds_set_d{0};
+            if (lds > 65536 && !lds_set_d.load()) {
+                hipError_t e = hipFuncSetAttribute((const void *)k_hsell_delta<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
+                if (e != hipSuccess) return (int)e;
+                lds_set_d.store(1);
+            }
+            k_hsell_delta<T><<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(
+                (const int32_t *)p.p0, (const uint32_t *)p.p1, (const T *)p.p2, (const uint32_t *)p.p4, x,
+                (T *)p.scratch, (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group);
+            break;
         }
         k_hsell<T><<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(
             (const int32_t *)p.p0, (const uint16_t *)p.p1, (const T *)p.p2, (const uint16_t *)p.p4, x,

@@ -200,6 +200,9 @@ static std::vector<PlanSpec> neighbours(const PlanSpec &b, spmv_dtype_t dtype) {
     const int vsize = dtype == SPMV_F64 ? 8 : 4;
     if (b.heavy > 0) {
         PlanSpec p = b;
+        p.hd = !b.hd;   // 8-bit column differences pay when the heavy rows are dense enough
+        add(p);
+        p = b;
         p.heavy = b.heavy * 2;
         add(p);
         if (b.heavy >= 128) {

@@ -106,6 +106,7 @@ PlanSpec parse_spec(const std::string &s) {
         else if (k == "dia_fill") p.dia_fill = num();
         else if (k == "heavy") p.heavy = (int64_t)num();
         else if (k == "tile") p.tile = (int)num();
+        else if (k == "hd") p.hd = (int)num();
         else if (k == "lpr") p.lpr = (int)num();
         else if (k == "chunk") p.chunk = (int64_t)num();
         else if (k == "sigma") p.sigma = (int)num();
@@ -133,6 +134,8 @@ PlanSpec parse_spec(const std::string &s) {
     if (p.r != 4 && p.r != 8 && p.r != 16) fail(SPMV_ERR_INVALID_ARG, "plan spec: r must be 4, 8 or 16");
     if (p.w != 0 && (p.w < 64 || p.w > 32768 || p.w % 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: w must be 0 or a multiple of 64 in [64, 32768]");
     if (p.rb < 64 || p.rb > 16384 || p.rb % 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: rb must be a multiple of 64 in [64, 16384]");
+    if (p.hd != 0 && p.hd != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: hd must be 0 or 1");
+    if (p.hd && !p.heavy) fail(SPMV_ERR_INVALID_ARG, "plan spec: hd needs heavy");
     if (p.xwin != 0 && p.xwin != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin must be 0 or 1");
     if (p.xwin && p.light != L_BSELL) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin needs light=bsell");
     if (p.light == L_BSELL && (p.dia || p.heavy)) fail(SPMV_ERR_INVALID_ARG, "plan spec: bsell cannot be combined with dia or heavy");
@@ -142,7 +145,7 @@ PlanSpec parse_spec(const std::string &s) {
 std::string print_spec(const PlanSpec &p) {
     std::ostringstream o;
     if (p.dia) o << "dia=1,dia_fill=" << p.dia_fill << ",";
-    if (p.heavy) o << "heavy=" << p.heavy << ",tile=" << p.tile << ",";
+    if (p.heavy) o << "heavy=" << p.heavy << ",tile=" << p.tile << (p.hd ? ",hd=1," : ",");
     o << "light=" << light_name(p.light);
     switch (p.light) {
     case L_CSRV: o << ",lpr=" << p.lpr << ",chunk=" << p.chunk << ",sigma=" << p.sigma; break;
@@ -167,6 +170,7 @@ std::string operator_chain(const PlanSpec &p) {
     if (p.heavy)
         o << " -> ROW_DIV(len>" << p.heavy << ")[HEAVY_SPLIT: COL_DIV(" << p.tile
           << ") -> BMTB_COL_BLOCK -> SORT_BMTB -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD"
+          << (p.hd ? " -> COMPRESS(8-bit column deltas)" : "")
           << " -> THREAD_TOTAL_RED -> GMEM_ATOM_RED]";
     auto sort = [&]() {
         if (p.sigma == -1) o << " -> SORT";

@@ -24,11 +24,11 @@ SPECS = {
     "C2": ["dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=256,rb=128", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
     "C3": ["light=xl,w=512,rb=1024", "heavy=1024,tile=2048,light=xl,w=1024,rb=512,chunk=2048", "light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=0", "light=csrv,chunk=512", "light=bin,smax=16,sigma=512,chunk=256",
            "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
-           "heavy=256,tile=512,light=sell,sigma=128"],
+           "heavy=256,tile=512,light=sell,sigma=128", "heavy=1024,tile=2048,hd=1,light=xl,w=1024,rb=512", "heavy=256,tile=512,hd=1,light=sell,sigma=128"],
     "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", "light=sell,sigma=512",
            "light=csrv,lpr=16"],
     "C5": ["heavy=64,tile=2048,light=xl,w=2048,rb=4096,chunk=4096", "light=xl,w=4096,rb=16384", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
-           "heavy=1000,tile=4096,light=csrv,lpr=2"],
+           "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=64,tile=2048,hd=1,light=xl", "heavy=64,tile=8192,hd=1,light=csrv"],
 }
 
 
