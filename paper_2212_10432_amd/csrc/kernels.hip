@@ -5,8 +5,9 @@
 //   BMTB (thread block) -> workgroup, BMW (warp, 32 lanes) -> wavefront (64 lanes), BMT -> lane.
 //
 // Every kernel streams the matrix arrays exactly once with non-temporal loads (they are never
-// reused, and must not evict x from the L2), gathers x through the ordinary cached path, and
-// writes each y element once.
+// reused, and must not evict x from the L2) and writes each y element once.  x is gathered through
+// the ordinary cached path, or from a copy of a window of x in LDS (heavy stripes, blocked SELL
+// with a window, the two-pass part).
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -490,7 +491,7 @@ __global__ __launch_bounds__(kWG) void k_xnb(const int32_t *__restrict__ cols,
 // [bbase[blk*K + s], bbase[(blk+1)*K + s]); seg_row[q] is the row (within the block) segment q
 // belongs to.  The slots are read with contiguous loads and added into one LDS accumulator per row
 // (SHMEM_OFFSET_RED: a shared-memory reduction by row offset); then y is written contiguously.
-constexpr int kRedRows = 1024;
+constexpr int kRedRows = kReduceBlockRows;   // the builder cuts the part into blocks of this many rows
 template <typename T, bool ROWS, bool ACC>
 __global__ __launch_bounds__(kWG) void k_reduce_lds(const uint16_t *__restrict__ seg_row,
                                                     const int32_t *__restrict__ bbase,
