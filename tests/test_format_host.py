@@ -246,3 +246,41 @@ def test_errors():
     assert e.value.status == lib.SPMV_ERR_UNSUPPORTED
     P.destroy()
     lib.spmv_plan_destroy(None)      # NULL is OK
+
+
+def test_random_matrices_random_plans_decode_to_input():
+    """Random shapes under random legal specs, built by the C++ builder in host memory: the arrays
+    equal the reference builder's and decode back to the input matrix."""
+    rng = np.random.default_rng(7)
+    lights = ["csrv,lpr=4,chunk=64", "sell,sigma=64", "bin,smax=4,sigma=64,chunk=128", "nnzb,r=4", "xs,k=8,sigma=128",
+              "xnb,k=16,r=8", "xl,w=64,rb=128,chunk=100", "xl,w=512,rb=64", "coo"]
+    for case in range(25):
+        nrows, ncols = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+        lens = rng.integers(0, int(rng.choice([3, 12, 40])), nrows)
+        lens[rng.random(nrows) < 0.3] = 0
+        for _ in range(int(rng.integers(0, 3))):
+            lens[int(rng.integers(0, nrows))] = int(rng.integers(50, 900))
+        rp = np.zeros(nrows + 1, np.int32)
+        np.cumsum(lens, out=rp[1:])
+        r = np.repeat(np.arange(nrows), lens)
+        # ascending columns inside a row (the reference builders assume it), repeats allowed
+        ci = np.sort(rng.integers(0, ncols, rp[-1]) + r * ncols).astype(np.int64) - r * ncols
+        ci = ci.astype(np.int32)
+        va = rng.integers(1, 9, rp[-1]).astype(np.float64)
+        A_in = as_scipy(nrows, ncols, r, ci, va)
+        head = f"heavy={int(rng.choice([8, 30]))},tile={int(rng.choice([64, 256]))}," + ("hd=1," if rng.random() < 0.5 else "") if rng.random() < 0.6 else ""
+        spec = head + "light=" + str(rng.choice(lights))
+        try:
+            P = lib.Plan(nrows, ncols, rp, ci, va, force_plan=spec, host_only=True)
+        except lib.SpmvError as e:
+            assert e.status == lib.SPMV_ERR_UNSUPPORTED, (spec, e)
+            continue
+        got = P.arrays()
+        want = ref.ref_plan(nrows, ncols, rp, ci, va, spec)
+        assert sorted(got) == sorted(want), (case, spec)
+        for k in want:
+            assert got[k].dtype == want[k].dtype and np.array_equal(got[k], want[k]), (case, spec, k)
+        p = ref.parse_spec(spec)
+        rr, cc, vv = ref.decode(got, nrows, ncols, block=p["block"], tile=p["tile"], xl_w=p["w"], xl_rb=p["rb"])
+        assert same_matrix(as_scipy(nrows, ncols, rr, cc, vv), A_in), (case, spec)
+        P.destroy()

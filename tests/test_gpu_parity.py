@@ -305,3 +305,64 @@ def test_matrix_market_file_to_gpu_result(tmp_path):
     x = inputs.vector(ncols, integer=True)
     (y,), d = gpu_spmv(mm, va, x, None, search_budget_ms=500)
     assert np.array_equal(y, oracle.spmv(rp, ci, va, x))
+
+
+def _random_spec(rng):
+    light = rng.choice(["csrv", "sell", "bin", "nnzb", "xs", "xnb", "xl", "coo"])
+    parts = []
+    if rng.random() < 0.5:
+        parts.append(f"heavy={int(rng.choice([8, 16, 40, 100]))},tile={int(rng.choice([64, 128, 512, 4096]))}")
+        if rng.random() < 0.5:
+            parts.append("hd=1")
+    parts.append(f"light={light}")
+    if light == "csrv":
+        parts.append(f"lpr={int(rng.choice([0, 1, 2, 8, 64]))},chunk={int(rng.choice([0, 64, 200]))},sigma={int(rng.choice([0, 64, -1]))}")
+    elif light == "sell":
+        parts.append(f"sigma={int(rng.choice([0, 64, 300, -1]))}")
+    elif light == "bin":
+        parts.append(f"smax={int(rng.choice([2, 8, 16]))},sigma={int(rng.choice([0, 128]))},chunk={int(rng.choice([0, 128]))}")
+    elif light == "nnzb":
+        parts.append(f"r={int(rng.choice([4, 8, 16]))}")
+    elif light == "xs":
+        parts.append(f"k={int(rng.choice([8, 16, 24, 32]))},sigma={int(rng.choice([0, 64, 1024]))}")
+    elif light == "xnb":
+        parts.append(f"k={int(rng.choice([8, 16, 24, 32]))},r={int(rng.choice([4, 8, 16]))}")
+    elif light == "xl":
+        parts.append(f"w={int(rng.choice([64, 128, 1024, 0]))},rb={int(rng.choice([64, 256, 4096, 16384]))},chunk={int(rng.choice([0, 64, 1000]))}")
+    if rng.random() < 0.3:
+        parts.append("remap=1")
+    return ",".join(parts)
+
+
+def test_random_matrices_random_plans():
+    """Differential test: random shapes (rectangular, empty rows and columns, repeated and unsorted
+    columns, a few long rows) under random legal plan specs; integer data, so bit-exact."""
+    rng = np.random.default_rng(20221113)
+
+    class M:
+        pass
+    for case in range(150):
+        nrows, ncols = int(rng.integers(1, 3000)), int(rng.integers(1, 3000))
+        lens = rng.integers(0, int(rng.choice([3, 12, 60])), nrows)
+        lens[rng.random(nrows) < 0.3] = 0
+        for _ in range(int(rng.integers(0, 4))):
+            lens[int(rng.integers(0, nrows))] = int(rng.integers(100, 4000))
+        rp = np.zeros(nrows + 1, np.int32)
+        np.cumsum(lens, out=rp[1:])
+        span = ncols if rng.random() < 0.5 else max(1, ncols // 7)      # scattered or clustered columns
+        ci = rng.integers(0, span, rp[-1]).astype(np.int32)
+        va = rng.integers(-3, 4, rp[-1]).astype(np.float64)
+        x = rng.integers(-3, 4, ncols).astype(np.float64)
+        m = M()
+        m.nrows, m.ncols, m.row_ptr, m.col_idx = nrows, ncols, rp, ci
+        want = oracle.spmv(rp, ci, va, x)
+        for _ in range(3):
+            spec = _random_spec(rng)
+            dt = np.float64 if rng.random() < 0.5 else np.float32
+            print(f"case {case}: {nrows}x{ncols} nnz {rp[-1]} {spec} {np.dtype(dt).name}", flush=True)
+            try:
+                (y,), _ = gpu_spmv(m, va.astype(dt), x.astype(dt), spec)
+            except lib.SpmvError as e:
+                assert e.status == lib.SPMV_ERR_UNSUPPORTED, (spec, e)      # e.g. too many heavy rows
+                continue
+            assert np.array_equal(y.astype(np.float64), want), (case, spec, dt)
