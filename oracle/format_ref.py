@@ -452,7 +452,8 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
     inside a run, each padded to a multiple of 16 entries with (value 0, local column 0, local row
     0).  items: (window, first entry, end entry) pieces of a window's entries, m = ceil(len / chunk)
     pieces of ceil16(ceil(len / m)) entries; chunk 0 means 32768.
-    glist: for block b the 16-entry groups of runs (0, b), (1, b), ...; gptr: its offsets per block."""
+    glist: for block b the 16-entry groups of runs (0, b), (1, b), ...; gptr: its offsets per block.
+    lrow is stored in glist order: lrow[16 p + t] is the local row of entry 16 glist[p] + t."""
     rows = np.asarray(rows, dtype=np.int32)
     n = rows.size
     if n == 0:
@@ -481,7 +482,8 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
     dst = start[run_sorted] + (np.arange(order.size) - first)
     vals[dst] = va[src[order]]
     lcol[dst] = (c[order] % W).astype(np.uint16)
-    lrow[dst] = (pos_of_entry[order] % RB).astype(np.uint16)
+    lrow_by_entry = np.zeros(tot, dtype=np.uint16)
+    lrow_by_entry[dst] = (pos_of_entry[order] % RB).astype(np.uint16)
     ceil16 = lambda v: -(-v // G) * G
     chunk = ceil16(chunk) if chunk > 0 else 32768
     items = []
@@ -502,8 +504,10 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
             glist.append(np.arange(start[j] // G, start[j + 1] // G, dtype=np.int32))
             ngroups += glist[-1].size
         gptr[b + 1] = gptr[b] + ngroups
-    out = {"xl.vals": vals, "xl.lcol": lcol, "xl.gptr": gptr,
-           "xl.glist": np.concatenate(glist).astype(np.int32) if glist else np.zeros(0, np.int32), "xl.lrow": lrow}
+    glist = np.concatenate(glist).astype(np.int32) if glist else np.zeros(0, np.int32)
+    # local rows in the order the reduce launch reads them: lrow[16 p + t] belongs to entry 16 glist[p] + t
+    lrow = lrow_by_entry.reshape(-1, G)[glist].reshape(-1) if tot else lrow
+    out = {"xl.vals": vals, "xl.lcol": lcol, "xl.gptr": gptr, "xl.glist": glist, "xl.lrow": lrow}
     if items:
         out["xl.items"] = np.array(items, dtype=np.int32)
     else:
@@ -595,7 +599,9 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
             blk = np.full(vv.size // 16, -1, dtype=np.int64)   # group -> row block, from the group list
             blk[gl] = np.repeat(np.arange(gp.size - 1), np.diff(gp))
             assert np.all(win >= 0) and np.all(blk >= 0) and np.unique(gl).size == gl.size
-            posn = np.repeat(blk, 16) * xl_rb + lr.astype(np.int64)
+            lr_by_entry = np.zeros(vv.size, dtype=np.int64)
+            lr_by_entry.reshape(-1, 16)[gl] = lr.reshape(-1, 16)
+            posn = np.repeat(blk, 16) * xl_rb + lr_by_entry
             rws = np.asarray(a["rows"]) if "rows" in a else np.arange(nrows)
             assert not np.any(vv[posn >= rws.size])
             keep = posn < rws.size

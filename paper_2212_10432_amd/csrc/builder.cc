@@ -979,12 +979,14 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
 // rows (an LDS-sized piece of y).  Entry (part position i, column c) belongs to run (s, b) =
 // (c / W, i / RB); runs are stored window by window, inside a window block by block, inside a run
 // by part position and then in row order; every run is padded to a multiple of 16 entries with
-// (value 0, local column 0, local row 0).  Entry g holds vals[g], lcol[g] = c - s*W and
-// lrow[g] = i - b*RB; its product goes to scratch[g].  The multiply launch works through items
+// (value 0, local column 0, local row 0).  Entry g holds vals[g] and lcol[g] = c - s*W; its product
+// goes to scratch[g].  The multiply launch works through items
 // (s, first entry, end entry): a window's entries cut into equal pieces of at most `chunk` entries
 // (32768 unless the spec says otherwise).  The
 // reduce launch of block b adds the 16-entry groups glist[gptr[b]] .. glist[gptr[b+1] - 1]: the
-// groups of runs (0, b), (1, b), ... in that order.
+// groups of runs (0, b), (1, b), ... in that order.  The local rows i - b*RB are stored in that
+// order too (lrow[16*p + t] belongs to entry 16*glist[p] + t), so a block reads them as one
+// contiguous piece instead of a fragment of a cache line per run.
 template <typename T>
 void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, int w_spec, int RB,
               int64_t chunk_spec, bool acc, const std::vector<int64_t> &lens, int threads) {
@@ -1014,13 +1016,27 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
         start[(size_t)j + 1] = start[(size_t)j] + (start[(size_t)j + 1] + G - 1) / G * G;
     const int64_t tot = start[(size_t)(S * B)];
     if (tot >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "xl: too many entries");
+    // group list of the reduce launch: block b reads the groups of runs (0, b), (1, b), ...
+    std::vector<int32_t> gptr((size_t)B + 1, 0);
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t c = 0;
+        for (int64_t s = 0; s < S; ++s) c += (start[(size_t)(s * B + b) + 1] - start[(size_t)(s * B + b)]) / G;
+        gptr[(size_t)b + 1] = (int32_t)(gptr[(size_t)b] + c);
+    }
     HostBuf<T> vals(tot);
     HostBuf<uint16_t> lcol(tot), lrow(tot);
+    HostBuf<int32_t> glist(tot / G);
     const T *av = (const T *)A.val;
     parallel_for(B, 1, threads, [&](int64_t bb, int64_t be, int) {
-        std::vector<int64_t> cur((size_t)S);
+        std::vector<int64_t> cur((size_t)S), lpos((size_t)S);
         for (int64_t b = bb; b < be; ++b) {
-            for (int64_t s = 0; s < S; ++s) cur[(size_t)s] = start[(size_t)(s * B + b)];
+            int64_t o = gptr[(size_t)b];
+            for (int64_t s = 0; s < S; ++s) {
+                const int64_t g0 = start[(size_t)(s * B + b)], g1 = start[(size_t)(s * B + b) + 1];
+                cur[(size_t)s] = g0;
+                lpos[(size_t)s] = o * G;           // the run's place in the block's own order
+                for (int64_t g = g0 / G; g < g1 / G; ++g) glist[o++] = (int32_t)g;
+            }
             for (int64_t i = b * RB; i < std::min(n, (b + 1) * RB); ++i) {
                 const int32_t r = rows[(size_t)i];
                 for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
@@ -1028,14 +1044,14 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
                     const int64_t g = cur[(size_t)s]++;
                     vals[g] = av[k];
                     lcol[g] = (uint16_t)(A.col[k] - s * W);
-                    lrow[g] = (uint16_t)(i - b * RB);
+                    lrow[lpos[(size_t)s]++] = (uint16_t)(i - b * RB);
                 }
             }
             for (int64_t s = 0; s < S; ++s)
                 for (int64_t g = cur[(size_t)s]; g < start[(size_t)(s * B + b) + 1]; ++g) {
                     vals[g] = T(0);
                     lcol[g] = 0;
-                    lrow[g] = 0;
+                    lrow[lpos[(size_t)s]++] = 0;
                 }
         }
     });
@@ -1054,23 +1070,6 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
         }
     }
     const int64_t nitems = (int64_t)items.size() / 3;
-    // group list of the reduce launch
-    std::vector<int32_t> gptr((size_t)B + 1, 0);
-    for (int64_t b = 0; b < B; ++b) {
-        int64_t c = 0;
-        for (int64_t s = 0; s < S; ++s) c += (start[(size_t)(s * B + b) + 1] - start[(size_t)(s * B + b)]) / G;
-        gptr[(size_t)b + 1] = (int32_t)(gptr[(size_t)b] + c);
-    }
-    HostBuf<int32_t> glist(tot / G);
-    parallel_for(B, 1, threads, [&](int64_t bb, int64_t be, int) {
-        for (int64_t b = bb; b < be; ++b) {
-            int64_t o = gptr[(size_t)b];
-            for (int64_t s = 0; s < S; ++s)
-                for (int64_t g = start[(size_t)(s * B + b)] / G; g < start[(size_t)(s * B + b) + 1] / G; ++g)
-                    glist[o++] = (int32_t)g;
-        }
-    });
-
     void *scratch = plan.mem.alloc((size_t)std::max<int64_t>(tot, 1) * sizeof(T), plan.mem.user);
     if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the xl part's scratch failed");
     {

@@ -890,6 +890,7 @@ __global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ it
 // Block blk adds the groups glist[gptr[blk]] .. glist[gptr[blk + 1] - 1].  A lane reads 16 bytes of
 // products, so 16 / N lanes share a group and one load instruction of a wavefront covers 64 * N
 // entries; a wavefront takes 64 list entries at a time and fetches the next 64 while it adds.
+// lrow is stored in list order: lrow[16*p + t] is the local row of entry 16*glist[p] + t.
 template <typename T, bool ROWS, bool ACC>
 __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__ gptr,
                                                      const int32_t *__restrict__ glist,
@@ -922,9 +923,8 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
             const int32_t gid = __shfl(mine, u * GPI + sub, kWave);
             ok[u] = gid >= 0;
             if (ok[u]) {
-                const int64_t q = (int64_t)gid * LPG + l;
-                v[u] = ldnt(pv + q);
-                r[u] = ldnt(pr + q);
+                v[u] = ldnt(pv + (int64_t)gid * LPG + l);
+                r[u] = ldnt(pr + (int64_t)(base + u * GPI + sub) * LPG + l);   // rows are in list order
             }
         }
 #pragma unroll
