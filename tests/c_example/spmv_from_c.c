@@ -1,7 +1,8 @@
 /* Plain C user of the library: build a small CSR matrix (or read a Matrix Market file), let the
  * library pick a plan, run y = A*x on the GPU and check y against a loop written here.
  *
- *   hipcc -x c examples/spmv_from_c.c -Iinclude -Lpaper_2212_10432_amd -lspmv_mi355 -o spmv_from_c
+ *   gcc -std=c99 -D__HIP_PLATFORM_AMD__ -I/opt/rocm/include -Iinclude tests/c_example/spmv_from_c.c \
+ *       -Lpaper_2212_10432_amd -lspmv_mi355 -L/opt/rocm/lib -lamdhip64 -lm -o spmv_from_c
  *   ./spmv_from_c [matrix.mtx]
  */
 #include <hip/hip_runtime_api.h>

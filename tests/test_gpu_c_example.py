@@ -1,4 +1,4 @@
-"""The C ABI used from plain C (examples/spmv_from_c.c, compiled with gcc against include/spmv.h
+"""The C ABI used from plain C (tests/c_example/spmv_from_c.c, compiled with gcc against include/spmv.h
 and the built library) on the GPU, and plan create/destroy cycles that must not leak device memory."""
 import os
 import shutil
@@ -23,7 +23,7 @@ def test_plain_c_program_runs_through_the_abi(tmp_path):
     exe = str(tmp_path / "spmv_from_c")
     libdir = os.path.dirname(lib.lib_path())
     cmd = ["gcc", "-std=c99", "-O2", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include", f"-I{ROOT}/include",
-           os.path.join(ROOT, "examples", "spmv_from_c.c"), f"-L{libdir}", "-lspmv_mi355", f"-L{rocm}/lib", "-lamdhip64", "-lm",
+           os.path.join(ROOT, "tests", "c_example", "spmv_from_c.c"), f"-L{libdir}", "-lspmv_mi355", f"-L{rocm}/lib", "-lamdhip64", "-lm",
            f"-Wl,-rpath,{libdir}", f"-Wl,-rpath,{rocm}/lib", "-o", exe]
     subprocess.run(cmd, check=True, capture_output=True, text=True, timeout=120)
     print("running the C example", flush=True)
