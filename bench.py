@@ -63,6 +63,10 @@ def main():
     log = (lambda *a: print(*a, file=sys.stderr, flush=True)) if args.verbose else (lambda *a: None)
 
     forced = json.load(open(args.plan_json)) if args.plan_json else {}
+    # achievable streaming ceiling of this device (2 GiB read, 1 GiB copied to 1 GiB): the second
+    # reference, beside the 8 TB/s peak, that achieved bandwidths are read against
+    ceil_read, ceil_copy = lib.spmv_stream_ceiling(2 << 30, 5, torch.cuda.current_stream().cuda_stream)
+    log(f"stream ceiling: read {ceil_read:.0f} GB/s, copy {ceil_copy:.0f} GB/s")
     items = []
     cpu = {"seconds": 0.0, "flops": 0.0, "cores": 0, "sample": []}
     cache = {}
@@ -208,6 +212,7 @@ def main():
         rec = dict(config=it["name"], workload=it["desc"], dtype=it["dtype"], nnz=it["nnz"], us=it["ms"] * 1e3,
                    gflops=2.0 * it["nnz"] / t / 1e9, bytes_csr=it["b_csr"], bytes_plan=it["b_plan"],
                    gbps_credited=credited / t / 1e9, hbm_frac=credited / t / HBM_PEAK,
+                   frac_of_read_ceiling=credited / t / 1e9 / ceil_read,
                    gbps_csr=it["b_csr"] / t / 1e9, gbps_plan=it["b_plan"] / t / 1e9,
                    plan=it["spec"], operators=it["operators"], launches=it["launches"],
                    launch_us=[v * 1e3 for v in it["launch_ms"]], launch_bytes=it["launch_bytes"],
@@ -236,6 +241,7 @@ def main():
         except Exception:
             traffic = None
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK / 1e9, unit="GB/s", frac=achieved / (HBM_PEAK / 1e9),
+                    frac_of_read_ceiling=achieved / ceil_read,
                     traffic=traffic, kernel=f"{dit['name']}:{dit['launches'][di]}",
                     launch_us=dit["launch_ms"][di] * 1e3, algorithmic_bytes=dom_bytes)
     if args.save_plans:
@@ -254,6 +260,8 @@ def main():
         "geomean_gflops": geomean([r["gflops"] for r in per_config]),
         "geomean_hbm_frac": geomean([r["hbm_frac"] for r in per_config]),
         "geomean_hbm_frac_without_C1": geomean([r["hbm_frac"] for r in per_config if r["config"] != "C1"]),
+        "stream_ceiling": {"read_gbps": ceil_read, "copy_gbps": ceil_copy, "bytes": 2 << 30,
+                           "note": "measured at start-up with the library's spmv_stream_ceiling"},
         "per_config": per_config,
         "roofline": roofline,
     }

@@ -150,6 +150,17 @@ spmv_status_t spmv_plan_bytes(const spmv_plan_t *plan, int64_t *b_plan, int64_t 
 spmv_status_t spmv_plan_launch_count(const spmv_plan_t *plan, int *n);
 spmv_status_t spmv_plan_launch_name(const spmv_plan_t *plan, int i, const char **name);
 
+/*
+ * Measurement helper: the streaming ceiling of the current device, against which achieved
+ * bandwidths are read (SpMV is memory-bound: Section I, Section VII-B).  Allocates `bytes` bytes of
+ * DEVICE memory (hipMalloc), reads them with 16-byte non-temporal loads, then copies one half to the
+ * other; *read_gbps and *copy_gbps (bytes read + written per second for the copy) receive the best
+ * of `repeats` timed launches on `stream`, in GB/s.  Synchronises the stream, frees the buffer.
+ * bytes >= 1 MiB (use >= 2 GiB to get past the caches), 1 <= repeats <= 1000.
+ */
+spmv_status_t spmv_stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps,
+                                  double *copy_gbps);
+
 /* ---- Matrix Market input ------------------------------------------------------------------ */
 
 /*

@@ -22,7 +22,7 @@ _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC"
 
 EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
            "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
-           "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error", "spmv_mm_read", "spmv_mm_free"]
+           "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error", "spmv_mm_read", "spmv_mm_free", "spmv_stream_ceiling"]
 
 
 class SpmvError(RuntimeError):
@@ -94,6 +94,8 @@ def load():
     lib.spmv_mm_read.argtypes = [ctypes.c_char_p, ci, P(i64), P(i64), P(i64), P(vp), P(vp), P(vp)]
     lib.spmv_mm_free.restype = ci
     lib.spmv_mm_free.argtypes = [vp, vp, vp]
+    lib.spmv_stream_ceiling.restype = ci
+    lib.spmv_stream_ceiling.argtypes = [ctypes.c_size_t, ci, vp, P(ctypes.c_double), P(ctypes.c_double)]
     _lib = lib
     return lib
 
@@ -188,6 +190,13 @@ def spmv_plan_describe(plan: int) -> dict:
     buf = ctypes.create_string_buffer(need.value)
     _check(lib.spmv_plan_describe(plan, buf, need.value, None))
     return json.loads(buf.value.decode())
+
+
+def spmv_stream_ceiling(nbytes: int = 2 << 30, repeats: int = 5, stream: int = 0):
+    """(read GB/s, copy GB/s) of the current device: best of `repeats` launches over `nbytes` bytes."""
+    r, c = ctypes.c_double(), ctypes.c_double()
+    _check(load().spmv_stream_ceiling(nbytes, repeats, stream, ctypes.byref(r), ctypes.byref(c)))
+    return r.value, c.value
 
 
 def spmv_mm_free(row_ptr: int, col_idx: int, values: int) -> None:

@@ -128,6 +128,23 @@ extern "C" {
 
 const char *spmv_last_error(void) { return g_last_error.c_str(); }
 
+spmv_status_t spmv_stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps,
+                                  double *copy_gbps) {
+    API_BEGIN
+    if (!read_gbps || !copy_gbps) fail(SPMV_ERR_INVALID_ARG, "spmv_stream_ceiling: NULL result pointer");
+    if (bytes < (1u << 20) || repeats < 1 || repeats > 1000)
+        fail(SPMV_ERR_INVALID_ARG, "spmv_stream_ceiling: bytes must be at least 1 MiB, repeats in [1, 1000]");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) {
+        (void)hipGetLastError();
+        fail(SPMV_ERR_HIP, "no HIP device available");
+    }
+    const int err = stream_ceiling(bytes, repeats, stream, read_gbps, copy_gbps);
+    if (err) fail(err == (int)hipErrorOutOfMemory ? SPMV_ERR_ALLOC : SPMV_ERR_HIP, std::string("stream ceiling: ") + hip_error_text(err));
+    return SPMV_OK;
+    API_END
+}
+
 spmv_status_t spmv_mm_read(const char *path, spmv_dtype_t dtype, int64_t *nrows, int64_t *ncols,
                            int64_t *nnz, int32_t **row_ptr, int32_t **col_idx, void **values) {
     if (row_ptr) *row_ptr = nullptr;

@@ -183,6 +183,8 @@ std::unique_ptr<Plan> build_plan(const HostCsr &A, const Census &cen, const Plan
 int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
                 void *y, void *stream);
 const char *hip_error_text(int err);
+// Streaming ceiling of the current device (read, copy) in GB/s; returns a hipError_t as int.
+int stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps, double *copy_gbps);
 
 // Search (Section VI): enumerate pruned candidates, time them, keep the fastest.
 std::vector<PlanSpec> enumerate_candidates(const Census &cen, spmv_dtype_t dtype);

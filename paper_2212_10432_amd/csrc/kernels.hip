@@ -1212,7 +1212,68 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     return (int)hipGetLastError();
 }
 
+// ---- streaming ceiling of the device (measurement helper) --------------------------------------
+typedef float ceil_f4 __attribute__((ext_vector_type(4)));
+// one workgroup per 8 x 256 vectors (read) or per 256 vectors (copy): many short workgroups keep
+// more requests in flight than a few persistent ones, and that is what reaches the ceiling
+__global__ __launch_bounds__(kWG) void k_stream_read(const ceil_f4 *__restrict__ p, int64_t n, float *sink) {
+    const int64_t i = (int64_t)blockIdx.x * (kWG * 8) + threadIdx.x;
+    ceil_f4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int64_t j = i + u * kWG;
+        if (j < n) a += ldnt(p + j);
+    }
+    if (a[0] + a[1] + a[2] + a[3] == 1.2345e30f) sink[0] = a[0];   // never true for the zero-filled buffer
+}
+__global__ __launch_bounds__(kWG) void k_stream_copy(const ceil_f4 *__restrict__ src, ceil_f4 *__restrict__ dst, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * kWG + threadIdx.x;
+    if (i < n) __builtin_nontemporal_store(ldnt(src + i), dst + i);
+}
+
 }  // namespace
+
+// Reads `bytes` bytes, then copies bytes/2 to the other half of the same buffer; best of `repeats`
+// timed launches each.  Returns a hipError_t as int.
+int stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps, double *copy_gbps) {
+    hipStream_t st = (hipStream_t)stream;
+    void *buf = nullptr;
+    float *sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t err = hipMalloc(&buf, bytes);
+    if (err == hipSuccess) err = hipMalloc((void **)&sink, sizeof(float));
+    if (err == hipSuccess) err = hipMemsetAsync(buf, 0, bytes, st);
+    if (err == hipSuccess) err = hipEventCreate(&e0);
+    if (err == hipSuccess) err = hipEventCreate(&e1);
+    const int64_t n16 = (int64_t)(bytes / 16);
+    const unsigned grid_r = (unsigned)((n16 + kWG * 8 - 1) / (kWG * 8)), grid_c = (unsigned)((n16 / 2 + kWG - 1) / kWG);
+    double best_r = 0, best_c = 0;
+    for (int it = 0; err == hipSuccess && it < repeats + 1; ++it) {   // the first round warms up
+        float ms = 0;
+        (void)hipEventRecord(e0, st);
+        k_stream_read<<<grid_r, kWG, 0, st>>>((const ceil_f4 *)buf, n16, sink);
+        (void)hipEventRecord(e1, st);
+        err = hipEventSynchronize(e1);
+        if (err != hipSuccess) break;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        if (it && ms > 0) best_r = std::max(best_r, (double)n16 * 16.0 / (ms * 1e-3) / 1e9);
+        (void)hipEventRecord(e0, st);
+        k_stream_copy<<<grid_c, kWG, 0, st>>>((const ceil_f4 *)buf, (ceil_f4 *)buf + n16 / 2, n16 / 2);
+        (void)hipEventRecord(e1, st);
+        err = hipEventSynchronize(e1);
+        if (err != hipSuccess) break;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        if (it && ms > 0) best_c = std::max(best_c, (double)(n16 / 2) * 32.0 / (ms * 1e-3) / 1e9);   // read + written
+    }
+    if (err == hipSuccess) err = hipGetLastError();
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (sink) (void)hipFree(sink);
+    if (buf) (void)hipFree(buf);
+    *read_gbps = best_r;
+    *copy_gbps = best_c;
+    return (int)err;
+}
 
 int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
                 void *y, void *stream) {

@@ -366,3 +366,11 @@ def test_random_matrices_random_plans():
                 assert e.status == lib.SPMV_ERR_UNSUPPORTED, (spec, e)      # e.g. too many heavy rows
                 continue
             assert np.array_equal(y.astype(np.float64), want), (case, spec, dt)
+
+
+def test_stream_ceiling_is_plausible():
+    read, copy = lib.spmv_stream_ceiling(1 << 30, 3)
+    assert 2000 < read < 8000 and 2000 < copy < 8000, (read, copy)      # GB/s on an MI355X (peak 8000)
+    with pytest.raises(lib.SpmvError) as e:
+        lib.spmv_stream_ceiling(1000, 3)
+    assert e.value.status == lib.SPMV_ERR_INVALID_ARG
