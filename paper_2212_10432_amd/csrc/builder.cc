@@ -461,6 +461,16 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
         if (widest.load() * (int64_t)sizeof(T) > kXwinMaxBytes)
             fail(SPMV_ERR_UNSUPPORTED, "bsell: the x window of a workgroup does not fit the LDS");
         p.lds_bytes = std::max<int64_t>(widest.load() * (int64_t)sizeof(T), 16);
+        // Do the block rows of every group stay inside the group's own range of 64 * 32 block rows
+        // (no sort, or SORT_SUB windows that are whole groups)?  Then the kernel collects a group's
+        // results in LDS, where the x window was, and writes them to y as one contiguous piece.
+        bool confined = true;
+        for (int64_t i = 0; i < nb && confined; ++i)
+            confined = brows[(size_t)i] / (kWave * kXwinGroup) == i / (kWave * kXwinGroup);
+        if (confined) {
+            p.uniform_w = 1;   // bsell with a window: results staged in LDS
+            p.lds_bytes = std::max<int64_t>(p.lds_bytes, (int64_t)kWave * kXwinGroup * B * (int64_t)sizeof(T));
+        }
         p.p4 = upload(plan, "bsell.xwin", 4, 2 * ng, win.data());
     }
     p.p0 = upload(plan, "bsell.slice_ptr", 8, nsl + 1, slice_ptr.data());

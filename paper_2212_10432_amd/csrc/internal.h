@@ -138,6 +138,7 @@ struct Part {
     int64_t per_group = 0;       // heavy part: stripes per workgroup
     void *scratch = nullptr;     // partial sums written by one launch and read by the next
     int uniform_w = -1;          // sell / csrv: width shared by every slice / row (-1: read the offsets)
+                                 // bsell with an x window: 1 = a group's block rows lie in its own range
     int delta = 0;               // heavy part: columns stored as 8-bit deltas
     int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
     const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;

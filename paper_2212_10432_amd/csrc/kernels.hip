@@ -631,7 +631,11 @@ __global__ __launch_bounds__(kWG) void k_bsell(const int64_t *__restrict__ slice
 // the shortest, so the 16 wavefronts finish together.
 constexpr int kXwinWaves = 16;
 constexpr int kXwinSlices = 2 * kXwinWaves;
-template <typename T, int B, bool ROWS>
+// LOCALY: every block row of the group lies in the group's own range of 64 * 32 block rows (no sort,
+// or sort windows that are whole groups).  The results are then collected in LDS, in the space of the
+// x window once every wavefront is done with it, and written to y as one contiguous piece: stores
+// scattered by the sort permutation, mixed into the stream one slice at a time, cost 14 % of the run.
+template <typename T, int B, bool ROWS, bool LOCALY>
 __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
     const int64_t *__restrict__ slice_ptr, const int32_t *__restrict__ bcols,
     const T *__restrict__ vals, const int32_t *__restrict__ brows, const int32_t *__restrict__ win,
@@ -643,22 +647,45 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
     for (int i = threadIdx.x; i < n; i += kXwinWaves * kWave) xs[i] = x[lo + i];
     __syncthreads();
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-#pragma unroll 1
+    T res[2][B];
+#pragma unroll
     for (int half = 0; half < 2; ++half) {
         const int64_t s = blk * kXwinSlices + (half ? kXwinSlices - 1 - wave : wave);
-        if (s >= nslices) continue;
-        const int64_t b = slice_ptr[s];
-        const int w = (int)((slice_ptr[s + 1] - b) >> 6);
         T acc[B];
 #pragma unroll
         for (int ri = 0; ri < B; ++ri) acc[ri] = T(0);
-        bsell_slice<T, B, true>(bcols + b + lane, vals + b * (B * B), w, lane, xs, lo, acc);
-        const int64_t r = s * 64 + lane;
-        if (r < nbrows_part) {
-            const int64_t br = ROWS ? (int64_t)brows[r] : r;
+        if (s < nslices) {
+            const int64_t b = slice_ptr[s];
+            const int w = (int)((slice_ptr[s + 1] - b) >> 6);
+            bsell_slice<T, B, true>(bcols + b + lane, vals + b * (B * B), w, lane, xs, lo, acc);
+            const int64_t r = s * 64 + lane;
+            if (!LOCALY && r < nbrows_part) {
+                const int64_t br = ROWS ? (int64_t)brows[r] : r;
 #pragma unroll
-            for (int ri = 0; ri < B; ++ri) y[br * B + ri] = acc[ri];
+                for (int ri = 0; ri < B; ++ri) y[br * B + ri] = acc[ri];
+            }
         }
+#pragma unroll
+        for (int ri = 0; ri < B; ++ri) res[half][ri] = acc[ri];
+    }
+    if (LOCALY) {
+        const int64_t row0 = blk * (kXwinSlices * 64);   // first block row of the group
+        __syncthreads();                                  // nobody reads the x window any more
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int64_t s = blk * kXwinSlices + (half ? kXwinSlices - 1 - wave : wave);
+            const int64_t r = s * 64 + lane;
+            if (s < nslices && r < nbrows_part) {
+                const int loc = (int)((ROWS ? (int64_t)brows[r] : r) - row0);
+#pragma unroll
+                for (int ri = 0; ri < B; ++ri) xs[loc * B + ri] = res[half][ri];
+            }
+        }
+        __syncthreads();
+        const int64_t left = nbrows_part - row0;
+        const int cnt = (int)(left < kXwinSlices * 64 ? left : kXwinSlices * 64) * B;
+        T *yg = y + row0 * B;
+        for (int i = threadIdx.x; i < cnt; i += kXwinWaves * kWave) yg[i] = xs[i];
     }
 }
 
@@ -1015,23 +1042,24 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (p.lds_bytes > 0) {   // x window in LDS: 32 slices per workgroup of 1024 threads
             const unsigned grid = blocks(p.units, kXwinSlices);
             const int threads = kXwinWaves * kWave;
-#define XWIN_GO(B, R)                                                                              \
+#define XWIN_GO(B, R, L)                                                                           \
     {                                                                                              \
         static std::atomic<int> lds_set{0};                                                        \
         if (lds_set.load() < p.lds_bytes) {                                                        \
-            hipError_t e = hipFuncSetAttribute((const void *)k_bsell_xwin<T, B, R>,                \
+            hipError_t e = hipFuncSetAttribute((const void *)k_bsell_xwin<T, B, R, L>,             \
                                                hipFuncAttributeMaxDynamicSharedMemorySize,        \
                                                (int)kMaxLds);                                      \
             if (e != hipSuccess) return (int)e;                                                    \
             lds_set.store((int)kMaxLds);                                                           \
         }                                                                                          \
-        k_bsell_xwin<T, B, R><<<grid, threads, (size_t)p.lds_bytes, st>>>(                         \
+        k_bsell_xwin<T, B, R, L><<<grid, threads, (size_t)p.lds_bytes, st>>>(                      \
             (const int64_t *)p.p0, (const int32_t *)p.p1, (const T *)p.p2, (const int32_t *)p.p3,  \
             (const int32_t *)p.p4, x, y, p.units, p.nrows, p.remap);                               \
     }
 #define XWIN_B(B)                                                                                  \
     case B:                                                                                        \
-        if (p.has_rows) XWIN_GO(B, true) else XWIN_GO(B, false)                                    \
+        if (p.uniform_w == 1) { if (p.has_rows) XWIN_GO(B, true, true) else XWIN_GO(B, false, true) }   \
+        else                  { if (p.has_rows) XWIN_GO(B, true, false) else XWIN_GO(B, false, false) } \
         break;
             switch (p.block) {
                 XWIN_B(2) XWIN_B(3) XWIN_B(4)
