@@ -598,6 +598,50 @@ __device__ __forceinline__ void bsell_slice(const int32_t *__restrict__ c, const
     }
 }
 
+// The same slice for the LDS-window kernel: two value buffers take turns and a buffer is refilled
+// with the block two ahead as soon as its block has been multiplied, so one to two blocks are in
+// flight.  A block's column is kept as loaded and turned into an LDS offset only when the block is
+// used.  No test stands between an issue and a use in the steady state: the compiler counts
+// outstanding loads per path, and a skipped issue on one path would turn the next wait into a drain.
+template <typename T, int B>
+__device__ __forceinline__ void bsell_slice2(const int32_t *__restrict__ c, const T *__restrict__ v,
+                                             int w, int lane, const T *__restrict__ xs, int xbase,
+                                             T *acc) {
+    constexpr int BB = B * B;
+    if (w <= 0) return;
+    int32_t ca = 0, cb = 0;
+    T a[BB], b[BB];
+    auto issue = [&](int j, int32_t &craw, T *buf) {
+        craw = ldnt(c + j * 64);
+        BlockLoad<T, B>::load(v + (int64_t)j * 64 * BB, lane, buf);
+    };
+    auto use = [&](int32_t craw, const T *buf) {
+        const int xc = craw * B - xbase;
+        T xv[B];
+#pragma unroll
+        for (int ci = 0; ci < B; ++ci) xv[ci] = xs[xc + ci];
+#pragma unroll
+        for (int ri = 0; ri < B; ++ri)
+#pragma unroll
+            for (int ci = 0; ci < B; ++ci) acc[ri] += buf[ri * B + ci] * xv[ci];
+    };
+    issue(0, ca, a);
+    if (w > 1) issue(1, cb, b);
+    int j = 0;
+    for (; j + 4 <= w; j += 2) {   // a holds block j, b block j + 1; blocks j + 2 and j + 3 exist
+        use(ca, a);
+        issue(j + 2, ca, a);
+        use(cb, b);
+        issue(j + 3, cb, b);
+    }
+    if (j < w) {   // the last one to three blocks (w is uniform over the wavefront)
+        use(ca, a);
+        if (j + 2 < w) issue(j + 2, ca, a);
+    }
+    if (j + 1 < w) use(cb, b);
+    if (j + 2 < w) use(ca, a);
+}
+
 template <typename T, int B, bool ROWS>
 __global__ __launch_bounds__(kWG) void k_bsell(const int64_t *__restrict__ slice_ptr,
                                                const int32_t *__restrict__ bcols,
@@ -657,7 +701,7 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
         if (s < nslices) {
             const int64_t b = slice_ptr[s];
             const int w = (int)((slice_ptr[s + 1] - b) >> 6);
-            bsell_slice<T, B, true>(bcols + b + lane, vals + b * (B * B), w, lane, xs, lo, acc);
+            bsell_slice2<T, B>(bcols + b + lane, vals + b * (B * B), w, lane, xs, lo, acc);
             const int64_t r = s * 64 + lane;
             if (!LOCALY && r < nbrows_part) {
                 const int64_t br = ROWS ? (int64_t)brows[r] : r;
