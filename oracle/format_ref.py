@@ -445,7 +445,7 @@ def ref_xnb(ncols, rp, ci, va, rows, K, R, nrows_total):
     return out
 
 
-def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
+def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total, skip=()):
     """Two passes with x windows in LDS.  Windows of W columns (0: 64 KiB worth of values), blocks of
     RB part positions.  Entry (part position i, column c) is in run (s, b) = (c // W, i // RB); runs
     are stored window by window, block by block inside a window, by part position and row order
@@ -453,7 +453,9 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
     0).  items: (window, first entry, end entry) pieces of a window's entries, m = ceil(len / chunk)
     pieces of ceil16(ceil(len / m)) entries; chunk 0 means 32768.
     glist: for block b the 16-entry groups of runs (0, b), (1, b), ...; gptr: its offsets per block.
-    lrow is stored in glist order: lrow[16 p + t] is the local row of entry 16 glist[p] + t."""
+    lrow is stored in glist order: lrow[16 p + t] is the local row of entry 16 glist[p] + t.
+    Rows listed in `skip` stay in the part but contribute no entries (heavy rows when nothing was
+    extracted before: the part's rows are then 0 .. nrows-1 and no row map is stored)."""
     rows = np.asarray(rows, dtype=np.int32)
     n = rows.size
     if n == 0:
@@ -465,8 +467,9 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total):
     S = max(1, -(-ncols // W))
     B = -(-n // RB)
     lens = (rp[rows + 1] - rp[rows]).astype(np.int64)
+    lens[np.isin(rows, np.asarray(skip, dtype=np.int64))] = 0               # rows kept in the part without their entries
     pos_of_entry = np.repeat(np.arange(n, dtype=np.int64), lens)           # part position i
-    src = np.concatenate([np.arange(rp[r], rp[r + 1], dtype=np.int64) for r in rows]) if lens.sum() else np.zeros(0, np.int64)
+    src = np.concatenate([np.arange(rp[r], rp[r] + L, dtype=np.int64) for r, L in zip(rows, lens)]) if lens.sum() else np.zeros(0, np.int64)
     c = ci[src].astype(np.int64)
     run = (c // W) * B + pos_of_entry // RB
     order = np.argsort(run, kind="stable")                                   # keeps (i, row order) inside a run
@@ -558,7 +561,10 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
     elif p["light"] == "xnb":
         out.update(ref_xnb(ncols, rp, ci, va, light, p["k"], p["r"], nrows))
     elif p["light"] == "xl":
-        out.update(ref_xl(ncols, rp, ci, va, light, p["w"], p["rb"], p["chunk"], nrows))
+        if not acc and heavy.size:
+            out.update(ref_xl(ncols, rp, ci, va, allrows, p["w"], p["rb"], p["chunk"], nrows, skip=heavy))
+        else:
+            out.update(ref_xl(ncols, rp, ci, va, light, p["w"], p["rb"], p["chunk"], nrows))
     elif p["light"] == "xs":
         out.update(ref_xs(ncols, rp, ci, va, light, p["k"], p["sigma"], nrows))
     elif p["light"] == "bin":

@@ -997,6 +997,9 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
 // groups of runs (0, b), (1, b), ... in that order.  The local rows i - b*RB are stored in that
 // order too (lrow[16*p + t] belongs to entry 16*glist[p] + t), so a block reads them as one
 // contiguous piece instead of a fragment of a cache line per run.
+// Row r contributes its first lens[r] entries: the caller passes 0 for rows that belong to another
+// part but are kept in `rows` so that the part's rows are simply 0 .. nrows-1 (no row map to read,
+// y written contiguously; the other part's launch overwrites those y elements afterwards).
 template <typename T>
 void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, int w_spec, int RB,
               int64_t chunk_spec, bool acc, const std::vector<int64_t> &lens, int threads) {
@@ -1018,7 +1021,7 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
         for (int64_t b = bb; b < be; ++b)
             for (int64_t i = b * RB; i < std::min(n, (b + 1) * RB); ++i) {
                 const int32_t r = rows[(size_t)i];
-                for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k)
+                for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r] + lens[(size_t)r]; ++k)
                     start[(size_t)((A.col[k] / W) * B + b) + 1] += 1;
             }
     });
@@ -1049,7 +1052,7 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
             }
             for (int64_t i = b * RB; i < std::min(n, (b + 1) * RB); ++i) {
                 const int32_t r = rows[(size_t)i];
-                for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
+                for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r] + lens[(size_t)r]; ++k) {
                     const int64_t s = A.col[k] / W;
                     const int64_t g = cur[(size_t)s]++;
                     vals[g] = av[k];
@@ -1409,7 +1412,16 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         build_coo<T>(*plan, A, light, acc, lens, zero_rows, threads);
         break;
     case L_XL:
-        build_xl<T>(*plan, A, light, spec.w, spec.rb, spec.chunk, acc, lens, threads);
+        if (!acc && !heavy.empty()) {
+            // keep the heavy rows in the part as rows without entries: identity row order
+            std::vector<int32_t> all((size_t)A.nrows);
+            std::iota(all.begin(), all.end(), 0);
+            std::vector<int64_t> lens_light(lens);
+            for (int32_t r : heavy) lens_light[(size_t)r] = 0;
+            build_xl<T>(*plan, A, all, spec.w, spec.rb, spec.chunk, acc, lens_light, threads);
+        } else {
+            build_xl<T>(*plan, A, light, spec.w, spec.rb, spec.chunk, acc, lens, threads);
+        }
         break;
     case L_BIN: {
         // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront per

@@ -1008,6 +1008,23 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
         mine = next;
     }
     __syncthreads();
+    if (!ROWS && (reinterpret_cast<uintptr_t>(y) & 15) == 0) {
+        // the block's rows are consecutive y elements: 16-byte stores (RB is a multiple of 64)
+        for (int i = threadIdx.x * N; i < RB; i += kXlWG * N) {
+            const int64_t pos = blk * RB + i;
+            if (pos + N <= n) {
+                V out;
+#pragma unroll
+                for (int k = 0; k < N; ++k) out[k] = (T)acc[i + k];
+                V *dst = reinterpret_cast<V *>(y + pos);
+                if (ACC) out += *dst;
+                *dst = out;
+            } else {
+                for (int k = 0; k < N && pos + k < n; ++k) y[pos + k] = ACC ? y[pos + k] + (T)acc[i + k] : (T)acc[i + k];
+            }
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < RB; i += kXlWG) {
         const int64_t pos = blk * RB + i;
         if (pos < n) {
