@@ -1018,7 +1018,7 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
                 for (int k = 0; k < N; ++k) out[k] = (T)acc[i + k];
                 V *dst = reinterpret_cast<V *>(y + pos);
                 if (ACC) out += *dst;
-                *dst = out;
+                __builtin_nontemporal_store(out, dst);
             } else {
                 for (int k = 0; k < N && pos + k < n; ++k) y[pos + k] = ACC ? y[pos + k] + (T)acc[i + k] : (T)acc[i + k];
             }
