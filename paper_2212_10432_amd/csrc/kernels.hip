@@ -171,7 +171,8 @@ __global__ __launch_bounds__(kWG) void k_dia_fixed(DiaOffsets offs, const T *__r
     T acc = T(0);
 #pragma unroll
     for (int d = 0; d < ND; ++d) acc += v[d] * xv[d];
-    y[i] = ACC ? y[i] + acc : acc;
+    if (ACC) y[i] += acc;
+    else __builtin_nontemporal_store(acc, y + i);
 }
 
 // ---- SELL: one wavefront per slice of 64 rows, one lane per row -----------------------------
@@ -729,7 +730,7 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
         const int64_t left = nbrows_part - row0;
         const int cnt = (int)(left < kXwinSlices * 64 ? left : kXwinSlices * 64) * B;
         T *yg = y + row0 * B;
-        for (int i = threadIdx.x; i < cnt; i += kXwinWaves * kWave) yg[i] = xs[i];
+        for (int i = threadIdx.x; i < cnt; i += kXwinWaves * kWave) __builtin_nontemporal_store(xs[i], yg + i);
     }
 }
 
@@ -801,7 +802,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nh; i += kHeavyWG) partial[(int64_t)blockIdx.x * nh + i] = ys[i];
+    for (int i = threadIdx.x; i < nh; i += kHeavyWG) __builtin_nontemporal_store(ys[i], partial + (int64_t)blockIdx.x * nh + i);
 }
 
 // The same part with 8-bit column differences (index compression): a lane starts at the first
@@ -871,7 +872,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restr
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nh; i += kHeavyWG) partial[(int64_t)blockIdx.x * nh + i] = ys[i];
+    for (int i = threadIdx.x; i < nh; i += kHeavyWG) __builtin_nontemporal_store(ys[i], partial + (int64_t)blockIdx.x * nh + i);
 }
 
 // y[rows[i]] (+)= sum over g < np of partial[g * n + i]: many partials (one per workgroup of the
