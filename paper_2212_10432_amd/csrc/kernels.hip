@@ -748,6 +748,30 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
 // hit the same few thousand y elements.
 // Entry j of lane `lane` of unit u = stripe * nsl + slice sits at unit_ptr[u] + 64*j + lane.
 constexpr int kHeavyWG = 512;
+// Four consecutive units of the same width W <= 4 (4 * 64 * W entries starting at entry p0, lane
+// rows starting at lr0): every load is issued before the first product.
+template <typename T, int W>
+__device__ __forceinline__ void narrow_quad(const uint16_t *__restrict__ lcol, const T *__restrict__ vals,
+                                            const uint16_t *__restrict__ lane_row, int32_t p0, int64_t lr0,
+                                            int lane, const T *__restrict__ xs, T *__restrict__ ys) {
+    uint16_t c[4 * W], lr[4];
+    T v[4 * W];
+#pragma unroll
+    for (int t = 0; t < 4 * W; ++t) {   // entry j of unit k is row k * W + j of the 4 * W rows of 64
+        c[t] = ldnt(lcol + p0 + t * 64 + lane);
+        v[t] = ldnt(vals + p0 + t * 64 + lane);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) lr[k] = ldnt(lane_row + lr0 + k * 64 + lane);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        T acc = T(0);
+#pragma unroll
+        for (int j = 0; j < W; ++j) acc += v[k * W + j] * xs[c[k * W + j]];
+        if (lr[k] != 0xFFFFu) ys[lr[k]] += acc;
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ unit_ptr,
                                                     const uint16_t *__restrict__ lcol,
@@ -769,36 +793,63 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
         const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
         for (int i = threadIdx.x; i < w; i += kHeavyWG) xs[i] = x[c0 + i];
         __syncthreads();
-        // the offsets and the row ids of the next slice are fetched while this one is summed:
-        // with many short slices per stripe the chain of dependent loads is what costs
-        int g = threadIdx.x >> 6;
-        int32_t b = 0, e = 0;
-        uint16_t lr = 0xFFFFu;
-        if (g < nsl) {
-            const int64_t u = (int64_t)s * nsl + g;
-            b = unit_ptr[u];
-            e = unit_ptr[u + 1];
-            lr = lane_row[u * 64 + lane];
+        // The stripe's unit offsets live in lane registers (nsl <= 128: lane i holds offsets i and
+        // 64 + i), so a unit costs no dependent load of its own.  Units are ordered by decreasing
+        // width: the first n_wide are wider than four entries and are walked one by one; the narrow
+        // ones after them are taken four at a time when the four widths agree, with all their loads
+        // issued together (a narrow unit alone is one dependent round trip for a few bytes).
+        const int64_t u0 = (int64_t)s * nsl;
+        const int32_t upa = (lane <= nsl) ? unit_ptr[u0 + lane] : 0;
+        const int32_t upb = (64 + lane <= nsl) ? unit_ptr[u0 + 64 + lane] : 0;
+        const int32_t uplast = unit_ptr[u0 + nsl];
+        auto offset_of = [&](int gq) -> int32_t {   // gq uniform over the wavefront, 0 <= gq <= nsl
+            const int32_t va = __shfl(upa, gq & 63, kWave), vb = __shfl(upb, gq & 63, kWave);
+            return gq >= 128 ? uplast : (gq >= 64 ? vb : va);
+        };
+        int n_wide = 0, n_used = 0;
+        {
+            const int32_t na = __shfl_down(upa, 1, kWave), fb = __shfl(upb, 0, kWave);
+            const int32_t wa = ((lane == 63) ? fb : na) - upa;                      // width * 64 of unit lane
+            const int32_t nb2 = __shfl_down(upb, 1, kWave);
+            const int32_t wb = ((lane == 63) ? uplast : nb2) - upb;                 // unit 64 + lane
+            const bool ina = lane < nsl, inb = 64 + lane < nsl;
+            n_wide = __popcll(__ballot(ina && wa > 4 * 64)) + __popcll(__ballot(inb && wb > 4 * 64));
+            n_used = __popcll(__ballot(ina && wa > 0)) + __popcll(__ballot(inb && wb > 0));
         }
-        while (g < nsl) {   // uniform over the wavefront
-            const int gn = g + kHeavyWG / kWave;
-            int32_t bn = 0, en = 0;
-            uint16_t lrn = 0xFFFFu;
-            if (gn < nsl) {
-                const int64_t un = (int64_t)s * nsl + gn;
-                bn = unit_ptr[un];
-                en = unit_ptr[un + 1];
-                lrn = lane_row[un * 64 + lane];
+        const int wave = threadIdx.x >> 6;
+        for (int g = wave; g < n_wide; g += kHeavyWG / kWave) {
+            const int32_t b = offset_of(g), e = offset_of(g + 1);
+            const uint16_t lr = lane_row[(u0 + g) * 64 + lane];
+            const T acc = sell_lane_sum<T, uint16_t, true>(lcol + b + lane, vals + b + lane, (e - b) >> 6, xs);
+            if (lr != 0xFFFFu) ys[lr] += acc;
+        }
+        for (int g0 = n_wide + 4 * wave; g0 < n_used; g0 += 4 * (kHeavyWG / kWave)) {
+            const int32_t p0 = offset_of(g0), p1 = offset_of(g0 + 1);
+            const int wq = (p1 - p0) >> 6;                                          // 1 .. 4
+            bool quad = g0 + 4 <= n_used;
+            int32_t p2 = p1, p3 = p1, p4 = p1;
+            if (quad) {
+                p2 = offset_of(g0 + 2);
+                p3 = offset_of(g0 + 3);
+                p4 = offset_of(g0 + 4);
+                quad = (p2 - p1) >> 6 == wq && (p3 - p2) >> 6 == wq && (p4 - p3) >> 6 == wq;
             }
-            const int wd = (e - b) >> 6;
-            if (wd != 0) {
-                const T acc = sell_lane_sum<T, uint16_t, true>(lcol + b + lane, vals + b + lane, wd, xs);
-                if (lr != 0xFFFFu) ys[lr] += acc;
+            if (quad) {
+                switch (wq) {
+                case 1: narrow_quad<T, 1>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
+                case 2: narrow_quad<T, 2>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
+                case 3: narrow_quad<T, 3>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
+                default: narrow_quad<T, 4>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
+                }
+            } else {
+                const int cnt = n_used - g0 < 4 ? n_used - g0 : 4;
+                for (int k = 0; k < cnt; ++k) {
+                    const int32_t b = offset_of(g0 + k), e = offset_of(g0 + k + 1);
+                    const uint16_t lr = lane_row[(u0 + g0 + k) * 64 + lane];
+                    const T acc = sell_lane_sum<T, uint16_t, false>(lcol + b + lane, vals + b + lane, (e - b) >> 6, xs);
+                    if (lr != 0xFFFFu) ys[lr] += acc;
+                }
             }
-            g = gn;
-            b = bn;
-            e = en;
-            lr = lrn;
         }
     }
     __syncthreads();
