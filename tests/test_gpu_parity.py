@@ -374,3 +374,32 @@ def test_stream_ceiling_is_plausible():
     with pytest.raises(lib.SpmvError) as e:
         lib.spmv_stream_ceiling(1000, 3)
     assert e.value.status == lib.SPMV_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("dt", [np.float64, np.float32])
+def test_many_heavy_rows_with_narrow_slices(dt):
+    """Several hundred heavy rows whose entries per column stripe are few: the heavy kernel then
+    walks many narrow slices (taken four at a time when their widths agree) besides a few wide ones."""
+    rng = np.random.default_rng(3)
+    nrows, ncols = 3000, 40000
+    lens = rng.integers(1, 6, nrows)
+    heavy_rows = rng.choice(nrows, 700, replace=False)
+    lens[heavy_rows] = rng.integers(120, 400, heavy_rows.size)
+    lens[heavy_rows[:5]] = 6000                      # a few really long rows: wide slices too
+    rp = np.zeros(nrows + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    ci = rng.integers(0, ncols, rp[-1]).astype(np.int32)
+    va = rng.integers(-3, 4, rp[-1]).astype(np.float64)
+    x = rng.integers(-3, 4, ncols).astype(np.float64)
+    want = oracle.spmv(rp, ci, va, x)
+
+    class M:
+        pass
+    m = M()
+    m.nrows, m.ncols, m.row_ptr, m.col_idx = nrows, ncols, rp, ci
+    for spec in ("heavy=100,tile=512,light=csrv", "heavy=100,tile=2048,light=xl,w=1024,rb=512", "heavy=100,tile=1024,hd=1,light=sell,sigma=64",
+                 "heavy=100,tile=64,light=coo"):
+        (y,), d = gpu_spmv(m, va.astype(dt), x.astype(dt), spec)
+        assert np.array_equal(y.astype(np.float64), want), (spec, dt)
+        heavy = [p for p in d["parts"] if p["name"] == "heavy"][0]
+        assert heavy["rows"] == 700
