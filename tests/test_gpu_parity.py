@@ -403,3 +403,48 @@ def test_many_heavy_rows_with_narrow_slices(dt):
         assert np.array_equal(y.astype(np.float64), want), (spec, dt)
         heavy = [p for p in d["parts"] if p["name"] == "heavy"][0]
         assert heavy["rows"] == 700
+
+
+def test_random_block_banded_matrices_blocked_and_diagonal_plans():
+    """Differential test for the plans that need structure: random block-banded matrices (block edge
+    2-4, partly filled blocks, repeated positions summed) under blocked-SELL plans with and without
+    the LDS x window and sort, diagonal extraction with several remainders, and the search."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(1)
+
+    class M:
+        pass
+    ran = 0
+    for case in range(30):
+        b = int(rng.choice([2, 3, 4]))
+        nb = int(rng.integers(1, 5000))
+        band = int(rng.choice([1, 3, 40, 700]))
+        per = rng.integers(1, 8, nb)
+        br = np.repeat(np.arange(nb), per)
+        bc = np.clip(br + rng.integers(-band, band + 1, br.size), 0, nb - 1)
+        keep = rng.random((br.size, b, b)) < float(rng.choice([1.0, 0.9, 0.5]))
+        rr = (br[:, None, None] * b + np.arange(b)[None, :, None] + np.zeros((1, 1, b), int))[keep]
+        cc = (bc[:, None, None] * b + np.zeros((1, b, 1), int) + np.arange(b)[None, None, :])[keep]
+        vv = rng.integers(-3, 4, rr.size).astype(np.float64)
+        n = nb * b
+        A = sp.coo_matrix((vv, (rr, cc)), shape=(n, n)).tocsr()
+        A.sort_indices()
+        rp, ci, va = A.indptr.astype(np.int32), A.indices.astype(np.int32), A.data.astype(np.float64)
+        x = rng.integers(-3, 4, n).astype(np.float64)
+        m = M()
+        m.nrows, m.ncols, m.row_ptr, m.col_idx = n, n, rp, ci
+        want = oracle.spmv(rp, ci, va, x)
+        specs = [f"light=bsell,block={b},sigma={int(rng.choice([0, 64, 2048, -1]))},xwin={int(rng.integers(0, 2))},remap={int(rng.integers(0, 2))}",
+                 f"light=bsell,block={b},sigma=2048,xwin=1,remap=1",
+                 "dia=1,dia_fill=0.3,light=" + str(rng.choice(["sell,sigma=64", "csrv", "xl,w=64,rb=64", "xnb,k=8,r=4", "coo"])), None]
+        for spec in specs:
+            dt = np.float64 if rng.random() < 0.5 else np.float32
+            print(f"case {case}: n {n} block {b} band {band} nnz {rp[-1]} {spec} {np.dtype(dt).name}", flush=True)
+            try:
+                (y,), _ = gpu_spmv(m, va.astype(dt), x.astype(dt), spec, search_budget_ms=100)
+            except lib.SpmvError as e:
+                assert e.status == lib.SPMV_ERR_UNSUPPORTED, (spec, e)     # no diagonal dense enough, window too wide
+                continue
+            ran += 1
+            assert np.array_equal(y.astype(np.float64), want), (case, spec, dt)
+    assert ran > 60
