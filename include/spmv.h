@@ -99,6 +99,25 @@ spmv_status_t spmv_plan_create(spmv_plan_t **out, int64_t nrows, int64_t ncols, 
 spmv_status_t spmv_run(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream);
 
 /*
+ * spmv_run for callers that cannot allocate device memory and cannot let the library do so either:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * launches as spmv_run, except that the partial sums and products that pass from one launch of
+ * the plan to the next (its "scratch_bytes") live in a static device array of the library,
+ * SPMV_STATIC_SCRATCH_BYTES per device, instead of the buffers the plan allocated when it was
+ * created.  The array's device address is looked up when a plan is created on the device (at the
+ * latest on the first call here); the call itself allocates and frees nothing, on host or device,
+ * and does not synchronise.  x_dev, y_dev, stream as for spmv_run.
+ * Errors: a plan whose scratch buffers (each rounded up to 256 bytes) do not fit the array ->
+ * SPMV_ERR_UNSUPPORTED, nothing is launched; otherwise as spmv_run.
+ * Every call on a device shares that device's array, and the array keeps the last call's contents:
+ * each plan's launches overwrite, or clear with a kernel, every element they later read, so a
+ * call never depends on what an earlier one left there.  Calls that overlap on one device (two
+ * streams, two threads) race on the array: order them, or use spmv_run.
+ */
+#define SPMV_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+spmv_status_t spmv_run_noalloc(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream);
+
+/*
  * Same as spmv_run, but records a HIP event on `stream` before the first and after every launch,
  * waits for the last one (this call SYNCHRONISES the stream) and writes the duration of launch i
  * in milliseconds to launch_ms[i] (spmv_plan_launch_count entries).  For benchmarks and profiles.

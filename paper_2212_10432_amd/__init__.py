@@ -20,7 +20,7 @@ SPMV_OK, SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_CSR, SPMV_ERR_UNSUPPORTED = 0, 1, 2,
 SPMV_ERR_ALLOC, SPMV_ERR_HIP, SPMV_ERR_INTERNAL = 4, 5, 6
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC", 5: "HIP", 6: "INTERNAL"}
 
-EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
+EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
            "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
            "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error", "spmv_mm_read", "spmv_mm_free", "spmv_stream_ceiling"]
 
@@ -68,6 +68,8 @@ def load():
     lib.spmv_plan_create.argtypes = [P(vp), i64, i64, i64, vp, vp, vp, ci, P(spmv_options_t)]
     lib.spmv_run.restype = ci
     lib.spmv_run.argtypes = [vp, vp, vp, vp]
+    lib.spmv_run_noalloc.restype = ci
+    lib.spmv_run_noalloc.argtypes = [vp, vp, vp, vp]
     lib.spmv_run_timed.restype = ci
     lib.spmv_run_timed.argtypes = [vp, vp, vp, vp, P(ctypes.c_float)]
     lib.spmv_plan_time.restype = ci
@@ -159,6 +161,11 @@ _callbacks = {}
 def spmv_run(plan: int, x_dev: int, y_dev: int, stream: int = 0) -> None:
     """x_dev / y_dev are device addresses (tensor.data_ptr()); stream is a hipStream_t value."""
     _check(load().spmv_run(plan, x_dev, y_dev, stream))
+
+
+def spmv_run_noalloc(plan: int, x_dev: int, y_dev: int, stream: int = 0) -> None:
+    """spmv_run with the plan's scratch in the library's static device array (no allocation anywhere)."""
+    _check(load().spmv_run_noalloc(plan, x_dev, y_dev, stream))
 
 
 def spmv_run_timed(plan: int, x_dev: int, y_dev: int, stream: int = 0):
@@ -284,7 +291,7 @@ class Plan:
         self.value_dtype = np.dtype(np.asarray(values).dtype)
         self.handle = spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, **kw)
 
-    def run(self, x, y, stream=None):
+    def run(self, x, y, stream=None, noalloc=False):
         if x.numel() != self.ncols or y.numel() != self.nrows:
             raise SpmvError(SPMV_ERR_INVALID_ARG, "x / y have the wrong length")
         if not (x.is_cuda and y.is_cuda and x.is_contiguous() and y.is_contiguous()):
@@ -295,7 +302,7 @@ class Plan:
         if stream is None:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
-        spmv_run(self.handle, x.data_ptr(), y.data_ptr(), int(stream))
+        (spmv_run_noalloc if noalloc else spmv_run)(self.handle, x.data_ptr(), y.data_ptr(), int(stream))
         return y
 
     def run_timed(self, x, y, stream=None):

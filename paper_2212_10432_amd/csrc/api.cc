@@ -225,6 +225,11 @@ spmv_status_t spmv_plan_create(spmv_plan_t **out, int64_t nrows, int64_t ncols, 
         (void)hipGetLastError();
         fail(SPMV_ERR_HIP, "no HIP device available");
     }
+    if (!o.host_only) {
+        // everything a launch needs beyond the plan itself is set up here, so that spmv_run only enqueues kernels
+        const int err = prepare_device();
+        if (err) fail(SPMV_ERR_HIP, std::string("device set-up failed: ") + hip_error_text(err));
+    }
     const Census cen = take_census(A, threads);
     std::unique_ptr<Plan> plan;
     if (forced) {
@@ -252,6 +257,48 @@ spmv_status_t spmv_run(const spmv_plan_t *plan, const void *x_dev, void *y_dev, 
     if (x_dev && x_dev == y_dev) fail(SPMV_ERR_INVALID_ARG, "x and y must not alias");
     for (const Part &part : p.parts) {
         const int err = launch_part(part, p.dtype, p.nrows, p.ncols, x_dev, y_dev, stream);
+        if (err) fail(SPMV_ERR_HIP, std::string("launch of ") + part.name + " failed: " + hip_error_text(err));
+    }
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_run_noalloc(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream) {
+    API_BEGIN
+    if (!plan || !plan->impl) fail(SPMV_ERR_INVALID_ARG, "plan is NULL");
+    const Plan &p = *plan->impl;
+    if (p.mem.host_only) fail(SPMV_ERR_UNSUPPORTED, "the plan was built host-only and cannot run");
+    if ((!x_dev && p.ncols > 0) || (!y_dev && p.nrows > 0)) fail(SPMV_ERR_INVALID_ARG, "x or y is NULL");
+    if (x_dev && x_dev == y_dev) fail(SPMV_ERR_INVALID_ARG, "x and y must not alias");
+    // place the plan's scratch buffers one after the other (256-byte aligned) in the static array
+    constexpr int kMaxBuffers = 16;
+    const void *owned[kMaxBuffers];
+    size_t offset[kMaxBuffers];
+    if (p.scratch.size() > (size_t)kMaxBuffers) fail(SPMV_ERR_UNSUPPORTED, "spmv_run_noalloc: the plan has too many scratch buffers");
+    size_t need = 0;
+    for (size_t i = 0; i < p.scratch.size(); ++i) {
+        owned[i] = p.scratch[i].ptr;
+        offset[i] = need;
+        const size_t bytes = (size_t)p.scratch[i].count * (size_t)p.scratch[i].elem_bytes;
+        need += (bytes + 255) / 256 * 256;
+    }
+    if (need > kStaticScratchBytes)
+        fail(SPMV_ERR_UNSUPPORTED, "spmv_run_noalloc: the plan needs " + std::to_string(need) + " bytes of scratch, the static buffer holds " +
+                                       std::to_string(kStaticScratchBytes));
+    void *base = nullptr;
+    if (need > 0) {
+        const int err = static_scratch(&base);
+        if (err) fail(SPMV_ERR_HIP, std::string("spmv_run_noalloc: static scratch unavailable: ") + hip_error_text(err));
+    }
+    for (const Part &part : p.parts) {
+        void *over = nullptr;
+        if (part.scratch) {
+            size_t i = 0;
+            while (i < p.scratch.size() && owned[i] != part.scratch) ++i;
+            if (i == p.scratch.size()) fail(SPMV_ERR_INTERNAL, "spmv_run_noalloc: a launch refers to an unknown scratch buffer");
+            over = (unsigned char *)base + offset[i];
+        }
+        const int err = launch_part(part, p.dtype, p.nrows, p.ncols, x_dev, y_dev, stream, over);
         if (err) fail(SPMV_ERR_HIP, std::string("launch of ") + part.name + " failed: " + hip_error_text(err));
     }
     return SPMV_OK;

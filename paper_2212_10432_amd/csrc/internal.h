@@ -28,6 +28,8 @@ constexpr int kReduceBlockRows = 1024;
 // launch's group list), and the LDS budget of an x window or of a block's accumulators.
 constexpr int kXlGroup = 16;
 constexpr int64_t kXlMaxLds = 128 * 1024;
+// Size of the library's static device scratch array (spmv_run_noalloc).
+constexpr size_t kStaticScratchBytes = SPMV_STATIC_SCRATCH_BYTES;
 
 struct Error {
     spmv_status_t code;
@@ -181,8 +183,14 @@ std::unique_ptr<Plan> build_plan(const HostCsr &A, const Census &cen, const Plan
                                  const Allocator &mem, int threads);
 
 // Kernel launchers (kernels.hip).  Returns a hipError_t as int.
+// scratch_override, when not NULL, replaces the part's own scratch buffer.
 int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
-                void *y, void *stream);
+                void *y, void *stream, void *scratch_override = nullptr);
+// Once per device, when a plan is created there: raises the dynamic-LDS limit of the kernels that
+// need more than 64 KiB and looks up the device address of the library's static scratch array.
+int prepare_device();
+// Device address of the static scratch array on the current device (kStaticScratchBytes bytes).
+int static_scratch(void **ptr);
 const char *hip_error_text(int err);
 // Streaming ceiling of the current device (read, copy) in GB/s; returns a hipError_t as int.
 int stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps, double *copy_gbps);

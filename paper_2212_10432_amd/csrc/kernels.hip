@@ -10,6 +10,8 @@
 // with a window, the two-pass part).
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "internal.h"
 
 namespace spmv {
@@ -1088,7 +1090,7 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
 
 // -------------------------------------------------------------------------------------------
 template <typename T>
-int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, hipStream_t st) {
+int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, hipStream_t st, void *scratch) {
     auto blocks = [](int64_t items, int64_t per) { return (unsigned)((items + per - 1) / per); };
     switch (p.kind) {
     case K_ZERO: {
@@ -1157,14 +1159,6 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
             const int threads = kXwinWaves * kWave;
 #define XWIN_GO(B, R, L)                                                                           \
     {                                                                                              \
-        static std::atomic<int> lds_set{0};                                                        \
-        if (lds_set.load() < p.lds_bytes) {                                                        \
-            hipError_t e = hipFuncSetAttribute((const void *)k_bsell_xwin<T, B, R, L>,             \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,        \
-                                               (int)kMaxLds);                                      \
-            if (e != hipSuccess) return (int)e;                                                    \
-            lds_set.store((int)kMaxLds);                                                           \
-        }                                                                                          \
         k_bsell_xwin<T, B, R, L><<<grid, threads, (size_t)p.lds_bytes, st>>>(                      \
             (const int64_t *)p.p0, (const int32_t *)p.p1, (const T *)p.p2, (const int32_t *)p.p3,  \
             (const int32_t *)p.p4, x, y, p.units, p.nrows, p.remap);                               \
@@ -1202,34 +1196,22 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     case K_STRIPE: {
         if (p.units == 0 || p.nslices == 0) return 0;
         const size_t lds = ((size_t)p.tile + (size_t)p.nrows) * sizeof(T);
-        static std::atomic<int> lds_set{0};
-        if (lds > 65536 && !lds_set.load()) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_hsell<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
-            if (e != hipSuccess) return (int)e;
-            lds_set.store(1);
-        }
         if (p.delta) {
-            static std::atomic<int> lds_set_d{0};
-            if (lds > 65536 && !lds_set_d.load()) {
-                hipError_t e = hipFuncSetAttribute((const void *)k_hsell_delta<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
-                if (e != hipSuccess) return (int)e;
-                lds_set_d.store(1);
-            }
             k_hsell_delta<T><<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(
                 (const int32_t *)p.p0, (const uint32_t *)p.p1, (const T *)p.p2, (const uint32_t *)p.p4, x,
-                (T *)p.scratch, (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group);
+                (T *)scratch, (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group);
             break;
         }
         k_hsell<T><<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(
             (const int32_t *)p.p0, (const uint16_t *)p.p1, (const T *)p.p2, (const uint16_t *)p.p4, x,
-            (T *)p.scratch, (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group);
+            (T *)scratch, (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group);
         break;
     }
     case K_XS: {
         if (p.units == 0) return 0;
         k_xs<T><<<(unsigned)(8 * p.ngroups), kWG, 0, st>>>((const int64_t *)p.p0, (const int32_t *)p.p1,
                                                           (const T *)p.p2, (const int64_t *)p.p4, x,
-                                                          (T *)p.scratch);
+                                                          (T *)scratch);
         break;
     }
     case K_REDUCE_ROWS: {
@@ -1237,7 +1219,7 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         const unsigned grid = blocks(p.nrows, kWG);
 #define RR_GO(R, A)                                                                               \
     k_reduce_rows<T, R, A><<<grid, kWG, 0, st>>>((const int32_t *)p.p0, (const int32_t *)p.p1,    \
-                                                  (const T *)p.scratch, (const int32_t *)p.p3, y, \
+                                                  (const T *)scratch, (const int32_t *)p.p3, y, \
                                                   p.nrows, 1)
         if (p.has_rows) { if (p.accumulate) RR_GO(true, true); else RR_GO(true, false); }
         else            { if (p.accumulate) RR_GO(false, true); else RR_GO(false, false); }
@@ -1270,7 +1252,7 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
 #define XNB_GO(RR, BM)                                                                             \
     k_xnb<T, RR, BM><<<(unsigned)(8 * p.ngroups), kWG, 0, st>>>(                                   \
         (const int32_t *)p.p0, (const T *)p.p1, (const BM *)p.p2, (const int32_t *)p.p3,           \
-        (const int64_t *)p.p4, x, (T *)p.scratch)
+        (const int64_t *)p.p4, x, (T *)scratch)
         switch (p.lanes) {
         case 4: XNB_GO(4, uint8_t); break;
         case 8: XNB_GO(8, uint8_t); break;
@@ -1282,7 +1264,7 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     }
     case K_ZERO_SCRATCH: {
         if (p.nrows == 0) return 0;
-        k_zero_rows<T><<<blocks(p.nrows, kWG), kWG, 0, st>>>((const int32_t *)p.p0, p.nrows, (T *)p.scratch);
+        k_zero_rows<T><<<blocks(p.nrows, kWG), kWG, 0, st>>>((const int32_t *)p.p0, p.nrows, (T *)scratch);
         break;
     }
     case K_REDUCE_LDS: {
@@ -1290,7 +1272,7 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         const unsigned grid = blocks(p.nrows, kRedRows);
 #define RL_GO(Rw, A)                                                                               \
     k_reduce_lds<T, Rw, A><<<grid, kWG, 0, st>>>((const uint16_t *)p.p0, (const int32_t *)p.p1,    \
-                                                 (const T *)p.scratch, (const int32_t *)p.p3, y,   \
+                                                 (const T *)scratch, (const int32_t *)p.p3, y,   \
                                                  p.nrows, p.lanes)
         if (p.has_rows) { if (p.accumulate) RL_GO(true, true); else RL_GO(true, false); }
         else            { if (p.accumulate) RL_GO(false, true); else RL_GO(false, false); }
@@ -1306,14 +1288,8 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     case K_XL_MUL: {
         if (p.units == 0) return 0;
         const size_t lds = (size_t)p.tile * sizeof(T);
-        static std::atomic<int> lds_set{0};
-        if (lds > 65536 && !lds_set.load()) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_xl_mul<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
-            if (e != hipSuccess) return (int)e;
-            lds_set.store(1);
-        }
         k_xl_mul<T><<<(unsigned)p.units, kXlWG, lds, st>>>((const int32_t *)p.p0, (const T *)p.p1,
-                                                          (const uint16_t *)p.p2, x, (T *)p.scratch,
+                                                          (const uint16_t *)p.p2, x, (T *)scratch,
                                                           p.tile, ncols);
         break;
     }
@@ -1322,16 +1298,8 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         const size_t lds = (size_t)p.tile * sizeof(double);
 #define XLR_GO(Rw, A)                                                                              \
     {                                                                                              \
-        static std::atomic<int> lds_set{0};                                                        \
-        if (lds > 65536 && !lds_set.load()) {                                                      \
-            hipError_t e = hipFuncSetAttribute((const void *)k_xl_reduce<T, Rw, A>,                \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,        \
-                                               (int)kMaxLds);                                      \
-            if (e != hipSuccess) return (int)e;                                                    \
-            lds_set.store(1);                                                                      \
-        }                                                                                          \
         k_xl_reduce<T, Rw, A><<<(unsigned)p.units, kXlWG, lds, st>>>(                              \
-            (const int32_t *)p.p0, (const int32_t *)p.p1, (const T *)p.scratch,                    \
+            (const int32_t *)p.p0, (const int32_t *)p.p1, (const T *)scratch,                    \
             (const uint16_t *)p.p2, (const int32_t *)p.p3, y, p.tile, p.nrows);                    \
     }
         if (p.has_rows) { if (p.accumulate) XLR_GO(true, true) else XLR_GO(true, false) }
@@ -1343,10 +1311,10 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (p.nrows == 0) return 0;
         if (p.accumulate)
             k_reduce_wide<T, true><<<blocks(p.nrows, kWave), kReduceWaves * kWave, 0, st>>>(
-                (const T *)p.scratch, (int)p.ngroups, p.nrows, (const int32_t *)p.p3, y);
+                (const T *)scratch, (int)p.ngroups, p.nrows, (const int32_t *)p.p3, y);
         else
             k_reduce_wide<T, false><<<blocks(p.nrows, kWave), kReduceWaves * kWave, 0, st>>>(
-                (const T *)p.scratch, (int)p.ngroups, p.nrows, (const int32_t *)p.p3, y);
+                (const T *)scratch, (int)p.ngroups, p.nrows, (const int32_t *)p.p3, y);
         break;
     }
     }
@@ -1416,11 +1384,83 @@ int stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps, d
     return (int)err;
 }
 
+namespace {
+
+// Kernels that take more than 64 KiB of dynamic LDS need the limit raised once per device; this is
+// done when a plan is created, never on the launch path (spmv_run only enqueues kernels).
+template <typename T>
+hipError_t raise_lds_limits() {
+    const void *fns[] = {
+        (const void *)k_hsell<T>, (const void *)k_hsell_delta<T>, (const void *)k_xl_mul<T>,
+        (const void *)k_xl_reduce<T, false, false>, (const void *)k_xl_reduce<T, false, true>,
+        (const void *)k_xl_reduce<T, true, false>, (const void *)k_xl_reduce<T, true, true>,
+#define XWIN_ALL(B)                                                                               \
+    (const void *)k_bsell_xwin<T, B, false, false>, (const void *)k_bsell_xwin<T, B, false, true>, \
+    (const void *)k_bsell_xwin<T, B, true, false>, (const void *)k_bsell_xwin<T, B, true, true>
+        XWIN_ALL(2), XWIN_ALL(3), XWIN_ALL(4)
+#undef XWIN_ALL
+    };
+    for (const void *f : fns) {
+        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxLds);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Scratch shared by every spmv_run_noalloc call on a device: a file-scope device array, so that no
+// allocation is ever needed for it.  Host code never uses the symbol itself as an address: the
+// device address is looked up once per device (each device holds its own copy) and kept.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_dev_mutex;
+bool g_dev_ready[kMaxDevices] = {false};
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+}  // namespace
+
+int prepare_device() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (g_dev_ready[dev]) return 0;
+    e = raise_lds_limits<double>();
+    if (e == hipSuccess) e = raise_lds_limits<float>();
+    void *ptr = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    g_scratch_ptr[dev] = ptr;
+    g_dev_ready[dev] = true;
+    return 0;
+}
+
+int static_scratch(void **ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    {
+        std::lock_guard<std::mutex> lock(g_dev_mutex);
+        if (g_dev_ready[dev]) {
+            *ptr = g_scratch_ptr[dev];
+            return 0;
+        }
+    }
+    const int err = prepare_device();   // first use of this device by the library
+    if (err) return err;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    *ptr = g_scratch_ptr[dev];
+    return 0;
+}
+
 int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
-                void *y, void *stream) {
+                void *y, void *stream, void *scratch_override) {
     hipStream_t st = (hipStream_t)stream;
-    if (dtype == SPMV_F64) return launch_typed<double>(p, nrows, ncols, (const double *)x, (double *)y, st);
-    return launch_typed<float>(p, nrows, ncols, (const float *)x, (float *)y, st);
+    void *scratch = scratch_override ? scratch_override : p.scratch;
+    if (dtype == SPMV_F64) return launch_typed<double>(p, nrows, ncols, (const double *)x, (double *)y, st, scratch);
+    return launch_typed<float>(p, nrows, ncols, (const float *)x, (float *)y, st, scratch);
 }
 
 const char *hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
