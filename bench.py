@@ -41,6 +41,7 @@ def main():
     ap.add_argument("--plan-json", default="", help="JSON file {config: plan spec}: skip the search for those matrices")
     ap.add_argument("--save-plans", default="", help="write the chosen plan specs to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-parity", action="store_true", help="skip the full-size check of every timed plan against the oracle")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -68,7 +69,7 @@ def main():
     ceil_read, ceil_copy = lib.spmv_stream_ceiling(2 << 30, 5, torch.cuda.current_stream().cuda_stream)
     log(f"stream ceiling: read {ceil_read:.0f} GB/s, copy {ceil_copy:.0f} GB/s")
     items = []
-    cpu = {"seconds": 0.0, "flops": 0.0, "cores": 0, "sample": []}
+    cpu = {"seconds": 0.0, "seconds_1t": 0.0, "flops": 0.0, "cores": 0, "sample": []}
     cache = {}
     for name in names:
         desc, fam, dt = CONFIGS[name]
@@ -98,23 +99,35 @@ def main():
                           for _ in range(copies - 1)]
         xs = [torch.from_numpy(x).to(dev) for _ in range(copies)]
         ys = [torch.empty(m.nrows, dtype=tdt, device=dev) for _ in range(copies)]
-        if not args.no_cpu:
+        # parity of the very plan that is timed, at full size (outside the timed region): one run,
+        # every y element against the oracle's tolerance |y - y_ref| <= tau (|A||x|)
+        parity = None
+        if not args.no_parity or not args.no_cpu:
             import oracle
+        if not args.no_parity:
+            ys[0].fill_(float("nan"))
+            plan.run(xs[0], ys[0])
+            torch.cuda.synchronize()
+            ok, worst = oracle.check(ys[0].cpu().numpy(), m.row_ptr, m.col_idx, vals, x, threads=len(os.sched_getaffinity(0)))
+            parity = dict(parity_ok=bool(ok), worst_err_over_tol=float(worst))
+            log(f"{name}: parity_ok={ok} worst error / tolerance = {worst:.3g}")
+        if not args.no_cpu:
             threads = len(os.sched_getaffinity(0))
-            oracle.spmv(m.row_ptr, m.col_idx, vals, x, threads=threads)          # warm-up
-            ts = []
-            for _ in range(3):
-                t0 = time.perf_counter()
-                oracle.spmv(m.row_ptr, m.col_idx, vals, x, threads=threads)
-                ts.append(time.perf_counter() - t0)
-            cpu["seconds"] += sorted(ts)[1]
+            for nt, key in ((threads, "seconds"), (1, "seconds_1t")):
+                oracle.spmv(m.row_ptr, m.col_idx, vals, x, threads=nt)          # warm-up
+                ts = []
+                for _ in range(5):
+                    t0 = time.perf_counter()
+                    oracle.spmv(m.row_ptr, m.col_idx, vals, x, threads=nt)
+                    ts.append(time.perf_counter() - t0)
+                cpu[key] += sorted(ts)[2]
             cpu["flops"] += 2.0 * m.nnz
             cpu["cores"] = threads
             cpu["sample"].append(name)
         items.append(dict(name=name, desc=desc, nnz=m.nnz, nrows=m.nrows, dtype=dt.name, plans=plans, xs=xs, ys=ys,
                           copies=copies, b_plan=b_plan, b_csr=b_csr, spec=d["spec"], operators=d["operators"],
                           launches=plan.launch_names(), launch_bytes=[p["bytes"] for p in d["parts"]],
-                          gen_s=t_gen, plan_s=t_plan,
+                          gen_s=t_gen, plan_s=t_plan, parity=parity,
                           search=[(c["spec"], c["run_us"], c["note"]) for c in d["search"]]))
         log(f"{name}: nnz={m.nnz} gen {t_gen:.1f}s plan {t_plan:.1f}s -> {d['spec']} (copies={copies})")
         del vals, x
@@ -177,10 +190,8 @@ def main():
         it["ms"] = e0.elapsed_time(e1) / (reps * nrep)
         it["ms_graph"] = it["ms"]
         if it["copies"] == 1:
-            # back-to-back launches from the library's own timing loop (what a C caller sees); for
-            # the launch-bound matrices this is faster than replaying a graph of kernel nodes
-            it["ms_loop"] = it["plans"][0].time(it["xs"][0], it["ys"][0], stream.cuda_stream, 25) * 1e-3
-            it["ms"] = min(it["ms"], it["ms_loop"])
+            # back-to-back launches from the library's own timing loop (what a C caller sees)
+            it["ms_loop"] = it["plans"][0].time(it["xs"][0], it["ys"][0], stream.cuda_stream, 25) * 1e-3   # reported beside, never used
         # warm (cache-resident) figure for rotated matrices: the same copy every time
         if it["copies"] > 1:
             gw = torch.cuda.CUDAGraph()
@@ -217,7 +228,13 @@ def main():
                    plan=it["spec"], operators=it["operators"], launches=it["launches"],
                    launch_us=[v * 1e3 for v in it["launch_ms"]], launch_bytes=it["launch_bytes"],
                    rotated_copies=it["copies"],
+                   # what this plan's own bytes would take at the read ceiling measured in this run:
+                   # the time below which only a plan that moves fewer bytes can go
+                   design_floor_us=it["b_plan"] / (ceil_read * 1e9) * 1e6,
+                   csr_floor_us=it["b_csr"] / (ceil_read * 1e9) * 1e6,
                    plan_create_s=it["plan_s"], search=it["search"])
+        if it["parity"] is not None:
+            rec.update(it["parity"])
         if "ms_warm" in it:
             rec["us_cache_warm"] = it["ms_warm"] * 1e3
         rec["us_graph_replay"] = it["ms_graph"] * 1e3
@@ -227,6 +244,13 @@ def main():
 
     def geomean(v):
         return float(np.exp(np.mean(np.log(v)))) if len(v) else None
+
+    # one score per configured matrix: the fp64 and fp32 runs of the hybrid matrix count as one
+    # (their geometric mean), so that the mean below is over the five matrices
+    by_matrix = {}
+    for r in per_config:
+        by_matrix.setdefault(CONFIGS[r["config"]][1], []).append(r["hbm_frac"])
+    matrix_frac = {k: geomean(v) for k, v in by_matrix.items()}
 
     # dominant kernel: the launch with the largest share of a step; its algorithmic bytes are the
     # format arrays it reads plus the x, scratch and y elements it touches (plan description)
@@ -249,25 +273,37 @@ def main():
 
     out = {
         "metric": "SpMV GFLOP/s (2*nnz/time) and achieved HBM GB/s (fraction of 8 TB/s peak) per matrix, 1 MI355X",
-        "value": 2.0 * tot_nnz / (tot_ms * 1e-3) / 1e9,
+        "value": 2.0 * tot_nnz / (wall_ms * 1e-3) / 1e9,
         "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": tot_ms, "wall_ms_per_step": wall_ms,
+        "ms_per_step": wall_ms, "sum_of_per_matrix_ms": tot_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64" if all(it["dtype"] == "float64" for it in items) else "f64+f32",
         "data": "synthetic",
         "config": {"workload": "+".join(names) + " (seeded synthetic stand-ins for SuiteSparse), one spmv_run per matrix per step"},
         "geomean_gflops": geomean([r["gflops"] for r in per_config]),
-        "geomean_hbm_frac": geomean([r["hbm_frac"] for r in per_config]),
-        "geomean_hbm_frac_without_C1": geomean([r["hbm_frac"] for r in per_config if r["config"] != "C1"]),
+        "hbm_frac_per_matrix": matrix_frac,
+        "geomean_hbm_frac": geomean(list(matrix_frac.values())),
+        "geomean_hbm_frac_without_C1": geomean([v for k, v in matrix_frac.items() if k != "C1"]),
+        "parity_ok": (all(r["parity_ok"] for r in per_config) if all("parity_ok" in r for r in per_config) else None),
         "stream_ceiling": {"read_gbps": ceil_read, "copy_gbps": ceil_copy, "bytes": 2 << 30,
                            "note": "measured at start-up with the library's spmv_stream_ceiling"},
         "per_config": per_config,
         "roofline": roofline,
     }
     if not args.no_cpu and cpu["seconds"] > 0:
+        model = ""
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         out["cpu_baseline"] = dict(value=cpu["flops"] / cpu["seconds"] / 1e9, unit="GFLOP/s", cores=cpu["cores"],
-                                   kind="oracle", sample="one full oracle SpMV (median of 3) on each of " + ",".join(cpu["sample"]))
+                                   kind="oracle", value_1_thread=cpu["flops"] / cpu["seconds_1t"] / 1e9, cpu_model=model,
+                                   sample="one full oracle SpMV (median of 5 after a warm-up; rows split over all cores, and on "
+                                          "one thread) on each of " + ",".join(cpu["sample"]))
     for it in items:
         for p in it["plans"]:
             p.destroy()

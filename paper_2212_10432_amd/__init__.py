@@ -135,6 +135,11 @@ def spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, *, force_plan=None,
     code = _dtype_code(values.dtype)
     if nnz is None:
         nnz = int(values.size)
+    # the library reads nrows + 1 offsets and nnz columns and values through raw pointers
+    if nrows < 0 or row_ptr.size != nrows + 1:
+        raise SpmvError(SPMV_ERR_INVALID_ARG, f"row_ptr has {row_ptr.size} entries, nrows + 1 = {nrows + 1} expected")
+    if nnz < 0 or col_idx.size < nnz or values.size < nnz:
+        raise SpmvError(SPMV_ERR_INVALID_ARG, f"col_idx / values hold {col_idx.size} / {values.size} entries, nnz = {nnz}")
     opts = spmv_options_t()
     opts.force_plan = force_plan.encode() if force_plan else None
     opts.search_budget_ms = float(search_budget_ms)

@@ -102,7 +102,8 @@ void read_matrix_market(const char *path, spmv_dtype_t dtype, MmCsr &out) {
         N = std::strtoll(q1, &q, 10);
         const char *q2 = q;
         L = std::strtoll(q2, &q, 10);
-        if (q1 == b || q2 == q1 || q == q2 || errno) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: bad size line");
+        // a number that starts after the end of this line was taken from the next one
+        if (q1 == b || q2 == q1 || q == q2 || errno || q > e) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: bad size line");
         break;
     }
     if (M < 0 || N < 0 || L < 0) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: missing or negative size line");
@@ -110,6 +111,9 @@ void read_matrix_market(const char *path, spmv_dtype_t dtype, MmCsr &out) {
     if (sym != "general" && M != N) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: a symmetric matrix must be square");
     std::vector<int32_t> ri, ci;
     std::vector<double> va;
+    // an entry line is at least four bytes ("1 1\n"): a count the file cannot hold is malformed
+    if (L > (long long)(end - cur) / 4 + 1)
+        fail(SPMV_ERR_INVALID_ARG, "Matrix Market: the size line announces " + std::to_string(L) + " entries, more than the file can hold");
     ri.reserve((size_t)L);
     ci.reserve((size_t)L);
     va.reserve((size_t)L);
@@ -121,12 +125,12 @@ void read_matrix_market(const char *path, spmv_dtype_t dtype, MmCsr &out) {
         const long long i = std::strtoll(b, &q, 10);
         const char *q1 = q;
         const long long j = std::strtoll(q1, &q, 10);
-        if (q1 == b || q == q1 || errno) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: bad entry line " + std::to_string(seen + 1));
+        if (q1 == b || q == q1 || errno || q > e) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: bad entry line " + std::to_string(seen + 1));
         double v = 1.0;
         if (!pattern) {
             const char *q2 = q;
             v = std::strtod(q2, &q);
-            if (q == q2) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: entry " + std::to_string(seen + 1) + " has no value");
+            if (q == q2 || q > e) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: entry " + std::to_string(seen + 1) + " has no value");
         }
         if (i < 1 || i > M || j < 1 || j > N)
             fail(SPMV_ERR_BAD_CSR, "Matrix Market: entry " + std::to_string(seen + 1) + " lies outside the matrix");

@@ -33,3 +33,15 @@ def test_binding_has_the_same_names():
 
 def test_last_error_is_empty_string_or_text():
     assert isinstance(lib.spmv_last_error(), str)
+
+
+def test_binding_checks_array_lengths_before_passing_pointers():
+    import numpy as np
+    import pytest
+    rp = np.array([0, 1, 2], np.int32)
+    with pytest.raises(lib.SpmvError) as e:          # row_ptr too short for nrows = 5
+        lib.spmv_plan_create(5, 2, rp, np.zeros(2, np.int32), np.ones(2), host_only=True, force_plan="light=csrv")
+    assert e.value.status == lib.SPMV_ERR_INVALID_ARG
+    with pytest.raises(lib.SpmvError) as e:          # nnz larger than the arrays
+        lib.spmv_plan_create(2, 2, rp, np.zeros(2, np.int32), np.ones(2), host_only=True, force_plan="light=csrv", nnz=7)
+    assert e.value.status == lib.SPMV_ERR_INVALID_ARG

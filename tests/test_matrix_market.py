@@ -105,6 +105,13 @@ def test_empty_matrix_and_crlf(tmp_path):
     ("%%MatrixMarket matrix coordinate real general\n2 2 1\n1 1\n", lib.SPMV_ERR_INVALID_ARG),
     ("%%MatrixMarket matrix coordinate real symmetric\n2 3 1\n1 1 1.0\n", lib.SPMV_ERR_INVALID_ARG),
     ("%%MatrixMarket matrix coordinate real skew-symmetric\n2 2 1\n1 1 1.0\n", lib.SPMV_ERR_INVALID_ARG),
+    # a truncated line must not borrow its missing numbers from the line after it
+    ("%%MatrixMarket matrix coordinate real general\n3 3 2\n1\n2 3 5.0\n", lib.SPMV_ERR_INVALID_ARG),
+    ("%%MatrixMarket matrix coordinate real general\n3 3 2\n1 2\n3 3 5.0\n", lib.SPMV_ERR_INVALID_ARG),
+    ("%%MatrixMarket matrix coordinate real general\n3 3\n2\n1 1 1.0\n2 2 1.0\n", lib.SPMV_ERR_INVALID_ARG),
+    ("%%MatrixMarket matrix coordinate pattern general\n3 3 2\n1\n2 3\n", lib.SPMV_ERR_INVALID_ARG),
+    # an entry count the file cannot possibly hold
+    ("%%MatrixMarket matrix coordinate real general\n3 3 2000000000\n1 1 1.0\n", lib.SPMV_ERR_INVALID_ARG),
 ])
 def test_malformed_files_are_refused(tmp_path, text, status):
     path = str(tmp_path / "bad.mtx")
