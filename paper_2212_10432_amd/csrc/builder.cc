@@ -284,7 +284,7 @@ void build_csrv(Plan &plan, const HostCsr &A, std::vector<int32_t> rows, int lpr
 // else goes to the remainder matrix.
 template <typename T>
 void build_dia(Plan &plan, const HostCsr &A, const std::vector<int32_t> &offs, OwnedCsr &rem,
-               int threads) {
+               int drows, int threads) {
     const int64_t nd = (int64_t)offs.size();
     const int64_t ld = (A.nrows + kWave - 1) / kWave * kWave;
     HostBuf<T> dv(nd * ld);
@@ -337,6 +337,7 @@ void build_dia(Plan &plan, const HostCsr &A, const std::vector<int32_t> &offs, O
     p.stored = nd * ld;
     p.units = A.nrows;
     p.ndiag = (int)nd;
+    p.lanes = nd <= 8 ? drows : 1;   // rows per lane (the kernel for more than eight diagonals has one)
     for (int64_t d = 0; d < std::min<int64_t>(nd, 8); ++d) p.dia_offsets[d] = offs[(size_t)d];
     p.ld = ld;
     const size_t a0 = plan.arrays.size();
@@ -1103,11 +1104,14 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
         p.units = nitems;
         p.tile = (int)W;
         p.scratch = scratch;
+        int64_t staged = 0;   // elements of x copied into LDS by one launch: a window per item
+        for (int64_t it = 0; it < nitems; ++it)
+            staged += std::min<int64_t>(W, A.ncols - (int64_t)items[(size_t)(3 * it)] * W);
         const size_t a1 = plan.arrays.size();
         p.p0 = upload(plan, "xl.items", 4, 3 * nitems, items.data());
         p.p1 = upload(plan, "xl.vals", (int)sizeof(T), tot, vals.p);
         p.p2 = upload(plan, "xl.lcol", 2, tot, lcol.p);
-        add_part(plan, p, a1, std::min<int64_t>(A.ncols, real), tot, 0);
+        add_part(plan, p, a1, staged, tot, 0);
     }
     Part r;
     r.kind = K_XL_REDUCE;
@@ -1363,7 +1367,7 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
             offs.swap(keep);
         }
         if (offs.empty()) fail(SPMV_ERR_UNSUPPORTED, "dia: the matrix has no diagonal populated enough");
-        build_dia<T>(*plan, *cur, offs, rem, threads);
+        build_dia<T>(*plan, *cur, offs, rem, spec.drows, threads);
         cur = &rem.view;
         acc = true;
         if (cur->nnz == 0) return plan;

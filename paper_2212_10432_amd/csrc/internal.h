@@ -86,13 +86,14 @@ enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZ
 struct PlanSpec {
     int dia = 0;             // extract well-populated diagonals into a DIA part first
     double dia_fill = 0.5;   //   minimum population of a diagonal to be extracted
+    int drows = 1;           //   rows per lane of the DIA kernel (1, 2 or 4)
     int64_t heavy = 0;       // ROW_DIV: rows longer than this go to the heavy part (0 = no split)
     int tile = 8192;         //   COL_DIV width of the heavy part (columns per LDS tile of x)
     int hd = 0;              //   1 = the heavy part stores 8-bit column deltas instead of 16-bit columns
     int light = L_CSRV;      // design of the remaining rows
     int lpr = 0;             // csrv: lanes per row (power of two <= 64; 0 = from the mean length)
     int64_t chunk = 0;       // csrv: rows longer than this are cut into segments (0 = never)
-                             // xl: most entries per workgroup of the multiply launch (0 = 32768)
+                             // xl: most entries per item of the multiply launch (0 = 32768)
     int sigma = 0;           // sell/bsell: sort window in rows (0 = no sort, -1 = whole part)
     int block = 3;           // bsell: block edge (2, 3 or 4)
     int smax = 16;           // bin: rows up to this length go to the SELL bin

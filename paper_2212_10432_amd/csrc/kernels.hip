@@ -177,6 +177,47 @@ __global__ __launch_bounds__(kWG) void k_dia_fixed(DiaOffsets offs, const T *__r
     else __builtin_nontemporal_store(acc, y + i);
 }
 
+// BMT_ROW_BLOCK(RPL): a lane owns RPL consecutive rows, so that the values of a diagonal arrive as
+// one RPL-wide vector load per lane and a quarter (half) as many workgroups have to start: at a few
+// microseconds per launch the ramp of the grid is a visible part of the run.
+template <typename T, int ND, int RPL, bool ACC>
+__global__ __launch_bounds__(kWG) void k_dia_rows(DiaOffsets offs, const T *__restrict__ vals,
+                                                  int64_t ld, const T *__restrict__ x,
+                                                  T *__restrict__ y, int64_t nrows, int64_t ncols) {
+    typedef T VT __attribute__((ext_vector_type(RPL)));
+    const int64_t i0 = ((int64_t)blockIdx.x * kWG + threadIdx.x) * RPL;
+    if (i0 >= nrows) return;   // ld is a multiple of 64 >= nrows: the vector loads below stay inside a diagonal
+    VT v[ND];
+    T xv[ND][RPL];
+#pragma unroll
+    for (int d = 0; d < ND; ++d) {
+        v[d] = ldnt(reinterpret_cast<const VT *>(vals + (int64_t)d * ld + i0));
+        const int64_t c0 = i0 + offs.o[d];
+#pragma unroll
+        for (int r = 0; r < RPL; ++r) {
+            const int64_t c = c0 + r;
+            xv[d][r] = (c >= 0 && c < ncols) ? x[c] : T(0);
+        }
+    }
+    VT acc;
+#pragma unroll
+    for (int r = 0; r < RPL; ++r) {
+        T a = T(0);
+#pragma unroll
+        for (int d = 0; d < ND; ++d) a += v[d][r] * xv[d][r];
+        acc[r] = a;
+    }
+    if (i0 + RPL <= nrows && (reinterpret_cast<uintptr_t>(y + i0) % sizeof(VT)) == 0) {
+        VT *dst = reinterpret_cast<VT *>(y + i0);
+        if (ACC) acc += *dst;
+        __builtin_nontemporal_store(acc, dst);
+    } else {
+#pragma unroll
+        for (int r = 0; r < RPL; ++r)
+            if (i0 + r < nrows) y[i0 + r] = ACC ? y[i0 + r] + acc[r] : acc[r];
+    }
+}
+
 // ---- SELL: one wavefront per slice of 64 rows, one lane per row -----------------------------
 // BMW_ROW_BLOCK(64) + BMT_ROW_BLOCK(1) + BMW_PAD + THREAD_TOTAL_RED.  Entry j of the row held by
 // `lane` sits at slice_ptr[s] + 64*j + lane, so every load of a wavefront is one contiguous run.
@@ -931,32 +972,38 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restr
 // y[rows[i]] (+)= sum over g < np of partial[g * n + i]: many partials (one per workgroup of the
 // heavy kernel), few rows.  16 wavefronts split the partials, LDS combines them.
 constexpr int kReduceWaves = 16;
+constexpr int kReduceRows = 32;   // rows per workgroup: the two halves of a wavefront take alternate partials
 template <typename T, bool ACC>
 __global__ __launch_bounds__(kReduceWaves * kWave) void k_reduce_wide(const T *__restrict__ partial,
                                                                       int np, int64_t n,
                                                                       const int32_t *__restrict__ rows,
                                                                       T *__restrict__ y) {
     __shared__ T red[kReduceWaves][kWave];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t i = (int64_t)blockIdx.x * kWave + lane;
-    // eight independent loads per step: the launch has few workgroups and lives on latency
-    T a[8] = {T(0), T(0), T(0), T(0), T(0), T(0), T(0), T(0)};
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
+    const int64_t i = (int64_t)blockIdx.x * kReduceRows + (lane & 31);
+    // The launch has few workgroups and lives on latency: a lane issues sixteen loads before it adds
+    // the first (partials 2*wave + half + 32*u), which covers 512 partials in a single round trip.
+    T acc = T(0);
     if (i < n) {
-        int g = wave;
-        for (; g + 7 * kReduceWaves < np; g += 8 * kReduceWaves) {
+        for (int g0 = 2 * wave + half; g0 < np; g0 += 32 * 16) {
+            T a[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) a[u] += partial[(int64_t)(g + u * kReduceWaves) * n + i];
+            for (int u = 0; u < 16; ++u) {
+                const int g = g0 + 32 * u;
+                a[u] = g < np ? ldnt(partial + (int64_t)g * n + i) : T(0);
+            }
+#pragma unroll
+            for (int u = 0; u < 16; u += 4) acc += (a[u] + a[u + 1]) + (a[u + 2] + a[u + 3]);
         }
-        for (; g < np; g += kReduceWaves) a[0] += partial[(int64_t)g * n + i];
     }
-    red[wave][lane] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+    red[wave][lane] = acc;
     __syncthreads();
-    if (wave == 0 && i < n) {
-        T acc = T(0);
+    if (wave == 0 && half == 0 && i < n) {
+        T sum = T(0);
 #pragma unroll
-        for (int k = 0; k < kReduceWaves; ++k) acc += red[k][lane];
+        for (int k = 0; k < kReduceWaves; ++k) sum += red[k][lane] + red[k][lane + 32];
         const int64_t r = rows[i];
-        y[r] = ACC ? y[r] + acc : acc;
+        y[r] = ACC ? y[r] + sum : sum;
     }
 }
 
@@ -978,7 +1025,10 @@ template <> struct XlVec<double> { typedef xl_d2 V; typedef xl_u2 I; static cons
 template <> struct XlVec<float> { typedef xl_f4 V; typedef xl_u4 I; static constexpr int N = 4; };
 
 constexpr int kXlWG = 1024;
-// item i = (window, first entry, end entry); both entry numbers are multiples of 16
+// item i = (window, first entry, end entry); both entry numbers are multiples of 16.  One workgroup
+// per item, each staging its window of x: workgroups that walk several items of a window and stage it
+// once were measured to be slower (the copies of x come from the memory-side cache, and many short
+// workgroups overlap one workgroup's staging with another's streaming).
 template <typename T>
 __global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ item,
                                                   const T *__restrict__ vals,
@@ -1106,12 +1156,21 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (p.ndiag >= 1 && p.ndiag <= 8) {
             DiaOffsets o;
             for (int d = 0; d < 8; ++d) o.o[d] = d < p.ndiag ? p.dia_offsets[d] : 0;
+#define DIA_GO(N, RPL)                                                                             \
+    {                                                                                              \
+        const unsigned g = blocks(nrows, (int64_t)kWG * RPL);                                      \
+        if (p.accumulate) k_dia_rows<T, N, RPL, true><<<g, kWG, 0, st>>>(o, vals, p.ld, x, y, nrows, ncols); \
+        else k_dia_rows<T, N, RPL, false><<<g, kWG, 0, st>>>(o, vals, p.ld, x, y, nrows, ncols);   \
+    }
 #define DIA_N(N)                                                                                   \
     case N:                                                                                        \
-        if (p.accumulate) k_dia_fixed<T, N, true><<<grid, kWG, 0, st>>>(o, vals, p.ld, x, y, nrows, ncols); \
+        if (p.lanes == 2) DIA_GO(N, 2)                                                             \
+        else if (p.lanes == 4) DIA_GO(N, 4)                                                        \
+        else if (p.accumulate) k_dia_fixed<T, N, true><<<grid, kWG, 0, st>>>(o, vals, p.ld, x, y, nrows, ncols); \
         else k_dia_fixed<T, N, false><<<grid, kWG, 0, st>>>(o, vals, p.ld, x, y, nrows, ncols);    \
         break;
             switch (p.ndiag) { DIA_N(1) DIA_N(2) DIA_N(3) DIA_N(4) DIA_N(5) DIA_N(6) DIA_N(7) DIA_N(8) }
+#undef DIA_GO
 #undef DIA_N
             break;
         }
@@ -1310,10 +1369,10 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     case K_REDUCE_WIDE: {
         if (p.nrows == 0) return 0;
         if (p.accumulate)
-            k_reduce_wide<T, true><<<blocks(p.nrows, kWave), kReduceWaves * kWave, 0, st>>>(
+            k_reduce_wide<T, true><<<blocks(p.nrows, kReduceRows), kReduceWaves * kWave, 0, st>>>(
                 (const T *)scratch, (int)p.ngroups, p.nrows, (const int32_t *)p.p3, y);
         else
-            k_reduce_wide<T, false><<<blocks(p.nrows, kWave), kReduceWaves * kWave, 0, st>>>(
+            k_reduce_wide<T, false><<<blocks(p.nrows, kReduceRows), kReduceWaves * kWave, 0, st>>>(
                 (const T *)scratch, (int)p.ngroups, p.nrows, (const int32_t *)p.p3, y);
         break;
     }

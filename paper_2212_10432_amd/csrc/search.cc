@@ -198,6 +198,14 @@ static std::vector<PlanSpec> neighbours(const PlanSpec &b, spmv_dtype_t dtype) {
     std::vector<PlanSpec> out;
     auto add = [&](PlanSpec p) { out.push_back(p); };
     const int vsize = dtype == SPMV_F64 ? 8 : 4;
+    if (b.dia) {   // BMT_ROW_BLOCK of the diagonal part: rows per lane
+        for (int r : {1, 2, 4})
+            if (r != b.drows) {
+                PlanSpec p = b;
+                p.drows = r;
+                add(p);
+            }
+    }
     if (b.heavy > 0) {
         PlanSpec p = b;
         p.hd = !b.hd;   // 8-bit column differences pay when the heavy rows are dense enough

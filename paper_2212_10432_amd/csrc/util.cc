@@ -104,6 +104,7 @@ PlanSpec parse_spec(const std::string &s) {
             else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown light design " + v);
         } else if (k == "dia") p.dia = (int)num();
         else if (k == "dia_fill") p.dia_fill = num();
+        else if (k == "drows") p.drows = (int)num();
         else if (k == "heavy") p.heavy = (int64_t)num();
         else if (k == "tile") p.tile = (int)num();
         else if (k == "hd") p.hd = (int)num();
@@ -122,6 +123,8 @@ PlanSpec parse_spec(const std::string &s) {
     }
     if (p.dia != 0 && p.dia != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia must be 0 or 1");
     if (!(p.dia_fill > 0 && p.dia_fill <= 1)) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia_fill must be in (0,1]");
+    if (p.drows != 1 && p.drows != 2 && p.drows != 4) fail(SPMV_ERR_INVALID_ARG, "plan spec: drows must be 1, 2 or 4");
+    if (p.drows != 1 && !p.dia) fail(SPMV_ERR_INVALID_ARG, "plan spec: drows needs dia=1");
     if (p.heavy < 0) fail(SPMV_ERR_INVALID_ARG, "plan spec: heavy must be >= 0");
     if (p.tile < 64 || p.tile > 65536 || p.tile % 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: tile must be a multiple of 64 in [64, 65536]");
     if (p.lpr != 0 && (!pow2(p.lpr) || p.lpr > 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: lpr must be 0 or a power of two <= 64");
@@ -145,6 +148,7 @@ PlanSpec parse_spec(const std::string &s) {
 std::string print_spec(const PlanSpec &p) {
     std::ostringstream o;
     if (p.dia) o << "dia=1,dia_fill=" << p.dia_fill << ",";
+    if (p.dia && p.drows != 1) o << "drows=" << p.drows << ",";
     if (p.heavy) o << "heavy=" << p.heavy << ",tile=" << p.tile << (p.hd ? ",hd=1," : ",");
     o << "light=" << light_name(p.light);
     switch (p.light) {
@@ -166,7 +170,7 @@ std::string print_spec(const PlanSpec &p) {
 std::string operator_chain(const PlanSpec &p) {
     std::ostringstream o;
     o << "COMPRESS";
-    if (p.dia) o << " -> DIA_EXTRACT(fill>=" << p.dia_fill << ")[BMT_ROW_BLOCK(1) -> THREAD_TOTAL_RED]";
+    if (p.dia) o << " -> DIA_EXTRACT(fill>=" << p.dia_fill << ")[BMT_ROW_BLOCK(" << p.drows << ") -> THREAD_TOTAL_RED]";
     if (p.heavy)
         o << " -> ROW_DIV(len>" << p.heavy << ")[HEAVY_SPLIT: COL_DIV(" << p.tile
           << ") -> BMTB_COL_BLOCK -> SORT_BMTB -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD"

@@ -18,7 +18,8 @@ pytestmark = pytest.mark.gpu
 SPECS = {
     "C1": ["light=xl,w=1024,rb=2048,chunk=4096", "light=xl", "light=coo", "light=xnb,k=8,r=4", "light=nnzb,r=4", "light=xs,k=8,sigma=256", "light=xs,k=32,sigma=0", "light=csrv", "light=csrv,lpr=1", "light=csrv,lpr=64,sigma=128", "light=sell", "light=sell,sigma=256,remap=1",
            "light=bin,smax=4,sigma=128"],
-    "C2": ["dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=512,rb=1024", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "light=xs,k=24,sigma=4096", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
+    "C2": ["dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=512,rb=1024", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "light=xs,k=24,sigma=4096", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1",
+           "dia=1,drows=2,light=sell", "dia=1,dia_fill=0.999,drows=4,light=csrv,lpr=1"],
     "C3": ["light=xl,w=4096,rb=8192", "heavy=1024,tile=2048,light=xl,w=16384,rb=16384,chunk=20000", "heavy=1024,tile=2048,light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=8192", "light=csrv,chunk=512", "light=csrv,lpr=32", "light=bin,smax=16,sigma=512,chunk=256",
            "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
            "heavy=256,tile=512,light=sell,sigma=128", "heavy=2048,tile=8192,light=bin,chunk=1024", "heavy=1024,tile=2048,hd=1,light=xl", "heavy=256,tile=512,hd=1,light=sell,sigma=128"],
