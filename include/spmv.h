@@ -118,6 +118,35 @@ spmv_status_t spmv_run(const spmv_plan_t *plan, const void *x_dev, void *y_dev, 
 spmv_status_t spmv_run_noalloc(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream);
 
 /*
+ * Y[:, v] = A * X[:, v] for k right-hand sides with one plan (multi-vector SpMM; the paper's tool
+ * produces a kernel that "can be directly called" for any vector, Section III -- this is the same
+ * call for several vectors at once).  Vector v of X starts at x_dev + v*ldx elements, vector v of
+ * Y at y_dev + v*ldy elements (ldx >= ncols, ldy >= nrows); every element of the k result vectors is
+ * overwritten.  Launches of the diagonal, SELL and CSR-segment designs read the matrix once for
+ * 8, 4 or 2 vectors at a time; launches that hand partial sums to each other through the plan's
+ * scratch run vector by vector on `stream`.  No allocation, no host synchronisation.
+ * k = 0 is a no-op; k outside [0, 4096] or a leading dimension that is too small ->
+ * SPMV_ERR_INVALID_ARG.
+ */
+spmv_status_t spmv_run_multi(const spmv_plan_t *plan, const void *x_dev, int64_t ldx, void *y_dev,
+                             int64_t ldy, int k, void *stream);
+
+/*
+ * Plan files.  The paper's tool leaves its result behind as generated code plus the format arrays
+ * it reads, to be used without searching again (Section III "Overview"; artifact description).
+ * spmv_plan_save writes the plan -- spec, census, launch list, every format array (copied from the
+ * device), search log -- to `path`; spmv_plan_load rebuilds an equivalent plan from such a file
+ * without the CSR matrix, the search or the host format construction.  Of `opts` only dev_alloc /
+ * dev_free / user and host_only are used (NULL = defaults); a host_only load needs no device.
+ * The file is little endian, carries a hash of its payload, and is meant to be read by the library
+ * version that wrote it: a file that is truncated, damaged or not a plan file gives
+ * SPMV_ERR_INVALID_ARG and *out = NULL.  A plan file is trusted input (its offsets are not
+ * re-derived from a matrix): load only files this library wrote.
+ */
+spmv_status_t spmv_plan_save(const spmv_plan_t *plan, const char *path);
+spmv_status_t spmv_plan_load(spmv_plan_t **out, const char *path, const spmv_options_t *opts);
+
+/*
  * Same as spmv_run, but records a HIP event on `stream` before the first and after every launch,
  * waits for the last one (this call SYNCHRONISES the stream) and writes the duration of launch i
  * in milliseconds to launch_ms[i] (spmv_plan_launch_count entries).  For benchmarks and profiles.

@@ -20,7 +20,7 @@ SPMV_OK, SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_CSR, SPMV_ERR_UNSUPPORTED = 0, 1, 2,
 SPMV_ERR_ALLOC, SPMV_ERR_HIP, SPMV_ERR_INTERNAL = 4, 5, 6
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC", 5: "HIP", 6: "INTERNAL"}
 
-EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
+EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_multi", "spmv_plan_save", "spmv_plan_load", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
            "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
            "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error", "spmv_mm_read", "spmv_mm_free", "spmv_stream_ceiling"]
 
@@ -70,6 +70,12 @@ def load():
     lib.spmv_run.argtypes = [vp, vp, vp, vp]
     lib.spmv_run_noalloc.restype = ci
     lib.spmv_run_noalloc.argtypes = [vp, vp, vp, vp]
+    lib.spmv_run_multi.restype = ci
+    lib.spmv_run_multi.argtypes = [vp, vp, i64, vp, i64, ci, vp]
+    lib.spmv_plan_save.restype = ci
+    lib.spmv_plan_save.argtypes = [vp, ctypes.c_char_p]
+    lib.spmv_plan_load.restype = ci
+    lib.spmv_plan_load.argtypes = [P(vp), ctypes.c_char_p, P(spmv_options_t)]
     lib.spmv_run_timed.restype = ci
     lib.spmv_run_timed.argtypes = [vp, vp, vp, vp, P(ctypes.c_float)]
     lib.spmv_plan_time.restype = ci
@@ -171,6 +177,32 @@ def spmv_run(plan: int, x_dev: int, y_dev: int, stream: int = 0) -> None:
 def spmv_run_noalloc(plan: int, x_dev: int, y_dev: int, stream: int = 0) -> None:
     """spmv_run with the plan's scratch in the library's static device array (no allocation anywhere)."""
     _check(load().spmv_run_noalloc(plan, x_dev, y_dev, stream))
+
+
+def spmv_run_multi(plan: int, x_dev: int, ldx: int, y_dev: int, ldy: int, k: int, stream: int = 0) -> None:
+    """k right-hand sides: vector v of X at x_dev + v*ldx elements, of Y at y_dev + v*ldy elements."""
+    _check(load().spmv_run_multi(plan, x_dev, ldx, y_dev, ldy, k, stream))
+
+
+def spmv_plan_save(plan: int, path: str) -> None:
+    _check(load().spmv_plan_save(plan, os.fsencode(path)))
+
+
+def spmv_plan_load(path: str, *, host_only=False, allocator=None) -> int:
+    """Plan handle rebuilt from a file written by spmv_plan_save (no matrix, no search needed)."""
+    lib = load()
+    opts = spmv_options_t()
+    opts.host_only = int(bool(host_only))
+    keep = None
+    if allocator is not None:
+        alloc_py, free_py = allocator
+        keep = (_ALLOC_FN(lambda nbytes, user: alloc_py(nbytes) or None), _FREE_FN(lambda ptr, user: free_py(ptr)))
+        opts.dev_alloc, opts.dev_free = keep
+    handle = ctypes.c_void_p()
+    _check(lib.spmv_plan_load(ctypes.byref(handle), os.fsencode(path), ctypes.byref(opts)))
+    if keep is not None:
+        _callbacks[handle.value] = keep
+    return handle.value
 
 
 def spmv_run_timed(plan: int, x_dev: int, y_dev: int, stream: int = 0):
@@ -309,6 +341,34 @@ class Plan:
             stream = torch.cuda.current_stream().cuda_stream
         (spmv_run_noalloc if noalloc else spmv_run)(self.handle, x.data_ptr(), y.data_ptr(), int(stream))
         return y
+
+    @classmethod
+    def load(cls, path, value_dtype=np.float64, **kw):
+        """A plan read back from a file written by save()."""
+        self = cls.__new__(cls)
+        self.handle = spmv_plan_load(path, **kw)
+        d = spmv_plan_describe(self.handle)
+        self.nrows, self.ncols = int(d["nrows"]), int(d["ncols"])
+        self.value_dtype = np.dtype(np.float64 if d["dtype"] == "f64" else np.float32)
+        return self
+
+    def save(self, path):
+        spmv_plan_save(self.handle, path)
+
+    def run_multi(self, X, Y, stream=None):
+        """X: (k, ncols) and Y: (k, nrows) contiguous device tensors, one right-hand side per row."""
+        if X.dim() != 2 or Y.dim() != 2 or X.shape[0] != Y.shape[0] or X.shape[1] != self.ncols or Y.shape[1] != self.nrows:
+            raise SpmvError(SPMV_ERR_INVALID_ARG, "X must be (k, ncols) and Y (k, nrows)")
+        if not (X.is_cuda and Y.is_cuda and X.is_contiguous() and Y.is_contiguous()):
+            raise SpmvError(SPMV_ERR_INVALID_ARG, "X / Y must be contiguous device tensors")
+        want = "float64" if self.value_dtype == np.float64 else "float32"
+        if str(X.dtype) != "torch." + want or str(Y.dtype) != "torch." + want:
+            raise SpmvError(SPMV_ERR_INVALID_ARG, "X / Y dtype differs from the plan's")
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        spmv_run_multi(self.handle, X.data_ptr(), self.ncols, Y.data_ptr(), self.nrows, int(X.shape[0]), int(stream))
+        return Y
 
     def run_timed(self, x, y, stream=None):
         if stream is None:

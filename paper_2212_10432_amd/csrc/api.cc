@@ -305,6 +305,97 @@ spmv_status_t spmv_run_noalloc(const spmv_plan_t *plan, const void *x_dev, void 
     API_END
 }
 
+spmv_status_t spmv_run_multi(const spmv_plan_t *plan, const void *x_dev, int64_t ldx, void *y_dev, int64_t ldy,
+                             int k, void *stream) {
+    API_BEGIN
+    if (!plan || !plan->impl) fail(SPMV_ERR_INVALID_ARG, "plan is NULL");
+    const Plan &p = *plan->impl;
+    if (p.mem.host_only) fail(SPMV_ERR_UNSUPPORTED, "the plan was built host-only and cannot run");
+    if (k < 0 || k > 4096) fail(SPMV_ERR_INVALID_ARG, "spmv_run_multi: k must be in [0, 4096]");
+    if (k == 0) return SPMV_OK;
+    if ((!x_dev && p.ncols > 0) || (!y_dev && p.nrows > 0)) fail(SPMV_ERR_INVALID_ARG, "X or Y is NULL");
+    if (x_dev && x_dev == y_dev) fail(SPMV_ERR_INVALID_ARG, "X and Y must not alias");
+    if (k > 1 && (ldx < p.ncols || ldy < p.nrows)) fail(SPMV_ERR_INVALID_ARG, "spmv_run_multi: ldx < ncols or ldy < nrows");
+    const size_t v = p.vsize();
+    auto xv = [&](int i) { return (const void *)((const char *)x_dev + (size_t)i * (size_t)ldx * v); };
+    auto yv = [&](int i) { return (void *)((char *)y_dev + (size_t)i * (size_t)ldy * v); };
+    auto fused = [](const Part &q) { return (q.kind == K_DIA && q.ndiag >= 1 && q.ndiag <= 8) || q.kind == K_SELL || q.kind == K_CSRV; };
+    auto one = [&](const Part &q, int i) {
+        const int err = launch_part(q, p.dtype, p.nrows, p.ncols, xv(i), yv(i), stream);
+        if (err) fail(SPMV_ERR_HIP, std::string("launch of ") + q.name + " failed: " + hip_error_text(err));
+    };
+    size_t i = 0;
+    while (i < p.parts.size()) {
+        if (fused(p.parts[i])) {
+            // the matrix stream is read once for 8, 4 or 2 vectors at a time
+            int done = 0;
+            while (done < k) {
+                const int left = k - done;
+                const int kk = left >= 8 ? 8 : (left >= 4 ? 4 : (left >= 2 ? 2 : 1));
+                int err = -1;
+                if (kk > 1) err = launch_part_multi(p.parts[i], p.dtype, p.nrows, p.ncols, xv(done), ldx, yv(done), ldy, kk, stream);
+                if (err > 0) fail(SPMV_ERR_HIP, std::string("launch of ") + p.parts[i].name + " failed: " + hip_error_text(err));
+                if (err < 0)
+                    for (int u = 0; u < kk; ++u) one(p.parts[i], done + u);
+                done += kk;
+            }
+            ++i;
+            continue;
+        }
+        // launches that hand partial sums to each other through the plan's scratch run vector by vector
+        size_t j = i;
+        while (j < p.parts.size() && !fused(p.parts[j])) ++j;
+        for (int u = 0; u < k; ++u)
+            for (size_t q = i; q < j; ++q) one(p.parts[q], u);
+        i = j;
+    }
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_save(const spmv_plan_t *plan, const char *path) {
+    API_BEGIN
+    if (!plan || !plan->impl || !path) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    save_plan(*plan->impl, path);
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_load(spmv_plan_t **out, const char *path, const spmv_options_t *opts) {
+    if (out) *out = nullptr;
+    API_BEGIN
+    if (!out || !path) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    spmv_options_t o;
+    std::memset(&o, 0, sizeof o);
+    if (opts) o = *opts;
+    if ((o.dev_alloc == nullptr) != (o.dev_free == nullptr))
+        fail(SPMV_ERR_INVALID_ARG, "dev_alloc and dev_free must be given together");
+    Allocator mem;
+    mem.alloc = o.dev_alloc ? o.dev_alloc : default_alloc;
+    mem.free = o.dev_free ? o.dev_free : default_free;
+    mem.user = o.user;
+    if (o.host_only) {
+        mem.alloc = host_alloc;
+        mem.free = host_free;
+        mem.user = nullptr;
+        mem.host_only = true;
+    } else {
+        int ndev = 0;
+        if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) {
+            (void)hipGetLastError();
+            fail(SPMV_ERR_HIP, "no HIP device available");
+        }
+        const int err = prepare_device();
+        if (err) fail(SPMV_ERR_HIP, std::string("device set-up failed: ") + hip_error_text(err));
+    }
+    std::unique_ptr<Plan> plan = load_plan(path, mem);
+    if (!o.host_only && hipDeviceSynchronize() != hipSuccess) fail(SPMV_ERR_HIP, "device error after loading the plan");
+    plan->describe_cache = describe_json(*plan);
+    *out = new spmv_plan{std::move(plan)};
+    return SPMV_OK;
+    API_END
+}
+
 spmv_status_t spmv_run_timed(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
                              float *launch_ms) {
     API_BEGIN

@@ -117,7 +117,7 @@ struct DevArray {
     bool read_per_run = true;    // counts towards the algorithmic bytes of one run
 };
 
-enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS, K_COO, K_XL_MUL, K_XL_REDUCE };
+enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS, K_COO, K_XL_MUL, K_XL_REDUCE, K_LAST = K_XL_REDUCE };
 
 // One kernel launch of spmv_run.  Pointers refer to entries of Plan::arrays.
 struct Part {
@@ -187,6 +187,10 @@ std::unique_ptr<Plan> build_plan(const HostCsr &A, const Census &cen, const Plan
 // scratch_override, when not NULL, replaces the part's own scratch buffer.
 int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
                 void *y, void *stream, void *scratch_override = nullptr);
+// The same launch for k = 2, 4 or 8 right-hand sides stored ldx / ldy elements apart; returns -1 when
+// the part has no fused multi-vector kernel (the caller runs the vectors one by one).
+int launch_part_multi(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
+                      int64_t ldx, void *y, int64_t ldy, int k, void *stream);
 // Once per device, when a plan is created there: raises the dynamic-LDS limit of the kernels that
 // need more than 64 KiB and looks up the device address of the library's static scratch array.
 int prepare_device();
@@ -203,6 +207,10 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
 double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream);
 
 std::string describe_json(const Plan &plan);
+
+// Plan files (serialize.cc).  Both throw Error.
+void save_plan(const Plan &plan, const char *path);
+std::unique_ptr<Plan> load_plan(const char *path, const Allocator &mem);
 
 // Matrix Market coordinate file -> CSR in malloc'ed arrays (mmio.cc).  Throws Error.
 struct MmCsr {

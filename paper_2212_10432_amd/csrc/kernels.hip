@@ -1138,6 +1138,195 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
     }
 }
 
+// ---- several right-hand sides at once (SpMM with a few vectors) -------------------------------
+// Y[:, v] = A * X[:, v] for K vectors stored one after the other (vector v of X at x + v*ldx, of Y at
+// y + v*ldy).  The matrix stream is read once for all K vectors, which is what pays for matrices
+// whose single-vector run is bound by launch latency or by the matrix stream.  Same layouts and the
+// same lane-to-entry mapping as the single-vector kernels; K accumulators per lane.
+template <typename T, int K>
+__global__ __launch_bounds__(kWG) void k_dia_multi(DiaOffsets offs, int nd, const T *__restrict__ vals,
+                                                   int64_t ld, const T *__restrict__ x, int64_t ldx,
+                                                   T *__restrict__ y, int64_t ldy, int64_t nrows,
+                                                   int64_t ncols, int acc_flag) {
+    const int64_t i = (int64_t)blockIdx.x * kWG + threadIdx.x;
+    if (i >= nrows) return;
+    T acc[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) acc[k] = T(0);
+#pragma unroll 2
+    for (int d = 0; d < nd; ++d) {
+        const int64_t c = i + offs.o[d];
+        const T v = ldnt(vals + (int64_t)d * ld + i);
+        if (c >= 0 && c < ncols) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) acc[k] += v * x[c + k * ldx];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        T *dst = y + i + k * ldy;
+        *dst = acc_flag ? *dst + acc[k] : acc[k];
+    }
+}
+
+template <typename T, int K>
+__global__ __launch_bounds__(kWG) void k_sell_multi(const int64_t *__restrict__ slice_ptr,
+                                                    const int32_t *__restrict__ cols,
+                                                    const T *__restrict__ vals,
+                                                    const int32_t *__restrict__ rows,
+                                                    const T *__restrict__ x, int64_t ldx,
+                                                    T *__restrict__ y, int64_t ldy, int64_t nslices,
+                                                    int64_t nrows_part, int remap, int uniform_w,
+                                                    int acc_flag) {
+    const int64_t blk = logical_block(blockIdx.x, gridDim.x, remap);
+    const int64_t s = blk * (kWG / kWave) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (s >= nslices) return;
+    const int64_t b = uniform_w >= 0 ? s * 64 * (int64_t)uniform_w : slice_ptr[s];
+    const int w = uniform_w >= 0 ? uniform_w : (int)((slice_ptr[s + 1] - b) >> 6);
+    const int32_t *c = cols + b + lane;
+    const T *v = vals + b + lane;
+    T acc[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) acc[k] = T(0);
+    int j = 0;
+    for (; j + 2 <= w; j += 2) {
+        const int32_t c0 = ldnt(c + j * 64), c1 = ldnt(c + (j + 1) * 64);
+        const T v0 = ldnt(v + j * 64), v1 = ldnt(v + (j + 1) * 64);
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc[k] += v0 * x[c0 + k * ldx];
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc[k] += v1 * x[c1 + k * ldx];
+    }
+    if (j < w) {
+        const int32_t c0 = ldnt(c + j * 64);
+        const T v0 = ldnt(v + j * 64);
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc[k] += v0 * x[c0 + k * ldx];
+    }
+    const int64_t r = s * 64 + lane;
+    if (r < nrows_part) {
+        const int64_t row = rows ? (int64_t)rows[r] : r;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            T *dst = y + row + k * ldy;
+            *dst = acc_flag ? *dst + acc[k] : acc[k];
+        }
+    }
+}
+
+template <typename T, int LPR, int K>
+__global__ __launch_bounds__(kWG) void k_csrv_multi(const int32_t *__restrict__ seg_ptr,
+                                                    const int32_t *__restrict__ seg_row,
+                                                    const int32_t *__restrict__ cols,
+                                                    const T *__restrict__ vals,
+                                                    const T *__restrict__ x, int64_t ldx,
+                                                    T *__restrict__ y, int64_t ldy, int64_t nseg,
+                                                    int remap, int uniform_len, int acc_flag) {
+    const int64_t blk = logical_block(blockIdx.x, gridDim.x, remap);
+    const int64_t g = (blk * kWG + threadIdx.x) / LPR;
+    const int t = threadIdx.x % LPR;
+    const bool live = g < nseg;
+    int32_t b = 0, e = 0;
+    if (live) {
+        if (uniform_len >= 0) {
+            b = (int32_t)g * uniform_len;
+            e = b + uniform_len;
+        } else {
+            b = seg_ptr[g];
+            e = seg_ptr[g + 1];
+        }
+    }
+    T acc[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) acc[k] = T(0);
+    int32_t q = b + t;
+    for (; q + LPR < e; q += 2 * LPR) {
+        const int32_t c0 = ldnt(cols + q), c1 = ldnt(cols + q + LPR);
+        const T v0 = ldnt(vals + q), v1 = ldnt(vals + q + LPR);
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc[k] += v0 * x[c0 + k * ldx];
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc[k] += v1 * x[c1 + k * ldx];
+    }
+    if (q < e) {
+        const int32_t c0 = ldnt(cols + q);
+        const T v0 = ldnt(vals + q);
+#pragma unroll
+        for (int k = 0; k < K; ++k) acc[k] += v0 * x[c0 + k * ldx];
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) acc[k] = group_sum<LPR>(acc[k]);
+    if (live && t == 0) {
+        int64_t row = g;
+        bool atomic = false;
+        if (seg_row) {
+            const int32_t r = seg_row[g];
+            atomic = r < 0;
+            row = atomic ? (int64_t)(~r) : (int64_t)r;
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            T *dst = y + row + k * ldy;
+            if (atomic) atomic_add(dst, acc[k]);
+            else *dst = acc_flag ? *dst + acc[k] : acc[k];
+        }
+    }
+}
+
+// Returns -1 when the part has no fused multi-vector kernel for this K (the caller then runs the
+// vectors one by one), otherwise a hipError_t as int.
+template <typename T>
+int launch_multi_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, int64_t ldx, T *y,
+                       int64_t ldy, int K, hipStream_t st) {
+    auto blocks = [](int64_t items, int64_t per) { return (unsigned)((items + per - 1) / per); };
+    if (K != 2 && K != 4 && K != 8) return -1;
+    switch (p.kind) {
+    case K_DIA: {
+        if (p.ndiag < 1 || p.ndiag > 8) return -1;
+        if (nrows == 0) return 0;
+        DiaOffsets o;
+        for (int d = 0; d < 8; ++d) o.o[d] = d < p.ndiag ? p.dia_offsets[d] : 0;
+        const unsigned grid = blocks(nrows, kWG);
+#define DIAM(KK) k_dia_multi<T, KK><<<grid, kWG, 0, st>>>(o, p.ndiag, (const T *)p.p1, p.ld, x, ldx, y, ldy, nrows, ncols, (int)p.accumulate)
+        if (K == 2) DIAM(2); else if (K == 4) DIAM(4); else DIAM(8);
+#undef DIAM
+        break;
+    }
+    case K_SELL: {
+        if (p.units == 0) return 0;
+        const unsigned grid = blocks(p.units, kWG / kWave);
+#define SELLM(KK)                                                                                  \
+    k_sell_multi<T, KK><<<grid, kWG, 0, st>>>((const int64_t *)p.p0, (const int32_t *)p.p1, (const T *)p.p2, \
+                                              p.has_rows ? (const int32_t *)p.p3 : nullptr, x, ldx, y, ldy, \
+                                              p.units, p.nrows, p.remap, p.uniform_w, (int)p.accumulate)
+        if (K == 2) SELLM(2); else if (K == 4) SELLM(4); else SELLM(8);
+#undef SELLM
+        break;
+    }
+    case K_CSRV: {
+        if (p.units == 0) return 0;
+#define CSRVM(L, KK)                                                                               \
+    k_csrv_multi<T, L, KK><<<blocks(p.units * L, kWG), kWG, 0, st>>>(                              \
+        (const int32_t *)p.p0, p.has_rows ? (const int32_t *)p.p1 : nullptr, (const int32_t *)p.p2, \
+        (const T *)p.p3, x, ldx, y, ldy, p.units, p.remap, p.uniform_w, (int)p.accumulate)
+#define CSRVM_L(L)                                                                                 \
+    case L:                                                                                        \
+        if (K == 2) CSRVM(L, 2); else if (K == 4) CSRVM(L, 4); else CSRVM(L, 8);                   \
+        break;
+        switch (p.lanes) {
+            CSRVM_L(1) CSRVM_L(2) CSRVM_L(4) CSRVM_L(8) CSRVM_L(16) CSRVM_L(32) CSRVM_L(64)
+        default: return (int)hipErrorInvalidValue;
+        }
+#undef CSRVM_L
+#undef CSRVM
+        break;
+    }
+    default: return -1;
+    }
+    return (int)hipGetLastError();
+}
+
 // -------------------------------------------------------------------------------------------
 template <typename T>
 int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, hipStream_t st, void *scratch) {
@@ -1520,6 +1709,13 @@ int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols,
     void *scratch = scratch_override ? scratch_override : p.scratch;
     if (dtype == SPMV_F64) return launch_typed<double>(p, nrows, ncols, (const double *)x, (double *)y, st, scratch);
     return launch_typed<float>(p, nrows, ncols, (const float *)x, (float *)y, st, scratch);
+}
+
+int launch_part_multi(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
+                      int64_t ldx, void *y, int64_t ldy, int k, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == SPMV_F64) return launch_multi_typed<double>(p, nrows, ncols, (const double *)x, ldx, (double *)y, ldy, k, st);
+    return launch_multi_typed<float>(p, nrows, ncols, (const float *)x, ldx, (float *)y, ldy, k, st);
 }
 
 const char *hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
