@@ -65,6 +65,39 @@ static Csr make(int64_t nrows, int64_t ncols, int maxlen, bool sorted, int64_t l
 }
 
 static int plans = 0;
+static const char *g_dir = "/tmp";
+
+// save the plan, read it back host-only, then feed every kind of damaged copy to the reader
+static void files(spmv_plan_t *p) {
+    const std::string path = std::string(g_dir) + "/plan.bin", bad = std::string(g_dir) + "/bad.bin";
+    if (spmv_plan_save(p, path.c_str()) != SPMV_OK) std::exit(6);
+    spmv_options_t o;
+    std::memset(&o, 0, sizeof o);
+    o.host_only = 1;
+    spmv_plan_t *q = nullptr;
+    if (spmv_plan_load(&q, path.c_str(), &o) != SPMV_OK) std::exit(7);
+    spmv_plan_destroy(q);
+    FILE *f = std::fopen(path.c_str(), "rb");
+    std::vector<unsigned char> data;
+    unsigned char chunk[4096];
+    size_t n;
+    while ((n = std::fread(chunk, 1, sizeof chunk, f)) > 0) data.insert(data.end(), chunk, chunk + n);
+    std::fclose(f);
+    for (int variant = 0; variant < 6; ++variant) {
+        std::vector<unsigned char> d = data;
+        if (variant == 0) d.resize(d.size() / 2);
+        if (variant == 1) d.resize(17);
+        if (variant == 2) d[d.size() / 3] ^= 0x40;
+        if (variant == 3) d[9] ^= 0x7f;          // the size field
+        if (variant == 4) d.push_back(1);
+        if (variant == 5) d.clear();
+        f = std::fopen(bad.c_str(), "wb");
+        if (!d.empty()) std::fwrite(d.data(), 1, d.size(), f);
+        std::fclose(f);
+        q = nullptr;
+        if (spmv_plan_load(&q, bad.c_str(), &o) == SPMV_OK || q) std::exit(8);
+    }
+}
 
 static void one(const Csr &m, const char *spec, spmv_dtype_t dt, bool must_build) {
     spmv_options_t o;
@@ -98,6 +131,7 @@ static void one(const Csr &m, const char *spec, spmv_dtype_t dt, bool must_build
     std::vector<char> d(need);
     spmv_plan_describe(p, d.data(), need, nullptr);
     if (spmv_run(p, m.va.data(), (void *)m.va.data(), nullptr) == SPMV_OK) std::exit(4);   // host-only plans refuse to run
+    if (plans % 7 == 0) files(p);
     spmv_plan_destroy(p);
 }
 
@@ -119,6 +153,7 @@ static void mm(const char *dir, const char *text, bool ok) {
 
 int main(int argc, char **argv) {
     const char *dir = argc > 1 ? argv[1] : "/tmp";
+    g_dir = dir;
     const char *specs[] = {
         "light=csrv", "light=csrv,lpr=8,sigma=64", "light=csrv,chunk=256", "light=sell", "light=sell,sigma=128,remap=1",
         "light=sell,sigma=-1", "light=bin,smax=4,sigma=128,chunk=512", "light=coo", "light=nnzb,r=4", "light=nnzb,r=16",
