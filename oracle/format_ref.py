@@ -369,6 +369,42 @@ def ref_nnzb(rp, ci, va, rows, R, acc, zero_rows):
             "nnzb.rows": np.array(keep, dtype=np.int32)}
 
 
+def ref_wbm(rp, ci, va, rows, acc, zero_rows, steps=8):
+    """One entry per lane, one row-start bitmap per wavefront step: the entries of the part's non-empty
+    rows form one stream, stored as it is and padded with (value 0, column 0) to a whole tile of
+    64*steps entries; bit g % 64 of mask[g // 64] marks an entry that starts a row; tile_row[i] counts
+    the row starts before tile i.  Rows open at a tile border, and empty rows, are zeroed first."""
+    lens = np.diff(rp).astype(np.int64)
+    keep = [int(r) for r in rows if lens[r] > 0]
+    if not acc:
+        zero_rows += [int(r) for r in rows if lens[r] == 0]
+    if not keep:
+        return {}
+    stream_c = np.concatenate([ci[_row_entries(rp, r)] for r in keep])
+    stream_v = np.concatenate([va[_row_entries(rp, r)] for r in keep])
+    starts = np.concatenate([[0], np.cumsum(lens[keep])])[:-1]
+    total = stream_c.size
+    tsz = WAVE * steps
+    ntiles = -(-total // tsz)
+    cols = np.zeros(ntiles * tsz, dtype=np.int32)
+    vals = np.zeros(ntiles * tsz, dtype=va.dtype)
+    cols[:total] = stream_c
+    vals[:total] = stream_v
+    mask = np.zeros(ntiles * steps, dtype=np.uint64)
+    for st in starts:
+        mask[st // WAVE] |= np.uint64(1) << np.uint64(st % WAVE)
+    tile_row = np.zeros(ntiles + 1, dtype=np.int32)
+    np.cumsum(np.bincount(starts // tsz, minlength=ntiles), out=tile_row[1:])
+    if not acc:
+        owner = np.repeat(np.arange(len(keep)), lens[keep])
+        for t in range(ntiles):
+            zero_rows.append(keep[owner[min(total, (t + 1) * tsz) - 1]])
+            if starts[owner[t * tsz]] != t * tsz:
+                zero_rows.append(keep[owner[t * tsz]])
+    return {"wbm.cols": cols, "wbm.vals": vals, "wbm.mask": mask, "wbm.tile_row": tile_row,
+            "wbm.rows": np.array(keep, dtype=np.int32)}
+
+
 def ref_xnb(ncols, rp, ci, va, rows, K, R, nrows_total):
     """XCD-striped nnz-balanced tiles.  K stripes of W = ceil(ncols/K) (rounded up to 64) columns, XCD k
     owning stripes k, k+8, ...; the streams are laid out XCD by XCD.  Inside a stripe the (row, stripe)
@@ -558,6 +594,8 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
                 zero_rows += [int(r) for r in light]
     elif p["light"] == "nnzb":
         out.update(ref_nnzb(rp, ci, va, light, p["r"], acc, zero_rows))
+    elif p["light"] == "wbm":
+        out.update(ref_wbm(rp, ci, va, light, acc, zero_rows))
     elif p["light"] == "xnb":
         out.update(ref_xnb(ncols, rp, ci, va, light, p["k"], p["r"], nrows))
     elif p["light"] == "xl":
@@ -571,7 +609,8 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
         L = lens[light]
         out.update(ref_sell(rp, ci, va, light[L <= p["smax"]], p["sigma"], nrows, "bin0.sell"))
         out.update(ref_csrv(rp, ci, va, light[(L > p["smax"]) & (L <= 128)], 8, 0, p["sigma"], acc, nrows, "bin1.csrv8", zero_rows))
-        out.update(ref_csrv(rp, ci, va, light[L > max(128, p["smax"])], 64, p["chunk"], 0, acc, nrows, "bin2.csrv64", zero_rows))
+        out.update(ref_csrv(rp, ci, va, light[L > max(128, p["smax"])], 256 if p.get("wg") else 64, p["chunk"], 0, acc, nrows,
+                            "bin2.csrwg" if p.get("wg") else "bin2.csrv64", zero_rows))
     else:
         raise ValueError(p["light"])
     out.update(ref_stripe(ncols, rp, ci, va, heavy, p["tile"], p["hd"]))
@@ -635,6 +674,13 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
             mark = ((bb[(g // tsz) * WAVE + (g % tsz) // R_].astype(np.int64) >> ((g % tsz) % R_)) & 1).astype(np.int64)
             segidx = np.cumsum(mark) - 1
             R.append(np.asarray(rws)[seg_row[segidx]].astype(np.int64)); C.append(cc[src]); V.append(vv[src])
+            continue
+        if pre == "wbm":
+            cc, vv, mk, rws = a["cols"], a["vals"], a["mask"], a["rows"]
+            g = np.arange(cc.size)
+            mark = ((mk[g // WAVE] >> (g % WAVE).astype(np.uint64)) & np.uint64(1)).astype(np.int64)
+            rowidx = np.cumsum(mark) - 1
+            R.append(rws[rowidx].astype(np.int64)); C.append(cc); V.append(vv)
             continue
         if pre == "nnzb":
             cc, vv, bb, rws = a["cols"], a["vals"], a["bits"], a["rows"]

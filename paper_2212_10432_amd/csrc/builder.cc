@@ -777,6 +777,81 @@ void build_nnzb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows_i
     add_part(plan, p, a0, std::min<int64_t>(A.ncols, total), 0, n);
 }
 
+// ---- one entry per lane, one bitmap per wavefront step ----------------------------------------------
+// The same stream as build_nnzb (the non-empty rows' entries in order), stored as it is: entry g at
+// position g, padded with (value 0, column 0) to a whole tile of 64 * kWbmTileSteps entries.
+// mask[g / 64] has bit g % 64 set when entry g starts a row; tile_row[i] = row starts before tile i.
+// Rows open at a tile border are accumulated with atomics and therefore zeroed first; empty rows too.
+template <typename T>
+void build_wbm(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows_in, bool acc,
+               const std::vector<int64_t> &lens, std::vector<int32_t> &zero_rows, int threads) {
+    std::vector<int32_t> rows;
+    rows.reserve(rows_in.size());
+    for (int32_t r : rows_in) {
+        if (lens[(size_t)r] > 0) rows.push_back(r);
+        else if (!acc) zero_rows.push_back(r);
+    }
+    const int64_t n = (int64_t)rows.size();
+    if (n == 0) return;
+    std::vector<int64_t> start((size_t)n + 1, 0);
+    for (int64_t i = 0; i < n; ++i) start[(size_t)i + 1] = start[(size_t)i] + lens[(size_t)rows[(size_t)i]];
+    const int64_t total = start[(size_t)n];
+    const int64_t tile_sz = (int64_t)kWave * kWbmTileSteps;
+    const int64_t ntiles = (total + tile_sz - 1) / tile_sz;
+    if (ntiles * tile_sz >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "wbm: too many entries");
+    HostBuf<int32_t> cols(ntiles * tile_sz);
+    HostBuf<T> vals(ntiles * tile_sz);
+    std::vector<uint64_t> mask((size_t)(ntiles * kWbmTileSteps), 0);
+    std::vector<int32_t> tile_row((size_t)ntiles + 1, 0);
+    const T *av = (const T *)A.val;
+    parallel_for(n, 1024, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t r = rows[(size_t)i];
+            const int64_t L = lens[(size_t)r], src = A.row_ptr[r], dst = start[(size_t)i];
+            std::memcpy(cols.p + dst, A.col + src, (size_t)L * 4);
+            std::memcpy(vals.p + dst, av + src, (size_t)L * sizeof(T));
+        }
+    });
+    for (int64_t g = total; g < ntiles * tile_sz; ++g) {
+        cols[g] = 0;
+        vals[g] = T(0);
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t g = start[(size_t)i];
+        mask[(size_t)(g / kWave)] |= (uint64_t)1 << (g % kWave);
+        tile_row[(size_t)(g / tile_sz) + 1] += 1;
+    }
+    for (int64_t t = 0; t < ntiles; ++t) tile_row[(size_t)t + 1] += tile_row[(size_t)t];
+    if (!acc) {
+        for (int64_t t = 0; t < ntiles; ++t) {
+            const int64_t last = std::min(total, (t + 1) * tile_sz) - 1;
+            const int64_t i_last = (int64_t)(std::upper_bound(start.begin(), start.end(), last) - start.begin()) - 1;
+            zero_rows.push_back(rows[(size_t)i_last]);
+            const int64_t first = t * tile_sz;
+            const int64_t i_first = (int64_t)(std::upper_bound(start.begin(), start.end(), first) - start.begin()) - 1;
+            if (start[(size_t)i_first] != first) zero_rows.push_back(rows[(size_t)i_first]);
+        }
+        std::sort(zero_rows.begin(), zero_rows.end());
+        zero_rows.erase(std::unique(zero_rows.begin(), zero_rows.end()), zero_rows.end());
+    }
+    Part p;
+    p.kind = K_WBM;
+    p.name = "wbm";
+    p.nrows = n;
+    p.nnz = total;
+    p.stored = ntiles * tile_sz;
+    p.units = ntiles;
+    p.accumulate = acc;
+    p.has_rows = true;
+    const size_t a0 = plan.arrays.size();
+    p.p0 = upload(plan, "wbm.cols", 4, ntiles * tile_sz, cols.p);
+    p.p1 = upload(plan, "wbm.vals", (int)sizeof(T), ntiles * tile_sz, vals.p);
+    p.p2 = upload(plan, "wbm.mask", 8, ntiles * kWbmTileSteps, mask.data());
+    p.p3 = upload(plan, "wbm.tile_row", 4, ntiles + 1, tile_row.data());
+    p.p4 = upload(plan, "wbm.rows", 4, n, rows.data());
+    add_part(plan, p, a0, std::min<int64_t>(A.ncols, total), 0, n);
+}
+
 // ---- XCD-striped nnz-balanced tiles ------------------------------------------------------------------
 // COL_DIV into K stripes of W columns as for the striped SELL.  The (row, stripe) segments of a
 // stripe follow each other in part order as one stream, cut into tiles of 64*R entries (transposed
@@ -1409,6 +1484,9 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
     case L_NNZB:
         build_nnzb<T>(*plan, A, light, spec.r, acc, lens, zero_rows, threads);
         break;
+    case L_WBM:
+        build_wbm<T>(*plan, A, light, acc, lens, zero_rows, threads);
+        break;
     case L_XNB:
         build_xnb<T>(*plan, A, light, spec.k, spec.r, acc, lens, threads);
         break;
@@ -1428,8 +1506,8 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         }
         break;
     case L_BIN: {
-        // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront per
-        // row (cut into segments of `chunk`)
+        // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront (or, with
+        // wg=1, one workgroup) per row (cut into segments of `chunk`)
         std::vector<int32_t> shorts, mids, longs;
         for (int32_t r : light) {
             const int64_t L = lens[(size_t)r];
@@ -1439,7 +1517,8 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
         }
         build_sell<T>(*plan, A, shorts, spec.sigma, acc, spec.remap, "bin0.sell", lens, threads);
         build_csrv<T>(*plan, A, mids, 8, 0, spec.sigma, acc, spec.remap, "bin1.csrv8", lens, zero_rows, threads);
-        build_csrv<T>(*plan, A, longs, 64, spec.chunk, 0, acc, spec.remap, "bin2.csrv64", lens, zero_rows, threads);
+        if (spec.wg) build_csrv<T>(*plan, A, longs, 256, spec.chunk, 0, acc, spec.remap, "bin2.csrwg", lens, zero_rows, threads);
+        else build_csrv<T>(*plan, A, longs, 64, spec.chunk, 0, acc, spec.remap, "bin2.csrv64", lens, zero_rows, threads);
         break;
     }
     default: fail(SPMV_ERR_INVALID_ARG, "unknown light design");

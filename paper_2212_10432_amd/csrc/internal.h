@@ -24,6 +24,8 @@ constexpr int kXwinGroup = 32;
 constexpr int64_t kXwinMaxBytes = 160 * 1024;
 // Rows per workgroup of the striped parts' reduce launch (their sums live in LDS).
 constexpr int kReduceBlockRows = 1024;
+// Wavefront-bitmap part: steps of 64 entries per wavefront (a tile is 64 * kWbmTileSteps entries).
+constexpr int kWbmTileSteps = 8;
 // Two-pass part with x windows in LDS: entries per group (the unit of padding and of the reduce
 // launch's group list), and the LDS budget of an x window or of a block's accumulators.
 constexpr int kXlGroup = 16;
@@ -81,7 +83,7 @@ struct Census {
 Census take_census(const HostCsr &A, int threads);
 
 // ---- plan specification --------------------------------------------------------------------
-enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZB = 5, L_XNB = 6, L_COO = 7, L_XL = 8 };
+enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZB = 5, L_XNB = 6, L_COO = 7, L_XL = 8, L_WBM = 9 };
 
 struct PlanSpec {
     int dia = 0;             // extract well-populated diagonals into a DIA part first
@@ -97,6 +99,7 @@ struct PlanSpec {
     int sigma = 0;           // sell/bsell: sort window in rows (0 = no sort, -1 = whole part)
     int block = 3;           // bsell: block edge (2, 3 or 4)
     int smax = 16;           // bin: rows up to this length go to the SELL bin
+    int wg = 0;              // bin: 1 = the long rows take one workgroup each (SHMEM_TOTAL_RED) instead of one wavefront
     int remap = 0;           // 1 = give each XCD a contiguous range of workgroups
     int r = 8;               // nnzb: consecutive non-zeros per lane (4, 8 or 16)
     int k = 8;               // xs: column stripes (8 or 16: one or two per XCD)
@@ -117,7 +120,7 @@ struct DevArray {
     bool read_per_run = true;    // counts towards the algorithmic bytes of one run
 };
 
-enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS, K_COO, K_XL_MUL, K_XL_REDUCE, K_LAST = K_XL_REDUCE };
+enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS, K_COO, K_XL_MUL, K_XL_REDUCE, K_WBM, K_LAST = K_WBM };
 
 // One kernel launch of spmv_run.  Pointers refer to entries of Plan::arrays.
 struct Part {

@@ -364,6 +364,58 @@ __global__ __launch_bounds__(kWG) void k_csrv(const int32_t *__restrict__ seg_pt
     }
 }
 
+// ---- CSR segments, one workgroup per segment ------------------------------------------------------
+// BMTB_ROW_BLOCK(1) + BMT_COL_BLOCK(256 lanes) + WARP_TOTAL_RED inside each wavefront + SHMEM_TOTAL_RED:
+// the whole workgroup reduces into one row through shared memory.  Same arrays as k_csrv.
+template <typename T, bool ROWS, bool ACC>
+__global__ __launch_bounds__(kWG) void k_csr_wg_row(const int32_t *__restrict__ seg_ptr,
+                                                    const int32_t *__restrict__ seg_row,
+                                                    const int32_t *__restrict__ cols,
+                                                    const T *__restrict__ vals,
+                                                    const T *__restrict__ x, T *__restrict__ y,
+                                                    int remap, int uniform_len) {
+    __shared__ T red[kWG / kWave];
+    const int64_t g = logical_block(blockIdx.x, gridDim.x, remap);
+    int32_t b, e;
+    if (uniform_len >= 0) {
+        b = (int32_t)g * uniform_len;
+        e = b + uniform_len;
+    } else {
+        b = seg_ptr[g];
+        e = seg_ptr[g + 1];
+    }
+    T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
+    int32_t k = b + (int32_t)threadIdx.x;
+    for (; k + 3 * kWG < e; k += 4 * kWG) {
+        const int32_t c0 = ldnt(cols + k), c1 = ldnt(cols + k + kWG);
+        const int32_t c2 = ldnt(cols + k + 2 * kWG), c3 = ldnt(cols + k + 3 * kWG);
+        const T v0 = ldnt(vals + k), v1 = ldnt(vals + k + kWG);
+        const T v2 = ldnt(vals + k + 2 * kWG), v3 = ldnt(vals + k + 3 * kWG);
+        a0 += v0 * x[c0];
+        a1 += v1 * x[c1];
+        a2 += v2 * x[c2];
+        a3 += v3 * x[c3];
+    }
+    for (; k < e; k += kWG) a0 += ldnt(vals + k) * x[ldnt(cols + k)];
+    const T wsum = group_sum<kWave>((a0 + a1) + (a2 + a3));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = wsum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        T acc = T(0);
+#pragma unroll
+        for (int w = 0; w < kWG / kWave; ++w) acc += red[w];
+        if (ROWS) {
+            const int32_t r = seg_row[g];
+            if (r < 0)
+                atomic_add(y + (int64_t)(~r), acc);
+            else
+                y[r] = ACC ? y[r] + acc : acc;
+        } else {
+            y[g] = ACC ? y[g] + acc : acc;
+        }
+    }
+}
+
 // ---- COO: one lane per stored entry ---------------------------------------------------------
 // BMT_NNZ_BLOCK(1) + GMEM_ATOM_RED: every product is added atomically into a y element zeroed by
 // an earlier launch.  The root format the paper starts from (Section I); kept as the fallback that
@@ -492,6 +544,75 @@ __device__ __forceinline__ void nnzb_tile(int64_t tile, int lane, const int32_t 
         const int ndone = tile_row[tile + 1] - 1 - tile_first;
         for (int j = lane; j < ndone; j += kWave) y[(int64_t)tile_first + j] = stage[j];
     }
+}
+
+// ---- one entry per lane, one row-start bitmap per wavefront step --------------------------------
+// BMW_NNZ_BLOCK(64*kWbmSteps) + BMT_NNZ_BLOCK(1) + WARP_BITMAP_RED: the part's entries form one stream
+// in row order, stored as it is; a wavefront owns kWbmSteps consecutive groups of 64 entries (a tile)
+// and in every step each lane multiplies one entry.  mask[tile*kWbmSteps + t] has bit l set when entry
+// l of that step starts a row: the wavefront's 64 products are summed by row with a segmented scan
+// steered by that one 64-bit word (the paper's 32-bit warp bitmap, widened to the 64-lane wavefront).
+// The lane at the end of a segment stores the row's sum; what is still open after lane 63 is carried
+// into the next step in a register; what enters a tile from the tile before, and what is open at its
+// end, is added atomically to y elements zeroed by an earlier launch (GMEM_ATOM_RED).
+constexpr int kWbmSteps = kWbmTileSteps;
+template <typename T, bool ACC>
+__global__ __launch_bounds__(kWG) void k_wbm(const int32_t *__restrict__ cols, const T *__restrict__ vals,
+                                             const uint64_t *__restrict__ mask,
+                                             const int32_t *__restrict__ tile_row,
+                                             const int32_t *__restrict__ rows, const T *__restrict__ x,
+                                             T *__restrict__ y, int64_t ntiles) {
+    const int64_t tile = (int64_t)blockIdx.x * (kWG / kWave) + (threadIdx.x >> 6);
+    if (tile >= ntiles) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t base = tile * (64 * kWbmSteps) + lane;
+    int32_t c[kWbmSteps];
+    T p[kWbmSteps];
+#pragma unroll
+    for (int t = 0; t < kWbmSteps; ++t) {
+        c[t] = ldnt(cols + base + t * 64);
+        p[t] = ldnt(vals + base + t * 64);
+    }
+    uint64_t m[kWbmSteps];
+#pragma unroll
+    for (int t = 0; t < kWbmSteps; ++t) m[t] = mask[tile * kWbmSteps + t];   // uniform over the wavefront
+#pragma unroll
+    for (int t = 0; t < kWbmSteps; ++t) p[t] *= x[c[t]];
+    const int32_t first = tile_row[tile];   // row starts before this tile
+    int32_t cnt = 0;                        // row starts seen in this tile so far
+    T carry = T(0);                         // sum of the segment still open after the previous step
+    const uint64_t upto = lane == 63 ? ~0ull : ((2ull << lane) - 1);   // bits 0 .. lane
+#pragma unroll
+    for (int t = 0; t < kWbmSteps; ++t) {
+        const uint64_t mk = m[t];
+        // a row start at lane 0 closes what the previous steps left open
+        if ((mk & 1ull) && lane == 0 && (t > 0)) {
+            const int32_t k = cnt;   // starts before this step: the open row is number first + k - 1
+            const int64_t r = rows[first + k - 1];
+            if (k == 0) atomic_add(y + r, carry);
+            else y[r] = ACC ? y[r] + carry : carry;
+        }
+        // head = first lane of this lane's segment: the highest row start at or below the lane, else 0
+        const uint64_t below = mk & upto;
+        const int head = below ? 63 - __builtin_clzll(below) : 0;
+        T val = p[t];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const T up = __shfl_up(val, o, kWave);
+            if (lane - o >= head) val += up;
+        }
+        if (head == 0 && !(mk & 1ull)) val += carry;   // the segment continues the open one
+        const bool ends = lane < 63 && ((mk >> (lane + 1)) & 1ull);
+        const int32_t k = cnt + (int32_t)__popcll(below);   // row starts at or before this entry, in the tile
+        if (ends) {
+            const int64_t r = rows[first + k - 1];
+            if (k == 0) atomic_add(y + r, val);
+            else y[r] = ACC ? y[r] + val : val;
+        }
+        carry = __shfl(val, 63, kWave);
+        cnt += (int32_t)__popcll(mk);
+    }
+    if (lane == 0) atomic_add(y + rows[first + cnt - 1], carry);   // open at the end of the tile
 }
 
 template <typename T, int R, typename BM, bool ACC>
@@ -1306,6 +1427,7 @@ int launch_multi_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, 
     }
     case K_CSRV: {
         if (p.units == 0) return 0;
+        if (p.lanes > kWave) return -1;
 #define CSRVM(L, KK)                                                                               \
     k_csrv_multi<T, L, KK><<<blocks(p.units * L, kWG), kWG, 0, st>>>(                              \
         (const int32_t *)p.p0, p.has_rows ? (const int32_t *)p.p1 : nullptr, (const int32_t *)p.p2, \
@@ -1392,6 +1514,16 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (p.has_rows) { if (p.accumulate) CSRV_GO(L, true, true); else CSRV_GO(L, true, false); } \
         else            { if (p.accumulate) CSRV_GO(L, false, true); else CSRV_GO(L, false, false); } \
         break;
+        if (p.lanes == kWG) {   // one workgroup per segment
+#define WGROW_GO(R, A)                                                                             \
+    k_csr_wg_row<T, R, A><<<(unsigned)p.units, kWG, 0, st>>>(                                      \
+        (const int32_t *)p.p0, (const int32_t *)p.p1, (const int32_t *)p.p2, (const T *)p.p3, x, y, \
+        p.remap, p.uniform_w)
+            if (p.has_rows) { if (p.accumulate) WGROW_GO(true, true); else WGROW_GO(true, false); }
+            else            { if (p.accumulate) WGROW_GO(false, true); else WGROW_GO(false, false); }
+#undef WGROW_GO
+            break;
+        }
         switch (p.lanes) {
             CSRV_L(1) CSRV_L(2) CSRV_L(4) CSRV_L(8) CSRV_L(16) CSRV_L(32) CSRV_L(64)
         default: return (int)hipErrorInvalidValue;
@@ -1493,6 +1625,17 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         default: return (int)hipErrorInvalidValue;
         }
 #undef NNZB_GO
+        break;
+    }
+    case K_WBM: {
+        if (p.units == 0) return 0;
+        const unsigned grid = blocks(p.units, kWG / kWave);
+        if (p.accumulate)
+            k_wbm<T, true><<<grid, kWG, 0, st>>>((const int32_t *)p.p0, (const T *)p.p1, (const uint64_t *)p.p2,
+                                                 (const int32_t *)p.p3, (const int32_t *)p.p4, x, y, p.units);
+        else
+            k_wbm<T, false><<<grid, kWG, 0, st>>>((const int32_t *)p.p0, (const T *)p.p1, (const uint64_t *)p.p2,
+                                                  (const int32_t *)p.p3, (const int32_t *)p.p4, x, y, p.units);
         break;
     }
     case K_XNB: {

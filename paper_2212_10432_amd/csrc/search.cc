@@ -173,6 +173,18 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             p.remap = 0;
             push(p);
         }
+        {   // the two remaining reductions of Table II, so that measurement rules them in or out:
+            // one row-start bitmap per wavefront step, and one workgroup per long row
+            PlanSpec p = bin_plan(th0);
+            p.light = L_WBM;
+            p.sigma = 0;
+            p.chunk = 0;
+            p.remap = 0;
+            push(p);
+            p = bin_plan(th0);
+            p.wg = 1;
+            push(p);
+        }
         if (th0 && tail_ok(4 * th0)) push(bin_plan(4 * th0));
         if (th0) push(bin_plan(0));
         if (c.max_len <= 1024) {

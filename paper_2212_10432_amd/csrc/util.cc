@@ -70,6 +70,7 @@ static const char *light_name(int l) {
     case L_XNB: return "xnb";
     case L_COO: return "coo";
     case L_XL: return "xl";
+    case L_WBM: return "wbm";
     }
     return "?";
 }
@@ -101,6 +102,7 @@ PlanSpec parse_spec(const std::string &s) {
             else if (v == "xnb") p.light = L_XNB;
             else if (v == "coo") p.light = L_COO;
             else if (v == "xl") p.light = L_XL;
+            else if (v == "wbm") p.light = L_WBM;
             else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown light design " + v);
         } else if (k == "dia") p.dia = (int)num();
         else if (k == "dia_fill") p.dia_fill = num();
@@ -113,6 +115,7 @@ PlanSpec parse_spec(const std::string &s) {
         else if (k == "sigma") p.sigma = (int)num();
         else if (k == "block") p.block = (int)num();
         else if (k == "smax") p.smax = (int)num();
+        else if (k == "wg") p.wg = (int)num();
         else if (k == "remap") p.remap = (int)num();
         else if (k == "xwin") p.xwin = (int)num();
         else if (k == "k") p.k = (int)num();
@@ -127,7 +130,10 @@ PlanSpec parse_spec(const std::string &s) {
     if (p.drows != 1 && !p.dia) fail(SPMV_ERR_INVALID_ARG, "plan spec: drows needs dia=1");
     if (p.heavy < 0) fail(SPMV_ERR_INVALID_ARG, "plan spec: heavy must be >= 0");
     if (p.tile < 64 || p.tile > 65536 || p.tile % 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: tile must be a multiple of 64 in [64, 65536]");
-    if (p.lpr != 0 && (!pow2(p.lpr) || p.lpr > 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: lpr must be 0 or a power of two <= 64");
+    if (p.lpr != 0 && p.lpr != 256 && (!pow2(p.lpr) || p.lpr > 64))
+        fail(SPMV_ERR_INVALID_ARG, "plan spec: lpr must be 0, a power of two <= 64, or 256 (one workgroup per row)");
+    if (p.wg != 0 && p.wg != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: wg must be 0 or 1");
+    if (p.wg && p.light != L_BIN) fail(SPMV_ERR_INVALID_ARG, "plan spec: wg needs light=bin");
     if (p.chunk < 0 || (p.chunk > 0 && p.chunk < 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: chunk must be 0 or >= 64");
     if (p.sigma < -1) fail(SPMV_ERR_INVALID_ARG, "plan spec: sigma must be >= -1");
     if (p.block < 2 || p.block > 4) fail(SPMV_ERR_INVALID_ARG, "plan spec: block must be 2, 3 or 4");
@@ -155,7 +161,10 @@ std::string print_spec(const PlanSpec &p) {
     case L_CSRV: o << ",lpr=" << p.lpr << ",chunk=" << p.chunk << ",sigma=" << p.sigma; break;
     case L_SELL: o << ",sigma=" << p.sigma; break;
     case L_BSELL: o << ",block=" << p.block << ",sigma=" << p.sigma << ",xwin=" << p.xwin; break;
-    case L_BIN: o << ",smax=" << p.smax << ",sigma=" << p.sigma << ",chunk=" << p.chunk; break;
+    case L_BIN:
+        o << ",smax=" << p.smax << ",sigma=" << p.sigma << ",chunk=" << p.chunk;
+        if (p.wg) o << ",wg=1";
+        break;
     case L_XS: o << ",k=" << p.k << ",sigma=" << p.sigma; break;
     case L_NNZB: o << ",r=" << p.r; break;
     case L_XNB: o << ",k=" << p.k << ",r=" << p.r; break;
@@ -183,9 +192,11 @@ std::string operator_chain(const PlanSpec &p) {
     switch (p.light) {
     case L_CSRV:
         sort();
-        o << " -> BMW_ROW_BLOCK -> BMT_COL_BLOCK(" << (p.lpr ? std::to_string(p.lpr) : std::string("auto")) << " lanes)";
+        if (p.lpr == 256) o << " -> BMTB_ROW_BLOCK(1) -> BMT_COL_BLOCK(256 lanes)";
+        else o << " -> BMW_ROW_BLOCK -> BMT_COL_BLOCK(" << (p.lpr ? std::to_string(p.lpr) : std::string("auto")) << " lanes)";
         if (p.chunk) o << " -> BMW_COL_BLOCK(" << p.chunk << ")";
         o << " -> WARP_TOTAL_RED";
+        if (p.lpr == 256) o << " -> SHMEM_TOTAL_RED";
         if (p.chunk) o << " -> GMEM_ATOM_RED";
         break;
     case L_SELL:
@@ -204,6 +215,9 @@ std::string operator_chain(const PlanSpec &p) {
         break;
     case L_COO:
         o << " -> BMT_NNZ_BLOCK(1) -> GMEM_ATOM_RED";
+        break;
+    case L_WBM:
+        o << " -> BMW_NNZ_BLOCK(" << 64 * kWbmTileSteps << ") -> BMT_NNZ_BLOCK(1) -> WARP_BITMAP_RED -> GMEM_ATOM_RED(tile borders)";
         break;
     case L_XNB:
         o << " -> COL_DIV(" << p.k << " stripes, stripe s on XCD s mod 8) -> BMW_NNZ_BLOCK(" << 64 * p.r
@@ -224,9 +238,10 @@ std::string operator_chain(const PlanSpec &p) {
         sort();
         o << " -> {BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD -> THREAD_TOTAL_RED"
           << " | BMT_COL_BLOCK(8 lanes) -> WARP_TOTAL_RED"
-          << " | BMT_COL_BLOCK(64 lanes)";
+          << (p.wg ? " | BMTB_ROW_BLOCK(1) -> BMT_COL_BLOCK(256 lanes)" : " | BMT_COL_BLOCK(64 lanes)");
         if (p.chunk) o << " -> BMW_COL_BLOCK(" << p.chunk << ")";
         o << " -> WARP_TOTAL_RED";
+        if (p.wg) o << " -> SHMEM_TOTAL_RED";
         if (p.chunk) o << " -> GMEM_ATOM_RED";
         o << "}";
         break;

@@ -19,15 +19,15 @@ TINY = {
 }
 
 SPECS = {
-    "C1": ["light=xl,w=128,rb=256,chunk=512", "light=coo", "light=xnb,k=8,r=4", "light=nnzb,r=4", "light=xs,k=8,sigma=256", "light=csrv", "light=csrv,lpr=4,sigma=128", "light=sell", "light=sell,sigma=256", "light=sell,sigma=-1",
+    "C1": ["light=wbm", "light=csrv,lpr=256", "light=xl,w=128,rb=256,chunk=512", "light=coo", "light=xnb,k=8,r=4", "light=nnzb,r=4", "light=xs,k=8,sigma=256", "light=csrv", "light=csrv,lpr=4,sigma=128", "light=sell", "light=sell,sigma=256", "light=sell,sigma=-1",
            "light=bin,smax=4,sigma=128"],
-    "C2": ["dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=256,rb=128", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
-    "C3": ["light=xl,w=512,rb=1024", "heavy=1024,tile=2048,light=xl,w=1024,rb=512,chunk=2048", "light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=0", "light=csrv,chunk=512", "light=bin,smax=16,sigma=512,chunk=256",
+    "C2": ["dia=1,dia_fill=0.999,light=wbm", "dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=256,rb=128", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
+    "C3": ["light=wbm", "heavy=1024,tile=2048,light=wbm", "light=bin,smax=16,sigma=512,chunk=256,wg=1", "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=0,wg=1", "light=csrv,lpr=256,chunk=512", "light=xl,w=512,rb=1024", "heavy=1024,tile=2048,light=xl,w=1024,rb=512,chunk=2048", "light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=0", "light=csrv,chunk=512", "light=bin,smax=16,sigma=512,chunk=256",
            "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
            "heavy=256,tile=512,light=sell,sigma=128", "heavy=1024,tile=2048,hd=1,light=xl,w=1024,rb=512", "heavy=256,tile=512,hd=1,light=sell,sigma=128"],
     "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", "light=sell,sigma=512",
            "light=csrv,lpr=16"],
-    "C5": ["heavy=64,tile=2048,light=xl,w=2048,rb=4096,chunk=4096", "light=xl,w=4096,rb=16384", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
+    "C5": ["heavy=64,tile=2048,light=wbm", "light=bin,smax=16,sigma=256,chunk=1024,wg=1", "heavy=64,tile=2048,light=xl,w=2048,rb=4096,chunk=4096", "light=xl,w=4096,rb=16384", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
            "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=64,tile=2048,hd=1,light=xl", "heavy=64,tile=8192,hd=1,light=csrv"],
 }
 
@@ -132,6 +132,24 @@ def test_closed_form_uniform_rows_need_no_padding_and_no_permutation():
     a = host_plan(m, "light=sell").arrays()
     assert "sell.origin_rows" not in a                                           # row = 64*slice + lane
     assert np.array_equal(a["sell.slice_ptr"], 640 * np.arange(-(-m.nrows // 64) + 1))
+
+
+def test_closed_form_wavefront_bitmaps_of_uniform_rows():
+    """Every row of C1 has 10 entries: entry g of the stream starts a row exactly when g % 10 == 0, a
+    tile of 512 entries is preceded by ceil(512 i / 10) row starts, and the stream is the CSR itself."""
+    m = TINY["C1"]()
+    a = host_plan(m, "light=wbm").arrays()
+    total = m.nnz
+    g = np.arange(a["wbm.cols"].size)
+    bits = ((a["wbm.mask"][g // 64] >> (g % 64).astype(np.uint64)) & np.uint64(1)).astype(bool)
+    assert np.array_equal(bits, (g % 10 == 0) & (g < total))
+    ntiles = -(-total // 512)
+    assert np.array_equal(a["wbm.tile_row"], np.minimum(-(-(512 * np.arange(ntiles + 1)) // 10), m.nrows))
+    assert np.array_equal(a["wbm.cols"][:total], m.col_idx) and np.array_equal(a["wbm.vals"][:total], m.values)
+    assert not a["wbm.vals"][total:].any() and np.array_equal(a["wbm.rows"], np.arange(m.nrows))
+    # rows cut by a tile border reduce through atomics: 512 i / 10 is whole only when i % 5 == 0
+    borders = sorted({(min(total, 512 * i) - 1) // 10 for i in range(1, ntiles + 1)} | {(512 * i) // 10 for i in range(1, ntiles) if (512 * i) % 10})
+    assert np.array_equal(a["zero.rows"], [r for r in borders if r < m.nrows])
 
 
 def test_closed_form_laplacian_diagonals():

@@ -16,16 +16,16 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 SPECS = {
-    "C1": ["light=xl,w=1024,rb=2048,chunk=4096", "light=xl", "light=coo", "light=xnb,k=8,r=4", "light=nnzb,r=4", "light=xs,k=8,sigma=256", "light=xs,k=32,sigma=0", "light=csrv", "light=csrv,lpr=1", "light=csrv,lpr=64,sigma=128", "light=sell", "light=sell,sigma=256,remap=1",
+    "C1": ["light=wbm", "light=csrv,lpr=256", "light=xl,w=1024,rb=2048,chunk=4096", "light=xl", "light=coo", "light=xnb,k=8,r=4", "light=nnzb,r=4", "light=xs,k=8,sigma=256", "light=xs,k=32,sigma=0", "light=csrv", "light=csrv,lpr=1", "light=csrv,lpr=64,sigma=128", "light=sell", "light=sell,sigma=256,remap=1",
            "light=bin,smax=4,sigma=128"],
-    "C2": ["dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=512,rb=1024", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "light=xs,k=24,sigma=4096", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1",
+    "C2": ["dia=1,dia_fill=0.999,light=wbm", "dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=512,rb=1024", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "light=xs,k=24,sigma=4096", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1",
            "dia=1,drows=2,light=sell", "dia=1,dia_fill=0.999,drows=4,light=csrv,lpr=1"],
-    "C3": ["light=xl,w=4096,rb=8192", "heavy=1024,tile=2048,light=xl,w=16384,rb=16384,chunk=20000", "heavy=1024,tile=2048,light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=8192", "light=csrv,chunk=512", "light=csrv,lpr=32", "light=bin,smax=16,sigma=512,chunk=256",
+    "C3": ["light=wbm", "heavy=1024,tile=2048,light=wbm", "light=bin,smax=16,sigma=512,chunk=256,wg=1", "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=0,wg=1", "light=csrv,lpr=256,chunk=512", "light=xl,w=4096,rb=8192", "heavy=1024,tile=2048,light=xl,w=16384,rb=16384,chunk=20000", "heavy=1024,tile=2048,light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=8192", "light=csrv,chunk=512", "light=csrv,lpr=32", "light=bin,smax=16,sigma=512,chunk=256",
            "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
            "heavy=256,tile=512,light=sell,sigma=128", "heavy=2048,tile=8192,light=bin,chunk=1024", "heavy=1024,tile=2048,hd=1,light=xl", "heavy=256,tile=512,hd=1,light=sell,sigma=128"],
     "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", "light=sell,sigma=512",
            "light=csrv,lpr=16"],
-    "C5": ["heavy=64,tile=2048,light=xl,w=8192,rb=16384", "light=xl,w=2048,rb=4096,chunk=100000", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
+    "C5": ["heavy=64,tile=2048,light=wbm", "light=bin,smax=16,sigma=256,chunk=1024,wg=1", "heavy=64,tile=2048,light=xl,w=8192,rb=16384", "light=xl,w=2048,rb=4096,chunk=100000", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
            "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=100,tile=8192,light=bin,sigma=8192,remap=1", "heavy=64,tile=2048,hd=1,light=xl", "heavy=64,tile=8192,hd=1,light=csrv"],
 }
 CASES = [(n, s) for n in SPECS for s in SPECS[n]]
@@ -98,7 +98,7 @@ def test_edge_cases():
     # empty matrix, matrix of empty rows, single entry
     for nrows, ncols in ((0, 0), (5, 7), (130, 3)):
         rp = np.zeros(nrows + 1, np.int32)
-        for spec in ("light=csrv", "light=sell", "light=bin", "heavy=4,light=sell", "light=xs", "light=nnzb", "light=xnb", "light=xl", "light=coo", None):
+        for spec in ("light=csrv", "light=sell", "light=bin", "heavy=4,light=sell", "light=xs", "light=nnzb", "light=wbm", "light=csrv,lpr=256", "light=bin,wg=1", "light=xnb", "light=xl", "light=coo", None):
             P = lib.Plan(nrows, ncols, rp, np.zeros(0, np.int32), np.zeros(0), force_plan=spec, search_budget_ms=200)
             x = torch.ones(max(ncols, 1), dtype=torch.float64, device=dev)[:ncols]
             y = torch.full((max(nrows, 1),), float("nan"), dtype=torch.float64, device=dev)[:nrows]
@@ -123,7 +123,7 @@ def test_edge_cases():
     m = M()
     m.nrows, m.ncols, m.row_ptr, m.col_idx = nrows, ncols, rp, ci
     for spec in ("light=csrv", "light=csrv,lpr=64,chunk=256", "light=sell,sigma=64", "light=bin,sigma=32,chunk=512",
-                 "heavy=100,tile=256,light=sell,sigma=64", "heavy=100,tile=64,light=bin", "heavy=100,tile=64,light=xs,k=8,sigma=64", "light=xs,k=16", "light=nnzb,r=4", "heavy=100,tile=64,light=nnzb,r=16", "light=xnb,k=8,r=4", "heavy=100,tile=64,light=xnb,k=16,r=8", "light=xl,w=64,rb=64", "heavy=100,tile=64,light=xl,w=256,rb=128,chunk=64", "heavy=100,tile=1024,hd=1,light=sell", "light=coo", None):
+                 "heavy=100,tile=256,light=sell,sigma=64", "heavy=100,tile=64,light=bin", "heavy=100,tile=64,light=xs,k=8,sigma=64", "light=xs,k=16", "light=nnzb,r=4", "heavy=100,tile=64,light=nnzb,r=16", "light=xnb,k=8,r=4", "heavy=100,tile=64,light=xnb,k=16,r=8", "light=xl,w=64,rb=64", "heavy=100,tile=64,light=xl,w=256,rb=128,chunk=64", "heavy=100,tile=1024,hd=1,light=sell", "light=wbm", "heavy=100,tile=64,light=wbm", "light=csrv,lpr=256,chunk=512", "light=bin,sigma=32,chunk=512,wg=1", "light=coo", None):
         for dt in (np.float64, np.float32):
             (y,), _ = gpu_spmv(m, va.astype(dt), x.astype(dt), spec, search_budget_ms=300)
             assert np.array_equal(y.astype(np.float64), want), (spec, dt)
@@ -139,7 +139,7 @@ def test_edge_cases():
     want = oracle.spmv(rp, ci, va, x)
     m.nrows = m.ncols = n
     m.row_ptr, m.col_idx = rp, ci
-    for spec in ("dia=1,light=sell", "dia=1,light=xs,k=8", "dia=1,light=csrv,lpr=2", "light=bsell,block=3", "light=bsell,block=2,sigma=32,xwin=1",
+    for spec in ("dia=1,light=sell", "dia=1,light=wbm", "dia=1,drows=4,light=csrv,lpr=256", "dia=1,light=xs,k=8", "dia=1,light=csrv,lpr=2", "light=bsell,block=3", "light=bsell,block=2,sigma=32,xwin=1",
                  "light=bsell,block=4,sigma=-1,remap=1"):
         (y,), _ = gpu_spmv(m, va, x, spec)
         assert np.array_equal(y, want), spec
