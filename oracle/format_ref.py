@@ -40,6 +40,32 @@ def parse_spec(spec: str) -> dict:
     return d
 
 
+def parse_tree(spec: str) -> dict:
+    """Plan tree: a flat spec is a leaf; rows(c1:..:cn){..}.., bin2(k){..}{..}, cut(rho:min){..} and
+    cols(k){..}.. divide the rows or columns of their sub-matrix among their children."""
+    t = spec.strip()
+    for word in ("rows", "bin2", "cut", "cols"):
+        if t.startswith(word + "("):
+            close = t.index(")")
+            cuts = [int(v) for v in t[len(word) + 1:close].split(":")]
+            kids, pos = [], close + 1
+            while pos < len(t):
+                assert t[pos] == "{", t
+                level, q = 0, pos
+                while True:
+                    level += t[q] == "{"
+                    level -= t[q] == "}"
+                    if level == 0:
+                        break
+                    q += 1
+                kids.append(parse_tree(t[pos + 1:q]))
+                pos = q + 1
+            return dict(node=word, cuts=cuts, kids=kids)
+    d = parse_spec(t)
+    d["node"] = "leaf"
+    return d
+
+
 def _sort_rows(rows, lens, sigma):
     rows = np.asarray(rows, dtype=np.int32)
     if sigma == 0 or rows.size < 2:
@@ -556,12 +582,11 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total, skip=()):
     return out
 
 
-def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
-    """All format arrays of the plan `spec` for a CSR matrix with ascending columns in each row."""
-    p = parse_spec(spec)
+def _ref_leaf(nrows, ncols, rp, ci, va, p, rows, whole, acc, span) -> dict:
+    """The arrays of one leaf (a flat design) over the rows `rows` (ascending) of the matrix."""
     out = {}
-    acc = False
     if p["dia"]:
+        assert whole and not acc
         offs = diag_census(nrows, ncols, rp, ci, p["dia_fill"])
         arrays, (rp, ci, va) = ref_dia(nrows, ncols, rp, ci, va, offs)
         out.update(arrays)
@@ -570,15 +595,16 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
             return out
     lens = np.diff(rp).astype(np.int64)
     if p["light"] == "bsell":
+        assert whole and not acc
         out.update(ref_bsell(nrows, ncols, rp, ci, va, p["block"], p["sigma"], p["xwin"]))
         return out
-    allrows = np.arange(nrows, dtype=np.int32)
-    heavy = allrows[lens > p["heavy"]] if p["heavy"] > 0 else allrows[:0]
-    is_light = np.ones(nrows, dtype=bool)
-    is_light[heavy] = False
+    rows = np.asarray(rows, dtype=np.int32)
+    is_heavy = (lens[rows] > p["heavy"]) if p["heavy"] > 0 else np.zeros(rows.size, dtype=bool)
+    heavy = rows[is_heavy]
+    is_light = ~is_heavy
     if acc:
-        is_light &= lens > 0
-    light = allrows[is_light]
+        is_light &= lens[rows] > 0
+    light = rows[is_light]
     zero_rows = []      # rows reduced through atomics (segments of a cut row); heavy rows have their own reduce launch
     if p["light"] == "csrv":
         lpr = p["lpr"]
@@ -599,8 +625,12 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
     elif p["light"] == "xnb":
         out.update(ref_xnb(ncols, rp, ci, va, light, p["k"], p["r"], nrows))
     elif p["light"] == "xl":
-        if not acc and heavy.size:
-            out.update(ref_xl(ncols, rp, ci, va, allrows, p["w"], p["rb"], p["chunk"], nrows, skip=heavy))
+        # the part may own rows it has no entries for: this leaf's heavy rows, or (span) the rows of the
+        # sibling leaves that run after it; their own launches overwrite those y elements later
+        owner = span if span is not None else (rows if heavy.size else None)
+        if not acc and owner is not None:
+            owner = np.asarray(owner, dtype=np.int32)
+            out.update(ref_xl(ncols, rp, ci, va, owner, p["w"], p["rb"], p["chunk"], nrows, skip=np.setdiff1d(owner, light)))
         else:
             out.update(ref_xl(ncols, rp, ci, va, light, p["w"], p["rb"], p["chunk"], nrows))
     elif p["light"] == "xs":
@@ -619,15 +649,100 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str) -> dict:
     return out
 
 
+def _column_stripe(rp, ci, va, rows, c0, c1):
+    """The rows `rows` restricted to columns [c0, c1); other rows empty; same row numbering."""
+    nrows = rp.size - 1
+    keep = np.zeros(ci.size, dtype=bool)
+    for r in rows:
+        e = _row_entries(rp, r)
+        keep[e] = (ci[e] >= c0) & (ci[e] < c1)
+    owner = np.repeat(np.arange(nrows), np.diff(rp))
+    cnt = np.bincount(owner[keep], minlength=nrows)
+    rp2 = np.zeros(nrows + 1, dtype=rp.dtype)
+    np.cumsum(cnt, out=rp2[1:])
+    return rp2, ci[keep], va[keep]
+
+
+def _ref_node(nrows, ncols, rp, ci, va, node, rows, whole, acc, span, prefix, out, leaves):
+    if node["node"] == "leaf":
+        arrays = _ref_leaf(nrows, ncols, rp, ci, va, node, rows, whole, acc, span)
+        out.update({prefix + k: v for k, v in arrays.items()})
+        leaves[prefix] = node
+        return
+    kids, cuts = node["kids"], node["cuts"]
+    kid = lambda i: kids[0] if len(kids) == 1 else kids[i]
+    lens = np.diff(rp).astype(np.int64)
+    rows = np.asarray(rows, dtype=np.int32)
+
+    def run_classes(classes, design, tag):
+        first = True
+        for i, cls in enumerate(classes):
+            if len(cls) == 0:
+                continue
+            k = kid(design[i])
+            can_span = (first and not acc and span is None and k["node"] == "leaf" and k["light"] == "xl"
+                        and not k["heavy"] and len(cls) < rows.size)
+            _ref_node(nrows, ncols, rp, ci, va, k, np.asarray(cls, dtype=np.int32), False, acc,
+                      rows if can_span else None, f"{prefix}{tag}{i}.", out, leaves)
+            first = False
+
+    if node["node"] == "rows":
+        c = np.searchsorted(np.asarray(cuts), lens[rows], side="left")       # cuts[c-1] < L <= cuts[c]
+        run_classes([rows[c == i] for i in range(len(cuts) + 1)], list(range(len(cuts) + 1)), "r")
+    elif node["node"] == "bin2":
+        k2 = cuts[0]
+        L = lens[rows]
+        b = np.where(L < 2, 0, np.minimum(k2, np.floor(np.log2(np.maximum(L, 1))).astype(np.int64)))
+        run_classes([rows[b == i] for i in range(k2 + 1)], [0] * k2 + [1], "b")
+    elif node["node"] == "cut":
+        rho, minrows = cuts
+        order = rows[np.argsort(-lens[rows], kind="stable")]
+        classes = [[]]
+        for i, r in enumerate(order):
+            classes[-1].append(int(r))
+            if (i + 1 < order.size and len(classes[-1]) >= minrows and lens[r] > 0
+                    and lens[r] >= rho * lens[order[i + 1]]):
+                classes.append([])
+        run_classes([sorted(c) for c in classes], [0] * len(classes), "p")
+    elif node["node"] == "cols":
+        K = cuts[0]
+        W = -(-ncols // K)
+        for j in range(K):
+            rp2, ci2, va2 = _column_stripe(rp, ci, va, rows, j * W, min(ncols, (j + 1) * W))
+            _ref_node(nrows, ncols, rp2, ci2, va2, kid(j), rows, False, acc or j > 0, None, f"{prefix}c{j}.", out, leaves)
+    else:
+        raise ValueError(node["node"])
+
+
+def ref_plan(nrows, ncols, rp, ci, va, spec: str, leaves=None) -> dict:
+    """All format arrays of the plan `spec` for a CSR matrix with ascending columns in each row.
+    `leaves` (a dict, optional) receives {name prefix: leaf parameters} for decode()."""
+    out = {}
+    _ref_node(nrows, ncols, rp, ci, va, parse_tree(spec), np.arange(nrows, dtype=np.int32), True, False, None, "",
+              out, leaves if leaves is not None else {})
+    return out
+
+
 # ---- decoding: plan arrays -> (row, col, value) triples --------------------------------------
 
-def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 8192, xl_w: int = 0, xl_rb: int = 16384):
+_PART_NAMES = ("bin0.sell", "bin1.csrv8", "bin2.csrv64", "bin2.csrwg", "zero", "coo", "xl", "xnb", "nnzb", "wbm", "xs", "dia",
+               "bsell", "sell", "csrv", "heavy")
+
+
+def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 8192, xl_w: int = 0, xl_rb: int = 16384,
+           leaves: dict | None = None):
     """Every stored entry of every part as COO triples (padding included: it carries value 0).
-    The part kind is recognised from the array names."""
+    The part kind is recognised from the array names; `leaves` ({name prefix: leaf parameters}, from
+    ref_plan) supplies block / tile / w / rb per leaf of a plan tree, the keyword arguments otherwise."""
     R, C, V = [], [], []
     prefixes = sorted({k.rsplit(".", 1)[0] for k in arrays})
-    for pre in prefixes:
-        a = {k.rsplit(".", 1)[1]: v for k, v in arrays.items() if k.rsplit(".", 1)[0] == pre}
+    for full in prefixes:
+        a = {k.rsplit(".", 1)[1]: v for k, v in arrays.items() if k.rsplit(".", 1)[0] == full}
+        pre = next(n for n in _PART_NAMES if full == n or full.endswith("." + n))
+        path = full[:len(full) - len(pre)]
+        if leaves is not None:
+            lp = leaves[path]
+            block, tile, xl_w, xl_rb = lp["block"], lp["tile"], lp["w"], lp["rb"]
         if pre == "zero":
             continue
         if pre == "coo":

@@ -64,7 +64,7 @@ const void *upload(Plan &plan, const std::string &name, int elem_bytes, int64_t 
     void *d = plan.mem.alloc(bytes, plan.mem.user);
     if (!d) fail(SPMV_ERR_ALLOC, "device allocation of " + std::to_string(bytes) + " bytes failed (" + name + ")");
     DevArray a;
-    a.name = name;
+    a.name = plan.prefix + name;
     a.ptr = d;
     a.elem_bytes = elem_bytes;
     a.count = count;
@@ -89,6 +89,7 @@ void add_part(Plan &plan, Part p, size_t first_array, int64_t x_elems, int64_t s
         if (plan.arrays[i].read_per_run) b += plan.arrays[i].count * plan.arrays[i].elem_bytes;
     b += v * (x_elems + scratch_elems + y_elems * (p.accumulate ? 2 : 1));
     p.bytes = b;
+    p.name = plan.prefix + p.name;
     plan.parts.push_back(p);
 }
 
@@ -601,7 +602,7 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the heavy part's scratch failed");
     {
         DevArray a;
-        a.name = "heavy.scratch";
+        a.name = plan.prefix + "heavy.scratch";
         a.ptr = scratch;
         a.elem_bytes = (int)sizeof(T);
         a.count = ngroups * nh;
@@ -1002,7 +1003,7 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
     if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the striped part's scratch failed");
     {
         DevArray a;
-        a.name = "xnb.scratch";
+        a.name = plan.prefix + "xnb.scratch";
         a.ptr = scratch;
         a.elem_bytes = (int)sizeof(T);
         a.count = nsegs;
@@ -1163,7 +1164,7 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
     if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the xl part's scratch failed");
     {
         DevArray a;
-        a.name = "xl.scratch";
+        a.name = plan.prefix + "xl.scratch";
         a.ptr = scratch;
         a.elem_bytes = (int)sizeof(T);
         a.count = tot;
@@ -1337,7 +1338,7 @@ void build_xs(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
     if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the striped part's scratch failed");
     {
         DevArray a;
-        a.name = "xs.scratch";
+        a.name = plan.prefix + "xs.scratch";
         a.ptr = scratch;
         a.elem_bytes = (int)sizeof(T);
         a.count = nunits * kWave;
@@ -1403,26 +1404,18 @@ void sorted_copy(const HostCsr &A, OwnedCsr &out, int threads) {
     out.view.val = out.val.data();
 }
 
+// One leaf of the plan tree: a flat design applied to the rows `rows` (ascending) of A.  `whole`:
+// the rows are all rows of the matrix the plan was made for and A is that matrix (needed by the
+// designs that work on the whole matrix).  `span`, when given, lists the rows a two-pass leaf should
+// own as rows without entries beside its own (see build_node); acc: y += instead of y =.
 template <typename T>
-std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const PlanSpec &spec,
-                                  const Allocator &mem, int threads) {
-    std::unique_ptr<Plan> plan(new Plan);
-    plan->dtype = A0.dtype;
-    plan->nrows = A0.nrows;
-    plan->ncols = A0.ncols;
-    plan->nnz = A0.nnz;
-    plan->spec = spec;
-    plan->mem = mem;
-    plan->census = cen;
-
-    OwnedCsr sorted, rem;
+void build_leaf(Plan &plan, const HostCsr &A0, const Census &cen, const PlanSpec &spec,
+                const std::vector<int32_t> &rows, bool whole, bool acc, const std::vector<int32_t> *span,
+                int threads) {
+    OwnedCsr rem;
     const HostCsr *cur = &A0;
-    if (!cen.cols_sorted) {
-        sorted_copy<T>(A0, sorted, threads);
-        cur = &sorted.view;
-    }
-    bool acc = false;
     if (spec.dia) {
+        if (!whole || acc) fail(SPMV_ERR_UNSUPPORTED, "dia: works on the whole matrix only");
         // offsets whose population reaches dia_fill (the census kept those >= 0.5)
         std::vector<int32_t> offs = cen.diag_offsets;
         if (spec.dia_fill > 0.5) {
@@ -1442,69 +1435,73 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
             offs.swap(keep);
         }
         if (offs.empty()) fail(SPMV_ERR_UNSUPPORTED, "dia: the matrix has no diagonal populated enough");
-        build_dia<T>(*plan, *cur, offs, rem, spec.drows, threads);
+        build_dia<T>(plan, *cur, offs, rem, spec.drows, threads);
         cur = &rem.view;
         acc = true;
-        if (cur->nnz == 0) return plan;
+        if (cur->nnz == 0) return;
     }
     const HostCsr &A = *cur;
-    std::vector<int64_t> lens((size_t)A.nrows);
-    parallel_for(A.nrows, 1 << 16, threads, [&](int64_t b, int64_t e, int) {
-        for (int64_t r = b; r < e; ++r) lens[(size_t)r] = A.len(r);
+    std::vector<int64_t> lens((size_t)A.nrows, 0);
+    parallel_for((int64_t)rows.size(), 1 << 16, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) lens[(size_t)rows[(size_t)i]] = A.len(rows[(size_t)i]);
     });
 
     if (spec.light == L_BSELL) {
-        build_bsell<T>(*plan, A, spec.block, spec.sigma, spec.remap, spec.xwin, threads);
-        return plan;
+        if (!whole || acc) fail(SPMV_ERR_UNSUPPORTED, "bsell: works on the whole matrix only");
+        build_bsell<T>(plan, A, spec.block, spec.sigma, spec.remap, spec.xwin, threads);
+        return;
     }
 
-    // ROW_DIV: heavy rows (longer than the threshold) against the rest.  After a DIA part wrote
-    // every y element, rows with nothing left are skipped.
+    // ROW_DIV: heavy rows (longer than the threshold) against the rest.  After an earlier part wrote
+    // every y element of these rows, rows with nothing left are skipped.
     std::vector<int32_t> heavy, light;
-    for (int64_t r = 0; r < A.nrows; ++r) {
+    for (int32_t r : rows) {
         const int64_t L = lens[(size_t)r];
-        if (spec.heavy > 0 && L > spec.heavy) heavy.push_back((int32_t)r);
-        else if (!(acc && L == 0)) light.push_back((int32_t)r);
+        if (spec.heavy > 0 && L > spec.heavy) heavy.push_back(r);
+        else if (!(acc && L == 0)) light.push_back(r);
     }
     // rows reduced through atomics are zeroed by the first launch
     std::vector<int32_t> zero_rows;
-    const size_t zero_slot = plan->parts.size();
+    const size_t zero_slot = plan.parts.size();
     // (heavy rows are written by their own reduce launch and need no zeroing)
 
     switch (spec.light) {
     case L_CSRV:
-        build_csrv<T>(*plan, A, light, spec.lpr, spec.chunk, spec.sigma, acc, spec.remap, "csrv", lens, zero_rows, threads);
+        build_csrv<T>(plan, A, light, spec.lpr, spec.chunk, spec.sigma, acc, spec.remap, "csrv", lens, zero_rows, threads);
         break;
     case L_SELL:
-        build_sell<T>(*plan, A, light, spec.sigma, acc, spec.remap, "sell", lens, threads);
+        build_sell<T>(plan, A, light, spec.sigma, acc, spec.remap, "sell", lens, threads);
         break;
     case L_XS:
-        build_xs<T>(*plan, A, light, spec.k, spec.sigma, acc, lens, threads);
+        build_xs<T>(plan, A, light, spec.k, spec.sigma, acc, lens, threads);
         break;
     case L_NNZB:
-        build_nnzb<T>(*plan, A, light, spec.r, acc, lens, zero_rows, threads);
+        build_nnzb<T>(plan, A, light, spec.r, acc, lens, zero_rows, threads);
         break;
     case L_WBM:
-        build_wbm<T>(*plan, A, light, acc, lens, zero_rows, threads);
+        build_wbm<T>(plan, A, light, acc, lens, zero_rows, threads);
         break;
     case L_XNB:
-        build_xnb<T>(*plan, A, light, spec.k, spec.r, acc, lens, threads);
+        build_xnb<T>(plan, A, light, spec.k, spec.r, acc, lens, threads);
         break;
     case L_COO:
-        build_coo<T>(*plan, A, light, acc, lens, zero_rows, threads);
+        build_coo<T>(plan, A, light, acc, lens, zero_rows, threads);
         break;
-    case L_XL:
-        if (!acc && !heavy.empty()) {
-            // keep the heavy rows in the part as rows without entries: identity row order
-            std::vector<int32_t> all((size_t)A.nrows);
-            std::iota(all.begin(), all.end(), 0);
-            std::vector<int64_t> lens_light(lens);
-            for (int32_t r : heavy) lens_light[(size_t)r] = 0;
-            build_xl<T>(*plan, A, all, spec.w, spec.rb, spec.chunk, acc, lens_light, threads);
+    case L_XL: {
+        // The part may own more rows than it has entries for: the heavy rows of this leaf, or (span)
+        // the rows of the sibling leaves that run after it.  They stay in as rows without entries,
+        // so that the part's rows are one contiguous range where possible (no row map to read, y
+        // written contiguously); the launches of their own parts overwrite those y elements later.
+        const std::vector<int32_t> *owner = span ? span : (heavy.empty() ? nullptr : &rows);
+        if (!acc && owner) {
+            std::vector<int64_t> lens_light((size_t)A.nrows, 0);
+            for (int32_t r : light) lens_light[(size_t)r] = lens[(size_t)r];
+            build_xl<T>(plan, A, *owner, spec.w, spec.rb, spec.chunk, acc, lens_light, threads);
         } else {
-            build_xl<T>(*plan, A, light, spec.w, spec.rb, spec.chunk, acc, lens, threads);
+            build_xl<T>(plan, A, light, spec.w, spec.rb, spec.chunk, acc, lens, threads);
         }
         break;
+    }
     case L_BIN: {
         // BIN: short rows -> SELL, medium rows -> 8 lanes per row, long rows -> one wavefront (or, with
         // wg=1, one workgroup) per row (cut into segments of `chunk`)
@@ -1515,28 +1512,180 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
             else if (L <= 128) mids.push_back(r);
             else longs.push_back(r);
         }
-        build_sell<T>(*plan, A, shorts, spec.sigma, acc, spec.remap, "bin0.sell", lens, threads);
-        build_csrv<T>(*plan, A, mids, 8, 0, spec.sigma, acc, spec.remap, "bin1.csrv8", lens, zero_rows, threads);
-        if (spec.wg) build_csrv<T>(*plan, A, longs, 256, spec.chunk, 0, acc, spec.remap, "bin2.csrwg", lens, zero_rows, threads);
-        else build_csrv<T>(*plan, A, longs, 64, spec.chunk, 0, acc, spec.remap, "bin2.csrv64", lens, zero_rows, threads);
+        build_sell<T>(plan, A, shorts, spec.sigma, acc, spec.remap, "bin0.sell", lens, threads);
+        build_csrv<T>(plan, A, mids, 8, 0, spec.sigma, acc, spec.remap, "bin1.csrv8", lens, zero_rows, threads);
+        if (spec.wg) build_csrv<T>(plan, A, longs, 256, spec.chunk, 0, acc, spec.remap, "bin2.csrwg", lens, zero_rows, threads);
+        else build_csrv<T>(plan, A, longs, 64, spec.chunk, 0, acc, spec.remap, "bin2.csrv64", lens, zero_rows, threads);
         break;
     }
     default: fail(SPMV_ERR_INVALID_ARG, "unknown light design");
     }
-    if (!heavy.empty()) build_stripe<T>(*plan, A, heavy, spec.tile, spec.hd, acc, lens, threads);
+    if (!heavy.empty()) build_stripe<T>(plan, A, heavy, spec.tile, spec.hd, acc, lens, threads);
 
     if (!zero_rows.empty()) {
         std::sort(zero_rows.begin(), zero_rows.end());
         Part z;
         z.kind = K_ZERO;
-        z.name = "zero";
+        z.name = plan.prefix + "zero";
         z.nrows = (int64_t)zero_rows.size();
         z.units = z.nrows;
         z.has_rows = true;
-        z.p0 = upload(*plan, "zero.rows", 4, z.nrows, zero_rows.data());
-        z.bytes = z.nrows * (4 + (int64_t)plan->vsize());
-        plan->parts.insert(plan->parts.begin() + (std::ptrdiff_t)zero_slot, z);
+        z.p0 = upload(plan, "zero.rows", 4, z.nrows, zero_rows.data());
+        z.bytes = z.nrows * (4 + (int64_t)plan.vsize());
+        plan.parts.insert(plan.parts.begin() + (std::ptrdiff_t)zero_slot, z);
     }
+}
+
+// Copy of the rows `rows` of A restricted to the columns [c0, c1): same row numbering, other rows empty.
+template <typename T>
+void column_stripe(const HostCsr &A, const std::vector<int32_t> &rows, int64_t c0, int64_t c1, OwnedCsr &out,
+                   int threads) {
+    out.row_ptr.assign((size_t)A.nrows + 1, 0);
+    parallel_for((int64_t)rows.size(), 1 << 12, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t r = rows[(size_t)i];
+            int32_t cnt = 0;
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) cnt += A.col[k] >= c0 && A.col[k] < c1;
+            out.row_ptr[(size_t)r + 1] = cnt;
+        }
+    });
+    for (int64_t r = 0; r < A.nrows; ++r) out.row_ptr[(size_t)r + 1] += out.row_ptr[(size_t)r];
+    const int64_t nnz = out.row_ptr[(size_t)A.nrows];
+    out.col.resize((size_t)nnz);
+    out.val.resize((size_t)nnz * sizeof(T));
+    const T *av = (const T *)A.val;
+    T *ov = (T *)out.val.data();
+    parallel_for((int64_t)rows.size(), 1 << 12, threads, [&](int64_t b, int64_t e, int) {
+        for (int64_t i = b; i < e; ++i) {
+            const int32_t r = rows[(size_t)i];
+            int64_t dst = out.row_ptr[(size_t)r];
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k)
+                if (A.col[k] >= c0 && A.col[k] < c1) {
+                    out.col[(size_t)dst] = A.col[k];
+                    ov[dst] = av[k];
+                    ++dst;
+                }
+        }
+    });
+    out.view = A;
+    out.view.nnz = nnz;
+    out.view.row_ptr = out.row_ptr.data();
+    out.view.col = out.col.data();
+    out.view.val = out.val.data();
+}
+
+// The plan tree (Section IV-B): an inner node hands each child its share of the node's rows or
+// columns; the children's launches follow each other in the order of the tree.  Array and launch
+// names of a child carry its path ("r1.", "b3.", "p0.", "c2."), so that a tree's arrays stay apart.
+template <typename T>
+void build_node(Plan &plan, const HostCsr &A, const Census &cen, const PlanSpec &node,
+                const std::vector<int32_t> &rows, bool whole, bool acc, const std::vector<int32_t> *span,
+                int threads) {
+    if (node.node == N_LEAF) {
+        build_leaf<T>(plan, A, cen, node, rows, whole, acc, span, threads);
+        return;
+    }
+    const std::string outer = plan.prefix;
+    auto kid = [&](size_t i) -> const PlanSpec & { return node.kids.size() == 1 ? node.kids[0] : node.kids[i]; };
+    // classes of rows in launch order; a two-pass leaf that comes first may own every row of the node
+    auto run_classes = [&](const std::vector<std::vector<int32_t>> &cls, const std::vector<size_t> &design, char tag) {
+        bool first = true;
+        for (size_t i = 0; i < cls.size(); ++i) {
+            if (cls[i].empty()) continue;
+            const PlanSpec &k = kid(design[i]);
+            plan.prefix = outer + tag + std::to_string(i) + ".";
+            const bool can_span = first && !acc && !span && k.node == N_LEAF && k.light == L_XL && !k.heavy && cls[i].size() < rows.size();
+            build_node<T>(plan, A, cen, k, cls[i], false, acc, can_span ? &rows : nullptr, threads);
+            first = false;
+        }
+        plan.prefix = outer;
+    };
+    switch (node.node) {
+    case N_ROWS: {
+        std::vector<std::vector<int32_t>> cls(node.cuts.size() + 1);
+        std::vector<size_t> design(cls.size());
+        for (size_t i = 0; i < cls.size(); ++i) design[i] = i;
+        for (int32_t r : rows) {
+            const int64_t L = A.len(r);
+            const size_t c = (size_t)(std::lower_bound(node.cuts.begin(), node.cuts.end(), L) - node.cuts.begin());
+            cls[c].push_back(r);   // cuts[c-1] < L <= cuts[c]
+        }
+        run_classes(cls, design, 'r');
+        break;
+    }
+    case N_BIN2: {
+        // bin b: 2^b <= length < 2^(b+1); empty rows go with bin 0; lengths from 2^k on form the last class
+        const int k = (int)node.cuts[0];
+        std::vector<std::vector<int32_t>> cls((size_t)k + 1);
+        std::vector<size_t> design((size_t)k + 1, 0);
+        design[(size_t)k] = 1;
+        for (int32_t r : rows) {
+            const int64_t L = A.len(r);
+            int b = 0;
+            while (b < k && L >= ((int64_t)2 << b)) ++b;
+            cls[(size_t)b].push_back(r);
+        }
+        run_classes(cls, design, 'b');
+        break;
+    }
+    case N_CUT: {
+        // stable sort by decreasing length; a part ends where the next row is rho times shorter and the
+        // part has reached its minimum size; inside a part the rows return to ascending order
+        std::vector<int32_t> order(rows);
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return A.len(a) > A.len(b); });
+        std::vector<std::vector<int32_t>> cls(1);
+        const int64_t rho = node.cuts[0], minrows = node.cuts[1];
+        for (size_t i = 0; i < order.size(); ++i) {
+            cls.back().push_back(order[i]);
+            if (i + 1 < order.size() && (int64_t)cls.back().size() >= minrows && A.len(order[i]) > 0 &&
+                A.len(order[i]) >= rho * A.len(order[i + 1]))
+                cls.emplace_back();
+        }
+        if (cls.size() > 64) fail(SPMV_ERR_UNSUPPORTED, "cut: more than 64 parts");
+        for (auto &c : cls) std::sort(c.begin(), c.end());
+        std::vector<size_t> design(cls.size(), 0);
+        run_classes(cls, design, 'p');
+        break;
+    }
+    case N_COLS: {
+        const int64_t K = node.cuts[0];
+        const int64_t W = (A.ncols + K - 1) / K;
+        for (int64_t j = 0; j < K; ++j) {
+            OwnedCsr stripe;
+            column_stripe<T>(A, rows, j * W, std::min(A.ncols, (j + 1) * W), stripe, threads);
+            plan.prefix = outer + "c" + std::to_string(j) + ".";
+            // the first stripe writes every row of the node (zeros where it has nothing), the others add
+            build_node<T>(plan, stripe.view, cen, kid((size_t)j), rows, false, acc || j > 0, nullptr, threads);
+        }
+        plan.prefix = outer;
+        break;
+    }
+    default: fail(SPMV_ERR_INVALID_ARG, "unknown plan node");
+    }
+}
+
+template <typename T>
+std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const PlanSpec &spec,
+                                  const Allocator &mem, int threads) {
+    std::unique_ptr<Plan> plan(new Plan);
+    plan->dtype = A0.dtype;
+    plan->nrows = A0.nrows;
+    plan->ncols = A0.ncols;
+    plan->nnz = A0.nnz;
+    plan->spec = spec;
+    plan->mem = mem;
+    plan->census = cen;
+
+    OwnedCsr sorted;
+    const HostCsr *cur = &A0;
+    if (!cen.cols_sorted) {
+        sorted_copy<T>(A0, sorted, threads);
+        cur = &sorted.view;
+    }
+    std::vector<int32_t> all((size_t)A0.nrows);
+    std::iota(all.begin(), all.end(), 0);
+    build_node<T>(*plan, *cur, cen, spec, all, true, false, nullptr, threads);
+    plan->prefix.clear();
     return plan;
 }
 

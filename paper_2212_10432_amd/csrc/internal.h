@@ -85,7 +85,21 @@ Census take_census(const HostCsr &A, int threads);
 // ---- plan specification --------------------------------------------------------------------
 enum LightKind { L_CSRV = 0, L_SELL = 1, L_BSELL = 2, L_BIN = 3, L_XS = 4, L_NNZB = 5, L_XNB = 6, L_COO = 7, L_XL = 8, L_WBM = 9 };
 
+// A plan is a tree (the paper's Operator Graph, Section IV-B: a chain of operators that branches at
+// every ROW_DIV / COL_DIV, each branch designed on its own).  Inner nodes divide the rows or columns of
+// their sub-matrix among their children; a leaf carries one flat design (everything below `node`).
+enum NodeKind {
+    N_LEAF = 0,
+    N_ROWS,   // ROW_DIV by row length: cuts c1 < c2 < ...; child i takes the rows with c_i < length <= c_(i+1)
+    N_BIN2,   // BIN: one part per power-of-two length class below 2^cuts[0] (child 0), the rest to child 1
+    N_CUT,    // ROW_DIV after SORT: cut where length[i] >= cuts[0] * length[i+1], parts of >= cuts[1] rows
+    N_COLS    // COL_DIV into cuts[0] equal column stripes; stripes after the first accumulate into y
+};
+
 struct PlanSpec {
+    int node = N_LEAF;
+    std::vector<int64_t> cuts;
+    std::vector<PlanSpec> kids;   // one per class / stripe, or a single design applied to all of them
     int dia = 0;             // extract well-populated diagonals into a DIA part first
     double dia_fill = 0.5;   //   minimum population of a diagonal to be extracted
     int drows = 1;           //   rows per lane of the DIA kernel (1, 2 or 4)
@@ -175,6 +189,7 @@ struct Plan {
     Census census;
     std::vector<CandidateLog> log;
     std::string describe_cache;
+    std::string prefix;              // while building: path of the tree node whose arrays are being made
     ~Plan();
     size_t vsize() const { return dtype == SPMV_F64 ? 8 : 4; }
     int64_t bytes_plan() const;

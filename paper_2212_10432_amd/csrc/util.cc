@@ -1,5 +1,6 @@
 // Host threading helpers and the plan-spec grammar.
 #include <algorithm>
+#include <cstring>
 #include <sstream>
 
 #include "internal.h"
@@ -77,7 +78,88 @@ static const char *light_name(int l) {
 
 static bool pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 
-PlanSpec parse_spec(const std::string &s) {
+static PlanSpec parse_leaf(const std::string &s);
+
+// node := leaf | ("rows" | "bin2" | "cut" | "cols") "(" n (":" n)* ")" ("{" node "}")+
+static PlanSpec parse_node(const std::string &s, int depth) {
+    if (depth > 6) fail(SPMV_ERR_INVALID_ARG, "plan spec: nested too deeply");
+    size_t b = 0, e = s.size();
+    while (b < e && (s[b] == ' ' || s[b] == '\t')) ++b;
+    while (e > b && (s[e - 1] == ' ' || s[e - 1] == '\t')) --e;
+    const std::string t = s.substr(b, e - b);
+    static const struct { const char *word; int kind; } heads[] = {{"rows(", N_ROWS}, {"bin2(", N_BIN2}, {"cut(", N_CUT}, {"cols(", N_COLS}};
+    int kind = N_LEAF;
+    size_t open = 0;
+    for (const auto &h : heads)
+        if (t.compare(0, std::strlen(h.word), h.word) == 0) {
+            kind = h.kind;
+            open = std::strlen(h.word);
+        }
+    if (kind == N_LEAF) {
+        if (t.find_first_of("{}()") != std::string::npos) fail(SPMV_ERR_INVALID_ARG, "plan spec: stray bracket in " + t);
+        return parse_leaf(t);
+    }
+    PlanSpec p;
+    p.node = kind;
+    const size_t close = t.find(')', open);
+    if (close == std::string::npos) fail(SPMV_ERR_INVALID_ARG, "plan spec: missing ')' in " + t);
+    {
+        std::stringstream ss(t.substr(open, close - open));
+        std::string tok;
+        while (std::getline(ss, tok, ':')) {
+            char *end = nullptr;
+            const long long v = std::strtoll(tok.c_str(), &end, 10);
+            if (tok.empty() || *end || v < 0) fail(SPMV_ERR_INVALID_ARG, "plan spec: bad number in " + t.substr(0, close + 1));
+            p.cuts.push_back((int64_t)v);
+        }
+    }
+    size_t pos = close + 1;
+    while (pos < t.size()) {
+        if (t[pos] != '{') fail(SPMV_ERR_INVALID_ARG, "plan spec: '{' expected in " + t);
+        int level = 0;
+        size_t q = pos;
+        for (; q < t.size(); ++q) {
+            if (t[q] == '{') ++level;
+            if (t[q] == '}' && --level == 0) break;
+        }
+        if (q == t.size()) fail(SPMV_ERR_INVALID_ARG, "plan spec: missing '}' in " + t);
+        p.kids.push_back(parse_node(t.substr(pos + 1, q - pos - 1), depth + 1));
+        pos = q + 1;
+    }
+    const size_t nk = p.kids.size();
+    auto need = [&](bool ok, const char *msg) {
+        if (!ok) fail(SPMV_ERR_INVALID_ARG, std::string("plan spec: ") + msg);
+    };
+    switch (kind) {
+    case N_ROWS:
+        need(!p.cuts.empty() && p.cuts.size() <= 16, "rows() takes 1 to 16 lengths");
+        for (size_t i = 1; i < p.cuts.size(); ++i) need(p.cuts[i] > p.cuts[i - 1], "rows(): lengths must ascend");
+        need(nk == 1 || nk == p.cuts.size() + 1, "rows(c1:..:cn) takes one design or n + 1");
+        break;
+    case N_BIN2:
+        need(p.cuts.size() == 1 && p.cuts[0] >= 1 && p.cuts[0] <= 20, "bin2(k) takes one exponent in [1, 20]");
+        need(nk == 2, "bin2(k) takes two designs: the bins below 2^k, the rows from 2^k on");
+        break;
+    case N_CUT:
+        need(p.cuts.size() == 2 && p.cuts[0] >= 2 && p.cuts[1] >= 1, "cut(rho:minrows) needs rho >= 2 and minrows >= 1");
+        need(nk == 1, "cut() takes one design");
+        break;
+    case N_COLS:
+        need(p.cuts.size() == 1 && p.cuts[0] >= 2 && p.cuts[0] <= 64, "cols(k) takes a stripe count in [2, 64]");
+        need(nk == 1 || (int64_t)nk == p.cuts[0], "cols(k) takes one design or k");
+        break;
+    }
+    std::function<void(const PlanSpec &)> no_whole = [&](const PlanSpec &q) {
+        if (q.node == N_LEAF) need(!q.dia && q.light != L_BSELL, "dia and bsell work on the whole matrix and cannot sit inside rows/bin2/cut/cols");
+        for (const PlanSpec &k : q.kids) no_whole(k);
+    };
+    for (const PlanSpec &k : p.kids) no_whole(k);
+    return p;
+}
+
+PlanSpec parse_spec(const std::string &s) { return parse_node(s, 0); }
+
+static PlanSpec parse_leaf(const std::string &s) {
     PlanSpec p;
     std::stringstream ss(s);
     std::string tok;
@@ -153,6 +235,13 @@ PlanSpec parse_spec(const std::string &s) {
 
 std::string print_spec(const PlanSpec &p) {
     std::ostringstream o;
+    if (p.node != N_LEAF) {
+        o << (p.node == N_ROWS ? "rows(" : p.node == N_BIN2 ? "bin2(" : p.node == N_CUT ? "cut(" : "cols(");
+        for (size_t i = 0; i < p.cuts.size(); ++i) o << (i ? ":" : "") << p.cuts[i];
+        o << ")";
+        for (const PlanSpec &k : p.kids) o << "{" << print_spec(k) << "}";
+        return o.str();
+    }
     if (p.dia) o << "dia=1,dia_fill=" << p.dia_fill << ",";
     if (p.dia && p.drows != 1) o << "drows=" << p.drows << ",";
     if (p.heavy) o << "heavy=" << p.heavy << ",tile=" << p.tile << (p.hd ? ",hd=1," : ",");
@@ -176,9 +265,37 @@ std::string print_spec(const PlanSpec &p) {
 
 // The same design as a chain of the paper's operators (Table II).  DIA_EXTRACT, HEAVY_SPLIT and
 // DENSE_BLOCK name the three strategies Section VII-F lists as not yet supported by the paper.
+static std::string leaf_chain(const PlanSpec &p, bool root);
+
 std::string operator_chain(const PlanSpec &p) {
+    if (p.node == N_LEAF) return leaf_chain(p, true);
+    std::function<std::string(const PlanSpec &)> walk = [&](const PlanSpec &q) -> std::string {
+        if (q.node == N_LEAF) {
+            const std::string c = leaf_chain(q, false);
+            return c.size() > 4 ? c.substr(4) : c;   // without the leading " -> "
+        }
+        std::ostringstream o;
+        switch (q.node) {
+        case N_ROWS:
+            o << "ROW_DIV(len";
+            for (int64_t c : q.cuts) o << "|" << c;
+            o << ")";
+            break;
+        case N_BIN2: o << "BIN(2^0..2^" << q.cuts[0] << ")"; break;
+        case N_CUT: o << "SORT -> ROW_DIV(len[i]>=" << q.cuts[0] << "*len[i+1], >=" << q.cuts[1] << " rows)"; break;
+        default: o << "COL_DIV(" << q.cuts[0] << ")"; break;
+        }
+        o << "{";
+        for (size_t i = 0; i < q.kids.size(); ++i) o << (i ? " | " : "") << walk(q.kids[i]);
+        o << "}";
+        return o.str();
+    };
+    return "COMPRESS -> " + walk(p);
+}
+
+static std::string leaf_chain(const PlanSpec &p, bool root) {
     std::ostringstream o;
-    o << "COMPRESS";
+    if (root) o << "COMPRESS";
     if (p.dia) o << " -> DIA_EXTRACT(fill>=" << p.dia_fill << ")[BMT_ROW_BLOCK(" << p.drows << ") -> THREAD_TOTAL_RED]";
     if (p.heavy)
         o << " -> ROW_DIV(len>" << p.heavy << ")[HEAVY_SPLIT: COL_DIV(" << p.tile

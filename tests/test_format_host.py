@@ -302,3 +302,74 @@ def test_random_matrices_random_plans_decode_to_input():
         rr, cc, vv = ref.decode(got, nrows, ncols, block=p["block"], tile=p["tile"], xl_w=p["w"], xl_rb=p["rb"])
         assert same_matrix(as_scipy(nrows, ncols, rr, cc, vv), A_in), (case, spec)
         P.destroy()
+
+
+# ---- plan trees (the paper's Operator Graph with branches, Section IV-B) ------------------------
+TREES = {
+    "C1": ["cols(4){light=sell,sigma=256}", "bin2(3){light=sell}{light=csrv,lpr=4}"],
+    "C3": ["rows(8:64:1024){light=sell,sigma=128}{light=csrv,lpr=8}{light=csrv,lpr=64}{heavy=1024,tile=512,light=csrv}",
+           "rows(16:256){light=xl,w=512,rb=1024}{light=nnzb,r=8}{heavy=256,tile=1024,hd=1,light=csrv}",
+           "bin2(6){light=sell}{light=wbm}", "cut(2:64){light=sell,sigma=0}", "cut(4:1){light=csrv,lpr=16}",
+           "rows(64){cols(2){light=sell}{light=xl,w=256,rb=512}}{light=csrv,lpr=64,chunk=512}",
+           "cols(3){rows(32){light=xl,w=256,rb=256}{light=csrv,lpr=16}}",
+           "rows(100){light=xs,k=8,sigma=256}{light=xnb,k=8,r=4}",
+           "rows(64:512){light=xl,w=1024,rb=512}{heavy=64,tile=512,light=csrv}{heavy=512,tile=2048,light=csrv}"],
+    "C5": ["cut(8:100){light=sell,sigma=0}", "rows(8){light=xl,w=2048,rb=4096}{heavy=8,tile=2048,hd=1,light=csrv}",
+           "rows(4:8){light=sell}{light=coo}{cols(2){heavy=8,tile=1024,light=csrv}}"],
+}
+TREE_CASES = [(n, s) for n in TREES for s in TREES[n]]
+
+
+@pytest.mark.parametrize("name,spec", TREE_CASES)
+@pytest.mark.parametrize("dt", [np.float64, np.float32])
+def test_plan_trees_match_reference_and_decode_to_input(name, spec, dt):
+    m = TINY[name]()
+    vals = m.values.astype(dt)
+    P = host_plan(m, spec, vals)
+    got = P.arrays()
+    leaves = {}
+    want = ref.ref_plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, vals, spec, leaves)
+    assert sorted(got) == sorted(want)
+    for k in got:
+        assert got[k].dtype == want[k].dtype and np.array_equal(got[k], want[k]), k
+    r, c, v = ref.decode(got, m.nrows, m.ncols, leaves=leaves)
+    assert same_matrix(as_scipy(m.nrows, m.ncols, r, c, v), as_scipy(m.nrows, m.ncols, np.repeat(np.arange(m.nrows), np.diff(m.row_ptr)), m.col_idx, vals))
+    d = P.describe()
+    assert sum(part["nnz"] for part in d["parts"]) == m.nnz
+    P2 = host_plan(m, d["spec"], vals)                       # the printed tree parses back to itself
+    assert P2.describe()["spec"] == d["spec"] and P2.describe()["operators"] == d["operators"]
+    P.destroy(); P2.destroy()
+
+
+def test_row_classes_of_a_tree_partition_the_rows():
+    """ROW_DIV by length class: child i owns exactly the rows with c_i < length <= c_(i+1); the
+    HYB-like cut of the hybrid family (lengths 2..8 against 5000) is found by the ratio rule."""
+    m = TINY["C3"]()
+    lens = np.diff(m.row_ptr)
+    a = host_plan(m, "rows(8:64){light=csrv,lpr=1,sigma=1}{light=csrv,lpr=8,sigma=1}{light=csrv,lpr=64,sigma=1}").arrays()
+    for i, (lo, hi) in enumerate([(-1, 8), (8, 64), (64, 10 ** 9)]):
+        rows = np.sort(a[f"r{i}.csrv.seg_row"])
+        assert np.array_equal(rows, np.flatnonzero((lens > lo) & (lens <= hi)))
+    m5 = TINY["C5"]()
+    a5 = host_plan(m5, "cut(8:1){light=csrv,lpr=1,sigma=1}").arrays()
+    assert np.array_equal(np.sort(a5["p0.csrv.seg_row"]), m5.meta["heavy_rows"])       # the five rows of 5000
+    assert a5["p1.csrv.seg_row"].size == m5.nrows - 5
+    a2 = host_plan(m, "bin2(4){light=csrv,lpr=1,sigma=1}{light=csrv,lpr=1,sigma=1}").arrays()
+    for b in range(5):
+        if f"b{b}.csrv.seg_row" in a2:
+            L = lens[a2[f"b{b}.csrv.seg_row"]]
+            assert np.all(L < 2) if b == 0 else (np.all(L >= 2 ** b) and (b == 4 or np.all(L < 2 ** (b + 1))))
+
+
+@pytest.mark.parametrize("spec", ["rows(8){light=sell}", "rows(8:4){light=sell}", "rows(){light=sell}", "bin2(4){light=sell}",
+                                  "cut(1:5){light=sell}", "cols(1){light=sell}", "cols(3){light=sell}{light=sell}",
+                                  "rows(8){dia=1,light=sell}{light=sell}", "rows(8){light=bsell}{light=sell}", "rows(8){light=sell}{light=sell",
+                                  "rows(8{light=sell}{light=sell}", "light=sell}", "rows(8)light=sell"])
+def test_malformed_trees_are_refused(spec):
+    m = TINY["C1"]()
+    if spec == "rows(8){light=sell}":
+        host_plan(m, spec).destroy()          # one design for every class is legal
+        return
+    with pytest.raises(lib.SpmvError) as e:
+        host_plan(m, spec)
+    assert e.value.status == lib.SPMV_ERR_INVALID_ARG

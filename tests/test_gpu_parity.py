@@ -28,6 +28,21 @@ SPECS = {
     "C5": ["heavy=64,tile=2048,light=wbm", "light=bin,smax=16,sigma=256,chunk=1024,wg=1", "heavy=64,tile=2048,light=xl,w=8192,rb=16384", "light=xl,w=2048,rb=4096,chunk=100000", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
            "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=100,tile=8192,light=bin,sigma=8192,remap=1", "heavy=64,tile=2048,hd=1,light=xl", "heavy=64,tile=8192,hd=1,light=csrv"],
 }
+# plan trees: ROW_DIV by length class, power-of-two BIN, the ratio cut after SORT, COL_DIV, nested
+TREES = {
+    "C1": ["cols(4){light=sell,sigma=256}", "bin2(3){light=sell}{light=csrv,lpr=4}"],
+    "C3": ["rows(8:64:1024){light=sell,sigma=128}{light=csrv,lpr=8}{light=csrv,lpr=64}{heavy=1024,tile=512,light=csrv}",
+           "rows(16:256){light=xl,w=512,rb=1024}{light=nnzb,r=8}{heavy=256,tile=1024,hd=1,light=csrv}",
+           "bin2(6){light=sell}{light=wbm}", "cut(2:64){light=sell,sigma=0}",
+           "rows(64){cols(2){light=sell}{light=xl,w=256,rb=512}}{light=csrv,lpr=64,chunk=512}",
+           "cols(3){rows(32){light=xl,w=256,rb=256}{light=csrv,lpr=16}}",
+           "rows(100){light=xs,k=8,sigma=256}{light=xnb,k=8,r=4}",
+           "rows(64:512){light=xl,w=4096,rb=8192}{heavy=64,tile=2048,light=csrv}{heavy=512,tile=2048,light=csrv}"],
+    "C5": ["cut(8:100){light=sell,sigma=0}", "rows(8){light=xl,w=2048,rb=4096}{heavy=8,tile=2048,hd=1,light=csrv}",
+           "rows(4:8){light=sell}{light=coo}{cols(2){heavy=8,tile=1024,light=csrv}}"],
+}
+for _n in TREES:
+    SPECS[_n] = SPECS[_n] + TREES[_n]
 CASES = [(n, s) for n in SPECS for s in SPECS[n]]
 
 
