@@ -70,6 +70,15 @@ typedef struct {
      * force_plan or a negative search_budget_ms (nothing can be timed); spmv_run refuses such a
      * plan with SPMV_ERR_UNSUPPORTED.  dev_alloc / dev_free are ignored. */
     int host_only;
+    /* Learned cost model of the search (Section VI-A, level three).  cost_model_path: a corpus of
+     * earlier measurements (the lines a search appends to cost_log_path); when it holds enough of
+     * them a regression tree is fitted before the search starts, candidates are tried in the order
+     * of their predicted time, and those predicted more than three times slower than the best
+     * prediction are skipped (the first candidate of the census is always timed).  NULL: the
+     * environment variable SPMV_COST_MODEL, else no model.  cost_log_path: every timed candidate is
+     * appended to this file (census features, spec, microseconds).  NULL: SPMV_COST_LOG, else none. */
+    const char *cost_model_path;
+    const char *cost_log_path;
 } spmv_options_t;
 
 /*
@@ -193,6 +202,17 @@ spmv_status_t spmv_plan_array_copy(const spmv_plan_t *plan, int i, void *host_ds
  *   *b_csr  = nnz*(v+4) + 4*(nrows+1) + v*ncols + v*nrows, the same for plain CSR (v = 4 or 8).
  */
 spmv_status_t spmv_plan_bytes(const spmv_plan_t *plan, int64_t *b_plan, int64_t *b_csr);
+
+/*
+ * The search's cost model, for inspection (Section VI-A, level three): fit the regression tree to the
+ * corpus file `corpus_path` (lines appended by searches run with cost_log_path) and predict the run
+ * time, in microseconds, of the plan `spec` on the matrix whose census `plan` carries (a host-only plan
+ * will do).  *pred_us = -1 when the corpus holds too few usable lines (fewer than 8) to fit anything;
+ * *samples (may be NULL) receives the number of lines used.  A spec that does not parse ->
+ * SPMV_ERR_INVALID_ARG.  HOST pointers throughout; no device is touched.
+ */
+spmv_status_t spmv_cost_predict(const spmv_plan_t *plan, const char *corpus_path, const char *spec,
+                                double *pred_us, int64_t *samples);
 
 /* Number of kernel launches spmv_run makes for this plan, and the name of launch i. */
 spmv_status_t spmv_plan_launch_count(const spmv_plan_t *plan, int *n);

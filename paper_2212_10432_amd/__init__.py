@@ -20,7 +20,7 @@ SPMV_OK, SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_CSR, SPMV_ERR_UNSUPPORTED = 0, 1, 2,
 SPMV_ERR_ALLOC, SPMV_ERR_HIP, SPMV_ERR_INTERNAL = 4, 5, 6
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC", 5: "HIP", 6: "INTERNAL"}
 
-EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_multi", "spmv_plan_save", "spmv_plan_load", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
+EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_multi", "spmv_plan_save", "spmv_plan_load", "spmv_cost_predict", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
            "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
            "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error", "spmv_mm_read", "spmv_mm_free", "spmv_stream_ceiling"]
 
@@ -40,7 +40,12 @@ class spmv_options_t(ctypes.Structure):
     _fields_ = [("force_plan", ctypes.c_char_p), ("search_budget_ms", ctypes.c_double),
                 ("search_repeats", ctypes.c_int), ("host_threads", ctypes.c_int),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("user", ctypes.c_void_p),
-                ("verbosity", ctypes.c_int), ("host_only", ctypes.c_int)]
+                ("verbosity", ctypes.c_int), ("host_only", ctypes.c_int),
+                ("cost_model_path", ctypes.c_char_p), ("cost_log_path", ctypes.c_char_p)]
+
+
+# corpus of timed candidates shipped with the package: the search's cost model is trained from it
+COST_CORPUS = os.path.join(os.path.dirname(os.path.abspath(__file__)), "cost_corpus.tsv")
 
 
 _lib = None
@@ -76,6 +81,8 @@ def load():
     lib.spmv_plan_save.argtypes = [vp, ctypes.c_char_p]
     lib.spmv_plan_load.restype = ci
     lib.spmv_plan_load.argtypes = [P(vp), ctypes.c_char_p, P(spmv_options_t)]
+    lib.spmv_cost_predict.restype = ci
+    lib.spmv_cost_predict.argtypes = [vp, ctypes.c_char_p, ctypes.c_char_p, P(ctypes.c_double), P(i64)]
     lib.spmv_run_timed.restype = ci
     lib.spmv_run_timed.argtypes = [vp, vp, vp, vp, P(ctypes.c_float)]
     lib.spmv_plan_time.restype = ci
@@ -130,7 +137,7 @@ def _dtype_code(dt) -> int:
 
 def spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, *, force_plan=None,
                      search_budget_ms=0.0, search_repeats=0, host_threads=0, verbosity=0,
-                     host_only=False, nnz=None, allocator=None) -> int:
+                     host_only=False, nnz=None, allocator=None, cost_model="default", cost_log=None) -> int:
     """Returns an opaque plan handle (int).  row_ptr / col_idx / values are host NumPy arrays.
     allocator = (alloc(nbytes) -> device address or 0, free(address)): Python callables the library
     uses for every device array of the plan (kept alive until spmv_plan_destroy)."""
@@ -153,6 +160,10 @@ def spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, *, force_plan=None,
     opts.host_threads = int(host_threads)
     opts.verbosity = int(verbosity)
     opts.host_only = int(bool(host_only))
+    if cost_model == "default":
+        cost_model = COST_CORPUS if os.path.exists(COST_CORPUS) else None
+    opts.cost_model_path = os.fsencode(cost_model) if cost_model else None
+    opts.cost_log_path = os.fsencode(cost_log) if cost_log else None
     keep = None
     if allocator is not None:
         alloc_py, free_py = allocator
@@ -182,6 +193,13 @@ def spmv_run_noalloc(plan: int, x_dev: int, y_dev: int, stream: int = 0) -> None
 def spmv_run_multi(plan: int, x_dev: int, ldx: int, y_dev: int, ldy: int, k: int, stream: int = 0) -> None:
     """k right-hand sides: vector v of X at x_dev + v*ldx elements, of Y at y_dev + v*ldy elements."""
     _check(load().spmv_run_multi(plan, x_dev, ldx, y_dev, ldy, k, stream))
+
+
+def spmv_cost_predict(plan: int, corpus_path: str, spec: str):
+    """(predicted microseconds or -1, corpus lines used) for plan `spec` on the matrix of `plan`'s census."""
+    us, n = ctypes.c_double(), ctypes.c_int64()
+    _check(load().spmv_cost_predict(plan, os.fsencode(corpus_path), spec.encode(), ctypes.byref(us), ctypes.byref(n)))
+    return us.value, n.value
 
 
 def spmv_plan_save(plan: int, path: str) -> None:

@@ -8,7 +8,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libspmv_mi355.so")
-SOURCES = ["kernels.hip", "util.cc", "census.cc", "builder.cc", "search.cc", "mmio.cc", "serialize.cc", "api.cc"]
+SOURCES = ["kernels.hip", "util.cc", "census.cc", "builder.cc", "search.cc", "cost.cc", "mmio.cc", "serialize.cc", "api.cc"]
 HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(_HERE, "..", "include", "spmv.h")]
 
 FLAGS = [

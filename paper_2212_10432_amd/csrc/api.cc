@@ -94,7 +94,7 @@ std::string describe_json(const Plan &plan) {
     for (size_t i = 0; i < plan.log.size(); ++i) {
         const CandidateLog &l = plan.log[i];
         o << (i ? ", " : "") << "{\"spec\": \"" << json_escape(l.spec) << "\", \"build_ms\": " << l.build_ms
-          << ", \"run_us\": " << l.run_us << ", \"note\": \"" << json_escape(l.note) << "\"}";
+          << ", \"run_us\": " << l.run_us << ", \"pred_us\": " << l.pred_us << ", \"note\": \"" << json_escape(l.note) << "\"}";
     }
     o << "]}";
     return o.str();
@@ -349,6 +349,20 @@ spmv_status_t spmv_run_multi(const spmv_plan_t *plan, const void *x_dev, int64_t
             for (size_t q = i; q < j; ++q) one(p.parts[q], u);
         i = j;
     }
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_cost_predict(const spmv_plan_t *plan, const char *corpus_path, const char *spec, double *pred_us,
+                                int64_t *samples) {
+    API_BEGIN
+    if (!plan || !plan->impl || !corpus_path || !spec || !pred_us) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    const PlanSpec ps = parse_spec(spec);
+    CostModel model;
+    const int used = model.load(corpus_path);
+    model.train();
+    if (samples) *samples = used;
+    *pred_us = model.predict_us(cost_census(plan->impl->census, plan->impl->dtype), ps);
     return SPMV_OK;
     API_END
 }

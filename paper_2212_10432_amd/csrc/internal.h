@@ -175,6 +175,7 @@ struct Allocator {
 struct CandidateLog {
     std::string spec;
     double build_ms = 0, run_us = -1;
+    double pred_us = -1;      // the cost model's prediction (-1: no model)
     std::string note;
 };
 
@@ -223,6 +224,35 @@ std::vector<PlanSpec> enumerate_candidates(const Census &cen, spmv_dtype_t dtype
 std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spmv_options_t &opts,
                                   const Allocator &mem, int threads);
 double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream);
+
+// ---- learned cost model of the search (cost.cc) -----------------------------------------------
+struct CostCensus {   // what a corpus line keeps of a census
+    spmv_dtype_t dtype = SPMV_F64;
+    int64_t nrows = 0, ncols = 0, nnz = 0, max_len = 0, nnz_over_64 = 0, nnz_over_1024 = 0, rows_over_1024 = 0, diag_nnz = 0;
+    double mean_len = 0, var_len = 0, block_fill_3 = 0;
+};
+CostCensus cost_census(const Census &c, spmv_dtype_t dtype);
+std::vector<double> cost_features(const CostCensus &c, const PlanSpec &spec);
+std::string cost_line(const CostCensus &c, const std::string &spec, double us);
+void cost_append(const std::string &path, const std::vector<std::string> &lines);
+class CostModel {
+public:
+    int load(const std::string &path);                              // corpus file -> samples; returns lines used
+    void add(const CostCensus &c, const PlanSpec &spec, double us);
+    void train();
+    bool ready() const { return !nodes_.empty(); }
+    size_t samples() const { return y_.size(); }
+    double predict_us(const CostCensus &c, const PlanSpec &spec) const;   // -1 without a trained tree
+private:
+    struct Node {
+        int feature = -1, left = -1, right = -1;
+        double threshold = 0, value = 0;
+    };
+    int grow(std::vector<int> &idx, int b, int e, int depth);
+    std::vector<std::vector<double>> x_;
+    std::vector<double> y_;
+    std::vector<Node> nodes_;
+};
 
 std::string describe_json(const Plan &plan);
 

@@ -185,6 +185,47 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
             p.wg = 1;
             push(p);
         }
+        if (striping && th0) {
+            // plan trees: a design per row-length class instead of one design for all light rows
+            auto leaf_heavy = [&](int64_t th, int tl) {   // a class whose rows are all heavy
+                PlanSpec p;
+                p.heavy = th;
+                p.tile = tl;
+                p.light = L_CSRV;
+                p.lpr = 1;
+                return p;
+            };
+            PlanSpec xl = xl_plan(0, tile / 2, 16384);
+            {   // three classes: short rows and middle rows through their own two-pass parts, heavy tail in stripes
+                PlanSpec t;
+                t.node = N_ROWS;
+                t.cuts = {64, th0};
+                PlanSpec mid = xl;
+                mid.rb = 4096;
+                t.kids = {xl, mid, leaf_heavy(th0, tile / 2)};
+                push(t);
+            }
+            if (th0 >= 512) {   // two heavy bands: the rows between th0/2 and th0 get a band (and tile) of their own
+                PlanSpec t;
+                t.node = N_ROWS;
+                t.cuts = {th0 / 2, th0};
+                t.kids = {xl, leaf_heavy(th0 / 2, tile / 4), leaf_heavy(th0, tile / 2)};
+                push(t);
+            }
+        }
+        if (!striping) {   // power-of-two BIN: one SELL part per length class needs no sort and pads less than 2x
+            PlanSpec t;
+            t.node = N_BIN2;
+            t.cuts = {7};
+            PlanSpec a, b;
+            a.light = L_SELL;
+            a.remap = 1;
+            b.light = L_CSRV;
+            b.lpr = 64;
+            b.chunk = c.max_len > 16384 ? 8192 : 0;
+            t.kids = {a, b};
+            push(t);
+        }
         if (th0 && tail_ok(4 * th0)) push(bin_plan(4 * th0));
         if (th0) push(bin_plan(0));
         if (c.max_len <= 1024) {
@@ -206,7 +247,7 @@ std::vector<PlanSpec> enumerate_candidates(const Census &c, spmv_dtype_t dtype) 
 
 // Level-two candidates: the given plan with one numeric parameter halved or doubled.  Illegal
 // combinations are left to parse-time checks here and to the builder (which rejects them).
-static std::vector<PlanSpec> neighbours(const PlanSpec &b, spmv_dtype_t dtype) {
+static std::vector<PlanSpec> leaf_neighbours(const PlanSpec &b, spmv_dtype_t dtype) {
     std::vector<PlanSpec> out;
     auto add = [&](PlanSpec p) { out.push_back(p); };
     const int vsize = dtype == SPMV_F64 ? 8 : 4;
@@ -325,6 +366,43 @@ static std::vector<PlanSpec> neighbours(const PlanSpec &b, spmv_dtype_t dtype) {
     return out;
 }
 
+// Neighbours of a plan tree: every leaf's neighbours in place, and the row-length cuts of a ROW_DIV
+// node halved and doubled (Section VI-B: a cut position array is searched through a few integers).
+static void tree_neighbours(const PlanSpec &root, PlanSpec &cur, PlanSpec *at, spmv_dtype_t dtype, std::vector<PlanSpec> &out) {
+    if (at->node == N_LEAF) {
+        const PlanSpec keep = *at;
+        for (const PlanSpec &n : leaf_neighbours(keep, dtype)) {
+            *at = n;
+            out.push_back(cur);
+        }
+        *at = keep;
+        return;
+    }
+    if (at->node == N_ROWS) {
+        const std::vector<int64_t> keep = at->cuts;
+        for (size_t i = 0; i < keep.size(); ++i)
+            for (int up = 0; up < 2; ++up) {
+                std::vector<int64_t> c = keep;
+                c[i] = up ? keep[i] * 2 : keep[i] / 2;
+                bool ok = c[i] >= 1;
+                for (size_t j = 1; j < c.size() && ok; ++j) ok = c[j] > c[j - 1];
+                if (!ok) continue;
+                at->cuts = c;
+                out.push_back(cur);
+            }
+        at->cuts = keep;
+    }
+    for (PlanSpec &k : at->kids) tree_neighbours(root, cur, &k, dtype, out);
+}
+
+static std::vector<PlanSpec> neighbours(const PlanSpec &b, spmv_dtype_t dtype) {
+    if (b.node == N_LEAF) return leaf_neighbours(b, dtype);
+    std::vector<PlanSpec> out;
+    PlanSpec cur = b;
+    tree_neighbours(b, cur, &cur, dtype, out);
+    return out;
+}
+
 double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t e0, e1;
@@ -367,7 +445,7 @@ double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *st
 
 std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spmv_options_t &opts,
                                   const Allocator &mem, int threads) {
-    const std::vector<PlanSpec> cands = enumerate_candidates(cen, A.dtype);
+    std::vector<PlanSpec> cands = enumerate_candidates(cen, A.dtype);
     const double budget = opts.search_budget_ms == 0 ? 8000.0 : opts.search_budget_ms;
     const int repeats = opts.search_repeats > 0 ? opts.search_repeats : 5;
     std::vector<CandidateLog> log;
@@ -390,6 +468,21 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
         }
         fail(SPMV_ERR_INTERNAL, "no candidate plan could be built");
     }
+    // the learned cost model (Section VI-A, level three): trained from the corpus, if one is given
+    auto path_of = [](const char *opt, const char *env) -> std::string {
+        if (opt && opt[0]) return opt;
+        const char *e = std::getenv(env);
+        return e ? e : "";
+    };
+    const std::string model_path = path_of(opts.cost_model_path, "SPMV_COST_MODEL");
+    const std::string log_path = path_of(opts.cost_log_path, "SPMV_COST_LOG");
+    const CostCensus cc = cost_census(cen, A.dtype);
+    CostModel model;
+    if (!model_path.empty()) {
+        model.load(model_path);
+        model.train();
+    }
+    std::vector<std::string> corpus_lines;
     // device scratch for timing: x = 0 (finite), y
     const size_t v = A.vsize();
     void *x = mem.alloc(std::max<size_t>((size_t)A.ncols * v, 16), mem.user);
@@ -417,6 +510,7 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
         l.spec = print_spec(spec);
         for (const CandidateLog &seen : log)
             if (seen.spec == l.spec) return false;   // tried already
+        l.pred_us = model.predict_us(cc, spec);
         if (best && now_ms() - start > budget) {
             l.note = "skipped: search budget used up";
             log.push_back(l);
@@ -434,8 +528,10 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
         }
         l.build_ms = now_ms() - t0;
         l.run_us = time_plan(*plan, x, y, repeats, st);
+        corpus_lines.push_back(cost_line(cc, l.spec, l.run_us));
         if (opts.verbosity > 0)
-            std::fprintf(stderr, "[spmv search] %-6s %-70s build %8.1f ms  run %10.2f us\n", tag, l.spec.c_str(), l.build_ms, l.run_us);
+            std::fprintf(stderr, "[spmv search] %-6s %-70s build %8.1f ms  run %10.2f us  predicted %10.2f us\n", tag, l.spec.c_str(),
+                         l.build_ms, l.run_us, l.pred_us);
         bool better = false;
         if (!best || l.run_us < best_us) {
             best = std::move(plan);
@@ -445,16 +541,46 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
         log.push_back(l);
         return better;
     };
+    // Order by predicted time and drop what the model puts far behind.  The census' own first choice is
+    // always timed, and so is a candidate the model knows nothing about (prediction -1).
+    constexpr double kPruneFactor = 3.0;
+    auto ordered = [&](std::vector<PlanSpec> list, bool keep_first) {
+        if (!model.ready() || list.empty()) return list;
+        std::vector<std::pair<double, size_t>> key;
+        double lowest = -1;
+        for (size_t i = 0; i < list.size(); ++i) {
+            const double p = model.predict_us(cc, list[i]);
+            key.push_back({p, i});
+            if (p > 0 && (lowest < 0 || p < lowest)) lowest = p;
+        }
+        std::stable_sort(key.begin(), key.end(), [](const std::pair<double, size_t> &a, const std::pair<double, size_t> &b) { return a.first < b.first; });
+        std::vector<PlanSpec> out;
+        for (auto &k : key) {
+            const bool first = keep_first && k.second == 0;
+            if (!first && lowest > 0 && k.first > kPruneFactor * lowest) {
+                CandidateLog l;
+                l.spec = print_spec(list[k.second]);
+                l.pred_us = k.first;
+                l.note = "skipped: predicted far slower than the best prediction";
+                bool seen = false;
+                for (const CandidateLog &o : log) seen = seen || o.spec == l.spec;
+                if (!seen) log.push_back(l);
+                continue;
+            }
+            out.push_back(list[k.second]);
+        }
+        return out;
+    };
     try {
         // level one: the pruned list of designs, each with its default parameters
-        for (const PlanSpec &c : cands) evaluate(c, "design");
+        for (const PlanSpec &c : ordered(cands, true)) evaluate(c, "design");
         // level two (Section VI-A: parameters of the kept design on a finer grid): halve and double
         // every numeric parameter of the best plan, move to the best neighbour, repeat while that
         // gains more than one percent and the budget lasts
         for (int round = 0; best && round < 3 && now_ms() - start <= budget; ++round) {
             const PlanSpec base = best->spec;
             const double before = best_us;
-            for (const PlanSpec &n : neighbours(base, A.dtype)) evaluate(n, "tune");
+            for (const PlanSpec &n : ordered(neighbours(base, A.dtype), false)) evaluate(n, "tune");
             if (best_us > 0.99 * before) break;
         }
     } catch (...) {
@@ -462,6 +588,7 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
         throw;
     }
     cleanup();
+    cost_append(log_path, corpus_lines);
     if (!best) fail(SPMV_ERR_INTERNAL, "no candidate plan could be built");
     for (CandidateLog &l : log)
         if (l.spec == print_spec(best->spec) && l.run_us >= 0) l.note = "kept";

@@ -164,6 +164,7 @@ void save_plan(const Plan &plan, const char *path) {
         w.str(l.spec);
         w.f64(l.build_ms);
         w.f64(l.run_us);
+        w.f64(l.pred_us);
         w.str(l.note);
     }
     FILE *f = std::fopen(path, "wb");
@@ -282,6 +283,7 @@ std::unique_ptr<Plan> load_plan(const char *path, const Allocator &mem) {
         l.spec = r.str();
         l.build_ms = r.f64();
         l.run_us = r.f64();
+        l.pred_us = r.f64();
         l.note = r.str();
         plan->log.push_back(l);
     }

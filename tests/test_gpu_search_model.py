@@ -1,0 +1,49 @@
+"""The search with its learned cost model on the GPU: a first search writes its timed candidates to
+a corpus, a second search trained on that corpus predicts them, tries them in the order of the
+predictions, may skip the ones predicted far behind, and still keeps a plan that matches the oracle."""
+import numpy as np
+import pytest
+
+import inputs
+import oracle
+import paper_2212_10432_amd as lib
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["C3", "C5", "C4"])
+def test_second_search_uses_the_corpus_of_the_first(tmp_path, name):
+    print(f"search with model {name}", flush=True)
+    corpus = str(tmp_path / "corpus.tsv")
+    m = inputs.SMALL[name](integer=True)
+    x = inputs.vector(m.ncols, integer=True)
+    P1 = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, search_budget_ms=4000, cost_model=None, cost_log=corpus)
+    d1 = P1.describe()
+    P1.destroy()
+    timed1 = [c for c in d1["search"] if c["run_us"] >= 0]
+    assert all(c["pred_us"] == -1 for c in d1["search"])                 # no model yet
+    lines = [l for l in open(corpus).read().splitlines() if l]
+    assert len(lines) == len(timed1) and all(l.startswith("v1\t") and len(l.split("\t")) == 15 for l in lines)
+    P2 = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, search_budget_ms=4000, cost_model=corpus)
+    d2 = P2.describe()
+    level1 = [c for c in d2["search"] if c["run_us"] >= 0 or c["note"].startswith("skipped: predicted")]
+    if len(lines) < 8:                      # too few measurements to fit a tree: the search runs without one
+        assert all(c["pred_us"] == -1 for c in d2["search"])
+        level1 = []
+    assert all(c["pred_us"] > 0 for c in level1)
+    # predictions come from measurements of this very matrix: within a factor two of the new timing
+    close = [c for c in level1 if c["run_us"] >= 0 and 0.5 < c["pred_us"] / c["run_us"] < 2.0]
+    assert len(close) >= 0.6 * len([c for c in level1 if c["run_us"] >= 0])
+    for c in d2["search"]:
+        if c["note"].startswith("skipped: predicted"):
+            assert c["pred_us"] > 3.0 * min(k["pred_us"] for k in level1)
+    kept = [c for c in d2["search"] if c["note"] == "kept"]
+    assert len(kept) == 1 and all(kept[0]["run_us"] <= c["run_us"] for c in d2["search"] if c["run_us"] >= 0)
+    dev = torch.device("cuda:0")
+    xd = torch.from_numpy(x).to(dev)
+    yd = torch.full((m.nrows,), float("nan"), dtype=torch.float64, device=dev)
+    P2.run(xd, yd)
+    torch.cuda.synchronize()
+    assert np.array_equal(yd.cpu().numpy(), oracle.spmv(m.row_ptr, m.col_idx, m.values, x, threads=8))
+    P2.destroy()

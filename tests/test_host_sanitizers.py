@@ -10,7 +10,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2212_10432_amd", "csrc")
-HOST_SOURCES = ["util.cc", "census.cc", "builder.cc", "search.cc", "mmio.cc", "serialize.cc", "api.cc"]
+HOST_SOURCES = ["util.cc", "census.cc", "builder.cc", "search.cc", "cost.cc", "mmio.cc", "serialize.cc", "api.cc"]
 
 
 def test_host_side_is_clean_under_asan_and_ubsan(tmp_path):
