@@ -214,6 +214,28 @@ spmv_status_t spmv_plan_bytes(const spmv_plan_t *plan, int64_t *b_plan, int64_t 
 spmv_status_t spmv_cost_predict(const spmv_plan_t *plan, const char *corpus_path, const char *spec,
                                 double *pred_us, int64_t *samples);
 
+/*
+ * Model-driven format compression, for inspection (Section V-D): fit the linear, step and
+ * periodic-linear models (each with a few "if" patches) to `count` 4- or 8-byte integers at `data`
+ * (HOST) and write the accepted model as text, e.g. "linear(base=0,step=640)", or "" when none
+ * reproduces every element, to buf (at most cap bytes including the NUL).  The same routine is applied
+ * to every metadata array of a plan ("arrays"[i]."model" in the description); a plan built with jit=1
+ * compiles the fitted expressions into its kernels in place of the array loads.
+ */
+spmv_status_t spmv_fit_array(const void *data, int elem_bytes, int64_t count, char *buf, size_t cap);
+
+/*
+ * Run-time kernel generation, compile-only check (Section V-C, "Kernel Builder"): for every launch of
+ * the plan that has a specialised kernel, generate its source (the library's device code preceded by
+ * the launch's constants and fitted index expressions) and compile it with hipRTC for the current
+ * device, or for gfx950 when there is none.  Nothing is loaded or launched, so a host-only plan on a
+ * machine without a GPU will do.  *compiled receives the number of launches compiled; failures are
+ * listed in log (may be NULL; at most cap bytes including the NUL).  A plan built from a spec with
+ * jit=1 on a device compiles, loads and uses these kernels by itself; its description then reports
+ * "jit": true per launch, and "jit_note" says why a launch kept its ahead-of-time kernel.
+ */
+spmv_status_t spmv_plan_jit_check(const spmv_plan_t *plan, int *compiled, char *log, size_t cap);
+
 /* Number of kernel launches spmv_run makes for this plan, and the name of launch i. */
 spmv_status_t spmv_plan_launch_count(const spmv_plan_t *plan, int *n);
 spmv_status_t spmv_plan_launch_name(const spmv_plan_t *plan, int i, const char **name);

@@ -20,7 +20,7 @@ SPMV_OK, SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_CSR, SPMV_ERR_UNSUPPORTED = 0, 1, 2,
 SPMV_ERR_ALLOC, SPMV_ERR_HIP, SPMV_ERR_INTERNAL = 4, 5, 6
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC", 5: "HIP", 6: "INTERNAL"}
 
-EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_multi", "spmv_plan_save", "spmv_plan_load", "spmv_cost_predict", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
+EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_multi", "spmv_plan_save", "spmv_plan_load", "spmv_cost_predict", "spmv_fit_array", "spmv_plan_jit_check", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
            "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
            "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error", "spmv_mm_read", "spmv_mm_free", "spmv_stream_ceiling"]
 
@@ -83,6 +83,10 @@ def load():
     lib.spmv_plan_load.argtypes = [P(vp), ctypes.c_char_p, P(spmv_options_t)]
     lib.spmv_cost_predict.restype = ci
     lib.spmv_cost_predict.argtypes = [vp, ctypes.c_char_p, ctypes.c_char_p, P(ctypes.c_double), P(i64)]
+    lib.spmv_fit_array.restype = ci
+    lib.spmv_fit_array.argtypes = [vp, ci, i64, ctypes.c_char_p, ctypes.c_size_t]
+    lib.spmv_plan_jit_check.restype = ci
+    lib.spmv_plan_jit_check.argtypes = [vp, P(ci), ctypes.c_char_p, ctypes.c_size_t]
     lib.spmv_run_timed.restype = ci
     lib.spmv_run_timed.argtypes = [vp, vp, vp, vp, P(ctypes.c_float)]
     lib.spmv_plan_time.restype = ci
@@ -200,6 +204,24 @@ def spmv_cost_predict(plan: int, corpus_path: str, spec: str):
     us, n = ctypes.c_double(), ctypes.c_int64()
     _check(load().spmv_cost_predict(plan, os.fsencode(corpus_path), spec.encode(), ctypes.byref(us), ctypes.byref(n)))
     return us.value, n.value
+
+
+def spmv_fit_array(a) -> str:
+    """The index model fitted to an int32 / int64 array ("" when none is exact)."""
+    a = np.ascontiguousarray(a)
+    if a.dtype not in (np.int32, np.int64):
+        raise SpmvError(SPMV_ERR_INVALID_ARG, "int32 or int64 arrays only")
+    buf = ctypes.create_string_buffer(1024)
+    _check(load().spmv_fit_array(a.ctypes.data, a.dtype.itemsize, a.size, buf, 1024))
+    return buf.value.decode()
+
+
+def spmv_plan_jit_check(plan: int):
+    """(number of launches whose specialised kernel compiled, log of failures)."""
+    n = ctypes.c_int()
+    buf = ctypes.create_string_buffer(1 << 16)
+    _check(load().spmv_plan_jit_check(plan, ctypes.byref(n), buf, 1 << 16))
+    return n.value, buf.value.decode()
 
 
 def spmv_plan_save(plan: int, path: str) -> None:

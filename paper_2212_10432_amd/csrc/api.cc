@@ -52,6 +52,11 @@ static void validate_csr(const HostCsr &A, int threads) {
 static std::string json_escape(const std::string &s) {
     std::string o;
     for (char ch : s) {
+        if (ch == '\n') {
+            o += "\\n";
+            continue;
+        }
+        if ((unsigned char)ch < 0x20) ch = ' ';
         if (ch == '"' || ch == '\\') o += '\\';
         o += ch;
     }
@@ -80,17 +85,18 @@ std::string describe_json(const Plan &plan) {
         o << (i ? ", " : "") << "{\"name\": \"" << p.name << "\", \"rows\": " << p.nrows
           << ", \"nnz\": " << p.nnz << ", \"stored\": " << p.stored << ", \"units\": " << p.units
           << ", \"bytes\": " << p.bytes << ", \"lanes\": " << p.lanes << ", \"accumulate\": " << (p.accumulate ? "true" : "false")
-          << ", \"origin_rows\": " << (p.has_rows ? "true" : "false") << "}";
+          << ", \"origin_rows\": " << (p.has_rows ? "true" : "false") << ", \"jit\": " << (p.jit_fn ? "true" : "false")
+          << ", \"jit_kernel\": \"" << json_escape(p.jit_kernel) << "\", \"jit_defines\": \"" << json_escape(p.jit_defines) << "\"}";
     }
     o << "], \"arrays\": [";
     for (size_t i = 0; i < plan.arrays.size(); ++i) {
         const DevArray &a = plan.arrays[i];
         o << (i ? ", " : "") << "{\"name\": \"" << a.name << "\", \"elem_bytes\": " << a.elem_bytes
-          << ", \"count\": " << a.count << "}";
+          << ", \"count\": " << a.count << ", \"model\": \"" << a.model.text() << "\"}";
     }
     int64_t scratch_bytes = 0;
     for (const DevArray &a : plan.scratch) scratch_bytes += a.count * a.elem_bytes;
-    o << "], \"scratch_bytes\": " << scratch_bytes << ", \"search\": [";
+    o << "], \"jit_note\": \"" << json_escape(plan.jit_note) << "\", \"scratch_bytes\": " << scratch_bytes << ", \"search\": [";
     for (size_t i = 0; i < plan.log.size(); ++i) {
         const CandidateLog &l = plan.log[i];
         o << (i ? ", " : "") << "{\"spec\": \"" << json_escape(l.spec) << "\", \"build_ms\": " << l.build_ms
@@ -363,6 +369,32 @@ spmv_status_t spmv_cost_predict(const spmv_plan_t *plan, const char *corpus_path
     model.train();
     if (samples) *samples = used;
     *pred_us = model.predict_us(cost_census(plan->impl->census, plan->impl->dtype), ps);
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_fit_array(const void *data, int elem_bytes, int64_t count, char *buf, size_t cap) {
+    API_BEGIN
+    if ((!data && count > 0) || !buf || cap == 0) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    if ((elem_bytes != 4 && elem_bytes != 8) || count < 0) fail(SPMV_ERR_INVALID_ARG, "spmv_fit_array: 4- or 8-byte integers, count >= 0");
+    const std::string t = fit_array(data, elem_bytes, count).text();
+    const size_t n = std::min(cap - 1, t.size());
+    std::memcpy(buf, t.data(), n);
+    buf[n] = 0;
+    return SPMV_OK;
+    API_END
+}
+
+spmv_status_t spmv_plan_jit_check(const spmv_plan_t *plan, int *compiled, char *log, size_t cap) {
+    API_BEGIN
+    if (!plan || !plan->impl || !compiled) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    std::string text;
+    *compiled = jit_check_plan(*plan->impl, text);
+    if (log && cap > 0) {
+        const size_t n = std::min(cap - 1, text.size());
+        std::memcpy(log, text.data(), n);
+        log[n] = 0;
+    }
     return SPMV_OK;
     API_END
 }

@@ -25,6 +25,7 @@
 namespace spmv {
 
 Plan::~Plan() {
+    jit_release_plan(*this);
     for (DevArray &a : arrays)
         if (a.ptr) mem.free(a.ptr, mem.user);
     for (DevArray &a : scratch)
@@ -69,6 +70,7 @@ const void *upload(Plan &plan, const std::string &name, int elem_bytes, int64_t 
     a.elem_bytes = elem_bytes;
     a.count = count;
     a.read_per_run = read_per_run;
+    if (count >= 2 && is_metadata_array(a.name)) a.model = fit_array(host, elem_bytes, count);
     plan.arrays.push_back(a);   // owned from here on, freed by ~Plan
     if (count > 0 && plan.mem.host_only) {
         std::memcpy(d, host, (size_t)count * (size_t)elem_bytes);
@@ -1686,6 +1688,7 @@ std::unique_ptr<Plan> build_typed(const HostCsr &A0, const Census &cen, const Pl
     std::iota(all.begin(), all.end(), 0);
     build_node<T>(*plan, *cur, cen, spec, all, true, false, nullptr, threads);
     plan->prefix.clear();
+    if (plan_wants_jit(spec)) jit_compile_plan(*plan);
     return plan;
 }
 

@@ -14,22 +14,10 @@
 #include <vector>
 
 #include "../../include/spmv.h"
+#include "constants.h"
 
 namespace spmv {
 
-// Lanes of a wavefront on CDNA4.  The paper's "warp" (32 lanes, Section IV-A) maps to this.
-constexpr int kWave = 64;
-// Blocked SELL with an LDS x window: slices per workgroup, and the LDS budget of a window.
-constexpr int kXwinGroup = 32;
-constexpr int64_t kXwinMaxBytes = 160 * 1024;
-// Rows per workgroup of the striped parts' reduce launch (their sums live in LDS).
-constexpr int kReduceBlockRows = 1024;
-// Wavefront-bitmap part: steps of 64 entries per wavefront (a tile is 64 * kWbmTileSteps entries).
-constexpr int kWbmTileSteps = 8;
-// Two-pass part with x windows in LDS: entries per group (the unit of padding and of the reduce
-// launch's group list), and the LDS budget of an x window or of a block's accumulators.
-constexpr int kXlGroup = 16;
-constexpr int64_t kXlMaxLds = 128 * 1024;
 // Size of the library's static device scratch array (spmv_run_noalloc).
 constexpr size_t kStaticScratchBytes = SPMV_STATIC_SCRATCH_BYTES;
 
@@ -120,10 +108,24 @@ struct PlanSpec {
     int xwin = 0;            // bsell: stage the x window of 32 slices in LDS when it fits
     int w = 0;               // xl: columns per LDS x window (0 = 64 KiB worth)
     int rb = 16384;          // xl: rows per block of the reduce launch (their sums live in LDS)
+    int jit = 0;             // 1 = compile this plan's kernels at run time with its constants and fitted index models
 };
 PlanSpec parse_spec(const std::string &s);
 std::string print_spec(const PlanSpec &p);
 std::string operator_chain(const PlanSpec &p);   // the design in the paper's operator names
+
+// ---- model-driven compression of index arrays (fit.cc; Section V-D) -----------------------------
+// value(i) = base + step * (i / period) + inner * (i % period), except at the patched indices.
+struct ArrayModel {
+    int kind = 0;   // 0 none, 1 linear (period 1), 2 step (inner 0), 3 periodic-linear
+    int64_t base = 0, step = 0, period = 1, inner = 0;
+    std::vector<std::pair<int64_t, int64_t>> patches;   // (index, value): the "if" branches for outliers
+    int64_t at(int64_t i) const;
+    std::string text() const;                          // for the plan description
+    std::string expr(const std::string &var) const;    // C expression for the run-time kernel compile
+};
+ArrayModel fit_array(const void *host_data, int elem_bytes, int64_t n);   // exact over every index, or kind 0
+bool is_metadata_array(const std::string &name);
 
 // ---- device layout -------------------------------------------------------------------------
 struct DevArray {
@@ -132,6 +134,7 @@ struct DevArray {
     int elem_bytes = 0;
     int64_t count = 0;
     bool read_per_run = true;    // counts towards the algorithmic bytes of one run
+    ArrayModel model;            // closed form of a metadata array, when one fits exactly
 };
 
 enum PartKind { K_ZERO = 0, K_DIA, K_SELL, K_CSRV, K_BSELL, K_STRIPE, K_REDUCE_WIDE, K_XS, K_REDUCE_ROWS, K_NNZB, K_XNB, K_ZERO_SCRATCH, K_REDUCE_LDS, K_COO, K_XL_MUL, K_XL_REDUCE, K_WBM, K_LAST = K_WBM };
@@ -163,6 +166,8 @@ struct Part {
     int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
     const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
     int64_t bytes = 0;           // algorithmic bytes of one launch: arrays read + x + scratch + y
+    void *jit_fn = nullptr;      // kernel compiled at run time for this launch (a hipFunction_t), else the ahead-of-time one
+    std::string jit_kernel, jit_defines;   // what was compiled: instantiation and specialisation constants
 };
 
 struct Allocator {
@@ -191,6 +196,8 @@ struct Plan {
     std::vector<CandidateLog> log;
     std::string describe_cache;
     std::string prefix;              // while building: path of the tree node whose arrays are being made
+    std::vector<void *> jit_modules; // hipModule_t of the kernels compiled at run time (unloaded with the plan)
+    std::string jit_note;            // why nothing was compiled, when a plan asked for it
     ~Plan();
     size_t vsize() const { return dtype == SPMV_F64 ? 8 : 4; }
     int64_t bytes_plan() const;
@@ -210,6 +217,15 @@ int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols,
 // the part has no fused multi-vector kernel (the caller runs the vectors one by one).
 int launch_part_multi(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
                       int64_t ldx, void *y, int64_t ldy, int k, void *stream);
+// Run-time kernel generation (jit.cc, kernels.hip).  jit_describe: instantiation name and #define lines
+// of the specialised kernel for one launch (false: this launch keeps its ahead-of-time kernel);
+// jit_compile_plan compiles and loads them; launch_jit launches one.
+bool jit_describe(const Plan &plan, const Part &p, std::string &kernel, std::string &defines);
+void jit_compile_plan(Plan &plan);
+bool plan_wants_jit(const PlanSpec &spec);
+int launch_jit(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x, void *y, void *stream, void *scratch);
+void jit_release_plan(Plan &plan);
+int jit_check_plan(const Plan &plan, std::string &log);
 // Once per device, when a plan is created there: raises the dynamic-LDS limit of the kernels that
 // need more than 64 KiB and looks up the device address of the library's static scratch array.
 int prepare_device();

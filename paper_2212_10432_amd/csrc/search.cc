@@ -251,6 +251,11 @@ static std::vector<PlanSpec> leaf_neighbours(const PlanSpec &b, spmv_dtype_t dty
     std::vector<PlanSpec> out;
     auto add = [&](PlanSpec p) { out.push_back(p); };
     const int vsize = dtype == SPMV_F64 ? 8 : 4;
+    {   // kernels compiled at run time with the plan's constants, against the ahead-of-time ones
+        PlanSpec p = b;
+        p.jit = !b.jit;
+        add(p);
+    }
     if (b.dia) {   // BMT_ROW_BLOCK of the diagonal part: rows per lane
         for (int r : {1, 2, 4})
             if (r != b.drows) {

@@ -235,6 +235,11 @@ std::unique_ptr<Plan> load_plan(const char *path, const Allocator &mem) {
         r.need(bytes);
         a.ptr = mem.alloc(std::max<size_t>(bytes, (size_t)a.elem_bytes), mem.user);
         if (!a.ptr) fail(SPMV_ERR_ALLOC, "plan load: device allocation of " + std::to_string(bytes) + " bytes failed (" + a.name + ")");
+        if (a.count >= 2 && is_metadata_array(a.name)) {
+            std::vector<int64_t> aligned((bytes + 7) / 8);   // the payload is not aligned for 4- or 8-byte reads
+            std::memcpy(aligned.data(), r.p, bytes);
+            a.model = fit_array(aligned.data(), a.elem_bytes, a.count);
+        }
         plan->arrays.push_back(a);   // owned from here on
         if (bytes) {
             if (mem.host_only) {
@@ -288,6 +293,7 @@ std::unique_ptr<Plan> load_plan(const char *path, const Allocator &mem) {
         plan->log.push_back(l);
     }
     if (r.p != r.end) fail(SPMV_ERR_INVALID_ARG, "plan load: trailing bytes after the plan");
+    if (plan_wants_jit(plan->spec)) jit_compile_plan(*plan);
     return plan;
 }
 

@@ -204,6 +204,7 @@ static PlanSpec parse_leaf(const std::string &s) {
         else if (k == "r") p.r = (int)num();
         else if (k == "w") p.w = (int)num();
         else if (k == "rb") p.rb = (int)num();
+        else if (k == "jit") p.jit = (int)num();
         else fail(SPMV_ERR_INVALID_ARG, "plan spec: unknown key " + k);
     }
     if (p.dia != 0 && p.dia != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: dia must be 0 or 1");
@@ -225,6 +226,7 @@ static PlanSpec parse_leaf(const std::string &s) {
     if (p.r != 4 && p.r != 8 && p.r != 16) fail(SPMV_ERR_INVALID_ARG, "plan spec: r must be 4, 8 or 16");
     if (p.w != 0 && (p.w < 64 || p.w > 32768 || p.w % 64)) fail(SPMV_ERR_INVALID_ARG, "plan spec: w must be 0 or a multiple of 64 in [64, 32768]");
     if (p.rb < 64 || p.rb > 16384 || p.rb % 64) fail(SPMV_ERR_INVALID_ARG, "plan spec: rb must be a multiple of 64 in [64, 16384]");
+    if (p.jit != 0 && p.jit != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: jit must be 0 or 1");
     if (p.hd != 0 && p.hd != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: hd must be 0 or 1");
     if (p.hd && !p.heavy) fail(SPMV_ERR_INVALID_ARG, "plan spec: hd needs heavy");
     if (p.xwin != 0 && p.xwin != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin must be 0 or 1");
@@ -260,6 +262,7 @@ std::string print_spec(const PlanSpec &p) {
     case L_XL: o << ",w=" << p.w << ",rb=" << p.rb << ",chunk=" << p.chunk; break;
     }
     o << ",remap=" << p.remap;
+    if (p.jit) o << ",jit=1";
     return o.str();
 }
 
