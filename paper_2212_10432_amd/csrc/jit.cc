@@ -12,6 +12,7 @@
 
 #include <map>
 #include <mutex>
+#include <sstream>
 
 #include "internal.h"
 #include "jit_source.inc"
@@ -23,6 +24,88 @@ bool plan_wants_jit(const PlanSpec &q) {
     for (const PlanSpec &k : q.kids)
         if (plan_wants_jit(k)) return true;
     return false;
+}
+
+// For one launch: the instantiation the ahead-of-time dispatch above would pick, spelled as a name
+// expression, and the #define lines that turn its run-time arguments into literals (and fitted offset
+// arrays into arithmetic).  Launch kinds without an entry here keep their ahead-of-time kernel.  The
+// instantiations named here are the ones the ahead-of-time dispatch in kernels.hip picks.
+bool jit_describe(const Plan &plan, const Part &p, std::string &kernel, std::string &defines) {
+    const char *T = plan.dtype == SPMV_F64 ? "double" : "float";
+    auto B = [](bool b) { return b ? "true" : "false"; };
+    std::ostringstream k, d;
+    auto def = [&](const char *name, int64_t v) { d << "#define SPMV_JIT_" << name << " " << v << "LL\n"; };
+    auto defi = [&](const char *name, int64_t v) { d << "#define SPMV_JIT_" << name << " " << v << "\n"; };
+    auto model = [&](const char *name, const void *ptr) {   // closed form of an offset array, if one was fitted
+        for (const DevArray &a : plan.arrays)
+            if (a.ptr == ptr && a.model.kind) d << "#define SPMV_JIT_" << name << "(i) " << a.model.expr("i") << "\n";
+    };
+    switch (p.kind) {
+    case K_DIA:
+        if (p.ndiag < 1 || p.ndiag > 8) return false;
+        if (p.lanes == 2 || p.lanes == 4) k << "spmv::dev::k_dia_rows<" << T << ", " << p.ndiag << ", " << p.lanes << ", " << B(p.accumulate) << ">";
+        else k << "spmv::dev::k_dia_fixed<" << T << ", " << p.ndiag << ", " << B(p.accumulate) << ">";
+        d << "#define SPMV_JIT_DIA_OFFS ";
+        for (int i = 0; i < 8; ++i) d << (i ? "," : "") << (i < p.ndiag ? p.dia_offsets[i] : 0);
+        d << "\n";
+        def("DIA_LD", p.ld);
+        def("DIA_NROWS", plan.nrows);
+        def("DIA_NCOLS", plan.ncols);
+        break;
+    case K_CSRV:
+        if (p.lanes > kWave) return false;
+        k << "spmv::dev::k_csrv<" << T << ", " << p.lanes << ", " << B(p.has_rows) << ", " << B(p.accumulate) << ">";
+        def("CSRV_NSEG", p.units);
+        defi("CSRV_ULEN", p.uniform_w);
+        defi("CSRV_REMAP", p.remap);
+        if (p.uniform_w < 0) model("SEG_PTR", p.p0);
+        break;
+    case K_SELL:
+        k << "spmv::dev::k_sell<" << T << ", " << B(p.has_rows) << ", " << B(p.accumulate) << ">";
+        def("SELL_NSLICES", p.units);
+        def("SELL_NROWS", p.nrows);
+        defi("SELL_REMAP", p.remap);
+        defi("SELL_UW", p.uniform_w);
+        if (p.uniform_w < 0) model("SLICE_PTR", p.p0);
+        break;
+    case K_BSELL:
+        if (p.lds_bytes > 0) k << "spmv::dev::k_bsell_xwin<" << T << ", " << p.block << ", " << B(p.has_rows) << ", " << B(p.uniform_w == 1) << ">";
+        else k << "spmv::dev::k_bsell<" << T << ", " << p.block << ", " << B(p.has_rows) << ">";
+        def("BSELL_NSLICES", p.units);
+        def("BSELL_NBROWS", p.nrows);
+        defi("BSELL_REMAP", p.remap);
+        model("SLICE_PTR", p.p0);
+        break;
+    case K_STRIPE:
+        k << (p.delta ? "spmv::dev::k_hsell_delta<" : "spmv::dev::k_hsell<") << T << ">";
+        defi("HS_NSL", p.nslices);
+        defi("HS_NH", p.nrows);
+        defi("HS_TILE", p.tile);
+        def("HS_NCOLS", plan.ncols);
+        defi("HS_NS", p.units);
+        defi("HS_SPW", p.per_group);
+        break;
+    case K_REDUCE_WIDE:
+        k << "spmv::dev::k_reduce_wide<" << T << ", " << B(p.accumulate) << ">";
+        defi("RW_NP", p.ngroups);
+        def("RW_N", p.nrows);
+        break;
+    case K_XL_MUL:
+        k << "spmv::dev::k_xl_mul<" << T << ">";
+        defi("XL_W", p.tile);
+        def("XL_NCOLS", plan.ncols);
+        break;
+    case K_XL_REDUCE:
+        k << "spmv::dev::k_xl_reduce<" << T << ", " << B(p.has_rows) << ", " << B(p.accumulate) << ">";
+        defi("XLR_RB", p.tile);
+        def("XLR_N", p.nrows);
+        model("GPTR", p.p0);
+        break;
+    default: return false;
+    }
+    kernel = k.str();
+    defines = d.str();
+    return true;
 }
 
 namespace {

@@ -161,7 +161,10 @@ int main(int argc, char **argv) {
         "heavy=100,tile=512,light=sell,sigma=64", "heavy=100,tile=512,hd=1,light=xl,w=128,rb=64", "heavy=100,tile=256,light=xnb,k=8,r=4",
         "dia=1,light=sell", "dia=1,dia_fill=0.9,light=csrv,lpr=2",
         "light=bsell,block=2,sigma=128", "light=bsell,block=3,sigma=0", "light=bsell,block=3,sigma=2048,xwin=1,remap=1",
-        "light=bsell,block=4,sigma=64,remap=1",
+        "light=bsell,block=4,sigma=64,remap=1", "light=wbm", "light=csrv,lpr=256,chunk=512", "light=bin,smax=4,sigma=128,chunk=512,wg=1",
+        "rows(4:32){light=sell,sigma=64}{light=csrv,lpr=8}{heavy=32,tile=256,light=csrv}", "bin2(5){light=sell}{light=wbm}",
+        "cut(4:16){light=sell,sigma=0}", "cols(3){rows(8){light=xl,w=128,rb=64}{light=nnzb,r=4}}", "light=sell,sigma=64,jit=1",
+        "heavy=100,tile=512,light=xl,w=128,rb=64,jit=1",
     };
     const Csr mats[] = {
         make(777, 1234, 40, false, 5, 0), make(1500, 900, 12, true, -1, 0), make(64, 64, 64, true, -1, 0),
@@ -191,7 +194,8 @@ int main(int argc, char **argv) {
         one(t, "dia=1,dia_fill=0.99,light=xl,w=64,rb=64", SPMV_F32, true);
     }
     // plan-spec strings that must be refused cleanly
-    const char *bad[] = {"light=", "light=nope", "tile=7", "heavy=-1", "hd=1", "light=bsell,dia=1", "k=9", "sigma", "rb=1", "=,=", ",,,"};
+    const char *bad[] = {"rows(4){light=sell", "rows(4:2){light=sell}", "cols(99){light=sell}", "rows(4){dia=1,light=sell}{light=sell}", "bin2(3){light=sell}",
+                         "light=", "light=nope", "tile=7", "heavy=-1", "hd=1", "light=bsell,dia=1", "k=9", "sigma", "rb=1", "=,=", ",,,"};
     for (const char *s : bad) one(mats[0], s, SPMV_F64, false);
     mm(dir, "%%MatrixMarket matrix coordinate real general\n3 3 3\n1 1 1.5\n3 2 -2\n2 3 4e1\n", true);
     mm(dir, "%%MatrixMarket matrix coordinate pattern symmetric\n3 3 2\n2 1\n3 3\n", true);
