@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--plan-json", default="", help="JSON file {config: plan spec}: skip the search for those matrices")
     ap.add_argument("--save-plans", default="", help="write the chosen plan specs to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-jit", action="store_true", help="skip the comparison of run-time specialised against ahead-of-time kernels")
+    ap.add_argument("--no-spmm", action="store_true", help="skip the multi-vector figure of the launch-bound matrices")
     ap.add_argument("--no-parity", action="store_true", help="skip the full-size check of every timed plan against the oracle")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
@@ -127,10 +129,10 @@ def main():
         items.append(dict(name=name, desc=desc, nnz=m.nnz, nrows=m.nrows, dtype=dt.name, plans=plans, xs=xs, ys=ys,
                           copies=copies, b_plan=b_plan, b_csr=b_csr, spec=d["spec"], operators=d["operators"],
                           launches=plan.launch_names(), launch_bytes=[p["bytes"] for p in d["parts"]],
-                          gen_s=t_gen, plan_s=t_plan, parity=parity,
-                          search=[(c["spec"], c["run_us"], c["note"]) for c in d["search"]]))
+                          gen_s=t_gen, plan_s=t_plan, parity=parity, matrix=(m, vals),
+                          search=[(c["spec"], c["run_us"], c["pred_us"], c["note"]) for c in d["search"]]))
         log(f"{name}: nnz={m.nnz} gen {t_gen:.1f}s plan {t_plan:.1f}s -> {d['spec']} (copies={copies})")
-        del vals, x
+        del x
     cache.clear()
 
     # All launches go to one side stream.  A step is captured once into a HIP graph (kernel nodes
@@ -207,12 +209,46 @@ def main():
                 e1.record(stream)
             e1.synchronize()
             it["ms_warm"] = e0.elapsed_time(e1) / (reps * nrep)
+        # run-time specialised kernels on / off for this plan, both timed the same way (the library's
+        # loop of back-to-back launches on the same copy: cache-warm for the small matrices)
+        if not args.no_jit:
+            spec = it["spec"]
+            if ",jit=1" in spec:
+                other = spec.replace(",jit=1", "")
+            elif "}" in spec:
+                other = spec.replace("}", ",jit=1}", 1)
+            else:
+                other = spec + ",jit=1"
+            m_, vals_ = it["matrix"]
+            alt = lib.Plan(m_.nrows, m_.ncols, m_.row_ptr, m_.col_idx, vals_, force_plan=other)
+            t_this = it["plans"][0].time(it["xs"][0], it["ys"][0], stream.cuda_stream, 25)
+            t_alt = alt.time(it["xs"][0], it["ys"][0], stream.cuda_stream, 25)
+            on, off = (t_this, t_alt) if ",jit=1" in spec else (t_alt, t_this)
+            it["jit"] = dict(jit_on_us=on, jit_off_us=off, timed_plan_uses_jit=",jit=1" in spec,
+                             launches_specialised=sum(1 for q in (alt if ",jit=1" not in spec else it["plans"][0]).describe()["parts"] if q["jit"]))
+            alt.destroy()
+        # several right-hand sides through one plan (the launch-bound matrices are where it pays)
+        if it["name"] in ("C1", "C2") and not args.no_spmm:
+            k = 8
+            tdt_ = it["xs"][0].dtype
+            X = torch.stack([it["xs"][0]] * k).contiguous()
+            Y = torch.empty((k, it["nrows"]), dtype=tdt_, device=dev)
+            with torch.cuda.stream(stream):
+                for _ in range(3):
+                    it["plans"][0].run_multi(X, Y, stream.cuda_stream)
+                e0.record(stream)
+                for _ in range(50):
+                    it["plans"][0].run_multi(X, Y, stream.cuda_stream)
+                e1.record(stream)
+            e1.synchronize()
+            it["spmm"] = dict(k=k, us_per_call=e0.elapsed_time(e1) / 50 * 1e3, us_per_vector=e0.elapsed_time(e1) / 50 / k * 1e3)
+            del X, Y
+        # per launch: each launch repeated back to back between two HIP events on the launch stream
+        # (rotated over the copies for the cache-sized matrices)
         per = np.zeros(len(it["launches"]))
-        nt = 10
-        for k in range(nt):
-            i = k % it["copies"]
-            per += np.array(it["plans"][i].run_timed(it["xs"][i], it["ys"][i], stream.cuda_stream))
-        it["launch_ms"] = (per / nt).tolist()
+        for i in range(it["copies"]):
+            per += np.array(it["plans"][i].time_launches(it["xs"][i], it["ys"][i], stream.cuda_stream, 10 if it["copies"] == 1 else 1))
+        it["launch_ms"] = (per / it["copies"] * 1e-3).tolist()
 
     per_config = []
     tot_ms = sum(it["ms"] for it in items)
@@ -235,6 +271,10 @@ def main():
                    plan_create_s=it["plan_s"], search=it["search"])
         if it["parity"] is not None:
             rec.update(it["parity"])
+        if "jit" in it:
+            rec["jit"] = it["jit"]
+        if "spmm" in it:
+            rec["spmm"] = it["spmm"]
         if "ms_warm" in it:
             rec["us_cache_warm"] = it["ms_warm"] * 1e3
         rec["us_graph_replay"] = it["ms_graph"] * 1e3

@@ -172,6 +172,17 @@ spmv_status_t spmv_run_timed(const spmv_plan_t *plan, const void *x_dev, void *y
 spmv_status_t spmv_plan_time(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
                              int repeats, double *median_us);
 
+/*
+ * Duration of each launch of the plan on its own, for roofline records: launch i is issued
+ * `repeats` + 1 times back to back on `stream` (the first is a warm-up) between two HIP events, after
+ * the launches before it ran, and launch_us[i] (spmv_plan_launch_count entries) receives the mean
+ * duration of one of the repeats in microseconds -- without the gaps that an event around every
+ * single launch would add.  Synchronises the stream.  Launches that accumulate into y run several
+ * times here: y_dev holds no meaningful result afterwards.  1 <= repeats <= 10000.
+ */
+spmv_status_t spmv_plan_time_launches(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
+                                      int repeats, float *launch_us);
+
 /* Free the plan's device arrays (through the allocator pair it was created with). NULL is OK. */
 spmv_status_t spmv_plan_destroy(spmv_plan_t *plan);
 

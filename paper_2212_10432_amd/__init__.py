@@ -20,7 +20,7 @@ SPMV_OK, SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_CSR, SPMV_ERR_UNSUPPORTED = 0, 1, 2,
 SPMV_ERR_ALLOC, SPMV_ERR_HIP, SPMV_ERR_INTERNAL = 4, 5, 6
 _STATUS = {0: "OK", 1: "INVALID_ARG", 2: "BAD_CSR", 3: "UNSUPPORTED", 4: "ALLOC", 5: "HIP", 6: "INTERNAL"}
 
-EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_multi", "spmv_plan_save", "spmv_plan_load", "spmv_cost_predict", "spmv_fit_array", "spmv_plan_jit_check", "spmv_run_timed", "spmv_plan_time", "spmv_plan_destroy", "spmv_plan_describe",
+EXPORTS = ["spmv_plan_create", "spmv_run", "spmv_run_noalloc", "spmv_run_multi", "spmv_plan_save", "spmv_plan_load", "spmv_cost_predict", "spmv_fit_array", "spmv_plan_jit_check", "spmv_run_timed", "spmv_plan_time", "spmv_plan_time_launches", "spmv_plan_destroy", "spmv_plan_describe",
            "spmv_plan_array_count", "spmv_plan_array_info", "spmv_plan_array_copy", "spmv_plan_bytes",
            "spmv_plan_launch_count", "spmv_plan_launch_name", "spmv_last_error", "spmv_mm_read", "spmv_mm_free", "spmv_stream_ceiling"]
 
@@ -89,6 +89,8 @@ def load():
     lib.spmv_plan_jit_check.argtypes = [vp, P(ci), ctypes.c_char_p, ctypes.c_size_t]
     lib.spmv_run_timed.restype = ci
     lib.spmv_run_timed.argtypes = [vp, vp, vp, vp, P(ctypes.c_float)]
+    lib.spmv_plan_time_launches.restype = ci
+    lib.spmv_plan_time_launches.argtypes = [vp, vp, vp, vp, ci, P(ctypes.c_float)]
     lib.spmv_plan_time.restype = ci
     lib.spmv_plan_time.argtypes = [vp, vp, vp, vp, ci, P(ctypes.c_double)]
     lib.spmv_plan_destroy.restype = ci
@@ -255,6 +257,16 @@ def spmv_run_timed(plan: int, x_dev: int, y_dev: int, stream: int = 0):
     return [ms[i] for i in range(n.value)]
 
 
+def spmv_plan_time_launches(plan: int, x_dev: int, y_dev: int, stream: int = 0, repeats: int = 10):
+    """Mean duration in microseconds of each launch, repeated back to back on its own (y is scratch afterwards)."""
+    lib = load()
+    n = ctypes.c_int()
+    _check(lib.spmv_plan_launch_count(plan, ctypes.byref(n)))
+    us = (ctypes.c_float * max(n.value, 1))()
+    _check(lib.spmv_plan_time_launches(plan, x_dev, y_dev, stream, repeats, us))
+    return [us[i] for i in range(n.value)]
+
+
 def spmv_plan_time(plan: int, x_dev: int, y_dev: int, stream: int = 0, repeats: int = 20) -> float:
     """Median time of one run in microseconds (batches of back-to-back launches, HIP events)."""
     us = ctypes.c_double()
@@ -415,6 +427,12 @@ class Plan:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
         return spmv_run_timed(self.handle, x.data_ptr(), y.data_ptr(), int(stream))
+
+    def time_launches(self, x, y, stream=None, repeats=10):
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        return spmv_plan_time_launches(self.handle, x.data_ptr(), y.data_ptr(), int(stream), repeats)
 
     def time(self, x, y, stream=None, repeats=20) -> float:
         if stream is None:

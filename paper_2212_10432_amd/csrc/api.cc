@@ -480,6 +480,48 @@ spmv_status_t spmv_run_timed(const spmv_plan_t *plan, const void *x_dev, void *y
     API_END
 }
 
+spmv_status_t spmv_plan_time_launches(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
+                                      int repeats, float *launch_us) {
+    API_BEGIN
+    if (!plan || !plan->impl || !launch_us) fail(SPMV_ERR_INVALID_ARG, "NULL argument");
+    const Plan &p = *plan->impl;
+    if (p.mem.host_only) fail(SPMV_ERR_UNSUPPORTED, "the plan was built host-only and cannot run");
+    if ((!x_dev && p.ncols > 0) || (!y_dev && p.nrows > 0)) fail(SPMV_ERR_INVALID_ARG, "x or y is NULL");
+    if (x_dev && x_dev == y_dev) fail(SPMV_ERR_INVALID_ARG, "x and y must not alias");
+    if (repeats < 1 || repeats > 10000) fail(SPMV_ERR_INVALID_ARG, "repeats out of range");
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        fail(SPMV_ERR_HIP, "hipEventCreate failed");
+    }
+    auto drop = [&]() {
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+    };
+    for (size_t i = 0; i < p.parts.size(); ++i) {
+        // launch i of one ordinary run has the inputs it expects: everything before it ran once
+        for (int r = 0; r < repeats + 1; ++r) {
+            if (r == 1) (void)hipEventRecord(e0, (hipStream_t)stream);   // the first launch warms up
+            const int err = launch_part(p.parts[i], p.dtype, p.nrows, p.ncols, x_dev, y_dev, stream);
+            if (err) {
+                drop();
+                fail(SPMV_ERR_HIP, std::string("launch of ") + p.parts[i].name + " failed: " + hip_error_text(err));
+            }
+        }
+        (void)hipEventRecord(e1, (hipStream_t)stream);
+        if (hipEventSynchronize(e1) != hipSuccess) {
+            drop();
+            fail(SPMV_ERR_HIP, "a kernel failed");
+        }
+        float ms = 0;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        launch_us[i] = ms * 1000.0f / (float)repeats;
+    }
+    drop();
+    return SPMV_OK;
+    API_END
+}
+
 spmv_status_t spmv_plan_time(const spmv_plan_t *plan, const void *x_dev, void *y_dev, void *stream,
                              int repeats, double *median_us) {
     API_BEGIN

@@ -110,8 +110,9 @@ Census take_census(const HostCsr &A, int threads) {
         }
     }
 
-    // aligned b x b blocks: fill estimated on a sample of block rows (needs sorted columns)
-    if (c.cols_sorted) {
+    // aligned b x b blocks: fill estimated on a sample of block rows (the sampled block columns are
+    // sorted here, so the order of the columns inside a row does not matter)
+    {
         for (int bsz = 2; bsz <= 4; ++bsz) {
             if (A.nrows % bsz || A.ncols % bsz || A.nrows < bsz) continue;
             const int64_t nb = A.nrows / bsz;

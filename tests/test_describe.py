@@ -45,3 +45,20 @@ def test_census_prunes_the_candidates():
     for name in ("C3", "C5"):                                                 # irregular: heavy split
         assert first[name]["census"]["irregular"] is True
         assert first[name]["spec"].startswith("heavy=")
+
+
+def test_block_census_does_not_need_sorted_columns():
+    """A block-structured matrix whose rows list their columns in any order still gets the blocked design."""
+    import numpy as np
+    m = inputs.SMALL["C4"]()
+    rng = np.random.default_rng(0)
+    ci, va = m.col_idx.copy(), m.values.copy()
+    for r in range(0, m.nrows, 7):
+        s, e = m.row_ptr[r], m.row_ptr[r + 1]
+        p = rng.permutation(e - s)
+        ci[s:e], va[s:e] = ci[s:e][p], va[s:e][p]
+    P = lib.Plan(m.nrows, m.ncols, m.row_ptr, ci, va, host_only=True, search_budget_ms=-1)
+    d = P.describe()
+    assert d["census"]["cols_sorted"] is False and abs(d["census"]["block_fill"]["3"] - 1.0) < 1e-12
+    assert "light=bsell,block=3" in d["spec"]
+    P.destroy()

@@ -92,7 +92,7 @@ def test_searched_plan_matches_oracle(name):
     timed = [c for c in d["search"] if c["run_us"] >= 0]
     kept = [c for c in timed if c["note"] == "kept"]
     assert len(kept) == 1 and kept[0]["spec"] == d["spec"]
-    assert all(kept[0]["run_us"] <= c["run_us"] for c in timed)
+    assert all(0.995 * kept[0]["run_us"] <= c["run_us"] for c in timed)      # near-ties keep the earlier candidate
 
 
 def test_device_arrays_equal_host_only_arrays():
