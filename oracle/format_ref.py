@@ -511,13 +511,16 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total, skip=()):
     """Two passes with x windows in LDS.  Windows of W columns (0: 64 KiB worth of values), blocks of
     RB part positions.  Entry (part position i, column c) is in run (s, b) = (c // W, i // RB); runs
     are stored window by window, block by block inside a window, by part position and row order
-    inside a run, each padded to a multiple of 16 entries with (value 0, local column 0, local row
-    0).  items: (window, first entry, end entry) pieces of a window's entries, m = ceil(len / chunk)
+    inside a run; a run is padded to a whole 16-byte vector (N = 2 doubles / 4 floats), a window to 16
+    entries, with (value 0, local column 0).
+    items: (window, first entry, end entry) pieces of a window's entries, m = ceil(len / chunk)
     pieces of ceil16(ceil(len / m)) entries; chunk 0 means 32768.
-    glist: for block b the 16-entry groups of runs (0, b), (1, b), ...; gptr: its offsets per block.
-    lrow is stored in glist order: lrow[16 p + t] is the local row of entry 16 glist[p] + t.
-    Rows listed in `skip` stay in the part but contribute no entries (heavy rows when nothing was
-    extracted before: the part's rows are then 0 .. nrows-1 and no row map is stored)."""
+    glist: for block b the groups of runs (0, b), (1, b), ...: a run cut into groups of up to 16
+    entries, a list entry being 8 * (first entry // N) + (entries in the group // N - 1); gptr: the
+    list's offsets per block.  lrow is stored in list order, 16 slots per group: lrow[16 p + t] is the
+    local row of entry N * (glist[p] >> 3) + t (0 in unused slots and for padding).
+    Rows listed in `skip` stay in the part but contribute no entries (rows of other parts kept so that
+    the part's rows are one contiguous range and no row map is stored)."""
     rows = np.asarray(rows, dtype=np.int32)
     n = rows.size
     if n == 0:
@@ -525,7 +528,7 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total, skip=()):
     ident = n == nrows_total and np.array_equal(rows, np.arange(nrows_total))
     if W == 0:
         W = 65536 // va.dtype.itemsize
-    G = 16
+    G, N = 16, 16 // va.dtype.itemsize
     S = max(1, -(-ncols // W))
     B = -(-n // RB)
     lens = (rp[rows + 1] - rp[rows]).astype(np.int64)
@@ -535,43 +538,47 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total, skip=()):
     c = ci[src].astype(np.int64)
     run = (c // W) * B + pos_of_entry // RB
     order = np.argsort(run, kind="stable")                                   # keeps (i, row order) inside a run
-    cnt = np.bincount(run, minlength=S * B).astype(np.int64)
-    padded = -(-cnt // G) * G
-    start = np.concatenate([[0], np.cumsum(padded)])
-    tot = int(start[-1])
+    cnt = np.bincount(run, minlength=S * B).astype(np.int64).reshape(S, B)
+    ceil_to = lambda v, q: -(-v // q) * q
+    padded = ceil_to(cnt, N)                                                 # a run holds whole 16-byte vectors
+    wstart = np.concatenate([[0], np.cumsum(ceil_to(padded.sum(axis=1), G))])   # a window starts on a multiple of 16
+    tot = int(wstart[-1])
+    rbeg = wstart[:-1, None] + np.cumsum(padded, axis=1) - padded            # (S, B): first entry of run (s, b)
     vals = np.zeros(tot, dtype=va.dtype)
     lcol = np.zeros(tot, dtype=np.uint16)
-    lrow = np.zeros(tot, dtype=np.uint16)
+    lrow_by_entry = np.zeros(tot, dtype=np.uint16)
     run_sorted = run[order]
-    first = np.concatenate([[0], np.cumsum(cnt)])[run_sorted]              # unpadded start of the entry's run
-    dst = start[run_sorted] + (np.arange(order.size) - first)
+    first = np.concatenate([[0], np.cumsum(cnt.reshape(-1))])[run_sorted]  # rank of the run's first entry among the real entries
+    dst = rbeg.reshape(-1)[run_sorted] + (np.arange(order.size) - first)
     vals[dst] = va[src[order]]
     lcol[dst] = (c[order] % W).astype(np.uint16)
-    lrow_by_entry = np.zeros(tot, dtype=np.uint16)
     lrow_by_entry[dst] = (pos_of_entry[order] % RB).astype(np.uint16)
-    ceil16 = lambda v: -(-v // G) * G
-    chunk = ceil16(chunk) if chunk > 0 else 32768
+    chunk = ceil_to(chunk, G) if chunk > 0 else 32768
     items = []
     for s_ in range(S):
-        b0, e0 = int(start[s_ * B]), int(start[(s_ + 1) * B])
+        b0, e0 = int(wstart[s_]), int(wstart[s_ + 1])
         if e0 == b0:
             continue
         m = -(-(e0 - b0) // chunk)
-        per = ceil16(-(-(e0 - b0) // m))
+        per = ceil_to(-(-(e0 - b0) // m), G)
         for cpos in range(b0, e0, per):
             items += [s_, cpos, min(e0, cpos + per)]
     gptr = np.zeros(B + 1, dtype=np.int32)
-    glist = []
+    glist, lrow = [], []
     for b in range(B):
-        ngroups = 0
+        ng = 0
         for s_ in range(S):
-            j = s_ * B + b
-            glist.append(np.arange(start[j] // G, start[j + 1] // G, dtype=np.int32))
-            ngroups += glist[-1].size
-        gptr[b + 1] = gptr[b] + ngroups
-    glist = np.concatenate(glist).astype(np.int32) if glist else np.zeros(0, np.int32)
-    # local rows in the order the reduce launch reads them: lrow[16 p + t] belongs to entry 16 glist[p] + t
-    lrow = lrow_by_entry.reshape(-1, G)[glist].reshape(-1) if tot else lrow
+            g0, L = int(rbeg[s_, b]), int(padded[s_, b])
+            for off in range(0, L, G):
+                ln = min(G, L - off)
+                glist.append(((g0 + off) // N) * 8 + (ln // N - 1))
+                slot = np.zeros(G, dtype=np.uint16)
+                slot[:ln] = lrow_by_entry[g0 + off:g0 + off + ln]
+                lrow.append(slot)
+                ng += 1
+        gptr[b + 1] = gptr[b] + ng
+    glist = np.array(glist, dtype=np.int32)
+    lrow = np.concatenate(lrow) if lrow else np.zeros(0, np.uint16)
     out = {"xl.vals": vals, "xl.lcol": lcol, "xl.gptr": gptr, "xl.glist": glist, "xl.lrow": lrow}
     if items:
         out["xl.items"] = np.array(items, dtype=np.int32)
@@ -753,18 +760,22 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
                 continue
             vv, lc, lr, it, gp, gl = a["vals"], a["lcol"], a["lrow"], a["items"], a["gptr"], a["glist"]
             W_ = xl_w if xl_w else 65536 // vv.dtype.itemsize
+            N_ = 16 // vv.dtype.itemsize
             win = np.full(vv.size, -1, dtype=np.int64)        # entry -> window, from the items
             for s_, b0, e0 in it.reshape(-1, 3):
                 win[b0:e0] = s_
-            blk = np.full(vv.size // 16, -1, dtype=np.int64)   # group -> row block, from the group list
-            blk[gl] = np.repeat(np.arange(gp.size - 1), np.diff(gp))
-            assert np.all(win >= 0) and np.all(blk >= 0) and np.unique(gl).size == gl.size
-            lr_by_entry = np.zeros(vv.size, dtype=np.int64)
-            lr_by_entry.reshape(-1, 16)[gl] = lr.reshape(-1, 16)
-            posn = np.repeat(blk, 16) * xl_rb + lr_by_entry
+            assert np.all(win >= 0)
+            blk_of_group = np.repeat(np.arange(gp.size - 1), np.diff(gp))
+            posn = np.full(vv.size, -1, dtype=np.int64)        # entry -> part position, from the group list
+            for p_, code in enumerate(gl):
+                g0, ln = (int(code) >> 3) * N_, ((int(code) & 7) + 1) * N_
+                assert np.all(posn[g0:g0 + ln] == -1) and not np.any(lr[16 * p_ + ln:16 * p_ + 16])
+                posn[g0:g0 + ln] = blk_of_group[p_] * xl_rb + lr[16 * p_:16 * p_ + ln].astype(np.int64)
+            assert not np.any(vv[posn < 0])                    # what no group lists is padding
             rws = np.asarray(a["rows"]) if "rows" in a else np.arange(nrows)
-            assert not np.any(vv[posn >= rws.size])
-            keep = posn < rws.size
+            listed = posn >= 0
+            assert not np.any(vv[listed & (posn >= rws.size)])
+            keep = listed & (posn < rws.size)
             R.append(rws[posn[keep]].astype(np.int64)); C.append(win[keep] * W_ + lc[keep].astype(np.int64)); V.append(vv[keep])
             continue
         if pre == "xnb":

@@ -1067,17 +1067,19 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
 // COL_DIV into windows of W columns (an LDS-sized piece of x), ROW_DIV of the part into blocks of RB
 // rows (an LDS-sized piece of y).  Entry (part position i, column c) belongs to run (s, b) =
 // (c / W, i / RB); runs are stored window by window, inside a window block by block, inside a run
-// by part position and then in row order; every run is padded to a multiple of 16 entries with
-// (value 0, local column 0, local row 0).  Entry g holds vals[g] and lcol[g] = c - s*W; its product
-// goes to scratch[g].  The multiply launch works through items
-// (s, first entry, end entry): a window's entries cut into equal pieces of at most `chunk` entries
-// (32768 unless the spec says otherwise).  The
-// reduce launch of block b adds the 16-entry groups glist[gptr[b]] .. glist[gptr[b+1] - 1]: the
-// groups of runs (0, b), (1, b), ... in that order.  The local rows i - b*RB are stored in that
-// order too (lrow[16*p + t] belongs to entry 16*glist[p] + t), so a block reads them as one
-// contiguous piece instead of a fragment of a cache line per run.
+// by part position and then in row order.  A run is padded to a whole 16-byte vector (N = 2 doubles or
+// 4 floats) and a window to 16 entries, with (value 0, local column 0): padding a run to 16 entries
+// would cost 7.5 entries per run, a tenth of everything this part streams when the runs are short.
+// Entry g holds vals[g] and lcol[g] = c - s*W; its product goes to scratch[g].  The multiply launch
+// works through items (s, first entry, end entry): a window's entries cut into equal pieces of at most
+// `chunk` entries (32768 unless the spec says otherwise), multiples of 16.
+// The reduce launch of block b adds the groups glist[gptr[b]] .. glist[gptr[b+1] - 1]: the runs (0, b),
+// (1, b), ... in that order, each cut into groups of up to 16 entries; a list entry is
+// 8 * (first entry / N) + (entries in the group / N - 1).  The local rows i - b*RB are stored in list
+// order, 16 slots per group (lrow[16*p + t] belongs to entry N*(glist[p] >> 3) + t; unused slots 0), so
+// a block reads them as one contiguous piece.
 // Row r contributes its first lens[r] entries: the caller passes 0 for rows that belong to another
-// part but are kept in `rows` so that the part's rows are simply 0 .. nrows-1 (no row map to read,
+// part but are kept in `rows` so that the part's rows are one contiguous range (no row map to read,
 // y written contiguously; the other part's launch overwrites those y elements afterwards).
 template <typename T>
 void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, int w_spec, int RB,
@@ -1091,43 +1093,60 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
     const int64_t S = std::max<int64_t>(1, (A.ncols + W - 1) / W);
     const int64_t B = (n + RB - 1) / RB;
     if (S * B > ((int64_t)1 << 26)) fail(SPMV_ERR_UNSUPPORTED, "xl: too many (window, row block) runs");
-    const int64_t G = kXlGroup;
+    const int64_t G = kXlGroup, N = 16 / (int64_t)sizeof(T);
     int64_t real = 0;
     for (int32_t r : rows) real += lens[(size_t)r];
-    // entries per run
-    std::vector<int64_t> start((size_t)(S * B) + 1, 0);
+    // entries per run (run j = s * B + b)
+    std::vector<int64_t> start((size_t)(S * B) + 1, 0), cnt((size_t)(S * B), 0);
     parallel_for(B, 1, threads, [&](int64_t bb, int64_t be, int) {
         for (int64_t b = bb; b < be; ++b)
             for (int64_t i = b * RB; i < std::min(n, (b + 1) * RB); ++i) {
                 const int32_t r = rows[(size_t)i];
                 for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r] + lens[(size_t)r]; ++k)
-                    start[(size_t)((A.col[k] / W) * B + b) + 1] += 1;
+                    cnt[(size_t)((A.col[k] / W) * B + b)] += 1;
             }
     });
-    for (int64_t j = 0; j < S * B; ++j)
-        start[(size_t)j + 1] = start[(size_t)j] + (start[(size_t)j + 1] + G - 1) / G * G;
+    // first entry of every run: runs padded to N, windows to 16
+    {
+        int64_t pos = 0;
+        for (int64_t s = 0; s < S; ++s) {
+            for (int64_t b = 0; b < B; ++b) {
+                start[(size_t)(s * B + b)] = pos;
+                pos += (cnt[(size_t)(s * B + b)] + N - 1) / N * N;
+            }
+            pos = (pos + G - 1) / G * G;
+        }
+        start[(size_t)(S * B)] = pos;
+    }
     const int64_t tot = start[(size_t)(S * B)];
-    if (tot >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "xl: too many entries");
+    if (tot >= ((int64_t)1 << 28) * N) fail(SPMV_ERR_UNSUPPORTED, "xl: too many entries");
     // group list of the reduce launch: block b reads the groups of runs (0, b), (1, b), ...
+    auto groups_of = [&](int64_t j) { return ((cnt[(size_t)j] + N - 1) / N * N + G - 1) / G; };
     std::vector<int32_t> gptr((size_t)B + 1, 0);
     for (int64_t b = 0; b < B; ++b) {
         int64_t c = 0;
-        for (int64_t s = 0; s < S; ++s) c += (start[(size_t)(s * B + b) + 1] - start[(size_t)(s * B + b)]) / G;
+        for (int64_t s = 0; s < S; ++s) c += groups_of(s * B + b);
+        if (gptr[(size_t)b] + c >= ((int64_t)1 << 27)) fail(SPMV_ERR_UNSUPPORTED, "xl: too many groups");
         gptr[(size_t)b + 1] = (int32_t)(gptr[(size_t)b] + c);
     }
+    const int64_t ngroups = gptr[(size_t)B];
     HostBuf<T> vals(tot);
-    HostBuf<uint16_t> lcol(tot), lrow(tot);
-    HostBuf<int32_t> glist(tot / G);
+    HostBuf<uint16_t> lcol(tot), lrow(ngroups * G);
+    HostBuf<int32_t> glist(ngroups);
     const T *av = (const T *)A.val;
     parallel_for(B, 1, threads, [&](int64_t bb, int64_t be, int) {
         std::vector<int64_t> cur((size_t)S), lpos((size_t)S);
         for (int64_t b = bb; b < be; ++b) {
             int64_t o = gptr[(size_t)b];
             for (int64_t s = 0; s < S; ++s) {
-                const int64_t g0 = start[(size_t)(s * B + b)], g1 = start[(size_t)(s * B + b) + 1];
+                const int64_t j = s * B + b, g0 = start[(size_t)j], padded = (cnt[(size_t)j] + N - 1) / N * N;
                 cur[(size_t)s] = g0;
                 lpos[(size_t)s] = o * G;           // the run's place in the block's own order
-                for (int64_t g = g0 / G; g < g1 / G; ++g) glist[o++] = (int32_t)g;
+                for (int64_t off = 0; off < padded; off += G) {
+                    const int64_t len = std::min<int64_t>(G, padded - off);
+                    for (int64_t t = len; t < G; ++t) lrow[o * G + t] = 0;   // slots past a short group
+                    glist[o++] = (int32_t)(((g0 + off) / N) * 8 + (len / N - 1));
+                }
             }
             for (int64_t i = b * RB; i < std::min(n, (b + 1) * RB); ++i) {
                 const int32_t r = rows[(size_t)i];
@@ -1139,14 +1158,24 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
                     lrow[lpos[(size_t)s]++] = (uint16_t)(i - b * RB);
                 }
             }
-            for (int64_t s = 0; s < S; ++s)
-                for (int64_t g = cur[(size_t)s]; g < start[(size_t)(s * B + b) + 1]; ++g) {
+            for (int64_t s = 0; s < S; ++s) {   // the padding of every run to a whole vector
+                const int64_t j = s * B + b, pe = start[(size_t)j] + (cnt[(size_t)j] + N - 1) / N * N;
+                for (int64_t g = cur[(size_t)s]; g < pe; ++g) {
                     vals[g] = T(0);
                     lcol[g] = 0;
                     lrow[lpos[(size_t)s]++] = 0;
                 }
+            }
         }
     });
+    for (int64_t s = 0; s < S; ++s) {   // the padding of every window to 16 entries
+        const int64_t last = s * B + B - 1;
+        const int64_t pb = start[(size_t)last] + (cnt[(size_t)last] + N - 1) / N * N, pe = start[(size_t)last + 1];
+        for (int64_t g = pb; g < pe; ++g) {
+            vals[g] = T(0);
+            lcol[g] = 0;
+        }
+    }
     // items of the multiply launch
     const int64_t chunk = chunk_spec > 0 ? (chunk_spec + G - 1) / G * G : 32768;
     std::vector<int32_t> items;
@@ -1202,8 +1231,8 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
     r.has_rows = !ident;
     const size_t a2 = plan.arrays.size();
     r.p0 = upload(plan, "xl.gptr", 4, B + 1, gptr.data());
-    r.p1 = upload(plan, "xl.glist", 4, tot / G, glist.p);
-    r.p2 = upload(plan, "xl.lrow", 2, tot, lrow.p);
+    r.p1 = upload(plan, "xl.glist", 4, ngroups, glist.p);
+    r.p2 = upload(plan, "xl.lrow", 2, ngroups * G, lrow.p);
     if (!ident) r.p3 = upload(plan, "xl.rows", 4, n, rows.data());
     add_part(plan, r, a2, 0, tot, n);
 }

@@ -1379,7 +1379,9 @@ __global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ it
 // Block blk adds the groups glist[gptr[blk]] .. glist[gptr[blk + 1] - 1].  A lane reads 16 bytes of
 // products, so 16 / N lanes share a group and one load instruction of a wavefront covers 64 * N
 // entries; a wavefront takes 64 list entries at a time and fetches the next 64 while it adds.
-// lrow is stored in list order: lrow[16*p + t] is the local row of entry 16*glist[p] + t.
+// A group is up to 16 consecutive entries of one run, starting at any multiple of N entries.
+// lrow is stored in list order, 16 slots per listed group: lrow[16*p + t] is the local row of entry
+// N*(glist[p] >> 3) + t.
 template <typename T, bool ROWS, bool ACC>
 __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__ gptr,
                                                      const int32_t *__restrict__ glist,
@@ -1412,9 +1414,11 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
 #pragma unroll
         for (int u = 0; u < IT; ++u) {
             const int32_t gid = __shfl(mine, u * GPI + sub, kWave);
-            ok[u] = gid >= 0;
+            // a list entry is (first 16-byte vector of the group) * 8 + (vectors in the group - 1): the last
+            // group of a run may be short, and the lanes past its end stay out
+            ok[u] = gid >= 0 && l <= (gid & 7);
             if (ok[u]) {
-                v[u] = ldnt(pv + (int64_t)gid * LPG + l);
+                v[u] = ldnt(pv + (int64_t)(gid >> 3) + l);
                 r[u] = ldnt(pr + (int64_t)(base + u * GPI + sub) * LPG + l);   // rows are in list order
             }
         }
