@@ -31,7 +31,7 @@ WAVE = 64
 
 def parse_spec(spec: str) -> dict:
     d = dict(dia=0, dia_fill=0.5, heavy=0, tile=8192, light="csrv", lpr=0, chunk=0,
-             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8, r=8, w=0, rb=16384, hd=0)
+             sigma=0, block=3, smax=16, remap=0, xwin=0, k=8, r=8, w=0, rb=16384, hd=0, piece=0)
     for tok in spec.split(","):
         if not tok:
             continue
@@ -232,70 +232,94 @@ def ref_bsell(nrows, ncols, rp, ci, va, B, sigma, xwin=0):
     return out
 
 
-def ref_stripe(ncols, rp, ci, va, hrows, tile, delta=0):
+def ref_stripe(ncols, rp, ci, va, hrows, tile, delta=0, piece=0):
     """Heavy rows cut into column stripes; inside a stripe the rows are ordered by decreasing number
     of entries in that stripe (stable), sliced by 64 and padded per slice (value 0, local column 0).
 
-    delta=1: 8-bit column differences.  A segment (row, stripe) with local columns c_0 <= c_1 <= ...
-    is stored as the byte sequence d_0 = 0, d_k = c_k - c_(k-1), where a gap g > 255 is first bridged
-    by (g - 1) // 255 entries (255, value 0).  Rows are ordered by the stored length (entries +
-    bridges), a slice is padded with (0, 0) to its longest segment rounded up to a multiple of 4.
+    delta=1: 8-bit column differences.  A lane with local columns c_0 <= c_1 <= ... is stored as the
+    byte sequence d_0 = 0, d_k = c_k - c_(k-1), where a gap g > 255 is first bridged by
+    (g - 1) // 255 entries (255, value 0).  Lanes are ordered by the stored length (entries +
+    bridges), a slice is padded with (0, 0) to its longest lane rounded up to a multiple of 4.
     lane_meta = c_0 << 16 | heavy row (0xFFFF: none).  dcols packs entries 4q..4q+3 of a lane into
-    one little-endian 32-bit word at unit_ptr[u] / 4 + 64 q + lane."""
+    one little-endian 32-bit word at unit_ptr[u] / 4 + 64 q + lane.
+
+    piece=P>0: a (row, stripe) segment is cut into runs of at most P entries, every run a lane of its
+    own (rows without entries in the stripe take none); P doubles for a stripe until it has at most
+    8192 lanes.  sunits[s] = first unit of stripe s."""
     nh = len(hrows)
     if nh == 0:
         return {}
     ns = -(-ncols // tile)
-    nsl = -(-nh // WAVE)
-    unit_ptr = [0]
-    lane_row = np.full(ns * nsl * WAVE, 0xFFFF, dtype=np.uint16)
-    lane_meta = np.full(ns * nsl * WAVE, 0xFFFF, dtype=np.uint32)
+    unit_ptr, sunits = [0], [0]
+    lane_row, lane_meta = [], []
     lcols, vals = [], []
+
+    def encode(lc, vv):
+        if not delta:
+            return lc.astype(np.uint16), vv, 0
+        d, v2 = [], []
+        for k in range(lc.size):
+            gap = int(lc[k] - lc[k - 1]) if k else 0
+            while gap > 255:
+                d.append(255); v2.append(0.0); gap -= 255
+            d.append(gap); v2.append(vv[k])
+        return np.array(d, dtype=np.uint8), np.array(v2, dtype=va.dtype), int(lc[0]) if lc.size else 0
+
     for s in range(ns):
-        segs = []
+        rowseg = []
         for r in hrows:
             e = _row_entries(rp, r)
             c = ci[e]
             m = (c >= s * tile) & (c < (s + 1) * tile)
-            lc, vv = (c[m] - s * tile).astype(np.int64), va[e][m]
-            if delta:
-                d, v2 = [], []
-                for k in range(lc.size):
-                    gap = int(lc[k] - lc[k - 1]) if k else 0
-                    while gap > 255:
-                        d.append(255); v2.append(0.0); gap -= 255
-                    d.append(gap); v2.append(vv[k])
-                segs.append((np.array(d, dtype=np.uint8), np.array(v2, dtype=va.dtype), int(lc[0]) if lc.size else 0))
-            else:
-                segs.append((lc.astype(np.uint16), vv, 0))
-        seglen = np.array([len(sg[0]) for sg in segs], dtype=np.int64)
-        order = np.argsort(-seglen, kind="stable")
-        lane_row[s * nsl * WAVE:s * nsl * WAVE + nh] = order
-        for g in range(nsl):
+            rowseg.append(((c[m] - s * tile).astype(np.int64), va[e][m]))
+        lanes = []                                # (heavy row, stored columns, stored values, first column)
+        if piece <= 0:
+            for h, (lc, vv) in enumerate(rowseg):
+                lanes.append((h,) + encode(lc, vv))
+        else:
+            P = piece
+            while sum(-(-lc.size // P) for lc, _ in rowseg) > 8192:
+                P *= 2
+            for h, (lc, vv) in enumerate(rowseg):
+                for o in range(0, lc.size, P):
+                    lanes.append((h,) + encode(lc[o:o + P], vv[o:o + P]))
+        key = np.array([len(l[1]) for l in lanes], dtype=np.int64)
+        order = np.argsort(-key, kind="stable")
+        nu = -(-len(lanes) // WAVE)
+        sunits.append(sunits[-1] + nu)
+        for g in range(nu):
             members = order[g * WAVE:(g + 1) * WAVE]
-            w = int(seglen[members].max())
+            w = int(key[members[0]])
             if delta:
                 w = -(-w // 4) * 4
             lc = np.zeros((w, WAVE), dtype=np.uint8 if delta else np.uint16)
             vv = np.zeros((w, WAVE), dtype=va.dtype)
-            for lane, h in enumerate(members):
-                L = seglen[h]
-                lc[:L, lane] = segs[h][0]
-                vv[:L, lane] = segs[h][1]
-                lane_meta[(s * nsl + g) * WAVE + lane] = (segs[h][2] << 16) | int(h)
+            lr = np.full(WAVE, 0xFFFF, dtype=np.uint16)
+            lm = np.full(WAVE, 0xFFFF, dtype=np.uint32)
+            for lane, i in enumerate(members):
+                h, cc, v2, c0 = lanes[i]
+                lc[:len(cc), lane] = cc
+                vv[:len(cc), lane] = v2
+                lr[lane] = h
+                lm[lane] = (c0 << 16) | h
             if delta:   # (w, 64) -> words: [w/4][lane][4]
                 lc = lc.reshape(w // 4, 4, WAVE).transpose(0, 2, 1)
             lcols.append(lc.reshape(-1))
             vals.append(vv.reshape(-1))
+            lane_row.append(lr)
+            lane_meta.append(lm)
             unit_ptr.append(unit_ptr[-1] + w * WAVE)
+    cat = lambda xs, dt: np.concatenate(xs).astype(dt) if xs else np.zeros(0, dtype=dt)
     out = {"heavy.unit_ptr": np.array(unit_ptr, dtype=np.int32),
-           "heavy.vals": np.concatenate(vals).astype(va.dtype), "heavy.rows": np.asarray(hrows, dtype=np.int32)}
+           "heavy.vals": cat(vals, va.dtype), "heavy.rows": np.asarray(hrows, dtype=np.int32)}
     if delta:
-        out["heavy.dcols"] = np.ascontiguousarray(np.concatenate(lcols)).view("<u4")
-        out["heavy.lane_meta"] = lane_meta
+        out["heavy.dcols"] = np.ascontiguousarray(cat(lcols, np.uint8)).view("<u4")
+        out["heavy.lane_meta"] = cat(lane_meta, np.uint32)
     else:
-        out["heavy.lcols"] = np.concatenate(lcols)
-        out["heavy.lane_row"] = lane_row
+        out["heavy.lcols"] = cat(lcols, np.uint16)
+        out["heavy.lane_row"] = cat(lane_row, np.uint16)
+    if piece > 0:
+        out["heavy.sunits"] = np.array(sunits, dtype=np.int32)
     return out
 
 
@@ -650,7 +674,7 @@ def _ref_leaf(nrows, ncols, rp, ci, va, p, rows, whole, acc, span) -> dict:
                             "bin2.csrwg" if p.get("wg") else "bin2.csrv64", zero_rows))
     else:
         raise ValueError(p["light"])
-    out.update(ref_stripe(ncols, rp, ci, va, heavy, p["tile"], p["hd"]))
+    out.update(ref_stripe(ncols, rp, ci, va, heavy, p["tile"], p["hd"], p.get("piece", 0)))
     if zero_rows:
         out["zero.rows"] = np.array(sorted(set(zero_rows)), dtype=np.int32)
     return out
@@ -731,6 +755,14 @@ def ref_plan(nrows, ncols, rp, ci, va, spec: str, leaves=None) -> dict:
 
 
 # ---- decoding: plan arrays -> (row, col, value) triples --------------------------------------
+
+def _unit_stripes(a, nunits, nh):
+    """Stripe of every unit of a heavy part: from sunits when the part has one, else ceil(nh/64) units a stripe."""
+    if "sunits" in a:
+        su = np.asarray(a["sunits"], dtype=np.int64)
+        return np.repeat(np.arange(su.size - 1), np.diff(su))
+    return np.arange(nunits) // max(1, -(-nh // WAVE))
+
 
 _PART_NAMES = ("bin0.sell", "bin1.csrv8", "bin2.csrv64", "bin2.csrwg", "zero", "coo", "xl", "xnb", "nnzb", "wbm", "xs", "dia",
                "bsell", "sell", "csrv", "heavy")
@@ -881,9 +913,9 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
         elif "dcols" in a:       # heavy stripes, 8-bit column differences
             up, dw, vv, hr, lm = a["unit_ptr"], a["dcols"], a["vals"], a["rows"], a["lane_meta"]
             db = np.ascontiguousarray(dw.astype("<u4")).view(np.uint8)       # byte 4*word + (entry % 4)
-            nsl = -(-len(hr) // WAVE)
+            stripe_of = _unit_stripes(a, len(up) - 1, len(hr))
             for u in range(len(up) - 1):
-                s = u // nsl
+                s = int(stripe_of[u])
                 base, w = int(up[u]), int(up[u + 1] - up[u]) // WAVE
                 j = np.arange(w)
                 for lane in range(WAVE):
@@ -896,9 +928,9 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
                     R.append(np.full(w, int(hr[h]), dtype=np.int64)); C.append(c0 + np.cumsum(d) + s * tile); V.append(vv[pos])
         elif "lcols" in a:       # heavy stripes
             up, lc, vv, hr, lr = a["unit_ptr"], a["lcols"], a["vals"], a["rows"], a["lane_row"]
-            nsl = -(-len(hr) // WAVE)
+            stripe_of = _unit_stripes(a, len(up) - 1, len(hr))
             for u in range(len(up) - 1):
-                s = u // nsl
+                s = int(stripe_of[u])
                 base, w = int(up[u]), int(up[u + 1] - up[u]) // WAVE
                 for lane in range(WAVE):
                     h = int(lr[u * WAVE + lane])

@@ -498,24 +498,26 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
 // (entries + bridges), and a slice's width is rounded up to a multiple of 4: the differences of
 // entries 4q .. 4q+3 of a lane form one 32-bit word (entry 4q in the low byte) at word
 // unit_ptr[u] / 4 + 64*q + lane.
+//
+// piece = P > 0: the entries of a (row, stripe) segment are cut into runs of at most P (the last one
+// shorter), each run a lane of its own, so that a few very long segments no longer set the padded
+// width of a whole slice; rows without entries in a stripe take no lane there.  sunits[s] is the
+// first unit of stripe s (piece = 0: every stripe has ceil(nh / 64) units and there is no such
+// array).  A stripe that would need more than 8192 lanes doubles its P until it does not.
 template <typename T>
-void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile, int delta,
+void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile, int delta, int piece,
                   bool acc, const std::vector<int64_t> &lens, int threads) {
     const int64_t nh = (int64_t)hrows.size();
     if (nh == 0) return;
     if ((size_t)tile * sizeof(T) > 65536) fail(SPMV_ERR_UNSUPPORTED, "heavy: tile does not fit 64 KiB of LDS");
     if (nh > 8192) fail(SPMV_ERR_UNSUPPORTED, "heavy: more than 8192 heavy rows (their accumulators live in LDS)");
     const int64_t ns = (A.ncols + tile - 1) / tile;
-    const int64_t nsl = (nh + kWave - 1) / kWave;
-    if (ns * nsl * kWave >= ((int64_t)1 << 28)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many (row, stripe) segments");
     int64_t total = 0;
     for (int32_t r : hrows) total += lens[(size_t)r];
     auto bridges = [](int64_t gap) { return gap > 255 ? (gap - 1) / 255 : (int64_t)0; };
     // seg_len[s * nh + h] and seg_off[s * nh + h]: the entries of heavy row h inside stripe s are
-    // A[row_ptr[r] + seg_off .. + seg_len)   (columns ascend inside a row); enc_len: stored length
+    // A[row_ptr[r] + seg_off .. + seg_len)   (columns ascend inside a row)
     std::vector<int32_t> seg_len((size_t)(ns * nh), 0), seg_off((size_t)(ns * nh), 0);
-    std::vector<int32_t> enc_len;
-    if (delta) enc_len.assign((size_t)(ns * nh), 0);
     parallel_for(nh, 4, threads, [&](int64_t b, int64_t e, int) {
         for (int64_t h = b; h < e; ++h) {
             const int32_t r = hrows[(size_t)h];
@@ -523,54 +525,88 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
             for (int64_t k = beg; k < A.row_ptr[r + 1]; ++k) {
                 const size_t i = (size_t)((int64_t)(A.col[k] / tile) * nh + h);
                 if (seg_len[i]++ == 0) seg_off[i] = (int32_t)(k - beg);
-                else if (delta) enc_len[i] += (int32_t)bridges((int64_t)A.col[k] - A.col[k - 1]);
-                if (delta) enc_len[i] += 1;
             }
         }
     });
-    const std::vector<int32_t> &key = delta ? enc_len : seg_len;
-    // per stripe: order of the heavy rows, slice widths
-    std::vector<uint16_t> lane_row((size_t)(ns * nsl * kWave), (uint16_t)0xFFFF);
-    std::vector<int64_t> unit_w((size_t)(ns * nsl), 0);
+    // A lane holds one run of consecutive entries of a heavy row inside a stripe: the whole
+    // (row, stripe) segment, or (piece > 0) one piece of it.  key = its stored length.
+    struct Lane {
+        int32_t h, off, len, key;
+    };
+    auto stored_len = [&](int32_t h, int32_t off, int32_t len) -> int32_t {
+        if (!delta || len == 0) return len;
+        const int64_t src = (int64_t)A.row_ptr[hrows[(size_t)h]] + off;
+        int64_t n = len;
+        for (int64_t k = 1; k < len; ++k) n += bridges((int64_t)A.col[src + k] - A.col[src + k - 1]);
+        return (int32_t)n;
+    };
+    std::vector<std::vector<Lane>> lanes((size_t)ns);
     parallel_for(ns, 1, threads, [&](int64_t sb, int64_t se, int) {
-        std::vector<int32_t> order((size_t)nh);
         for (int64_t s = sb; s < se; ++s) {
-            const int32_t *sl = key.data() + s * nh;
-            std::iota(order.begin(), order.end(), 0);
-            std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return sl[a] > sl[b]; });
-            for (int64_t i = 0; i < nh; ++i) lane_row[(size_t)(s * nsl * kWave + i)] = (uint16_t)order[(size_t)i];
-            for (int64_t g = 0; g < nsl; ++g) {
-                int64_t w = sl[order[(size_t)(g * kWave)]];
-                if (delta) w = (w + 3) / 4 * 4;
-                unit_w[(size_t)(s * nsl + g)] = w;
+            std::vector<Lane> &ls = lanes[(size_t)s];
+            const int32_t *sl = seg_len.data() + s * nh, *so = seg_off.data() + s * nh;
+            if (piece <= 0) {
+                for (int32_t h = 0; h < (int32_t)nh; ++h) ls.push_back({h, so[h], sl[h], stored_len(h, so[h], sl[h])});
+            } else {
+                // the piece length doubles until the stripe has at most 8192 lanes (128 units)
+                int64_t P = piece, cnt;
+                for (;; P *= 2) {
+                    cnt = 0;
+                    for (int64_t h = 0; h < nh; ++h) cnt += (sl[h] + P - 1) / P;
+                    if (cnt <= 8192) break;
+                }
+                for (int32_t h = 0; h < (int32_t)nh; ++h)
+                    for (int64_t o = 0; o < sl[h]; o += P) {
+                        const int32_t len = (int32_t)std::min<int64_t>(P, sl[h] - o);
+                        ls.push_back({h, (int32_t)(so[h] + o), len, stored_len(h, (int32_t)(so[h] + o), len)});
+                    }
             }
+            std::stable_sort(ls.begin(), ls.end(), [](const Lane &a, const Lane &b) { return a.key > b.key; });
         }
     });
-    std::vector<int32_t> unit_ptr((size_t)(ns * nsl) + 1, 0);
-    int64_t padded = 0;
-    for (int64_t u = 0; u < ns * nsl; ++u) {
-        padded += unit_w[(size_t)u] * kWave;
-        if (padded >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many entries");
-        unit_ptr[(size_t)u + 1] = (int32_t)padded;
+    // units: slices of 64 lanes, padded to their first (longest) lane
+    std::vector<int32_t> sunits((size_t)ns + 1, 0);
+    for (int64_t s = 0; s < ns; ++s) {
+        const int64_t nu = ((int64_t)lanes[(size_t)s].size() + kWave - 1) / kWave;
+        if (sunits[(size_t)s] + nu >= ((int64_t)1 << 22)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many (row, stripe) segments");
+        sunits[(size_t)s + 1] = (int32_t)(sunits[(size_t)s] + nu);
     }
+    const int64_t nunits = sunits[(size_t)ns];
+    int64_t nsl = 0;   // units of the largest stripe
+    for (int64_t s = 0; s < ns; ++s) nsl = std::max<int64_t>(nsl, sunits[(size_t)s + 1] - sunits[(size_t)s]);
+    std::vector<int32_t> unit_ptr((size_t)nunits + 1, 0), unit_stripe((size_t)nunits, 0);
+    int64_t padded = 0;
+    for (int64_t s = 0; s < ns; ++s)
+        for (int64_t u = sunits[(size_t)s]; u < sunits[(size_t)s + 1]; ++u) {
+            int64_t w = lanes[(size_t)s][(size_t)((u - sunits[(size_t)s]) * kWave)].key;
+            if (delta) w = (w + 3) / 4 * 4;
+            padded += w * kWave;
+            if (padded >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "heavy: too many entries");
+            unit_ptr[(size_t)u + 1] = (int32_t)padded;
+            unit_stripe[(size_t)u] = (int32_t)s;
+        }
+    std::vector<uint16_t> lane_row;
+    std::vector<uint32_t> lane_meta;
+    if (delta) lane_meta.assign((size_t)(nunits * kWave), 0xFFFFu);
+    else lane_row.assign((size_t)(nunits * kWave), (uint16_t)0xFFFF);
     HostBuf<uint16_t> lcol(delta ? 0 : padded);
     HostBuf<uint8_t> dcol(delta ? padded : 0);
-    std::vector<uint32_t> lane_meta;
-    if (delta) lane_meta.assign((size_t)(ns * nsl * kWave), 0xFFFFu);
     HostBuf<T> vals(padded);
     const T *av = (const T *)A.val;
-    parallel_for(ns * nsl, 8, threads, [&](int64_t ub, int64_t ue, int) {
+    parallel_for(nunits, 8, threads, [&](int64_t ub, int64_t ue, int) {
         for (int64_t u = ub; u < ue; ++u) {
-            const int64_t s = u / nsl, base = unit_ptr[(size_t)u], w = unit_w[(size_t)u];
+            const int64_t s = unit_stripe[(size_t)u], base = unit_ptr[(size_t)u];
+            const int64_t w = (unit_ptr[(size_t)u + 1] - base) / kWave;
+            const std::vector<Lane> &ls = lanes[(size_t)s];
             for (int lane = 0; lane < kWave; ++lane) {
-                const uint16_t h = lane_row[(size_t)(u * kWave + lane)];
-                int64_t L = 0, src = 0;
-                if (h != 0xFFFF) {
-                    L = seg_len[(size_t)(s * nh + h)];
-                    src = (int64_t)A.row_ptr[hrows[h]] + seg_off[(size_t)(s * nh + h)];
-                }
+                const int64_t li = (u - sunits[(size_t)s]) * kWave + lane;
+                const bool have = li < (int64_t)ls.size();
+                const uint16_t h = have ? (uint16_t)ls[(size_t)li].h : (uint16_t)0xFFFF;
+                const int64_t L = have ? ls[(size_t)li].len : 0;
+                const int64_t src = have ? (int64_t)A.row_ptr[hrows[h]] + ls[(size_t)li].off : 0;
                 int64_t j = 0;
                 if (!delta) {
+                    lane_row[(size_t)(u * kWave + lane)] = h;
                     for (; j < L; ++j) {
                         lcol[base + j * kWave + lane] = (uint16_t)(A.col[src + j] - s * tile);
                         vals[base + j * kWave + lane] = av[src + j];
@@ -625,13 +661,14 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     p.delta = delta;
     p.has_rows = true;
     const size_t a0 = plan.arrays.size();
-    p.p0 = upload(plan, "heavy.unit_ptr", 4, ns * nsl + 1, unit_ptr.data());
+    p.p0 = upload(plan, "heavy.unit_ptr", 4, nunits + 1, unit_ptr.data());
     if (delta) p.p1 = upload(plan, "heavy.dcols", 4, padded / 4, dcol.p);
     else p.p1 = upload(plan, "heavy.lcols", 2, padded, lcol.p);
     p.p2 = upload(plan, "heavy.vals", (int)sizeof(T), padded, vals.p);
     p.p3 = upload(plan, "heavy.rows", 4, nh, hrows.data());
-    if (delta) p.p4 = upload(plan, "heavy.lane_meta", 4, ns * nsl * kWave, lane_meta.data());
-    else p.p4 = upload(plan, "heavy.lane_row", 2, ns * nsl * kWave, lane_row.data());
+    if (delta) p.p4 = upload(plan, "heavy.lane_meta", 4, nunits * kWave, lane_meta.data());
+    else p.p4 = upload(plan, "heavy.lane_row", 2, nunits * kWave, lane_row.data());
+    if (piece > 0) p.p5 = upload(plan, "heavy.sunits", 4, ns + 1, sunits.data());
     plan.arrays[a0 + 3].read_per_run = false;   // heavy.rows is read by the reduce launch
     add_part(plan, p, a0, A.ncols, ngroups * nh, 0);
     plan.arrays[a0 + 3].read_per_run = true;
@@ -1551,7 +1588,7 @@ void build_leaf(Plan &plan, const HostCsr &A0, const Census &cen, const PlanSpec
     }
     default: fail(SPMV_ERR_INVALID_ARG, "unknown light design");
     }
-    if (!heavy.empty()) build_stripe<T>(plan, A, heavy, spec.tile, spec.hd, acc, lens, threads);
+    if (!heavy.empty()) build_stripe<T>(plan, A, heavy, spec.tile, spec.hd, spec.piece, acc, lens, threads);
 
     if (!zero_rows.empty()) {
         std::sort(zero_rows.begin(), zero_rows.end());

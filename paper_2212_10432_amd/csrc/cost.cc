@@ -76,6 +76,7 @@ std::vector<double> cost_features(const CostCensus &c, const PlanSpec &spec) {
     f.push_back(q.k);
     f.push_back(lg(q.w ? (double)q.w : 65536.0 / v));
     f.push_back(lg((double)q.rb));
+    f.push_back(lg((double)q.piece + 1));
     return f;
 }
 

@@ -1097,7 +1097,15 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
 constexpr int kHeavyWG = 512;
 // Four consecutive units of the same width W <= 4 (4 * 64 * W entries starting at entry p0, lane
 // rows starting at lr0): every load is issued before the first product.
-template <typename T, int W>
+// PIECES: several lanes of a stripe may hold pieces of the same heavy row, so the lane sums meet in the
+// row's LDS accumulator through an atomic add.
+template <typename T, bool PIECES>
+__device__ __forceinline__ void heavy_add(T *ys, unsigned lr, T acc) {
+    if (PIECES) atomic_add(ys + lr, acc);
+    else ys[lr] += acc;
+}
+
+template <typename T, int W, bool PIECES>
 __device__ __forceinline__ void narrow_quad(const uint16_t *__restrict__ lcol, const T *__restrict__ vals,
                                             const uint16_t *__restrict__ lane_row, int32_t p0, int64_t lr0,
                                             int lane, const T *__restrict__ xs, T *__restrict__ ys) {
@@ -1115,19 +1123,20 @@ __device__ __forceinline__ void narrow_quad(const uint16_t *__restrict__ lcol, c
         T acc = T(0);
 #pragma unroll
         for (int j = 0; j < W; ++j) acc += v[k * W + j] * xs[c[k * W + j]];
-        if (lr[k] != 0xFFFFu) ys[lr[k]] += acc;
+        if (lr[k] != 0xFFFFu) heavy_add<T, PIECES>(ys, lr[k], acc);
     }
 }
 
-template <typename T>
+template <typename T, bool PIECES>
 __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ unit_ptr,
                                                     const uint16_t *__restrict__ lcol,
                                                     const T *__restrict__ vals,
                                                     const uint16_t *__restrict__ lane_row,
+                                                    const int32_t *__restrict__ sunits,
                                                     const T *__restrict__ x, T *__restrict__ partial,
                                                     int nsl_arg, int nh_arg, int tile_arg, int64_t ncols_arg, int ns_arg,
                                                     int stripes_per_wg_arg) {
-    const int nsl = JIT_HS_NSL(nsl_arg), nh = JIT_HS_NH(nh_arg), tile = JIT_HS_TILE(tile_arg), ns = JIT_HS_NS(ns_arg);
+    const int nsl_all = JIT_HS_NSL(nsl_arg), nh = JIT_HS_NH(nh_arg), tile = JIT_HS_TILE(tile_arg), ns = JIT_HS_NS(ns_arg);
     const int stripes_per_wg = JIT_HS_SPW(stripes_per_wg_arg);
     const int64_t ncols = JIT_HS_NCOLS(ncols_arg);
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1143,12 +1152,14 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
         const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
         for (int i = threadIdx.x; i < w; i += kHeavyWG) xs[i] = x[c0 + i];
         __syncthreads();
+        // units of this stripe: nsl_all everywhere, or (PIECES) the stripe's own count, at most 128
+        const int64_t u0 = PIECES ? (int64_t)sunits[s] : (int64_t)s * nsl_all;
+        const int nsl = PIECES ? sunits[s + 1] - sunits[s] : nsl_all;
         // The stripe's unit offsets live in lane registers (nsl <= 128: lane i holds offsets i and
         // 64 + i), so a unit costs no dependent load of its own.  Units are ordered by decreasing
         // width: the first n_wide are wider than four entries and are walked one by one; the narrow
         // ones after them are taken four at a time when the four widths agree, with all their loads
         // issued together (a narrow unit alone is one dependent round trip for a few bytes).
-        const int64_t u0 = (int64_t)s * nsl;
         const int32_t upa = (lane <= nsl) ? unit_ptr[u0 + lane] : 0;
         const int32_t upb = (64 + lane <= nsl) ? unit_ptr[u0 + 64 + lane] : 0;
         const int32_t uplast = unit_ptr[u0 + nsl];
@@ -1171,7 +1182,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
             const int32_t b = offset_of(g), e = offset_of(g + 1);
             const uint16_t lr = lane_row[(u0 + g) * 64 + lane];
             const T acc = sell_lane_sum<T, uint16_t, true>(lcol + b + lane, vals + b + lane, (e - b) >> 6, xs);
-            if (lr != 0xFFFFu) ys[lr] += acc;
+            if (lr != 0xFFFFu) heavy_add<T, PIECES>(ys, lr, acc);
         }
         for (int g0 = n_wide + 4 * wave; g0 < n_used; g0 += 4 * (kHeavyWG / kWave)) {
             const int32_t p0 = offset_of(g0), p1 = offset_of(g0 + 1);
@@ -1186,10 +1197,10 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
             }
             if (quad) {
                 switch (wq) {
-                case 1: narrow_quad<T, 1>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
-                case 2: narrow_quad<T, 2>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
-                case 3: narrow_quad<T, 3>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
-                default: narrow_quad<T, 4>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
+                case 1: narrow_quad<T, 1, PIECES>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
+                case 2: narrow_quad<T, 2, PIECES>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
+                case 3: narrow_quad<T, 3, PIECES>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
+                default: narrow_quad<T, 4, PIECES>(lcol, vals, lane_row, p0, (u0 + g0) * 64, lane, xs, ys); break;
                 }
             } else {
                 const int cnt = n_used - g0 < 4 ? n_used - g0 : 4;
@@ -1197,7 +1208,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
                     const int32_t b = offset_of(g0 + k), e = offset_of(g0 + k + 1);
                     const uint16_t lr = lane_row[(u0 + g0 + k) * 64 + lane];
                     const T acc = sell_lane_sum<T, uint16_t, false>(lcol + b + lane, vals + b + lane, (e - b) >> 6, xs);
-                    if (lr != 0xFFFFu) ys[lr] += acc;
+                    if (lr != 0xFFFFu) heavy_add<T, PIECES>(ys, lr, acc);
                 }
             }
         }
@@ -1233,15 +1244,16 @@ __device__ __forceinline__ void hdelta_step(const uint32_t *__restrict__ dw, con
     }
 }
 
-template <typename T>
+template <typename T, bool PIECES>
 __global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restrict__ unit_ptr,
                                                           const uint32_t *__restrict__ dcols,
                                                           const T *__restrict__ vals,
                                                           const uint32_t *__restrict__ lane_meta,
+                                                          const int32_t *__restrict__ sunits,
                                                           const T *__restrict__ x, T *__restrict__ partial,
                                                           int nsl_arg, int nh_arg, int tile_arg, int64_t ncols_arg, int ns_arg,
                                                           int stripes_per_wg_arg) {
-    const int nsl = JIT_HS_NSL(nsl_arg), nh = JIT_HS_NH(nh_arg), tile = JIT_HS_TILE(tile_arg), ns = JIT_HS_NS(ns_arg);
+    const int nsl_all = JIT_HS_NSL(nsl_arg), nh = JIT_HS_NH(nh_arg), tile = JIT_HS_TILE(tile_arg), ns = JIT_HS_NS(ns_arg);
     const int stripes_per_wg = JIT_HS_SPW(stripes_per_wg_arg);
     const int64_t ncols = JIT_HS_NCOLS(ncols_arg);
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1257,8 +1269,10 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restr
         const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
         for (int i = threadIdx.x; i < w; i += kHeavyWG) xs[i] = x[c0 + i];
         __syncthreads();
+        const int64_t u0 = PIECES ? (int64_t)sunits[s] : (int64_t)s * nsl_all;
+        const int nsl = PIECES ? sunits[s + 1] - sunits[s] : nsl_all;
         for (int g = threadIdx.x >> 6; g < nsl; g += kHeavyWG / kWave) {
-            const int64_t u = (int64_t)s * nsl + g;
+            const int64_t u = u0 + g;
             const int32_t b = unit_ptr[u];
             const int wd = (unit_ptr[u + 1] - b) >> 6;   // a multiple of 4
             if (wd == 0) continue;
@@ -1272,7 +1286,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restr
             for (; j + 8 <= wd; j += 8) hdelta_step<T, 2>(dw, vv, j, c, xs, a0, a1, a2, a3);
             for (; j < wd; j += 4) hdelta_step<T, 1>(dw, vv, j, c, xs, a0, a1, a2, a3);
             const uint32_t lr = meta & 0xFFFFu;
-            if (lr != 0xFFFFu) ys[lr] += (a0 + a1) + (a2 + a3);
+            if (lr != 0xFFFFu) heavy_add<T, PIECES>(ys, lr, (a0 + a1) + (a2 + a3));
         }
     }
     __syncthreads();

@@ -94,6 +94,8 @@ struct PlanSpec {
     int64_t heavy = 0;       // ROW_DIV: rows longer than this go to the heavy part (0 = no split)
     int tile = 8192;         //   COL_DIV width of the heavy part (columns per LDS tile of x)
     int hd = 0;              //   1 = the heavy part stores 8-bit column deltas instead of 16-bit columns
+    int piece = 0;           //   > 0: a heavy row's entries inside a stripe are cut into pieces of at most this many,
+                             //   each piece a lane of its own (0: one lane per row and stripe)
     int light = L_CSRV;      // design of the remaining rows
     int lpr = 0;             // csrv: lanes per row (power of two <= 64; 0 = from the mean length)
     int64_t chunk = 0;       // csrv: rows longer than this are cut into segments (0 = never)
@@ -164,7 +166,7 @@ struct Part {
                                  // bsell with an x window: 1 = a group's block rows lie in its own range
     int delta = 0;               // heavy part: columns stored as 8-bit deltas
     int64_t lds_bytes = 0;       // bsell: size of the LDS x window (0 = gather from memory)
-    const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr;
+    const void *p0 = nullptr, *p1 = nullptr, *p2 = nullptr, *p3 = nullptr, *p4 = nullptr, *p5 = nullptr;
     int64_t bytes = 0;           // algorithmic bytes of one launch: arrays read + x + scratch + y
     void *jit_fn = nullptr;      // kernel compiled at run time for this launch (a hipFunction_t), else the ahead-of-time one
     std::string jit_kernel, jit_defines;   // what was compiled: instantiation and specialisation constants

@@ -193,15 +193,19 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     case K_STRIPE: {
         if (p.units == 0 || p.nslices == 0) return 0;
         const size_t lds = ((size_t)p.tile + (size_t)p.nrows) * sizeof(T);
+        const int32_t *sunits = (const int32_t *)p.p5;   // units per stripe when the rows are cut into pieces
+#define HS_GO(KERNEL, CT)                                                                          \
+    KERNEL<<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(                                            \
+        (const int32_t *)p.p0, (const CT *)p.p1, (const T *)p.p2, (const CT *)p.p4, sunits, x, (T *)scratch, \
+        (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group)
         if (p.delta) {
-            k_hsell_delta<T><<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(
-                (const int32_t *)p.p0, (const uint32_t *)p.p1, (const T *)p.p2, (const uint32_t *)p.p4, x,
-                (T *)scratch, (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group);
-            break;
+            if (sunits) HS_GO((k_hsell_delta<T, true>), uint32_t);
+            else HS_GO((k_hsell_delta<T, false>), uint32_t);
+        } else {
+            if (sunits) HS_GO((k_hsell<T, true>), uint16_t);
+            else HS_GO((k_hsell<T, false>), uint16_t);
         }
-        k_hsell<T><<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(
-            (const int32_t *)p.p0, (const uint16_t *)p.p1, (const T *)p.p2, (const uint16_t *)p.p4, x,
-            (T *)scratch, (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group);
+#undef HS_GO
         break;
     }
     case K_XS: {
@@ -399,7 +403,7 @@ namespace {
 template <typename T>
 hipError_t raise_lds_limits() {
     const void *fns[] = {
-        (const void *)k_hsell<T>, (const void *)k_hsell_delta<T>, (const void *)k_xl_mul<T>,
+        (const void *)k_hsell<T, false>, (const void *)k_hsell<T, true>, (const void *)k_hsell_delta<T, false>, (const void *)k_hsell_delta<T, true>, (const void *)k_xl_mul<T>,
         (const void *)k_xl_reduce<T, false, false>, (const void *)k_xl_reduce<T, false, true>,
         (const void *)k_xl_reduce<T, true, false>, (const void *)k_xl_reduce<T, true, true>,
 #define XWIN_ALL(B)                                                                               \
@@ -476,7 +480,7 @@ int launch_jit_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T 
     int na = 0;
     // argument storage that outlives the switch
     DiaOffsets o;
-    const void *q0 = p.p0, *q1 = p.p1, *q2 = p.p2, *q3 = p.p3, *q4 = p.p4;
+    const void *q0 = p.p0, *q1 = p.p1, *q2 = p.p2, *q3 = p.p3, *q4 = p.p4, *q5 = p.p5;
     int64_t a64[4];
     int a32[8];
     const T *xx = x;
@@ -524,7 +528,7 @@ int launch_jit_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T 
         block = kHeavyWG;
         lds = ((size_t)p.tile + (size_t)p.nrows) * sizeof(T);
         a32[0] = (int)p.nslices; a32[1] = (int)p.nrows; a32[2] = p.tile; a64[0] = ncols; a32[3] = (int)p.units; a32[4] = (int)p.per_group;
-        P(&q0); P(&q1); P(&q2); P(&q4); P(&xx); P(&sc); P(&a32[0]); P(&a32[1]); P(&a32[2]); P(&a64[0]); P(&a32[3]); P(&a32[4]);
+        P(&q0); P(&q1); P(&q2); P(&q4); P(&q5); P(&xx); P(&sc); P(&a32[0]); P(&a32[1]); P(&a32[2]); P(&a64[0]); P(&a32[3]); P(&a32[4]);
         break;
     case K_REDUCE_WIDE:
         if (p.nrows == 0) return 0;

@@ -268,6 +268,12 @@ static std::vector<PlanSpec> leaf_neighbours(const PlanSpec &b, spmv_dtype_t dty
         PlanSpec p = b;
         p.hd = !b.hd;   // 8-bit column differences pay when the heavy rows are dense enough
         add(p);
+        for (int pc : {0, 16, 32, 64})   // lanes of bounded length: less padding, more lanes
+            if (pc != b.piece) {
+                p = b;
+                p.piece = pc;
+                add(p);
+            }
         p = b;
         p.heavy = b.heavy * 2;
         add(p);

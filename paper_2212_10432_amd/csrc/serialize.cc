@@ -4,7 +4,7 @@
 // codes can be directly called"; artifact description); here the kernels are part of the library,
 // so the file holds the plan spec, the census, the launch list and every format array.
 //
-// Layout (little endian): magic "SPMVPLN1", u64 payload size, u64 FNV-1a hash of the payload, then
+// Layout (little endian): magic "SPMVPLN2", u64 payload size, u64 FNV-1a hash of the payload, then
 // the payload: scalars and strings in the order written by save_plan below, every array as
 // (name, element size, count, flag, raw bytes).  Pointers inside a launch record are stored as
 // indices into the array list (-1: none); scratch buffers are stored as sizes only.
@@ -17,7 +17,7 @@
 namespace spmv {
 namespace {
 
-constexpr char kMagic[8] = {'S', 'P', 'M', 'V', 'P', 'L', 'N', '1'};
+constexpr char kMagic[8] = {'S', 'P', 'M', 'V', 'P', 'L', 'N', '2'};
 
 uint64_t fnv1a(const unsigned char *p, size_t n) {
     uint64_t h = 1469598103934665603ull;
@@ -156,7 +156,7 @@ void save_plan(const Plan &plan, const char *path) {
         w.str(q.name);
         part_scalars(q, [&](int64_t &v) { w.i64(v); });
         w.i64(array_index(p.p0)); w.i64(array_index(p.p1)); w.i64(array_index(p.p2));
-        w.i64(array_index(p.p3)); w.i64(array_index(p.p4));
+        w.i64(array_index(p.p3)); w.i64(array_index(p.p4)); w.i64(array_index(p.p5));
         w.i64(scratch_index(p.scratch));
     }
     w.i64((int64_t)plan.log.size());
@@ -274,7 +274,7 @@ std::unique_ptr<Plan> load_plan(const char *path, const Allocator &mem) {
         part_scalars(q, [&](int64_t &v) { v = r.i64(); });
         if ((int)q.kind < 0 || (int)q.kind > (int)K_LAST) fail(SPMV_ERR_INVALID_ARG, "plan load: unknown launch kind");
         q.p0 = array_ptr(r.i64()); q.p1 = array_ptr(r.i64()); q.p2 = array_ptr(r.i64());
-        q.p3 = array_ptr(r.i64()); q.p4 = array_ptr(r.i64());
+        q.p3 = array_ptr(r.i64()); q.p4 = array_ptr(r.i64()); q.p5 = array_ptr(r.i64());
         const int64_t si = r.i64();
         if (si != -1) {
             if (si < 0 || si >= (int64_t)plan->scratch.size()) fail(SPMV_ERR_INVALID_ARG, "plan load: scratch index out of range");

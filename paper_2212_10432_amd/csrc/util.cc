@@ -192,6 +192,7 @@ static PlanSpec parse_leaf(const std::string &s) {
         else if (k == "heavy") p.heavy = (int64_t)num();
         else if (k == "tile") p.tile = (int)num();
         else if (k == "hd") p.hd = (int)num();
+        else if (k == "piece") p.piece = (int)num();
         else if (k == "lpr") p.lpr = (int)num();
         else if (k == "chunk") p.chunk = (int64_t)num();
         else if (k == "sigma") p.sigma = (int)num();
@@ -229,6 +230,8 @@ static PlanSpec parse_leaf(const std::string &s) {
     if (p.jit != 0 && p.jit != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: jit must be 0 or 1");
     if (p.hd != 0 && p.hd != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: hd must be 0 or 1");
     if (p.hd && !p.heavy) fail(SPMV_ERR_INVALID_ARG, "plan spec: hd needs heavy");
+    if (p.piece < 0 || p.piece > 8192 || (p.piece & 3)) fail(SPMV_ERR_INVALID_ARG, "plan spec: piece must be 0 or a multiple of 4 up to 8192");
+    if (p.piece && !p.heavy) fail(SPMV_ERR_INVALID_ARG, "plan spec: piece needs heavy");
     if (p.xwin != 0 && p.xwin != 1) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin must be 0 or 1");
     if (p.xwin && p.light != L_BSELL) fail(SPMV_ERR_INVALID_ARG, "plan spec: xwin needs light=bsell");
     if (p.light == L_BSELL && (p.dia || p.heavy)) fail(SPMV_ERR_INVALID_ARG, "plan spec: bsell cannot be combined with dia or heavy");
@@ -246,7 +249,11 @@ std::string print_spec(const PlanSpec &p) {
     }
     if (p.dia) o << "dia=1,dia_fill=" << p.dia_fill << ",";
     if (p.dia && p.drows != 1) o << "drows=" << p.drows << ",";
-    if (p.heavy) o << "heavy=" << p.heavy << ",tile=" << p.tile << (p.hd ? ",hd=1," : ",");
+    if (p.heavy) {
+        o << "heavy=" << p.heavy << ",tile=" << p.tile << (p.hd ? ",hd=1" : "");
+        if (p.piece) o << ",piece=" << p.piece;
+        o << ",";
+    }
     o << "light=" << light_name(p.light);
     switch (p.light) {
     case L_CSRV: o << ",lpr=" << p.lpr << ",chunk=" << p.chunk << ",sigma=" << p.sigma; break;
@@ -302,7 +309,8 @@ static std::string leaf_chain(const PlanSpec &p, bool root) {
     if (p.dia) o << " -> DIA_EXTRACT(fill>=" << p.dia_fill << ")[BMT_ROW_BLOCK(" << p.drows << ") -> THREAD_TOTAL_RED]";
     if (p.heavy)
         o << " -> ROW_DIV(len>" << p.heavy << ")[HEAVY_SPLIT: COL_DIV(" << p.tile
-          << ") -> BMTB_COL_BLOCK -> SORT_BMTB -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD"
+          << ") -> BMTB_COL_BLOCK" << (p.piece ? " -> BMT_COL_BLOCK(" + std::to_string(p.piece) + ")" : std::string())
+          << " -> SORT_BMTB -> BMW_ROW_BLOCK(64) -> BMT_ROW_BLOCK(1) -> BMW_PAD"
           << (p.hd ? " -> COMPRESS(8-bit column deltas)" : "")
           << " -> THREAD_TOTAL_RED -> GMEM_ATOM_RED]";
     auto sort = [&]() {

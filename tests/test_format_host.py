@@ -24,11 +24,13 @@ SPECS = {
     "C2": ["dia=1,dia_fill=0.999,light=wbm", "dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=256,rb=128", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2", "dia=1,dia_fill=0.999,light=csrv,lpr=1"],
     "C3": ["light=wbm", "heavy=1024,tile=2048,light=wbm", "light=bin,smax=16,sigma=512,chunk=256,wg=1", "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=0,wg=1", "light=csrv,lpr=256,chunk=512", "light=xl,w=512,rb=1024", "heavy=1024,tile=2048,light=xl,w=1024,rb=512,chunk=2048", "light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=0", "light=csrv,chunk=512", "light=bin,smax=16,sigma=512,chunk=256",
            "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
-           "heavy=256,tile=512,light=sell,sigma=128", "heavy=1024,tile=2048,hd=1,light=xl,w=1024,rb=512", "heavy=256,tile=512,hd=1,light=sell,sigma=128"],
+           "heavy=256,tile=512,light=sell,sigma=128", "heavy=1024,tile=2048,hd=1,light=xl,w=1024,rb=512", "heavy=256,tile=512,hd=1,light=sell,sigma=128",
+           "heavy=256,tile=512,piece=16,light=sell,sigma=128", "heavy=1024,tile=2048,hd=1,piece=32,light=xl,w=1024,rb=512", "heavy=64,tile=4096,piece=4,light=csrv"],
     "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", "light=sell,sigma=512",
            "light=csrv,lpr=16"],
     "C5": ["heavy=64,tile=2048,light=wbm", "light=bin,smax=16,sigma=256,chunk=1024,wg=1", "heavy=64,tile=2048,light=xl,w=2048,rb=4096,chunk=4096", "light=xl,w=4096,rb=16384", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
-           "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=64,tile=2048,hd=1,light=xl", "heavy=64,tile=8192,hd=1,light=csrv"],
+           "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=64,tile=2048,hd=1,light=xl", "heavy=64,tile=8192,hd=1,light=csrv",
+           "heavy=64,tile=8192,hd=1,piece=64,light=csrv", "heavy=64,tile=2048,piece=8,light=xl,w=2048,rb=4096"],
 }
 
 
@@ -194,6 +196,32 @@ def test_closed_form_hybrid_heavy_split_selects_the_generated_rows():
         assert "zero.rows" not in a          # heavy rows are summed from scratch, not through atomics
 
 
+def test_closed_form_pieces_of_full_rows_need_no_padding():
+    """Heavy rows of equal length cut into pieces that divide it: every lane is full, and the count of
+    units per stripe follows from the counts alone.  20 rows of 4096 entries in one stripe make 20480
+    pieces of 4, more than a stripe's 8192 lanes, so the piece length doubles to 16 (5120 lanes)."""
+    nh, L, nlight = 20, 4096, 300
+    lens = np.concatenate([np.full(nh, L), np.full(nlight, 2)])
+    rp = np.zeros(lens.size + 1, np.int32)
+    np.cumsum(lens, out=rp[1:])
+    ci = np.concatenate([np.tile(np.arange(L), nh), np.tile([1, 7], nlight)]).astype(np.int32)
+    va = np.arange(1, rp[-1] + 1, dtype=np.float32)
+    for piece, eff in ((4, 16), (64, 64), (4096, 4096)):
+        spec = f"heavy=64,tile=8192,piece={piece},light=csrv"
+        P = lib.Plan(lens.size, L, rp, ci, va, force_plan=spec, host_only=True)
+        a = P.arrays()
+        lanes = nh * L // eff
+        units = -(-lanes // 64)
+        assert np.array_equal(a["heavy.sunits"], [0, units])
+        assert a["heavy.vals"].size == units * 64 * eff and np.count_nonzero(a["heavy.vals"]) == nh * L
+        assert np.array_equal(np.diff(a["heavy.unit_ptr"]), np.full(units, 64 * eff))
+        assert np.array_equal(a["heavy.lane_row"][:lanes], np.repeat(np.arange(nh), L // eff))   # stable order: row by row
+        want = ref.ref_plan(lens.size, L, rp, ci, va, spec)
+        for k in want:
+            assert np.array_equal(a[k], want[k]), k
+        P.destroy()
+
+
 def test_duplicates_and_unsorted_columns_are_accepted():
     rng = np.random.default_rng(5)
     nrows, ncols = 300, 300
@@ -242,7 +270,7 @@ def test_errors():
     with pytest.raises(E) as e:
         lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan="light=csrv", nnz=m.nnz - 1)
     assert e.value.status == lib.SPMV_ERR_BAD_CSR
-    for spec in ("light=nope", "lpr=3", "tile=100", "sigma=-2", "block=5", "foo=1", "light", "heavy=4,light=bsell"):
+    for spec in ("light=nope", "lpr=3", "tile=100", "sigma=-2", "block=5", "foo=1", "light", "heavy=4,light=bsell", "piece=16,light=csrv", "heavy=64,piece=6,light=csrv"):
         with pytest.raises(E) as e:
             lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan=spec)
         assert e.value.status == lib.SPMV_ERR_INVALID_ARG, spec
@@ -286,7 +314,8 @@ def test_random_matrices_random_plans_decode_to_input():
         ci = ci.astype(np.int32)
         va = rng.integers(1, 9, rp[-1]).astype(np.float64)
         A_in = as_scipy(nrows, ncols, r, ci, va)
-        head = f"heavy={int(rng.choice([8, 30]))},tile={int(rng.choice([64, 256]))}," + ("hd=1," if rng.random() < 0.5 else "") if rng.random() < 0.6 else ""
+        head = (f"heavy={int(rng.choice([8, 30]))},tile={int(rng.choice([64, 256]))}," + ("hd=1," if rng.random() < 0.5 else "")
+                + (f"piece={int(rng.choice([4, 8, 16]))}," if rng.random() < 0.5 else "")) if rng.random() < 0.6 else ""
         spec = head + "light=" + str(rng.choice(lights))
         try:
             P = lib.Plan(nrows, ncols, rp, ci, va, force_plan=spec, host_only=True)
