@@ -538,7 +538,9 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total, skip=()):
     inside a run; a run is padded to a whole 16-byte vector (N = 2 doubles / 4 floats), a window to 16
     entries, with (value 0, local column 0).
     items: (window, first entry, end entry) pieces of a window's entries, m = ceil(len / chunk)
-    pieces of ceil16(ceil(len / m)) entries; chunk 0 means 32768.
+    pieces of ceil16(ceil(len / m)) entries; chunk 0 means 128 KiB of values.  Item i runs on XCD i mod 8: a window's
+    items all go, one after the other, to the XCD that has the fewest items so far (lowest on a tie), the
+    eight sequences are interleaved and the shorter ones filled with empty items (0, 0, 0).
     glist: for block b the groups of runs (0, b), (1, b), ...: a run cut into groups of up to 16
     entries, a list entry being 8 * (first entry // N) + (entries in the group // N - 1); gptr: the
     list's offsets per block.  lrow is stored in list order, 16 slots per group: lrow[16 p + t] is the
@@ -577,16 +579,21 @@ def ref_xl(ncols, rp, ci, va, rows, W, RB, chunk, nrows_total, skip=()):
     vals[dst] = va[src[order]]
     lcol[dst] = (c[order] % W).astype(np.uint16)
     lrow_by_entry[dst] = (pos_of_entry[order] % RB).astype(np.uint16)
-    chunk = ceil_to(chunk, G) if chunk > 0 else 32768
-    items = []
+    chunk = ceil_to(chunk, G) if chunk > 0 else 131072 // va.dtype.itemsize
+    per_xcd = [[] for _ in range(8)]              # items whose number is k mod 8 run on XCD k
     for s_ in range(S):
         b0, e0 = int(wstart[s_]), int(wstart[s_ + 1])
         if e0 == b0:
             continue
         m = -(-(e0 - b0) // chunk)
         per = ceil_to(-(-(e0 - b0) // m), G)
+        k = min(range(8), key=lambda q: (len(per_xcd[q]), q))   # the XCD with the fewest items so far
         for cpos in range(b0, e0, per):
-            items += [s_, cpos, min(e0, cpos + per)]
+            per_xcd[k].append([s_, cpos, min(e0, cpos + per)])
+    items = []
+    for j in range(max(len(q) for q in per_xcd)):
+        for q in per_xcd:
+            items += q[j] if j < len(q) else [0, 0, 0]
     gptr = np.zeros(B + 1, dtype=np.int32)
     glist, lrow = [], []
     for b in range(B):

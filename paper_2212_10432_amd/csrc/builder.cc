@@ -1109,7 +1109,7 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
 // would cost 7.5 entries per run, a tenth of everything this part streams when the runs are short.
 // Entry g holds vals[g] and lcol[g] = c - s*W; its product goes to scratch[g].  The multiply launch
 // works through items (s, first entry, end entry): a window's entries cut into equal pieces of at most
-// `chunk` entries (32768 unless the spec says otherwise), multiples of 16.
+// `chunk` entries (128 KiB of values unless the spec says otherwise), multiples of 16.
 // The reduce launch of block b adds the groups glist[gptr[b]] .. glist[gptr[b+1] - 1]: the runs (0, b),
 // (1, b), ... in that order, each cut into groups of up to 16 entries; a list entry is
 // 8 * (first entry / N) + (entries in the group / N - 1).  The local rows i - b*RB are stored in list
@@ -1213,20 +1213,36 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
             lcol[g] = 0;
         }
     }
-    // items of the multiply launch
-    const int64_t chunk = chunk_spec > 0 ? (chunk_spec + G - 1) / G * G : 32768;
-    std::vector<int32_t> items;
+    // Items of the multiply launch.  Workgroup i runs on XCD i mod 8, and every XCD has an L2 of its own:
+    // all items of a window get numbers of one residue mod 8, one after the other, so that only the
+    // first of them stages the window from memory and the others find it in that XCD's L2.  Windows are
+    // dealt, in order, to the residue with the fewest items so far (the lowest on a tie); residues that
+    // end up shorter are filled with empty items (0, 0, 0), which return at once.
+    const int64_t chunk = chunk_spec > 0 ? (chunk_spec + G - 1) / G * G : 131072 / (int64_t)sizeof(T);
+    std::vector<int32_t> lane_items[8];
+    int64_t staged = 0;   // elements of x that one launch brings in from memory: every non-empty window once
     for (int64_t s = 0; s < S; ++s) {
         const int64_t b0 = start[(size_t)(s * B)], e0 = start[(size_t)((s + 1) * B)];
         if (e0 == b0) continue;
+        staged += std::min<int64_t>(W, A.ncols - s * W);
         const int64_t m = (e0 - b0 + chunk - 1) / chunk;
         const int64_t per = ((e0 - b0 + m - 1) / m + G - 1) / G * G;
+        int l = 0;
+        for (int k = 1; k < 8; ++k)
+            if (lane_items[k].size() < lane_items[l].size()) l = k;
         for (int64_t c = b0; c < e0; c += per) {
-            items.push_back((int32_t)s);
-            items.push_back((int32_t)c);
-            items.push_back((int32_t)std::min(e0, c + per));
+            lane_items[l].push_back((int32_t)s);
+            lane_items[l].push_back((int32_t)c);
+            lane_items[l].push_back((int32_t)std::min(e0, c + per));
         }
     }
+    size_t longest = 0;
+    for (int k = 0; k < 8; ++k) longest = std::max(longest, lane_items[k].size() / 3);
+    std::vector<int32_t> items;
+    items.reserve(longest * 24);
+    for (size_t j = 0; j < longest; ++j)
+        for (int k = 0; k < 8; ++k)
+            for (int t = 0; t < 3; ++t) items.push_back(3 * j + t < lane_items[k].size() ? lane_items[k][3 * j + t] : 0);
     const int64_t nitems = (int64_t)items.size() / 3;
     void *scratch = plan.mem.alloc((size_t)std::max<int64_t>(tot, 1) * sizeof(T), plan.mem.user);
     if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the xl part's scratch failed");
@@ -1248,9 +1264,6 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
         p.units = nitems;
         p.tile = (int)W;
         p.scratch = scratch;
-        int64_t staged = 0;   // elements of x copied into LDS by one launch: a window per item
-        for (int64_t it = 0; it < nitems; ++it)
-            staged += std::min<int64_t>(W, A.ncols - (int64_t)items[(size_t)(3 * it)] * W);
         const size_t a1 = plan.arrays.size();
         p.p0 = upload(plan, "xl.items", 4, 3 * nitems, items.data());
         p.p1 = upload(plan, "xl.vals", (int)sizeof(T), tot, vals.p);

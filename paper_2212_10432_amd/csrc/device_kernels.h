@@ -1353,8 +1353,11 @@ template <> struct XlVec<float> { typedef xl_f4 V; typedef xl_u4 I; static const
 constexpr int kXlWG = 1024;
 // item i = (window, first entry, end entry); both entry numbers are multiples of 16.  One workgroup
 // per item, each staging its window of x: workgroups that walk several items of a window and stage it
-// once were measured to be slower (the copies of x come from the memory-side cache, and many short
-// workgroups overlap one workgroup's staging with another's streaming).
+// once were measured to be slower (many short workgroups overlap one workgroup's staging with
+// another's streaming, and the end of the launch is less ragged).  The items of a window follow each
+// other on one XCD (item number mod 8), so all but the first stage from that XCD's L2; issuing the
+// first loads of the stream before the staging, or keeping two steps in flight, was measured to
+// change nothing.
 template <typename T>
 __global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ item,
                                                   const T *__restrict__ vals,
@@ -1370,6 +1373,7 @@ __global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ it
     T *xs = reinterpret_cast<T *>(smem);
     const int s = item[3 * blockIdx.x];
     const int64_t b = item[3 * blockIdx.x + 1], e = item[3 * blockIdx.x + 2];
+    if (b >= e) return;   // a filler item (uniform over the workgroup)
     const int64_t c0 = (int64_t)s * W;
     const int w = (int)((ncols - c0) < (int64_t)W ? (ncols - c0) : (int64_t)W);
     for (int i = threadIdx.x; i < w; i += kXlWG) xs[i] = x[c0 + i];

@@ -309,7 +309,7 @@ static std::vector<PlanSpec> leaf_neighbours(const PlanSpec &b, spmv_dtype_t dty
         p = b;
         p.rb = b.rb * 2;
         if ((int64_t)p.rb * 8 <= kXlMaxLds) add(p);
-        const int64_t ch = b.chunk ? b.chunk : 32768;
+        const int64_t ch = b.chunk ? b.chunk : 131072 / vsize;
         p = b;
         p.chunk = ch * 2;
         add(p);

@@ -222,6 +222,35 @@ def test_closed_form_pieces_of_full_rows_need_no_padding():
         P.destroy()
 
 
+def test_two_pass_items_keep_a_window_on_one_xcd():
+    """Item i of the multiply launch runs on XCD i mod 8: every window's pieces share one residue and follow
+    each other there; the pieces of a window tile its entries; fillers are empty and only at the ends."""
+    m = TINY["C3"]()
+    for spec in ("light=xl,w=256,rb=1024,chunk=64", "light=xl,w=512,rb=512,chunk=4096"):
+        P = host_plan(m, spec)
+        it = P.arrays()["xl.items"].reshape(-1, 3)
+        assert it.shape[0] % 8 == 0
+        real = it[:, 2] > it[:, 1]
+        assert np.all(it[~real] == 0)
+        seen = {}
+        for k in range(8):
+            lane = it[k::8]
+            r = real[k::8]
+            assert not np.any(r[np.argmin(r):]) or np.all(r)       # fillers only after the last real item
+            lane = lane[r]
+            w = lane[:, 0]
+            change = np.flatnonzero(np.diff(w)) + 1
+            for seg in np.split(np.arange(len(w)), change):
+                assert int(w[seg[0]]) not in seen                   # a window appears in one place only
+                seen[int(w[seg[0]])] = k
+                assert np.array_equal(lane[seg[1:], 1], lane[seg[:-1], 2])   # pieces are adjacent
+        counts = [int(real[k::8].sum()) for k in range(8)]
+        per_window = np.bincount(it[real, 0])
+        assert max(counts) - min(counts) <= per_window.max()        # dealt to the shortest sequence
+        assert int((it[real, 2] - it[real, 1]).sum()) == P.arrays()["xl.vals"].size
+        P.destroy()
+
+
 def test_duplicates_and_unsorted_columns_are_accepted():
     rng = np.random.default_rng(5)
     nrows, ncols = 300, 300
