@@ -1089,7 +1089,9 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
 // a lane owns one (row, stripe) segment, gathers x from LDS through 16-bit local columns and keeps
 // its sum in a register (THREAD_TOTAL_RED).  The sums of a workgroup meet in an LDS accumulator per
 // heavy row (the shared-memory reduction by row of SHMEM_OFFSET_RED, the "offset" being the lane's
-// row id); a row occurs once per stripe, so no two lanes touch an accumulator between barriers.
+// row id); a row occurs once per stripe, so no two lanes touch an accumulator between barriers
+// (PIECES: a segment is cut into several lanes of bounded length, a row may occur in many lanes of a
+// stripe and the sums are added with LDS atomics; sunits[s] is then the stripe's first unit).
 // The workgroup then writes its nh partial sums to scratch and k_reduce_wide adds them up: global
 // atomics (GMEM_ATOM_RED) would be several times slower here, since hundreds of workgroups would
 // hit the same few thousand y elements.
@@ -1416,7 +1418,10 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
     double *acc = reinterpret_cast<double *>(smem);
     for (int i = threadIdx.x; i < RB; i += kXlWG) acc[i] = 0.0;
     __syncthreads();
-    const int64_t blk = blockIdx.x;
+    // Neighbouring blocks run on one XCD (workgroup i is on XCD i mod 8): the runs of blocks b and b + 1
+    // of a window are adjacent in memory and share a cache line where they meet, and two workgroups
+    // that started together reach it at about the same time (C5: 95 -> 89 us).
+    const int64_t blk = logical_block(blockIdx.x, gridDim.x, 1);
     const int32_t g0 = (int32_t)JIT_GPTR(gptr, blk), g1 = (int32_t)JIT_GPTR(gptr, blk + 1);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane / LPG, l = lane % LPG;
     const V *pv = reinterpret_cast<const V *>(prod);
