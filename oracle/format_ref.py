@@ -669,6 +669,15 @@ def _ref_leaf(nrows, ncols, rp, ci, va, p, rows, whole, acc, span) -> dict:
         if not acc and owner is not None:
             owner = np.asarray(owner, dtype=np.int32)
             out.update(ref_xl(ncols, rp, ci, va, owner, p["w"], p["rb"], p["chunk"], nrows, skip=np.setdiff1d(owner, light)))
+            if heavy.size:
+                # this part's reduce launch also adds the heavy part's partial sums: per block of RB part
+                # positions the range of heavy rows in it (hptr) and their local rows (hloc)
+                pos = np.searchsorted(owner, heavy)
+                assert np.array_equal(owner[pos], heavy)
+                nblocks = -(-owner.size // p["rb"])
+                hptr = np.concatenate([[0], np.cumsum(np.bincount(pos // p["rb"], minlength=nblocks))]).astype(np.int32)
+                out["xl.hptr"] = hptr
+                out["xl.hloc"] = (pos % p["rb"]).astype(np.uint16)
         else:
             out.update(ref_xl(ncols, rp, ci, va, light, p["w"], p["rb"], p["chunk"], nrows))
     elif p["light"] == "xs":

@@ -296,15 +296,15 @@ spmv_status_t spmv_run_noalloc(const spmv_plan_t *plan, const void *x_dev, void 
         const int err = static_scratch(&base);
         if (err) fail(SPMV_ERR_HIP, std::string("spmv_run_noalloc: static scratch unavailable: ") + hip_error_text(err));
     }
+    auto placed = [&](const void *own) -> void * {
+        if (!own) return nullptr;
+        size_t i = 0;
+        while (i < p.scratch.size() && owned[i] != own) ++i;
+        if (i == p.scratch.size()) fail(SPMV_ERR_INTERNAL, "spmv_run_noalloc: a launch refers to an unknown scratch buffer");
+        return (unsigned char *)base + offset[i];
+    };
     for (const Part &part : p.parts) {
-        void *over = nullptr;
-        if (part.scratch) {
-            size_t i = 0;
-            while (i < p.scratch.size() && owned[i] != part.scratch) ++i;
-            if (i == p.scratch.size()) fail(SPMV_ERR_INTERNAL, "spmv_run_noalloc: a launch refers to an unknown scratch buffer");
-            over = (unsigned char *)base + offset[i];
-        }
-        const int err = launch_part(part, p.dtype, p.nrows, p.ncols, x_dev, y_dev, stream, over);
+        const int err = launch_part(part, p.dtype, p.nrows, p.ncols, x_dev, y_dev, stream, placed(part.scratch), placed(part.scratch2));
         if (err) fail(SPMV_ERR_HIP, std::string("launch of ") + part.name + " failed: " + hip_error_text(err));
     }
     return SPMV_OK;

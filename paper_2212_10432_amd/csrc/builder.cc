@@ -485,6 +485,17 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
     (void)real_blocks;
 }
 
+// A heavy part whose partial sums are added by the two-pass reduce launch of the same leaf instead
+// of a launch of their own.
+struct HeavyFold {
+    // made by the leaf: heavy rows hptr[b] .. hptr[b+1]-1 lie in block b of the two-pass part, at local rows hloc
+    std::vector<int32_t> hptr;
+    std::vector<uint16_t> hloc;
+    // made by the heavy part: workgroup g leaves the sum of heavy row h at partial[g * nh + h]
+    void *partial = nullptr;
+    int64_t ngroups = 0;
+};
+
 // ---- heavy rows in column stripes --------------------------------------------------------------
 // COL_DIV into stripes of `tile` columns; inside a stripe SORT_BMTB orders the heavy rows by the
 // number of entries they have there (stable, decreasing), slices of 64 rows are padded to their
@@ -506,7 +517,7 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
 // array).  A stripe that would need more than 8192 lanes doubles its P until it does not.
 template <typename T>
 void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrows, int tile, int delta, int piece,
-                  bool acc, const std::vector<int64_t> &lens, int threads) {
+                  bool acc, const std::vector<int64_t> &lens, int threads, HeavyFold *fold = nullptr) {
     const int64_t nh = (int64_t)hrows.size();
     if (nh == 0) return;
     if ((size_t)tile * sizeof(T) > 65536) fail(SPMV_ERR_UNSUPPORTED, "heavy: tile does not fit 64 KiB of LDS");
@@ -671,7 +682,12 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     if (piece > 0) p.p5 = upload(plan, "heavy.sunits", 4, ns + 1, sunits.data());
     plan.arrays[a0 + 3].read_per_run = false;   // heavy.rows is read by the reduce launch
     add_part(plan, p, a0, A.ncols, ngroups * nh, 0);
-    plan.arrays[a0 + 3].read_per_run = true;
+    plan.arrays[a0 + 3].read_per_run = fold == nullptr;
+    if (fold) {   // the two-pass reduce launch of the same leaf adds the partial sums
+        fold->partial = scratch;
+        fold->ngroups = ngroups;
+        return;
+    }
     Part r;   // sums the workgroups' partial sums into y (overwrites, or adds after a DIA part)
     r.kind = K_REDUCE_WIDE;
     r.name = "heavy.reduce";
@@ -1120,7 +1136,8 @@ void build_xnb(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, i
 // y written contiguously; the other part's launch overwrites those y elements afterwards).
 template <typename T>
 void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, int w_spec, int RB,
-              int64_t chunk_spec, bool acc, const std::vector<int64_t> &lens, int threads) {
+              int64_t chunk_spec, bool acc, const std::vector<int64_t> &lens, int threads,
+              const HeavyFold *fold = nullptr) {
     const int64_t n = (int64_t)rows.size();
     if (n == 0) return;
     const bool ident = is_identity(rows, A.nrows);
@@ -1284,7 +1301,20 @@ void build_xl(Plan &plan, const HostCsr &A, const std::vector<int32_t> &rows, in
     r.p1 = upload(plan, "xl.glist", 4, ngroups, glist.p);
     r.p2 = upload(plan, "xl.lrow", 2, ngroups * G, lrow.p);
     if (!ident) r.p3 = upload(plan, "xl.rows", 4, n, rows.data());
-    add_part(plan, r, a2, 0, tot, n);
+    int64_t partials = 0;
+    if (fold) {
+        // the leaf's heavy rows are rows of this part (without entries): block b adds the heavy
+        // launch's partial sums of the heavy rows hptr[b] .. hptr[b+1]-1, whose local rows are hloc
+        if ((int64_t)fold->hptr.size() != B + 1) fail(SPMV_ERR_INTERNAL, "xl: heavy rows counted for other row blocks");
+        const int64_t nh = (int64_t)fold->hloc.size();
+        r.p4 = upload(plan, "xl.hptr", 4, B + 1, fold->hptr.data());
+        r.p5 = upload(plan, "xl.hloc", 2, nh, fold->hloc.data());
+        r.scratch2 = fold->partial;
+        r.ngroups = fold->ngroups;
+        r.nslices = nh;
+        partials = fold->ngroups * nh;
+    }
+    add_part(plan, r, a2, 0, tot + partials, n);
 }
 
 // ---- XCD-striped SELL ----------------------------------------------------------------------------
@@ -1544,6 +1574,7 @@ void build_leaf(Plan &plan, const HostCsr &A0, const Census &cen, const PlanSpec
     // rows reduced through atomics are zeroed by the first launch
     std::vector<int32_t> zero_rows;
     const size_t zero_slot = plan.parts.size();
+    bool heavy_done = false;
     // (heavy rows are written by their own reduce launch and need no zeroing)
 
     switch (spec.light) {
@@ -1577,7 +1608,22 @@ void build_leaf(Plan &plan, const HostCsr &A0, const Census &cen, const PlanSpec
         if (!acc && owner) {
             std::vector<int64_t> lens_light((size_t)A.nrows, 0);
             for (int32_t r : light) lens_light[(size_t)r] = lens[(size_t)r];
-            build_xl<T>(plan, A, *owner, spec.w, spec.rb, spec.chunk, acc, lens_light, threads);
+            // the heavy part runs first and leaves its partial sums to this part's reduce launch
+            HeavyFold fold;
+            if (!heavy.empty()) {
+                const int64_t nb = ((int64_t)owner->size() + spec.rb - 1) / spec.rb;
+                fold.hptr.assign((size_t)nb + 1, 0);
+                fold.hloc.resize(heavy.size());
+                for (size_t h = 0; h < heavy.size(); ++h) {
+                    const int64_t pos = std::lower_bound(owner->begin(), owner->end(), heavy[h]) - owner->begin();
+                    fold.hptr[(size_t)(pos / spec.rb) + 1] += 1;
+                    fold.hloc[h] = (uint16_t)(pos % spec.rb);
+                }
+                for (int64_t b = 0; b < nb; ++b) fold.hptr[(size_t)b + 1] += fold.hptr[(size_t)b];
+                build_stripe<T>(plan, A, heavy, spec.tile, spec.hd, spec.piece, acc, lens, threads, &fold);
+                heavy_done = true;
+            }
+            build_xl<T>(plan, A, *owner, spec.w, spec.rb, spec.chunk, acc, lens_light, threads, heavy.empty() ? nullptr : &fold);
         } else {
             build_xl<T>(plan, A, light, spec.w, spec.rb, spec.chunk, acc, lens, threads);
         }
@@ -1601,7 +1647,7 @@ void build_leaf(Plan &plan, const HostCsr &A0, const Census &cen, const PlanSpec
     }
     default: fail(SPMV_ERR_INVALID_ARG, "unknown light design");
     }
-    if (!heavy.empty()) build_stripe<T>(plan, A, heavy, spec.tile, spec.hd, spec.piece, acc, lens, threads);
+    if (!heavy.empty() && !heavy_done) build_stripe<T>(plan, A, heavy, spec.tile, spec.hd, spec.piece, acc, lens, threads);
 
     if (!zero_rows.empty()) {
         std::sort(zero_rows.begin(), zero_rows.end());

@@ -1402,13 +1402,23 @@ __global__ __launch_bounds__(kXlWG) void k_xl_mul(const int32_t *__restrict__ it
 // A group is up to 16 consecutive entries of one run, starting at any multiple of N entries.
 // lrow is stored in list order, 16 slots per listed group: lrow[16*p + t] is the local row of entry
 // N*(glist[p] >> 3) + t.
-template <typename T, bool ROWS, bool ACC>
+//
+// HEAVY: the leaf also has a heavy part whose rows this part owns as rows without entries.  Block blk
+// then adds, for its heavy rows hptr[blk] .. hptr[blk + 1] - 1 (local row hloc[h]), the np partial
+// sums hpartial[g * nh + h] that the heavy launch's workgroups left, so that no launch of its own is
+// needed for them (a launch that lives on latency: 8 to 10 us for a few megabytes).  A lane loads two
+// of them with every step's products and adds them with those, so their latency costs nothing; what
+// the steps do not cover is added at the end.
+template <typename T, bool ROWS, bool ACC, bool HEAVY>
 __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__ gptr,
                                                      const int32_t *__restrict__ glist,
                                                      const T *__restrict__ prod,
                                                      const uint16_t *__restrict__ lrow,
                                                      const int32_t *__restrict__ rows,
-                                                     T *__restrict__ y, int RB_arg, int64_t n_arg) {
+                                                     T *__restrict__ y, int RB_arg, int64_t n_arg,
+                                                     const int32_t *__restrict__ hptr,
+                                                     const uint16_t *__restrict__ hloc,
+                                                     const T *__restrict__ hpartial, int np, int nh) {
     const int RB = JIT_XLR_RB(RB_arg);
     const int64_t n = JIT_XLR_N(n_arg);
     typedef typename XlVec<T>::V V;
@@ -1424,6 +1434,15 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
     const int64_t blk = logical_block(blockIdx.x, gridDim.x, 1);
     const int32_t g0 = (int32_t)JIT_GPTR(gptr, blk), g1 = (int32_t)JIT_GPTR(gptr, blk + 1);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane / LPG, l = lane % LPG;
+    // partial sum i of the block: workgroup i / nhb of the heavy launch, heavy row h0 + i % nhb;
+    // lane t takes the partial sums t, t + 1024, ...: the q-th of them is number hq
+    constexpr int HK = 2;
+    int h0 = 0, nhb = 0, htot = 0, hq = 0;
+    if (HEAVY) {
+        h0 = hptr[blk];
+        nhb = hptr[blk + 1] - h0;
+        htot = nhb * np;
+    }
     const V *pv = reinterpret_cast<const V *>(prod);
     const I *pr = reinterpret_cast<const I *>(lrow);
     int32_t base = g0 + wave * kWave;
@@ -1434,6 +1453,21 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
         V v[IT];
         I r[IT];
         bool ok[IT];
+        T hv[HK];
+        int hl[HK];
+        if (HEAVY) {
+#pragma unroll
+            for (int u = 0; u < HK; ++u) {
+                const int i = (hq + u) * kXlWG + (int)threadIdx.x;
+                hl[u] = -1;
+                if (i < htot) {
+                    const int g = i / nhb, j = i - g * nhb;
+                    hl[u] = hloc[h0 + j];
+                    hv[u] = ldnt(hpartial + (int64_t)g * nh + h0 + j);
+                }
+            }
+            hq += HK;
+        }
 #pragma unroll
         for (int u = 0; u < IT; ++u) {
             const int32_t gid = __shfl(mine, u * GPI + sub, kWave);
@@ -1451,8 +1485,19 @@ __global__ __launch_bounds__(kXlWG) void k_xl_reduce(const int32_t *__restrict__
 #pragma unroll
                 for (int k = 0; k < N; ++k) atomic_add(&acc[r[u][k]], (double)v[u][k]);
             }
+        if (HEAVY) {
+#pragma unroll
+            for (int u = 0; u < HK; ++u)
+                if (hl[u] >= 0) atomic_add(&acc[hl[u]], (double)hv[u]);
+        }
         base = nbase;
         mine = next;
+    }
+    if (HEAVY) {
+        for (int i = hq * kXlWG + (int)threadIdx.x; i < htot; i += kXlWG) {
+            const int g = i / nhb, j = i - g * nhb;
+            atomic_add(&acc[hloc[h0 + j]], (double)ldnt(hpartial + (int64_t)g * nh + h0 + j));
+        }
     }
     __syncthreads();
     if (!ROWS && (reinterpret_cast<uintptr_t>(y) & 15) == 0) {

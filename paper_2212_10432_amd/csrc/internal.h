@@ -162,6 +162,7 @@ struct Part {
     int64_t ngroups = 0;         // heavy part: workgroups (= partial-sum rows in scratch)
     int64_t per_group = 0;       // heavy part: stripes per workgroup
     void *scratch = nullptr;     // partial sums written by one launch and read by the next
+    void *scratch2 = nullptr;    // two-pass reduce that also sums a heavy part: that part's partial sums
     int uniform_w = -1;          // sell / csrv: width shared by every slice / row (-1: read the offsets)
                                  // bsell with an x window: 1 = a group's block rows lie in its own range
     int delta = 0;               // heavy part: columns stored as 8-bit deltas
@@ -212,9 +213,9 @@ std::unique_ptr<Plan> build_plan(const HostCsr &A, const Census &cen, const Plan
                                  const Allocator &mem, int threads);
 
 // Kernel launchers (kernels.hip).  Returns a hipError_t as int.
-// scratch_override, when not NULL, replaces the part's own scratch buffer.
+// scratch_override / scratch2_override, when not NULL, replace the part's own scratch buffers.
 int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
-                void *y, void *stream, void *scratch_override = nullptr);
+                void *y, void *stream, void *scratch_override = nullptr, void *scratch2_override = nullptr);
 // The same launch for k = 2, 4 or 8 right-hand sides stored ldx / ldy elements apart; returns -1 when
 // the part has no fused multi-vector kernel (the caller runs the vectors one by one).
 int launch_part_multi(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
@@ -225,7 +226,8 @@ int launch_part_multi(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t 
 bool jit_describe(const Plan &plan, const Part &p, std::string &kernel, std::string &defines);
 void jit_compile_plan(Plan &plan);
 bool plan_wants_jit(const PlanSpec &spec);
-int launch_jit(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x, void *y, void *stream, void *scratch);
+int launch_jit(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x, void *y, void *stream, void *scratch,
+               void *scratch2);
 void jit_release_plan(Plan &plan);
 int jit_check_plan(const Plan &plan, std::string &log);
 // Once per device, when a plan is created there: raises the dynamic-LDS limit of the kernels that

@@ -96,7 +96,7 @@ bool jit_describe(const Plan &plan, const Part &p, std::string &kernel, std::str
         def("XL_NCOLS", plan.ncols);
         break;
     case K_XL_REDUCE:
-        k << "spmv::dev::k_xl_reduce<" << T << ", " << B(p.has_rows) << ", " << B(p.accumulate) << ">";
+        k << "spmv::dev::k_xl_reduce<" << T << ", " << B(p.has_rows) << ", " << B(p.accumulate) << ", " << B(p.p4 != nullptr) << ">";
         defi("XLR_RB", p.tile);
         def("XLR_N", p.nrows);
         model("GPTR", p.p0);

@@ -68,7 +68,7 @@ int launch_multi_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, 
 
 // -------------------------------------------------------------------------------------------
 template <typename T>
-int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, hipStream_t st, void *scratch) {
+int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, hipStream_t st, void *scratch, void *scratch2) {
     auto blocks = [](int64_t items, int64_t per) { return (unsigned)((items + per - 1) / per); };
     switch (p.kind) {
     case K_ZERO: {
@@ -308,14 +308,21 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
     case K_XL_REDUCE: {
         if (p.units == 0) return 0;
         const size_t lds = (size_t)p.tile * sizeof(double);
-#define XLR_GO(Rw, A)                                                                              \
+#define XLR_GO(Rw, A, H)                                                                           \
     {                                                                                              \
-        k_xl_reduce<T, Rw, A><<<(unsigned)p.units, kXlWG, lds, st>>>(                              \
+        k_xl_reduce<T, Rw, A, H><<<(unsigned)p.units, kXlWG, lds, st>>>(                           \
             (const int32_t *)p.p0, (const int32_t *)p.p1, (const T *)scratch,                    \
-            (const uint16_t *)p.p2, (const int32_t *)p.p3, y, p.tile, p.nrows);                    \
+            (const uint16_t *)p.p2, (const int32_t *)p.p3, y, p.tile, p.nrows,                     \
+            (const int32_t *)p.p4, (const uint16_t *)p.p5, (const T *)scratch2, (int)p.ngroups,    \
+            (int)p.nslices);                                                                       \
     }
-        if (p.has_rows) { if (p.accumulate) XLR_GO(true, true) else XLR_GO(true, false) }
-        else            { if (p.accumulate) XLR_GO(false, true) else XLR_GO(false, false) }
+#define XLR_H(Rw, A)                                                                               \
+    {                                                                                              \
+        if (p.p4) XLR_GO(Rw, A, true) else XLR_GO(Rw, A, false)                                    \
+    }
+        if (p.has_rows) { if (p.accumulate) XLR_H(true, true) else XLR_H(true, false) }
+        else            { if (p.accumulate) XLR_H(false, true) else XLR_H(false, false) }
+#undef XLR_H
 #undef XLR_GO
         break;
     }
@@ -404,8 +411,10 @@ template <typename T>
 hipError_t raise_lds_limits() {
     const void *fns[] = {
         (const void *)k_hsell<T, false>, (const void *)k_hsell<T, true>, (const void *)k_hsell_delta<T, false>, (const void *)k_hsell_delta<T, true>, (const void *)k_xl_mul<T>,
-        (const void *)k_xl_reduce<T, false, false>, (const void *)k_xl_reduce<T, false, true>,
-        (const void *)k_xl_reduce<T, true, false>, (const void *)k_xl_reduce<T, true, true>,
+        (const void *)k_xl_reduce<T, false, false, false>, (const void *)k_xl_reduce<T, false, true, false>,
+        (const void *)k_xl_reduce<T, true, false, false>, (const void *)k_xl_reduce<T, true, true, false>,
+        (const void *)k_xl_reduce<T, false, false, true>, (const void *)k_xl_reduce<T, false, true, true>,
+        (const void *)k_xl_reduce<T, true, false, true>, (const void *)k_xl_reduce<T, true, true, true>,
 #define XWIN_ALL(B)                                                                               \
     (const void *)k_bsell_xwin<T, B, false, false>, (const void *)k_bsell_xwin<T, B, false, true>, \
     (const void *)k_bsell_xwin<T, B, true, false>, (const void *)k_bsell_xwin<T, B, true, true>
@@ -471,7 +480,7 @@ int static_scratch(void **ptr) {
 // Launch of a run-time compiled kernel: the grid, workgroup, LDS size and argument list of the
 // ahead-of-time launch of the same kind (launch_typed above), handed to the module launch call.
 template <typename T>
-int launch_jit_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, hipStream_t st, void *scratch) {
+int launch_jit_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, hipStream_t st, void *scratch, void *scratch2) {
     auto blocks = [](int64_t items, int64_t per) { return (unsigned)((items + per - 1) / per); };
     hipFunction_t fn = (hipFunction_t)p.jit_fn;
     unsigned grid = 0, block = kWG;
@@ -485,7 +494,7 @@ int launch_jit_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T 
     int a32[8];
     const T *xx = x;
     T *yy = y;
-    void *sc = scratch;
+    void *sc = scratch, *sc2 = scratch2;
     auto P = [&](void *ptr) { args[na++] = ptr; };
     switch (p.kind) {
     case K_DIA: {
@@ -550,27 +559,29 @@ int launch_jit_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T 
         grid = (unsigned)p.units;
         block = kXlWG;
         lds = (size_t)p.tile * sizeof(double);
-        a32[0] = p.tile; a64[0] = p.nrows;
-        P(&q0); P(&q1); P(&sc); P(&q2); P(&q3); P(&yy); P(&a32[0]); P(&a64[0]);
+        a32[0] = p.tile; a64[0] = p.nrows; a32[1] = (int)p.ngroups; a32[2] = (int)p.nslices;
+        P(&q0); P(&q1); P(&sc); P(&q2); P(&q3); P(&yy); P(&a32[0]); P(&a64[0]); P(&q4); P(&q5); P(&sc2); P(&a32[1]); P(&a32[2]);
         break;
     default: return (int)hipErrorInvalidValue;
     }
     return (int)hipModuleLaunchKernel(fn, grid, 1, 1, block, 1, 1, (unsigned)lds, st, args, nullptr);
 }
 
-int launch_jit(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x, void *y, void *stream, void *scratch) {
+int launch_jit(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x, void *y, void *stream, void *scratch,
+               void *scratch2) {
     hipStream_t st = (hipStream_t)stream;
-    if (dtype == SPMV_F64) return launch_jit_typed<double>(p, nrows, ncols, (const double *)x, (double *)y, st, scratch);
-    return launch_jit_typed<float>(p, nrows, ncols, (const float *)x, (float *)y, st, scratch);
+    if (dtype == SPMV_F64) return launch_jit_typed<double>(p, nrows, ncols, (const double *)x, (double *)y, st, scratch, scratch2);
+    return launch_jit_typed<float>(p, nrows, ncols, (const float *)x, (float *)y, st, scratch, scratch2);
 }
 
 int launch_part(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,
-                void *y, void *stream, void *scratch_override) {
+                void *y, void *stream, void *scratch_override, void *scratch2_override) {
     hipStream_t st = (hipStream_t)stream;
     void *scratch = scratch_override ? scratch_override : p.scratch;
-    if (p.jit_fn) return launch_jit(p, dtype, nrows, ncols, x, y, stream, scratch);
-    if (dtype == SPMV_F64) return launch_typed<double>(p, nrows, ncols, (const double *)x, (double *)y, st, scratch);
-    return launch_typed<float>(p, nrows, ncols, (const float *)x, (float *)y, st, scratch);
+    void *scratch2 = scratch2_override ? scratch2_override : p.scratch2;
+    if (p.jit_fn) return launch_jit(p, dtype, nrows, ncols, x, y, stream, scratch, scratch2);
+    if (dtype == SPMV_F64) return launch_typed<double>(p, nrows, ncols, (const double *)x, (double *)y, st, scratch, scratch2);
+    return launch_typed<float>(p, nrows, ncols, (const float *)x, (float *)y, st, scratch, scratch2);
 }
 
 int launch_part_multi(const Part &p, spmv_dtype_t dtype, int64_t nrows, int64_t ncols, const void *x,

@@ -158,6 +158,7 @@ void save_plan(const Plan &plan, const char *path) {
         w.i64(array_index(p.p0)); w.i64(array_index(p.p1)); w.i64(array_index(p.p2));
         w.i64(array_index(p.p3)); w.i64(array_index(p.p4)); w.i64(array_index(p.p5));
         w.i64(scratch_index(p.scratch));
+        w.i64(scratch_index(p.scratch2));
     }
     w.i64((int64_t)plan.log.size());
     for (const CandidateLog &l : plan.log) {
@@ -275,10 +276,11 @@ std::unique_ptr<Plan> load_plan(const char *path, const Allocator &mem) {
         if ((int)q.kind < 0 || (int)q.kind > (int)K_LAST) fail(SPMV_ERR_INVALID_ARG, "plan load: unknown launch kind");
         q.p0 = array_ptr(r.i64()); q.p1 = array_ptr(r.i64()); q.p2 = array_ptr(r.i64());
         q.p3 = array_ptr(r.i64()); q.p4 = array_ptr(r.i64()); q.p5 = array_ptr(r.i64());
-        const int64_t si = r.i64();
-        if (si != -1) {
+        for (void **dst : {&q.scratch, &q.scratch2}) {
+            const int64_t si = r.i64();
+            if (si == -1) continue;
             if (si < 0 || si >= (int64_t)plan->scratch.size()) fail(SPMV_ERR_INVALID_ARG, "plan load: scratch index out of range");
-            q.scratch = plan->scratch[(size_t)si].ptr;
+            *dst = plan->scratch[(size_t)si].ptr;
         }
         plan->parts.push_back(q);
     }

@@ -4,9 +4,9 @@
 
 namespace spmv {
 
-int launch_part(const Part &, spmv_dtype_t, int64_t, int64_t, const void *, void *, void *, void *) { return 1; }
+int launch_part(const Part &, spmv_dtype_t, int64_t, int64_t, const void *, void *, void *, void *, void *) { return 1; }
 int launch_part_multi(const Part &, spmv_dtype_t, int64_t, int64_t, const void *, int64_t, void *, int64_t, int, void *) { return 1; }
-int launch_jit(const Part &, spmv_dtype_t, int64_t, int64_t, const void *, void *, void *, void *) { return 1; }
+int launch_jit(const Part &, spmv_dtype_t, int64_t, int64_t, const void *, void *, void *, void *, void *) { return 1; }
 int prepare_device() { return 1; }
 int static_scratch(void **) { return 1; }
 int stream_ceiling(size_t, int, void *, double *, double *) { return 1; }

@@ -222,6 +222,25 @@ def test_closed_form_pieces_of_full_rows_need_no_padding():
         P.destroy()
 
 
+def test_heavy_rows_of_a_two_pass_leaf_have_no_reduce_launch_of_their_own():
+    """`heavy=..,light=xl`: the heavy launch runs first and the two-pass reduce launch adds its partial sums
+    (hptr: heavy rows per row block, hloc: their local rows); with another light design the heavy part keeps
+    its own reduce launch."""
+    m = TINY["C5"]()
+    P = host_plan(m, "heavy=64,tile=2048,light=xl,w=2048,rb=4096")
+    assert [q["name"] for q in P.describe()["parts"]] == ["heavy", "xl", "xl.reduce"]
+    a = P.arrays()
+    hr = a["heavy.rows"]
+    assert np.array_equal(hr, m.meta["heavy_rows"])
+    assert np.array_equal(a["xl.hloc"], hr % 4096)                       # the part owns every row: position = row
+    assert np.array_equal(np.diff(a["xl.hptr"]), np.bincount(hr // 4096, minlength=-(-m.nrows // 4096)))
+    P.destroy()
+    P = host_plan(m, "heavy=64,tile=2048,light=sell,sigma=1024")
+    assert [q["name"] for q in P.describe()["parts"]] == ["sell", "heavy", "heavy.reduce"]
+    assert "xl.hptr" not in P.arrays()
+    P.destroy()
+
+
 def test_two_pass_items_keep_a_window_on_one_xcd():
     """Item i of the multiply launch runs on XCD i mod 8: every window's pieces share one residue and follow
     each other there; the pieces of a window tile its entries; fillers are empty and only at the ends."""
