@@ -232,6 +232,27 @@ def ref_bsell(nrows, ncols, rp, ci, va, B, sigma, xwin=0):
     return out
 
 
+def _count_pieces(rowseg, P, delta):
+    """Number of pieces when every segment is cut greedily into runs of stored length <= P."""
+    total = 0
+    for lc, _ in rowseg:
+        if lc.size == 0:
+            continue
+        if delta:
+            gap = np.diff(lc)
+            cost = np.concatenate([[1], 1 + np.where(gap > 255, (gap - 1) // 255, 0)])
+        else:
+            cost = np.ones(lc.size, dtype=np.int64)
+        stored = 0
+        for k, c in enumerate(cost):
+            if k == 0 or stored + c > P:
+                total += 1
+                stored = 1           # the first entry of a run stores no bridges
+            else:
+                stored += c
+    return total
+
+
 def ref_stripe(ncols, rp, ci, va, hrows, tile, delta=0, piece=0):
     """Heavy rows cut into column stripes; inside a stripe the rows are ordered by decreasing number
     of entries in that stripe (stable), sliced by 64 and padded per slice (value 0, local column 0).
@@ -243,9 +264,11 @@ def ref_stripe(ncols, rp, ci, va, hrows, tile, delta=0, piece=0):
     lane_meta = c_0 << 16 | heavy row (0xFFFF: none).  dcols packs entries 4q..4q+3 of a lane into
     one little-endian 32-bit word at unit_ptr[u] / 4 + 64 q + lane.
 
-    piece=P>0: a (row, stripe) segment is cut into runs of at most P entries, every run a lane of its
-    own (rows without entries in the stripe take none); P doubles for a stripe until it has at most
-    8192 lanes.  sunits[s] = first unit of stripe s."""
+    piece=P>0: a (row, stripe) segment is cut into runs of at most P stored entries (a run takes entries
+    while its stored length, bridges included, stays within P; the run after it starts with an absolute
+    column, so the bridges of the gap between them are not stored), every run a lane of its own (rows
+    without entries in the stripe take none); P doubles for a stripe until it has at most 8192 lanes.
+    sunits[s] = first unit of stripe s."""
     nh = len(hrows)
     if nh == 0:
         return {}
@@ -278,11 +301,16 @@ def ref_stripe(ncols, rp, ci, va, hrows, tile, delta=0, piece=0):
                 lanes.append((h,) + encode(lc, vv))
         else:
             P = piece
-            while sum(-(-lc.size // P) for lc, _ in rowseg) > 8192:
+            while _count_pieces(rowseg, P, delta) > 8192:
                 P *= 2
             for h, (lc, vv) in enumerate(rowseg):
-                for o in range(0, lc.size, P):
-                    lanes.append((h,) + encode(lc[o:o + P], vv[o:o + P]))
+                o = 0
+                while o < lc.size:       # a piece takes entries while its stored length stays within P
+                    n = 1
+                    while o + n < lc.size and len(encode(lc[o:o + n + 1], vv[o:o + n + 1])[0]) <= P:
+                        n += 1
+                    lanes.append((h,) + encode(lc[o:o + n], vv[o:o + n]))
+                    o += n
         key = np.array([len(l[1]) for l in lanes], dtype=np.int64)
         order = np.argsort(-key, kind="stable")
         nu = -(-len(lanes) // WAVE)

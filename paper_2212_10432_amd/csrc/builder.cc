@@ -510,9 +510,10 @@ struct HeavyFold {
 // entries 4q .. 4q+3 of a lane form one 32-bit word (entry 4q in the low byte) at word
 // unit_ptr[u] / 4 + 64*q + lane.
 //
-// piece = P > 0: the entries of a (row, stripe) segment are cut into runs of at most P (the last one
-// shorter), each run a lane of its own, so that a few very long segments no longer set the padded
-// width of a whole slice; rows without entries in a stripe take no lane there.  sunits[s] is the
+// piece = P > 0: the entries of a (row, stripe) segment are cut into runs of at most P stored entries
+// (greedily: a run takes entries while its stored length, bridging entries included, stays within P),
+// each run a lane of its own, so that a few very long segments no longer set the padded width of a
+// whole slice; rows without entries in a stripe take no lane there.  sunits[s] is the
 // first unit of stripe s (piece = 0: every stripe has ceil(nh / 64) units and there is no such
 // array).  A stripe that would need more than 8192 lanes doubles its P until it does not.
 template <typename T>
@@ -559,18 +560,30 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
             if (piece <= 0) {
                 for (int32_t h = 0; h < (int32_t)nh; ++h) ls.push_back({h, so[h], sl[h], stored_len(h, so[h], sl[h])});
             } else {
-                // the piece length doubles until the stripe has at most 8192 lanes (128 units)
-                int64_t P = piece, cnt;
-                for (;; P *= 2) {
-                    cnt = 0;
-                    for (int64_t h = 0; h < nh; ++h) cnt += (sl[h] + P - 1) / P;
-                    if (cnt <= 8192) break;
-                }
-                for (int32_t h = 0; h < (int32_t)nh; ++h)
-                    for (int64_t o = 0; o < sl[h]; o += P) {
-                        const int32_t len = (int32_t)std::min<int64_t>(P, sl[h] - o);
-                        ls.push_back({h, (int32_t)(so[h] + o), len, stored_len(h, (int32_t)(so[h] + o), len)});
+                // A piece takes entries while its stored length stays within P (with column differences a
+                // piece that ends in front of a wide gap starts the next one at that gap's far side, so the
+                // bridging entries of the gap are not stored at all).  P doubles until the stripe has at
+                // most 8192 lanes (128 units).
+                for (int64_t P = piece;; P *= 2) {
+                    ls.clear();
+                    for (int32_t h = 0; h < (int32_t)nh; ++h) {
+                        const int64_t src = (int64_t)A.row_ptr[hrows[(size_t)h]] + so[h];
+                        int32_t o = 0;
+                        while (o < sl[h]) {
+                            int32_t len = 1;
+                            int64_t stored = 1;
+                            while (o + len < sl[h]) {
+                                const int64_t add = 1 + (delta ? bridges((int64_t)A.col[src + o + len] - A.col[src + o + len - 1]) : 0);
+                                if (stored + add > P) break;
+                                stored += add;
+                                ++len;
+                            }
+                            ls.push_back({h, so[h] + o, len, (int32_t)stored});
+                            o += len;
+                        }
                     }
+                    if (ls.size() <= 8192) break;
+                }
             }
             std::stable_sort(ls.begin(), ls.end(), [](const Lane &a, const Lane &b) { return a.key > b.key; });
         }
