@@ -658,7 +658,10 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
         }
     });
     // workgroups: a few consecutive stripes each, about two workgroups per compute unit
-    const int64_t per_group = std::max<int64_t>(1, ns / 512);
+    // Two workgroups of 512 lanes per compute unit when their x tiles and row accumulators both fit its
+    // LDS (160 KiB), else one of 1024 lanes: sixteen wavefronts per compute unit either way.
+    const bool big = 2 * ((int64_t)tile + nh) * (int64_t)sizeof(T) > 160 * 1024;
+    const int64_t per_group = std::max<int64_t>(1, ns / (big ? 256 : 512));
     const int64_t ngroups = (ns + per_group - 1) / per_group;
     void *scratch = plan.mem.alloc((size_t)(ngroups * nh) * sizeof(T), plan.mem.user);
     if (!scratch) fail(SPMV_ERR_ALLOC, "device allocation of the heavy part's scratch failed");
@@ -683,6 +686,7 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
     p.scratch = scratch;
     p.tile = tile;
     p.delta = delta;
+    p.lanes = big ? 1024 : 512;
     p.has_rows = true;
     const size_t a0 = plan.arrays.size();
     p.p0 = upload(plan, "heavy.unit_ptr", 4, nunits + 1, unit_ptr.data());

@@ -1096,7 +1096,10 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
 // atomics (GMEM_ATOM_RED) would be several times slower here, since hundreds of workgroups would
 // hit the same few thousand y elements.
 // Entry j of lane `lane` of unit u = stripe * nsl + slice sits at unit_ptr[u] + 64*j + lane.
+// Lanes per workgroup: 512 when two workgroups (x tile + row accumulators each) fit the LDS of a compute
+// unit, else 1024, so that the compute unit still holds sixteen wavefronts (chosen by the builder).
 constexpr int kHeavyWG = 512;
+constexpr int kHeavyWGBig = 1024;
 // Four consecutive units of the same width W <= 4 (4 * 64 * W entries starting at entry p0, lane
 // rows starting at lr0): every load is issued before the first product.
 // PIECES: several lanes of a stripe may hold pieces of the same heavy row, so the lane sums meet in the
@@ -1129,8 +1132,8 @@ __device__ __forceinline__ void narrow_quad(const uint16_t *__restrict__ lcol, c
     }
 }
 
-template <typename T, bool PIECES>
-__global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ unit_ptr,
+template <typename T, bool PIECES, int WG>
+__global__ __launch_bounds__(WG) void k_hsell(const int32_t *__restrict__ unit_ptr,
                                                     const uint16_t *__restrict__ lcol,
                                                     const T *__restrict__ vals,
                                                     const uint16_t *__restrict__ lane_row,
@@ -1144,7 +1147,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
     extern __shared__ __align__(16) unsigned char smem[];
     T *xs = reinterpret_cast<T *>(smem);
     T *ys = xs + tile;
-    for (int i = threadIdx.x; i < nh; i += kHeavyWG) ys[i] = T(0);
+    for (int i = threadIdx.x; i < nh; i += WG) ys[i] = T(0);
     const int lane = threadIdx.x & 63;
     const int s0 = blockIdx.x * stripes_per_wg;
     const int s1 = (s0 + stripes_per_wg < ns) ? s0 + stripes_per_wg : ns;
@@ -1152,7 +1155,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
         __syncthreads();   // the previous stripe's gathers are done (first pass: ys is zeroed)
         const int64_t c0 = (int64_t)s * tile;
         const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
-        for (int i = threadIdx.x; i < w; i += kHeavyWG) xs[i] = x[c0 + i];
+        for (int i = threadIdx.x; i < w; i += WG) xs[i] = x[c0 + i];
         __syncthreads();
         // units of this stripe: nsl_all everywhere, or (PIECES) the stripe's own count, at most 128
         const int64_t u0 = PIECES ? (int64_t)sunits[s] : (int64_t)s * nsl_all;
@@ -1180,13 +1183,13 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
             n_used = __popcll(__ballot(ina && wa > 0)) + __popcll(__ballot(inb && wb > 0));
         }
         const int wave = threadIdx.x >> 6;
-        for (int g = wave; g < n_wide; g += kHeavyWG / kWave) {
+        for (int g = wave; g < n_wide; g += WG / kWave) {
             const int32_t b = offset_of(g), e = offset_of(g + 1);
             const uint16_t lr = lane_row[(u0 + g) * 64 + lane];
             const T acc = sell_lane_sum<T, uint16_t, true>(lcol + b + lane, vals + b + lane, (e - b) >> 6, xs);
             if (lr != 0xFFFFu) heavy_add<T, PIECES>(ys, lr, acc);
         }
-        for (int g0 = n_wide + 4 * wave; g0 < n_used; g0 += 4 * (kHeavyWG / kWave)) {
+        for (int g0 = n_wide + 4 * wave; g0 < n_used; g0 += 4 * (WG / kWave)) {
             const int32_t p0 = offset_of(g0), p1 = offset_of(g0 + 1);
             const int wq = (p1 - p0) >> 6;                                          // 1 .. 4
             bool quad = g0 + 4 <= n_used;
@@ -1216,7 +1219,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell(const int32_t *__restrict__ 
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nh; i += kHeavyWG) __builtin_nontemporal_store(ys[i], partial + (int64_t)blockIdx.x * nh + i);
+    for (int i = threadIdx.x; i < nh; i += WG) __builtin_nontemporal_store(ys[i], partial + (int64_t)blockIdx.x * nh + i);
 }
 
 // The same part with 8-bit column differences (index compression): a lane starts at the first
@@ -1246,8 +1249,8 @@ __device__ __forceinline__ void hdelta_step(const uint32_t *__restrict__ dw, con
     }
 }
 
-template <typename T, bool PIECES>
-__global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restrict__ unit_ptr,
+template <typename T, bool PIECES, int WG>
+__global__ __launch_bounds__(WG) void k_hsell_delta(const int32_t *__restrict__ unit_ptr,
                                                           const uint32_t *__restrict__ dcols,
                                                           const T *__restrict__ vals,
                                                           const uint32_t *__restrict__ lane_meta,
@@ -1261,7 +1264,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restr
     extern __shared__ __align__(16) unsigned char smem[];
     T *xs = reinterpret_cast<T *>(smem);
     T *ys = xs + tile;
-    for (int i = threadIdx.x; i < nh; i += kHeavyWG) ys[i] = T(0);
+    for (int i = threadIdx.x; i < nh; i += WG) ys[i] = T(0);
     const int lane = threadIdx.x & 63;
     const int s0 = blockIdx.x * stripes_per_wg;
     const int s1 = (s0 + stripes_per_wg < ns) ? s0 + stripes_per_wg : ns;
@@ -1269,11 +1272,11 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restr
         __syncthreads();   // the previous stripe's gathers are done (first pass: ys is zeroed)
         const int64_t c0 = (int64_t)s * tile;
         const int w = (int)((ncols - c0) < (int64_t)tile ? (ncols - c0) : (int64_t)tile);
-        for (int i = threadIdx.x; i < w; i += kHeavyWG) xs[i] = x[c0 + i];
+        for (int i = threadIdx.x; i < w; i += WG) xs[i] = x[c0 + i];
         __syncthreads();
         const int64_t u0 = PIECES ? (int64_t)sunits[s] : (int64_t)s * nsl_all;
         const int nsl = PIECES ? sunits[s + 1] - sunits[s] : nsl_all;
-        for (int g = threadIdx.x >> 6; g < nsl; g += kHeavyWG / kWave) {
+        for (int g = threadIdx.x >> 6; g < nsl; g += WG / kWave) {
             const int64_t u = u0 + g;
             const int32_t b = unit_ptr[u];
             const int wd = (unit_ptr[u + 1] - b) >> 6;   // a multiple of 4
@@ -1292,7 +1295,7 @@ __global__ __launch_bounds__(kHeavyWG) void k_hsell_delta(const int32_t *__restr
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nh; i += kHeavyWG) __builtin_nontemporal_store(ys[i], partial + (int64_t)blockIdx.x * nh + i);
+    for (int i = threadIdx.x; i < nh; i += WG) __builtin_nontemporal_store(ys[i], partial + (int64_t)blockIdx.x * nh + i);
 }
 
 // y[rows[i]] (+)= sum over g < np of partial[g * n + i]: many partials (one per workgroup of the

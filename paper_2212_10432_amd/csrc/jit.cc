@@ -77,7 +77,7 @@ bool jit_describe(const Plan &plan, const Part &p, std::string &kernel, std::str
         model("SLICE_PTR", p.p0);
         break;
     case K_STRIPE:
-        k << (p.delta ? "spmv::dev::k_hsell_delta<" : "spmv::dev::k_hsell<") << T << ", " << B(p.p5 != nullptr) << ">";
+        k << (p.delta ? "spmv::dev::k_hsell_delta<" : "spmv::dev::k_hsell<") << T << ", " << B(p.p5 != nullptr) << ", " << (p.lanes == 1024 ? 1024 : 512) << ">";
         defi("HS_NSL", p.nslices);
         defi("HS_NH", p.nrows);
         defi("HS_TILE", p.tile);

@@ -194,17 +194,21 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
         if (p.units == 0 || p.nslices == 0) return 0;
         const size_t lds = ((size_t)p.tile + (size_t)p.nrows) * sizeof(T);
         const int32_t *sunits = (const int32_t *)p.p5;   // units per stripe when the rows are cut into pieces
-#define HS_GO(KERNEL, CT)                                                                          \
-    KERNEL<<<(unsigned)p.ngroups, kHeavyWG, lds, st>>>(                                            \
+#define HS_GO(KERNEL, CT, WGL)                                                                     \
+    KERNEL<<<(unsigned)p.ngroups, WGL, lds, st>>>(                                                 \
         (const int32_t *)p.p0, (const CT *)p.p1, (const T *)p.p2, (const CT *)p.p4, sunits, x, (T *)scratch, \
         (int)p.nslices, (int)p.nrows, p.tile, ncols, (int)p.units, (int)p.per_group)
+#define HS_WG(NAME, PIECES, CT)                                                                    \
+    {                                                                                              \
+        if (p.lanes == kHeavyWGBig) HS_GO((NAME<T, PIECES, kHeavyWGBig>), CT, kHeavyWGBig);        \
+        else HS_GO((NAME<T, PIECES, kHeavyWG>), CT, kHeavyWG);                                     \
+    }
         if (p.delta) {
-            if (sunits) HS_GO((k_hsell_delta<T, true>), uint32_t);
-            else HS_GO((k_hsell_delta<T, false>), uint32_t);
+            if (sunits) HS_WG(k_hsell_delta, true, uint32_t) else HS_WG(k_hsell_delta, false, uint32_t)
         } else {
-            if (sunits) HS_GO((k_hsell<T, true>), uint16_t);
-            else HS_GO((k_hsell<T, false>), uint16_t);
+            if (sunits) HS_WG(k_hsell, true, uint16_t) else HS_WG(k_hsell, false, uint16_t)
         }
+#undef HS_WG
 #undef HS_GO
         break;
     }
@@ -410,7 +414,10 @@ namespace {
 template <typename T>
 hipError_t raise_lds_limits() {
     const void *fns[] = {
-        (const void *)k_hsell<T, false>, (const void *)k_hsell<T, true>, (const void *)k_hsell_delta<T, false>, (const void *)k_hsell_delta<T, true>, (const void *)k_xl_mul<T>,
+        (const void *)k_hsell<T, false, kHeavyWG>, (const void *)k_hsell<T, true, kHeavyWG>,
+        (const void *)k_hsell_delta<T, false, kHeavyWG>, (const void *)k_hsell_delta<T, true, kHeavyWG>,
+        (const void *)k_hsell<T, false, kHeavyWGBig>, (const void *)k_hsell<T, true, kHeavyWGBig>,
+        (const void *)k_hsell_delta<T, false, kHeavyWGBig>, (const void *)k_hsell_delta<T, true, kHeavyWGBig>, (const void *)k_xl_mul<T>,
         (const void *)k_xl_reduce<T, false, false, false>, (const void *)k_xl_reduce<T, false, true, false>,
         (const void *)k_xl_reduce<T, true, false, false>, (const void *)k_xl_reduce<T, true, true, false>,
         (const void *)k_xl_reduce<T, false, false, true>, (const void *)k_xl_reduce<T, false, true, true>,
@@ -534,7 +541,7 @@ int launch_jit_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T 
     case K_STRIPE:
         if (p.units == 0 || p.nslices == 0) return 0;
         grid = (unsigned)p.ngroups;
-        block = kHeavyWG;
+        block = p.lanes == kHeavyWGBig ? kHeavyWGBig : kHeavyWG;
         lds = ((size_t)p.tile + (size_t)p.nrows) * sizeof(T);
         a32[0] = (int)p.nslices; a32[1] = (int)p.nrows; a32[2] = p.tile; a64[0] = ncols; a32[3] = (int)p.units; a32[4] = (int)p.per_group;
         P(&q0); P(&q1); P(&q2); P(&q4); P(&q5); P(&xx); P(&sc); P(&a32[0]); P(&a32[1]); P(&a32[2]); P(&a64[0]); P(&a32[3]); P(&a32[4]);

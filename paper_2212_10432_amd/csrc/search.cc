@@ -280,6 +280,8 @@ static std::vector<PlanSpec> leaf_neighbours(const PlanSpec &b, spmv_dtype_t dty
         if (b.heavy >= 128) {
             p.heavy = b.heavy / 2;
             add(p);
+            p.heavy = b.heavy / 4 * 3;   // the heavy part holds at most 8192 rows: half the threshold often has too many
+            add(p);
         }
         if (b.tile * 2 * vsize <= 65536) {
             p = b;
