@@ -52,8 +52,20 @@ typedef enum {
 
 /* All fields optional; a NULL options pointer, or a zeroed struct, means defaults. */
 typedef struct {
-    /* Plan-spec string ("key=value,key=value"): skip the search and build exactly this plan.
-     * NULL or "" = search.  The grammar is printed by spmv_plan_describe ("spec"). */
+    /* Plan-spec string: skip the search and build exactly this plan.  NULL or "" = search.
+     * spmv_plan_describe prints the spec of any plan ("spec") in this grammar (operators of Table II):
+     *   leaf  = key=value,key=value,...   one design for a set of rows:
+     *     dia=0|1, dia_fill=f, drows=1|2|4      well-populated diagonals first, the rest accumulates
+     *     heavy=T, tile=W, hd=0|1, piece=P      rows longer than T: column stripes of W with x in LDS,
+     *                                           8-bit column differences, lanes of at most P entries
+     *     light=csrv|sell|bsell|bin|nnzb|wbm|xs|xnb|xl|coo   design of the remaining rows, with
+     *     lpr, chunk, sigma, block, xwin, smax, wg, r, k, w, rb, remap   (its blocking parameters)
+     *     jit=0|1                               kernels compiled at run time for this plan
+     *   node  = rows(c1:...:cn){spec}...{spec}  ROW_DIV by row length, n+1 classes
+     *         | bin2(k){spec}{spec}             BIN: lengths below / from 2^k
+     *         | cut(rho:min){spec}              ROW_DIV where the sorted lengths drop by the ratio rho
+     *         | cols(k){spec}...{spec}          COL_DIV into k stripes, the later ones accumulate
+     * A malformed spec is SPMV_ERR_INVALID_ARG; one the matrix cannot satisfy SPMV_ERR_UNSUPPORTED. */
     const char *force_plan;
     /* Wall-clock cap for the search in milliseconds.  0 = default (8000).  Negative = no timing:
      * the first candidate of the pruned list is taken (a deterministic function of the census). */
