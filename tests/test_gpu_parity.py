@@ -324,12 +324,14 @@ def test_matrix_market_file_to_gpu_result(tmp_path):
 
 
 def _random_spec(rng):
-    light = rng.choice(["csrv", "sell", "bin", "nnzb", "xs", "xnb", "xl", "coo"])
+    light = rng.choice(["csrv", "sell", "bin", "nnzb", "xs", "xnb", "xl", "xl", "coo", "wbm"])
     parts = []
     if rng.random() < 0.5:
         parts.append(f"heavy={int(rng.choice([8, 16, 40, 100]))},tile={int(rng.choice([64, 128, 512, 4096]))}")
         if rng.random() < 0.5:
             parts.append("hd=1")
+        if rng.random() < 0.4:
+            parts.append(f"piece={int(rng.choice([4, 8, 32]))}")
     parts.append(f"light={light}")
     if light == "csrv":
         parts.append(f"lpr={int(rng.choice([0, 1, 2, 8, 64]))},chunk={int(rng.choice([0, 64, 200]))},sigma={int(rng.choice([0, 64, -1]))}")
