@@ -1,6 +1,6 @@
 // Learned cost model of the search (Section VI-A, level three: the paper fits a regression model to
 // the measured points of the coarse grid and uses it to decide which further points are worth a
-// run; it names XGBoost).  Here: one regression tree (CART, squared error) over features of the
+// run; it names XGBoost).  Here: gradient-boosted regression trees (squared error) over features of the
 // census and of the plan spec, trained when a search starts from a corpus of earlier measurements
 // (one line per timed candidate, appended by every search that is given a log path).  The search
 // uses the prediction to order its candidates and to skip those predicted far slower than the best.
@@ -115,58 +115,82 @@ void cost_append(const std::string &path, const std::vector<std::string> &lines)
     for (const std::string &l : lines) f << l << "\n";
 }
 
-// ---- the regression tree -----------------------------------------------------------------------
-int CostModel::grow(std::vector<int> &idx, int b, int e, int depth) {
+// ---- gradient-boosted regression trees --------------------------------------------------------
+// Squared loss on log2(microseconds per stored entry): the model starts from the mean and every round
+// fits a shallow tree to what is still unexplained and adds a tenth of it.  Many shallow trees carry
+// over to matrices the corpus has not seen better than one deep tree, which only looks measurements up.
+namespace {
+constexpr int kRounds = 300, kMaxDepth = 4, kMinSplit = 6;
+constexpr double kRate = 0.1;
+}  // namespace
+
+// Best split of the samples marked `node` in mark[]: every feature's samples are walked in the order
+// sorted once in train().
+int CostModel::grow(std::vector<Node> &tree, const std::vector<double> &target, std::vector<int> &mark, int node,
+                    int count, int depth) {
     double sum = 0;
-    for (int i = b; i < e; ++i) sum += y_[(size_t)idx[(size_t)i]];
-    const double mean = sum / (e - b);
+    const int n = (int)x_.size();
+    for (int i = 0; i < n; ++i)
+        if (mark[(size_t)i] == node) sum += target[(size_t)i];
     Node nd;
-    nd.value = mean;
-    const int me = (int)nodes_.size();
-    nodes_.push_back(nd);
-    if (e - b < 4 || depth >= 12) return me;
+    nd.value = sum / count;
+    const int me = (int)tree.size();
+    tree.push_back(nd);
+    if (count < kMinSplit || depth >= kMaxDepth) return me;
     double sse = 0;
-    for (int i = b; i < e; ++i) sse += (y_[(size_t)idx[(size_t)i]] - mean) * (y_[(size_t)idx[(size_t)i]] - mean);
-    if (sse < 1e-9) return me;
-    const size_t nf = x_[0].size();
-    double best = sse * (1 - 1e-9);
+    for (int i = 0; i < n; ++i)
+        if (mark[(size_t)i] == node) sse += (target[(size_t)i] - nd.value) * (target[(size_t)i] - nd.value);
+    if (sse < 1e-12) return me;
+    double best = sse * (1 - 1e-9), bt = 0;
     int bf = -1;
-    double bt = 0;
-    std::vector<std::pair<double, double>> col((size_t)(e - b));
+    const size_t nf = x_[0].size();
     for (size_t f = 0; f < nf; ++f) {
-        for (int i = b; i < e; ++i) col[(size_t)(i - b)] = {x_[(size_t)idx[(size_t)i]][f], y_[(size_t)idx[(size_t)i]]};
-        std::sort(col.begin(), col.end());
-        if (col.front().first == col.back().first) continue;
-        double ls = 0, ls2 = 0, ts = 0, ts2 = 0;
-        for (auto &p : col) {
-            ts += p.second;
-            ts2 += p.second * p.second;
-        }
-        const int n = e - b;
-        for (int i = 0; i + 1 < n; ++i) {
-            ls += col[(size_t)i].second;
-            ls2 += col[(size_t)i].second * col[(size_t)i].second;
-            if (col[(size_t)i].first == col[(size_t)i + 1].first) continue;
-            const int nl = i + 1, nr = n - nl;
-            const double rs = ts - ls, rs2 = ts2 - ls2;
-            const double cost = (ls2 - ls * ls / nl) + (rs2 - rs * rs / nr);
-            if (cost < best) {
-                best = cost;
-                bf = (int)f;
-                bt = 0.5 * (col[(size_t)i].first + col[(size_t)i + 1].first);
+        double ls = 0, ls2 = 0;
+        double ts = sum, ts2 = sse + sum * sum / count;
+        int nl = 0;
+        double prev = 0;
+        bool have = false;
+        for (int i : order_[f]) {
+            if (mark[(size_t)i] != node) continue;
+            const double v = x_[(size_t)i][f], t = target[(size_t)i];
+            if (have && v != prev && nl >= 2 && count - nl >= 2) {
+                const double rs = ts - ls, rs2 = ts2 - ls2;
+                const double cost = (ls2 - ls * ls / nl) + (rs2 - rs * rs / (count - nl));
+                if (cost < best) {
+                    best = cost;
+                    bf = (int)f;
+                    bt = 0.5 * (prev + v);
+                }
             }
+            ls += t;
+            ls2 += t * t;
+            ++nl;
+            prev = v;
+            have = true;
         }
     }
     if (bf < 0) return me;
-    const int mid = (int)(std::partition(idx.begin() + b, idx.begin() + e, [&](int i) { return x_[(size_t)i][(size_t)bf] <= bt; }) - idx.begin());
-    if (mid == b || mid == e) return me;
-    nodes_[(size_t)me].feature = bf;
-    nodes_[(size_t)me].threshold = bt;
-    const int l = grow(idx, b, mid, depth + 1);
-    const int r = grow(idx, mid, e, depth + 1);
-    nodes_[(size_t)me].left = l;
-    nodes_[(size_t)me].right = r;
+    const int left_id = next_mark_++, right_id = next_mark_++;
+    int nl = 0;
+    for (int i = 0; i < n; ++i)
+        if (mark[(size_t)i] == node) {
+            const bool l = x_[(size_t)i][(size_t)bf] <= bt;
+            mark[(size_t)i] = l ? left_id : right_id;
+            nl += l;
+        }
+    tree[(size_t)me].feature = bf;
+    tree[(size_t)me].threshold = bt;
+    const int l = grow(tree, target, mark, left_id, nl, depth + 1);
+    const int r = grow(tree, target, mark, right_id, count - nl, depth + 1);
+    tree[(size_t)me].left = l;
+    tree[(size_t)me].right = r;
     return me;
+}
+
+static double tree_value(const std::vector<CostModel::Node> &t, const std::vector<double> &f) {
+    int n = 0;
+    while (t[(size_t)n].feature >= 0) n = f[(size_t)t[(size_t)n].feature] <= t[(size_t)n].threshold ? t[(size_t)n].left : t[(size_t)n].right;
+    return t[(size_t)n].value;
 }
 
 void CostModel::add(const CostCensus &c, const PlanSpec &spec, double us) {
@@ -176,19 +200,44 @@ void CostModel::add(const CostCensus &c, const PlanSpec &spec, double us) {
 }
 
 void CostModel::train() {
-    nodes_.clear();
-    if (x_.size() < 8) return;   // too little to say anything
-    std::vector<int> idx(x_.size());
-    for (size_t i = 0; i < idx.size(); ++i) idx[i] = (int)i;
-    grow(idx, 0, (int)idx.size(), 0);
+    trees_.clear();
+    const int n = (int)x_.size();
+    if (n < 8) return;   // too little to say anything
+    const size_t nf = x_[0].size();
+    order_.assign(nf, std::vector<int>());
+    for (size_t f = 0; f < nf; ++f) {
+        order_[f].resize((size_t)n);
+        for (int i = 0; i < n; ++i) order_[f][(size_t)i] = i;
+        std::stable_sort(order_[f].begin(), order_[f].end(), [&](int a, int b) { return x_[(size_t)a][f] < x_[(size_t)b][f]; });
+    }
+    base_ = 0;
+    for (double v : y_) base_ += v;
+    base_ /= n;
+    std::vector<double> resid((size_t)n);
+    for (int i = 0; i < n; ++i) resid[(size_t)i] = y_[(size_t)i] - base_;
+    std::vector<int> mark((size_t)n);
+    for (int m = 0; m < kRounds; ++m) {
+        std::fill(mark.begin(), mark.end(), 0);
+        next_mark_ = 1;
+        std::vector<Node> tree;
+        grow(tree, resid, mark, 0, n, 0);
+        double worst = 0;
+        for (int i = 0; i < n; ++i) {
+            resid[(size_t)i] -= kRate * tree_value(tree, x_[(size_t)i]);
+            worst = std::max(worst, std::fabs(resid[(size_t)i]));
+        }
+        trees_.push_back(std::move(tree));
+        if (worst < 1e-3) break;   // every sample explained to a tenth of a percent
+    }
+    order_.clear();
 }
 
 double CostModel::predict_us(const CostCensus &c, const PlanSpec &spec) const {
-    if (nodes_.empty() || c.nnz < 1) return -1;
+    if (trees_.empty() || c.nnz < 1) return -1;
     const std::vector<double> f = cost_features(c, spec);
-    int n = 0;
-    while (nodes_[(size_t)n].feature >= 0) n = f[(size_t)nodes_[(size_t)n].feature] <= nodes_[(size_t)n].threshold ? nodes_[(size_t)n].left : nodes_[(size_t)n].right;
-    return std::exp2(nodes_[(size_t)n].value + std::log2((double)c.nnz));
+    double v = base_;
+    for (const std::vector<Node> &t : trees_) v += kRate * tree_value(t, f);
+    return std::exp2(v + std::log2((double)c.nnz));
 }
 
 int CostModel::load(const std::string &path) {

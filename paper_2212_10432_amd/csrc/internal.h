@@ -257,21 +257,25 @@ std::string cost_line(const CostCensus &c, const std::string &spec, double us);
 void cost_append(const std::string &path, const std::vector<std::string> &lines);
 class CostModel {
 public:
-    int load(const std::string &path);                              // corpus file -> samples; returns lines used
-    void add(const CostCensus &c, const PlanSpec &spec, double us);
-    void train();
-    bool ready() const { return !nodes_.empty(); }
-    size_t samples() const { return y_.size(); }
-    double predict_us(const CostCensus &c, const PlanSpec &spec) const;   // -1 without a trained tree
-private:
     struct Node {
         int feature = -1, left = -1, right = -1;
         double threshold = 0, value = 0;
     };
-    int grow(std::vector<int> &idx, int b, int e, int depth);
+    int load(const std::string &path);                              // corpus file -> samples; returns lines used
+    void add(const CostCensus &c, const PlanSpec &spec, double us);
+    void train();
+    bool ready() const { return !trees_.empty(); }
+    size_t samples() const { return y_.size(); }
+    double predict_us(const CostCensus &c, const PlanSpec &spec) const;   // -1 without a trained model
+private:
+    int grow(std::vector<Node> &tree, const std::vector<double> &target, std::vector<int> &mark, int node, int count,
+             int depth);
     std::vector<std::vector<double>> x_;
     std::vector<double> y_;
-    std::vector<Node> nodes_;
+    std::vector<std::vector<int>> order_;   // while training: the samples sorted by every feature
+    std::vector<std::vector<Node>> trees_;
+    double base_ = 0;
+    int next_mark_ = 1;
 };
 
 std::string describe_json(const Plan &plan);

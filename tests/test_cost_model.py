@@ -86,3 +86,28 @@ def test_tree_specs_are_features_too(tmp_path):
     b, _ = lib.spmv_cost_predict(P.handle, path, tree)
     assert n == 8 and 1.5 < a / b < 2.6
     P.destroy()
+
+
+@pytest.mark.parametrize("name,make", [("powerlaw-70k", lambda: inputs.powerlaw(n=70_001, cap=9_000)),
+                                       ("hybrid-130k", lambda: inputs.hybrid(n=130_003, n_heavy=7, heavy_len=20_000))])
+def test_shipped_corpus_carries_over_to_a_matrix_left_out(tmp_path, name, make):
+    """Leave one matrix out of the shipped corpus (measured on the MI355X), train on the rest, predict the
+    candidates that were timed on that matrix: the predicted order must follow the measured one, and the
+    best of the model's first three must be close to the best measured."""
+    from scipy.stats import spearmanr
+    m = make()
+    lines = [l.rstrip("\n") for l in open(lib.COST_CORPUS) if l.startswith("v1")]
+    same = lambda t: t[2] == str(m.nrows) and t[4] == str(m.nnz)
+    mine = [l.split("\t") for l in lines if same(l.split("\t")) and l.split("\t")[1] == "1"]
+    rest = [l for l in lines if not same(l.split("\t"))]
+    assert len(mine) >= 10 and len(rest) > 500
+    path = str(tmp_path / "rest.tsv")
+    with open(path, "w") as f:
+        f.write("\n".join(rest) + "\n")
+    P = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan="light=csrv")
+    pred = np.array([lib.spmv_cost_predict(P.handle, path, t[13])[0] for t in mine])
+    meas = np.array([float(t[14]) for t in mine])
+    P.destroy()
+    assert spearmanr(pred, meas).correlation > 0.5
+    assert meas[np.argsort(pred)[:3]].min() <= 1.25 * meas.min()
+    assert meas[pred <= 3 * pred.min()].min() <= 1.05 * meas.min()      # what the search's pruning rule would keep
