@@ -380,7 +380,7 @@ int stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps, d
     const int64_t n16 = (int64_t)(bytes / 16);
     const unsigned grid_r = (unsigned)((n16 + kWG * 8 - 1) / (kWG * 8)), grid_c = (unsigned)((n16 / 2 + kWG - 1) / kWG);
     double best_r = 0, best_c = 0;
-    for (int it = 0; err == hipSuccess && it < repeats + 1; ++it) {   // the first round warms up
+    for (int it = 0; err == hipSuccess && it < repeats + 1; ++it) {   // the first pass warms up
         float ms = 0;
         (void)hipEventRecord(e0, st);
         k_stream_read<<<grid_r, kWG, 0, st>>>((const ceil_f4 *)buf, n16, sink);
