@@ -229,6 +229,13 @@ def ref_bsell(nrows, ncols, rp, ci, va, B, sigma, xwin=0):
             lo, hi = (int(seg.min()), int(seg.max())) if seg.size else (0, -1)
             win += [lo * B, (hi - lo + 1) * B]
         out["bsell.xwin"] = np.array(win, dtype=np.int32)
+        # index compression: the block column as a 16-bit offset from the group's first block column
+        local = np.zeros(bcols.size, dtype=np.uint16)
+        for g in range(-(-nsl // G)):
+            b0, b1 = slice_ptr[g * G], slice_ptr[min(nsl, (g + 1) * G)]
+            local[b0:b1] = bcols[b0:b1] - win[2 * g] // B
+        del out["bsell.bcols"]
+        out["bsell.bcols16"] = local
     return out
 
 
@@ -919,7 +926,13 @@ def decode(arrays: dict, nrows: int, ncols: int, block: int = 3, tile: int = 819
                 ok = (c >= 0) & (c < ncols)
                 R.append(r[ok]); C.append(c[ok]); V.append(dv[d * ld:d * ld + nrows][ok])
         elif pre == "bsell":
-            sp, bc, vv = a["slice_ptr"], a["bcols"], a["vals"]
+            sp, vv = a["slice_ptr"], a["vals"]
+            if "bcols16" in a:       # offsets from the first block column of the group of 32 slices
+                lo = np.asarray(a["xwin"])[0::2] // block
+                first = np.repeat(lo, np.diff(sp[np.minimum(np.arange(lo.size + 1) * 32, len(sp) - 1)]))
+                bc = a["bcols16"].astype(np.int64) + first
+            else:
+                bc = a["bcols"]
             nb = nrows // block
             order = a.get("origin_brows", np.arange(nb, dtype=np.int32))
             BB = block * block

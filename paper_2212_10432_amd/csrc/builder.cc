@@ -441,6 +441,7 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
     p.has_rows = sigma != 0;
     p.remap = remap;
     const size_t a0 = plan.arrays.size();
+    std::vector<uint16_t> bcols16;
     if (xwin) {
         // x window of each group of 32 slices: [lo, lo + n) in scalar columns
         const int64_t ng = (nsl + kXwinGroup - 1) / kXwinGroup;
@@ -476,9 +477,21 @@ void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int 
             p.lds_bytes = std::max<int64_t>(p.lds_bytes, (int64_t)kWave * kXwinGroup * B * (int64_t)sizeof(T));
         }
         p.p4 = upload(plan, "bsell.xwin", 4, 2 * ng, win.data());
+        // index compression: a block's column as a 16-bit offset from its group's window
+        if (widest.load() / B >= 65536) fail(SPMV_ERR_UNSUPPORTED, "bsell: the x window of a workgroup is too wide for 16-bit columns");
+        bcols16.resize((size_t)total);
+        parallel_for(ng, 4, threads, [&](int64_t gb, int64_t ge, int) {
+            for (int64_t g = gb; g < ge; ++g) {
+                const int64_t b0 = slice_ptr[(size_t)(g * kXwinGroup)];
+                const int64_t b1 = slice_ptr[(size_t)std::min(nsl, (g + 1) * kXwinGroup)];
+                const int32_t lo = win[(size_t)(2 * g)] / B;
+                for (int64_t i = b0; i < b1; ++i) bcols16[(size_t)i] = (uint16_t)(bcols[i] - lo);
+            }
+        });
     }
     p.p0 = upload(plan, "bsell.slice_ptr", 8, nsl + 1, slice_ptr.data());
-    p.p1 = upload(plan, "bsell.bcols", 4, total, bcols.p);
+    if (xwin) p.p1 = upload(plan, "bsell.bcols16", 2, total, bcols16.data());
+    else p.p1 = upload(plan, "bsell.bcols", 4, total, bcols.p);
     p.p2 = upload(plan, "bsell.vals", (int)sizeof(T), total * BB, vals.p);
     if (p.has_rows) p.p3 = upload(plan, "bsell.origin_brows", 4, nb, brows.data());
     add_part(plan, p, a0, A.ncols, 0, A.nrows);

@@ -947,8 +947,8 @@ __device__ __forceinline__ void bsell_slice(const int32_t *__restrict__ c, const
 // flight.  A block's column is kept as loaded and turned into an LDS offset only when the block is
 // used.  No test stands between an issue and a use in the steady state: the compiler counts
 // outstanding loads per path, and a skipped issue on one path would turn the next wait into a drain.
-template <typename T, int B>
-__device__ __forceinline__ void bsell_slice2(const int32_t *__restrict__ c, const T *__restrict__ v,
+template <typename T, int B, typename CT>
+__device__ __forceinline__ void bsell_slice2(const CT *__restrict__ c, const T *__restrict__ v,
                                              int w, int lane, const T *__restrict__ xs, int xbase,
                                              T *acc) {
     constexpr int BB = B * B;
@@ -956,7 +956,7 @@ __device__ __forceinline__ void bsell_slice2(const int32_t *__restrict__ c, cons
     int32_t ca = 0, cb = 0;
     T a[BB], b[BB];
     auto issue = [&](int j, int32_t &craw, T *buf) {
-        craw = ldnt(c + j * 64);
+        craw = (int32_t)ldnt(c + j * 64);
         BlockLoad<T, B>::load(v + (int64_t)j * 64 * BB, lane, buf);
     };
     auto use = [&](int32_t craw, const T *buf) {
@@ -1021,13 +1021,15 @@ __global__ __launch_bounds__(kWG) void k_bsell(const int64_t *__restrict__ slice
 // the shortest, so the 16 wavefronts finish together.
 constexpr int kXwinWaves = 16;
 constexpr int kXwinSlices = 2 * kXwinWaves;
+// The block columns are stored as 16-bit offsets from the window's first block column (index
+// compression: 2 bytes per block instead of 4).
 // LOCALY: every block row of the group lies in the group's own range of 64 * 32 block rows (no sort,
 // or sort windows that are whole groups).  The results are then collected in LDS, in the space of the
 // x window once every wavefront is done with it, and written to y as one contiguous piece: stores
 // scattered by the sort permutation, mixed into the stream one slice at a time, cost 14 % of the run.
 template <typename T, int B, bool ROWS, bool LOCALY>
 __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
-    const int64_t *__restrict__ slice_ptr, const int32_t *__restrict__ bcols,
+    const int64_t *__restrict__ slice_ptr, const uint16_t *__restrict__ bcols,
     const T *__restrict__ vals, const int32_t *__restrict__ brows, const int32_t *__restrict__ win,
     const T *__restrict__ x, T *__restrict__ y, int64_t nslices_arg, int64_t nbrows_part_arg, int remap_arg) {
     const int64_t nslices = JIT_BSELL_NSLICES(nslices_arg), nbrows_part = JIT_BSELL_NBROWS(nbrows_part_arg);
@@ -1049,7 +1051,7 @@ __global__ __launch_bounds__(kXwinWaves * kWave) void k_bsell_xwin(
         if (s < nslices) {
             const int64_t b = JIT_SLICE_PTR(slice_ptr, s);
             const int w = (int)((JIT_SLICE_PTR(slice_ptr, s + 1) - b) >> 6);
-            bsell_slice2<T, B>(bcols + b + lane, vals + b * (B * B), w, lane, xs, lo, acc);
+            bsell_slice2<T, B, uint16_t>(bcols + b + lane, vals + b * (B * B), w, lane, xs, 0, acc);
             const int64_t r = s * 64 + lane;
             if (!LOCALY && r < nbrows_part) {
                 const int64_t br = ROWS ? (int64_t)brows[r] : r;

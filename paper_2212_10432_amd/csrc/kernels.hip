@@ -157,7 +157,7 @@ int launch_typed(const Part &p, int64_t nrows, int64_t ncols, const T *x, T *y, 
 #define XWIN_GO(B, R, L)                                                                           \
     {                                                                                              \
         k_bsell_xwin<T, B, R, L><<<grid, threads, (size_t)p.lds_bytes, st>>>(                      \
-            (const int64_t *)p.p0, (const int32_t *)p.p1, (const T *)p.p2, (const int32_t *)p.p3,  \
+            (const int64_t *)p.p0, (const uint16_t *)p.p1, (const T *)p.p2, (const int32_t *)p.p3, \
             (const int32_t *)p.p4, x, y, p.units, p.nrows, p.remap);                               \
     }
 #define XWIN_B(B)                                                                                  \
