@@ -154,6 +154,146 @@ def test_closed_form_wavefront_bitmaps_of_uniform_rows():
     assert np.array_equal(a["zero.rows"], [r for r in borders if r < m.nrows])
 
 
+def _both(m, spec, vals=None):
+    """The library's arrays and the reference builder's, for pins that must hold for each of them."""
+    v = m.values if vals is None else vals
+    P = host_plan(m, spec, v)
+    a = P.arrays()
+    P.destroy()
+    return a, ref.ref_plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, v, spec)
+
+
+def test_closed_form_csr_segments_of_uniform_rows():
+    """Rows of exactly 10 entries: sorted (stably) they keep their order, segment i is row i at 10 i.  Rows of
+    exactly 200 entries cut into segments of at most 64: four segments at 200 i + {0, 64, 128, 192}, marked
+    as segments that add through atomics (~row), and every row is zeroed first."""
+    m = TINY["C1"]()
+    n = m.nrows
+    for a in _both(m, "light=csrv,lpr=4,sigma=128"):
+        assert np.array_equal(a["csrv.seg_ptr"], 10 * np.arange(n + 1))
+        assert np.array_equal(a["csrv.seg_row"], np.arange(n))
+        assert np.array_equal(a["csrv.cols"], m.col_idx) and np.array_equal(a["csrv.vals"], m.values)
+    m = inputs.uniform(n=300, k=200)       # rows of exactly 200 entries, cut into segments of at most 64
+    n = m.nrows
+    for a in _both(m, "light=csrv,lpr=64,chunk=64"):
+        want = (200 * np.arange(n)[:, None] + np.array([0, 64, 128, 192])[None, :]).reshape(-1)
+        assert np.array_equal(a["csrv.seg_ptr"], np.append(want, 200 * n))
+        assert np.array_equal(a["csrv.seg_row"], ~np.repeat(np.arange(n), 4))
+        assert np.array_equal(a["zero.rows"], np.arange(n))
+
+
+def test_closed_form_nnz_balanced_tiles_of_uniform_rows():
+    """Rows of exactly 10 entries, R = 8 entries per lane: entry g of the stream belongs to lane (g % 512) // 8
+    of tile g // 512 and is stored at 512 (g // 512) + 64 (g % 8) + (g % 512) // 8; it starts a row exactly
+    when g % 10 == 0; ceil(512 i / 10) rows start before tile i."""
+    m = TINY["C1"]()
+    total, R = m.nnz, 8
+    g = np.arange(total)
+    dst = 512 * (g // 512) + 64 * (g % 8) + (g % 512) // 8
+    for a in _both(m, "light=nnzb,r=8"):
+        assert a["nnzb.cols"].size == 512 * -(-total // 512)
+        assert np.array_equal(a["nnzb.cols"][dst], m.col_idx) and np.array_equal(a["nnzb.vals"][dst], m.values)
+        assert np.count_nonzero(a["nnzb.vals"]) == np.count_nonzero(m.values)
+        bit = (a["nnzb.bits"][64 * (g // 512) + (g % 512) // 8] >> (g % 8)) & 1
+        assert np.array_equal(bit.astype(bool), g % 10 == 0)
+        assert int(np.unpackbits(a["nnzb.bits"].view(np.uint8)).sum()) == m.nrows       # nothing set in the padding
+        ntiles = -(-total // 512)
+        assert np.array_equal(a["nnzb.tile_row"], np.minimum(-(-(512 * np.arange(ntiles + 1)) // 10), m.nrows))
+        assert np.array_equal(a["nnzb.rows"], np.arange(m.nrows))
+
+
+def test_hand_worked_two_pass_layout():
+    """A 128 x 128 matrix with the diagonal (i, i) = 1 + i and the anti-diagonal (i, 127 - i) = -(1 + i), windows of
+    64 columns, blocks of 64 rows, fp64 (vectors of 2 entries).  Every (window, block) run has 64 entries, so
+    nothing is padded.  Memory order: window 0 = [run(0,0): the diagonal of rows 0..63 | run(0,1): the
+    anti-diagonal of rows 64..127], window 1 = [run(1,0): the anti-diagonal of rows 0..63 | run(1,1): the
+    diagonal of rows 64..127]."""
+    n = 128
+    i = np.arange(n)
+    lo, hi = np.minimum(i, 127 - i), np.maximum(i, 127 - i)
+    ci = np.stack([lo, hi], axis=1).reshape(-1).astype(np.int32)
+    on_diag = np.stack([lo == i, hi == i], axis=1).reshape(-1)
+    va = np.where(on_diag, 1.0, -1.0) * (1 + np.repeat(i, 2))
+    rp = (2 * np.arange(n + 1)).astype(np.int32)
+    spec = "light=xl,w=64,rb=64"
+    P = lib.Plan(n, n, rp, ci, va, force_plan=spec, host_only=True)
+    got = P.arrays()
+    P.destroy()
+    first, second = i[:64], i[64:]
+    vals = np.concatenate([1.0 + first, -(1.0 + second), -(1.0 + first), 1.0 + second])
+    lcol = np.concatenate([first, 127 - second, 63 - first, second - 64]).astype(np.uint16)
+    code = lambda e: (e // 2) * 8 + 7                          # a full group: first vector, 8 vectors
+    glist = np.array([code(e) for e in (0, 16, 32, 48, 128, 144, 160, 176, 64, 80, 96, 112, 192, 208, 224, 240)], dtype=np.int32)
+    items = np.zeros((8, 3), dtype=np.int32)                   # window 0 on XCD 0, window 1 on XCD 1, six fillers
+    items[0], items[1] = (0, 0, 128), (1, 128, 256)
+    for a in (got, ref.ref_plan(n, n, rp, ci, va, spec)):
+        assert np.array_equal(a["xl.vals"], vals)
+        assert np.array_equal(a["xl.lcol"], lcol)
+        assert np.array_equal(a["xl.gptr"], [0, 8, 16])
+        assert np.array_equal(a["xl.glist"], glist)
+        assert np.array_equal(a["xl.lrow"], np.tile(np.arange(64, dtype=np.uint16), 4))
+        assert np.array_equal(a["xl.items"].reshape(-1, 3), items)
+        assert "xl.rows" not in a                               # the part owns every row in order
+
+
+def _one_entry_per_row_and_stripe():
+    """64 rows x 1024 columns; row i has one entry in each of the 16 stripes of 64 columns: (i, 64 j + i) =
+    1000 j + i + 1."""
+    i, j = np.meshgrid(np.arange(64), np.arange(16), indexing="ij")
+    ci = (64 * j + i).reshape(-1).astype(np.int32)
+    va = (1000.0 * j + i + 1).reshape(-1)
+    rp = (16 * np.arange(65)).astype(np.int32)
+    return rp, ci, va
+
+
+def test_hand_worked_xcd_striped_sell():
+    """16 stripes on 8 XCDs: XCD k owns stripes k and k + 8, so the units (one slice of 64 rows, one entry
+    wide, per stripe) follow each other as stripes 0, 8, 1, 9, ...; lane l of unit u owns slot 64 u + l, and
+    row i lists its 16 slots in stripe order."""
+    rp, ci, va = _one_entry_per_row_and_stripe()
+    spec = "light=xs,k=16,sigma=0"
+    P = lib.Plan(64, 1024, rp, ci, va, force_plan=spec, host_only=True)
+    got = P.arrays()
+    P.destroy()
+    stripe_of_unit = np.array([u // 2 + 8 * (u % 2) for u in range(16)])
+    unit_of_stripe = np.argsort(stripe_of_unit)
+    lane = np.arange(64)
+    for a in (got, ref.ref_plan(64, 1024, rp, ci, va, spec)):
+        assert np.array_equal(a["xs.unit_ptr"], 64 * np.arange(17))
+        assert np.array_equal(a["xs.xbase"], 2 * np.arange(9))
+        assert np.array_equal(a["xs.cols"].reshape(16, 64), 64 * stripe_of_unit[:, None] + lane[None, :])
+        assert np.array_equal(a["xs.vals"].reshape(16, 64), 1000.0 * stripe_of_unit[:, None] + lane[None, :] + 1)
+        assert np.array_equal(a["xs.pptr"], 16 * np.arange(65))
+        assert np.array_equal(a["xs.pslot"].reshape(64, 16), 64 * unit_of_stripe[None, :] + lane[:, None])
+        assert "xs.rows" not in a
+
+
+def test_hand_worked_xcd_striped_nnz_balanced_tiles():
+    """The same matrix with tiles of 64 lanes x 4 entries: a stripe's 64 one-entry segments fill a quarter of
+    its tile (lanes 0..15, all four bits set), the rest is padding at the stripe's first column; tiles
+    follow each other as stripes 0, 8, 1, 9, ...; segment 64 t + i is row i of tile t's stripe."""
+    rp, ci, va = _one_entry_per_row_and_stripe()
+    spec = "light=xnb,k=16,r=4"
+    P = lib.Plan(64, 1024, rp, ci, va, force_plan=spec, host_only=True)
+    got = P.arrays()
+    P.destroy()
+    stripe_of_tile = np.array([t // 2 + 8 * (t % 2) for t in range(16)])
+    tile_of_stripe = np.argsort(stripe_of_tile)
+    pos = np.arange(256)                                            # position in a stripe's stream
+    at = 64 * (pos % 4) + pos // 4                                  # where the tile stores it
+    for a in (got, ref.ref_plan(64, 1024, rp, ci, va, spec)):
+        cols, vals = a["xnb.cols"].reshape(16, 256), a["xnb.vals"].reshape(16, 256)
+        for t, s_ in enumerate(stripe_of_tile):
+            assert np.array_equal(cols[t][at], np.where(pos < 64, 64 * s_ + pos, 64 * s_))
+            assert np.array_equal(vals[t][at], np.where(pos < 64, 1000.0 * s_ + pos + 1, 0.0))
+        assert np.array_equal(a["xnb.bits"].reshape(16, 64), np.tile(np.where(np.arange(64) < 16, 15, 0), (16, 1)))
+        assert np.array_equal(a["xnb.tile_row"], 64 * np.arange(17))
+        assert np.array_equal(a["xnb.xbase"], 2 * np.arange(9))
+        assert np.array_equal(a["xnb.seg_row"], np.tile(np.arange(64), 16))
+        assert np.array_equal(a["xnb.bbase"], np.concatenate([64 * tile_of_stripe, 64 * tile_of_stripe + 64]))
+        assert np.array_equal(a["xnb.open_slots"], 64 * np.arange(1, 17) - 1)
+
+
 def test_closed_form_laplacian_diagonals():
     g = 37
     m = TINY["C2"]()
