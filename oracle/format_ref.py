@@ -19,8 +19,11 @@ missing from the paper; they are built from their textbook definitions.
 
 Parity pins: tests/test_format_host.py checks these builders against closed forms (C1: stable sort
 is the identity and padding is zero; C2: five diagonals at {-g,-1,0,1,g} with 4g explicit zeros;
-C4: 3x3 fill is 100 %; C5: the heavy split selects exactly the generator's heavy rows) and checks
-that decode(reference arrays) reproduces the input matrix.
+C4: 3x3 fill is 100 %; C5: the heavy split selects exactly the generator's heavy rows; uniform rows:
+CSR segments, nnz-balanced tiles and wavefront bitmaps at their closed-form places), against layouts
+written out by hand (two-pass part: a 128 x 128 diagonal + anti-diagonal matrix; XCD-striped SELL and
+XCD-striped tiles: 64 rows with one entry in each of 16 stripes; heavy pieces: 20 full rows), and checks
+that decode(reference arrays) reproduces the input matrix for every plan.
 """
 from __future__ import annotations
 
