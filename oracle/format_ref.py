@@ -672,7 +672,23 @@ def _ref_leaf(nrows, ncols, rp, ci, va, p, rows, whole, acc, span) -> dict:
     lens = np.diff(rp).astype(np.int64)
     if p["light"] == "bsell":
         assert whole and not acc
-        out.update(ref_bsell(nrows, ncols, rp, ci, va, p["block"], p["sigma"], p["xwin"]))
+        B = p["block"]
+        nrB, ncB = nrows // B * B, ncols // B * B
+        if nrB == nrows and ncB == ncols:
+            out.update(ref_bsell(nrows, ncols, rp, ci, va, B, p["sigma"], p["xwin"]))
+            return out
+        # ragged edge: whole blocks go to the blocked part, the last rows and columns to a CSR part that
+        # accumulates; the rows past the last whole block row are zeroed first
+        r_of = np.repeat(np.arange(nrows), np.diff(rp))
+        inside = (r_of < nrB) & (ci < ncB)
+        rp_m = np.concatenate([[0], np.cumsum(np.bincount(r_of[inside], minlength=nrows)[:nrB])]).astype(np.int32)
+        out.update(ref_bsell(nrB, ncB, rp_m, ci[inside], va[inside], B, p["sigma"], p["xwin"]))
+        rp_r = np.concatenate([[0], np.cumsum(np.bincount(r_of[~inside], minlength=nrows))]).astype(np.int32)
+        with_entries = np.flatnonzero(np.diff(rp_r) > 0).astype(np.int32)
+        if with_entries.size:
+            out.update(ref_csrv(rp_r, ci[~inside], va[~inside], with_entries, 0, 0, 0, True, nrows, "csrv", []))
+        if nrB < nrows:
+            out["zero.rows"] = np.arange(nrB, nrows, dtype=np.int32)
         return out
     rows = np.asarray(rows, dtype=np.int32)
     is_heavy = (lens[rows] > p["heavy"]) if p["heavy"] > 0 else np.zeros(rows.size, dtype=bool)

@@ -352,8 +352,8 @@ void build_dia(Plan &plan, const HostCsr &A, const std::vector<int32_t> &offs, O
 // ---- dense B x B blocks in SELL order ----------------------------------------------------------
 template <typename T>
 void build_bsell(Plan &plan, const HostCsr &A, int B, int sigma, int remap, int xwin, int threads) {
-    if (A.nrows % B || A.ncols % B)
-        fail(SPMV_ERR_UNSUPPORTED, "bsell: matrix dimensions are not multiples of the block edge");
+    if (A.nrows % B || A.ncols % B)   // the caller takes a ragged edge off first
+        fail(SPMV_ERR_INTERNAL, "bsell: matrix dimensions are not multiples of the block edge");
     const int64_t nb = A.nrows / B;
     if (nb == 0) return;
     // block columns of a block row: merge of the B rows' (col / B), ascending, distinct
@@ -1589,7 +1589,77 @@ void build_leaf(Plan &plan, const HostCsr &A0, const Census &cen, const PlanSpec
 
     if (spec.light == L_BSELL) {
         if (!whole || acc) fail(SPMV_ERR_UNSUPPORTED, "bsell: works on the whole matrix only");
-        build_bsell<T>(plan, A, spec.block, spec.sigma, spec.remap, spec.xwin, threads);
+        const int B = spec.block;
+        const int64_t nrB = A.nrows / B * B, ncB = A.ncols / B * B;
+        if (nrB == A.nrows && ncB == A.ncols) {
+            build_bsell<T>(plan, A, B, spec.sigma, spec.remap, spec.xwin, threads);
+            return;
+        }
+        // Ragged edge: the last nrows mod B rows and the last ncols mod B columns do not fill whole
+        // blocks.  The blocked part takes the matrix without them; their entries form a CSR part
+        // that accumulates afterwards, and the rows past the last whole block row are zeroed first.
+        if (nrB == 0 || ncB == 0) fail(SPMV_ERR_UNSUPPORTED, "bsell: the matrix is smaller than one block");
+        OwnedCsr main, rest;
+        main.row_ptr.assign((size_t)nrB + 1, 0);
+        rest.row_ptr.assign((size_t)A.nrows + 1, 0);
+        for (int64_t r = 0; r < A.nrows; ++r) {
+            int64_t in = 0, out = 0;
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) (r < nrB && A.col[k] < ncB ? in : out) += 1;
+            if (r < nrB) main.row_ptr[(size_t)r + 1] = (int32_t)(main.row_ptr[(size_t)r] + in);
+            rest.row_ptr[(size_t)r + 1] = (int32_t)(rest.row_ptr[(size_t)r] + out);
+        }
+        const size_t v = sizeof(T);
+        main.col.resize((size_t)main.row_ptr[(size_t)nrB]);
+        main.val.resize(main.col.size() * v);
+        rest.col.resize((size_t)rest.row_ptr[(size_t)A.nrows]);
+        rest.val.resize(rest.col.size() * v);
+        const T *av = (const T *)A.val;
+        for (int64_t r = 0; r < A.nrows; ++r) {
+            int64_t im = r < nrB ? main.row_ptr[(size_t)r] : 0, ir = rest.row_ptr[(size_t)r];
+            for (int64_t k = A.row_ptr[r]; k < A.row_ptr[r + 1]; ++k) {
+                if (r < nrB && A.col[k] < ncB) {
+                    main.col[(size_t)im] = A.col[k];
+                    ((T *)main.val.data())[im++] = av[k];
+                } else {
+                    rest.col[(size_t)ir] = A.col[k];
+                    ((T *)rest.val.data())[ir++] = av[k];
+                }
+            }
+        }
+        main.view = A;
+        main.view.nrows = nrB;
+        main.view.ncols = ncB;
+        main.view.nnz = (int64_t)main.col.size();
+        main.view.row_ptr = main.row_ptr.data();
+        main.view.col = main.col.data();
+        main.view.val = main.val.data();
+        rest.view = A;
+        rest.view.nnz = (int64_t)rest.col.size();
+        rest.view.row_ptr = rest.row_ptr.data();
+        rest.view.col = rest.col.data();
+        rest.view.val = rest.val.data();
+        build_bsell<T>(plan, main.view, B, spec.sigma, spec.remap, spec.xwin, threads);
+        if (nrB < A.nrows) {
+            std::vector<int32_t> tail;
+            for (int64_t r = nrB; r < A.nrows; ++r) tail.push_back((int32_t)r);
+            Part z;
+            z.kind = K_ZERO;
+            z.name = plan.prefix + "zero";
+            z.nrows = (int64_t)tail.size();
+            z.units = z.nrows;
+            z.has_rows = true;
+            z.p0 = upload(plan, "zero.rows", 4, z.nrows, tail.data());
+            z.bytes = z.nrows * (4 + (int64_t)plan.vsize());
+            plan.parts.push_back(z);
+        }
+        std::vector<int64_t> rl((size_t)A.nrows, 0);
+        std::vector<int32_t> with;
+        for (int64_t r = 0; r < A.nrows; ++r) {
+            rl[(size_t)r] = rest.view.len(r);
+            if (rl[(size_t)r] > 0) with.push_back((int32_t)r);
+        }
+        std::vector<int32_t> none;
+        if (!with.empty()) build_csrv<T>(plan, rest.view, with, 0, 0, 0, true, 0, "csrv", rl, none, threads);
         return;
     }
 

@@ -114,7 +114,7 @@ Census take_census(const HostCsr &A, int threads) {
     // sorted here, so the order of the columns inside a row does not matter)
     {
         for (int bsz = 2; bsz <= 4; ++bsz) {
-            if (A.nrows % bsz || A.ncols % bsz || A.nrows < bsz) continue;
+            if (A.nrows < bsz || A.ncols < bsz) continue;   // a ragged edge is not sampled: whole block rows only
             const int64_t nb = A.nrows / bsz;
             const int64_t nsample = std::min<int64_t>(nb, 2048);
             int64_t blocks = 0, entries = 0;

@@ -410,6 +410,36 @@ def test_two_pass_items_keep_a_window_on_one_xcd():
         P.destroy()
 
 
+@pytest.mark.parametrize("extra_rows,extra_cols", [(1, 1), (2, 0), (0, 2), (1, 2)])
+@pytest.mark.parametrize("spec", ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=2048,xwin=1,remap=1"])
+def test_blocks_with_a_ragged_edge(spec, extra_rows, extra_cols):
+    """Dimensions that are not multiples of the block edge: whole blocks go to the blocked part, the last
+    rows and columns to a CSR part that accumulates; the arrays match the reference and decode to the input."""
+    m = TINY["C4"]()
+    rng = np.random.default_rng(3)
+    A = sp.csr_matrix((m.values, m.col_idx, m.row_ptr), shape=(m.nrows, m.ncols))
+    if extra_cols:
+        A = sp.hstack([A, sp.random(m.nrows, extra_cols, density=0.3, random_state=1, data_rvs=lambda k: rng.integers(1, 9, k).astype(float))])
+    if extra_rows:
+        A = sp.vstack([A, sp.random(extra_rows, A.shape[1], density=0.02, random_state=2, data_rvs=lambda k: rng.integers(1, 9, k).astype(float))])
+    A = A.tocsr(); A.sort_indices()
+    nr, nc = A.shape
+    rp, ci, va = A.indptr.astype(np.int32), A.indices.astype(np.int32), A.data.astype(np.float64)
+    P = lib.Plan(nr, nc, rp, ci, va, force_plan=spec, host_only=True)
+    got = P.arrays()
+    names = [q["name"] for q in P.describe()["parts"]]
+    P.destroy()
+    assert names == ["bsell"] + (["zero"] if extra_rows else []) + ["csrv"]
+    want = ref.ref_plan(nr, nc, rp, ci, va, spec)
+    assert sorted(got) == sorted(want)
+    for k in want:
+        assert np.array_equal(got[k], want[k]), k
+    if extra_rows:
+        assert np.array_equal(got["zero.rows"], np.arange(nr - extra_rows, nr))
+    r, c, v = ref.decode(got, nr, nc, block=3)
+    assert same_matrix(as_scipy(nr, nc, r, c, v), as_scipy(nr, nc, np.repeat(np.arange(nr), np.diff(rp)), ci, va))
+
+
 def test_duplicates_and_unsorted_columns_are_accepted():
     rng = np.random.default_rng(5)
     nrows, ncols = 300, 300
@@ -462,8 +492,8 @@ def test_errors():
         with pytest.raises(E) as e:
             lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan=spec)
         assert e.value.status == lib.SPMV_ERR_INVALID_ARG, spec
-    with pytest.raises(E) as e:      # 1000 rows are not a multiple of 3
-        lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan="light=bsell,block=3")
+    with pytest.raises(E) as e:      # smaller than one block
+        lib.Plan(2, 2, np.array([0, 1, 2], np.int32), np.array([0, 1], np.int32), np.ones(2), host_only=True, force_plan="light=bsell,block=3")
     assert e.value.status == lib.SPMV_ERR_UNSUPPORTED
     with pytest.raises(E) as e:      # no populated diagonal in a random matrix
         lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan="dia=1,light=sell")

@@ -466,3 +466,38 @@ def test_random_block_banded_matrices_blocked_and_diagonal_plans():
             ran += 1
             assert np.array_equal(y.astype(np.float64), want), (case, spec, dt)
     assert ran > 60
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("extra_rows,extra_cols", [(1, 1), (2, 0), (0, 1)])
+def test_blocked_plans_on_dimensions_with_a_ragged_edge(extra_rows, extra_cols):
+    """A block-structured matrix whose dimensions are not multiples of 3: the blocked part takes the whole
+    blocks, a CSR part the last rows and columns; forced and searched plans against the oracle, bit-exact
+    on integer values."""
+    import scipy.sparse as sp
+    m = inputs.SMALL["C4"](integer=True)
+    rng = np.random.default_rng(11)
+    ints = lambda k: rng.integers(1, 4, k).astype(np.float64)
+    A = sp.csr_matrix((m.values, m.col_idx, m.row_ptr), shape=(m.nrows, m.ncols))
+    if extra_cols:
+        A = sp.hstack([A, sp.random(m.nrows, extra_cols, density=0.2, random_state=1, data_rvs=ints)])
+    if extra_rows:
+        A = sp.vstack([A, sp.random(extra_rows, A.shape[1], density=0.01, random_state=2, data_rvs=ints)])
+    A = A.tocsr(); A.sort_indices()
+    nr, nc = A.shape
+    rp, ci, va = A.indptr.astype(np.int32), A.indices.astype(np.int32), A.data.astype(np.float64)
+    x = inputs.vector(nc, integer=True)
+    want = oracle.spmv(rp, ci, va, x)
+    dev = torch.device("cuda:0")
+    xd = torch.from_numpy(x).to(dev)
+    for spec in ("light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", None):
+        print(f"case ragged {extra_rows} {extra_cols} {spec}", flush=True)
+        P = lib.Plan(nr, nc, rp, ci, va, force_plan=spec, search_budget_ms=1500)
+        yd = torch.full((nr,), float("nan"), dtype=torch.float64, device=dev)
+        P.run(xd, yd)
+        torch.cuda.synchronize()
+        d = P.describe()
+        P.destroy()
+        assert np.array_equal(yd.cpu().numpy(), want), (spec, d["spec"])
+        if spec is None:   # the census sees the blocks despite the edge: blocked candidates were built and timed
+            assert any("bsell" in c["spec"] and c["run_us"] > 0 for c in d["search"]), d["search"]
