@@ -164,7 +164,8 @@ int main(int argc, char **argv) {
         "light=bsell,block=4,sigma=64,remap=1", "light=wbm", "light=csrv,lpr=256,chunk=512", "light=bin,smax=4,sigma=128,chunk=512,wg=1",
         "rows(4:32){light=sell,sigma=64}{light=csrv,lpr=8}{heavy=32,tile=256,light=csrv}", "bin2(5){light=sell}{light=wbm}",
         "cut(4:16){light=sell,sigma=0}", "cols(3){rows(8){light=xl,w=128,rb=64}{light=nnzb,r=4}}", "light=sell,sigma=64,jit=1",
-        "heavy=100,tile=512,light=xl,w=128,rb=64,jit=1",
+        "heavy=100,tile=512,light=xl,w=128,rb=64,jit=1", "heavy=100,tile=512,piece=8,light=xl,w=128,rb=64",
+        "heavy=100,tile=256,hd=1,piece=16,light=csrv", "heavy=40,tile=4096,piece=4,light=sell,sigma=64",
     };
     const Csr mats[] = {
         make(777, 1234, 40, false, 5, 0), make(1500, 900, 12, true, -1, 0), make(64, 64, 64, true, -1, 0),
