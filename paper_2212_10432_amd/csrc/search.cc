@@ -599,17 +599,39 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
         return out;
     };
     try {
-        // level one: the pruned list of designs, each with its default parameters
-        for (const PlanSpec &c : ordered(cands, true)) evaluate(c, "design");
+        // level one: the pruned list of designs, each with its default parameters.  With a model the
+        // designs predicted more than 1.3 times behind the best prediction wait until the parameters of
+        // the leading design have been tuned: the budget goes to the top of the list first.
+        std::vector<PlanSpec> near, far;
+        {
+            const std::vector<PlanSpec> l1 = ordered(cands, true);
+            double lowest = -1;
+            for (const PlanSpec &c : l1) {
+                const double p = model.predict_us(cc, c);
+                if (p > 0 && (lowest < 0 || p < lowest)) lowest = p;
+            }
+            for (size_t i = 0; i < l1.size(); ++i) {
+                const double p = model.predict_us(cc, l1[i]);
+                const bool first = print_spec(l1[i]) == print_spec(cands[0]);
+                (model.ready() && !first && p > 0 && lowest > 0 && p > 1.3 * lowest ? far : near).push_back(l1[i]);
+            }
+        }
+        for (const PlanSpec &c : near) evaluate(c, "design");
         // level two (Section VI-A: parameters of the kept design on a finer grid): halve and double
         // every numeric parameter of the best plan, move to the best neighbour, repeat while that
         // gains more than one percent and the budget lasts
-        for (int round = 0; best && round < 3 && now_ms() - start <= budget; ++round) {
-            const PlanSpec base = best->spec;
-            const double before = best_us;
-            for (const PlanSpec &n : ordered(neighbours(base, A.dtype), false)) evaluate(n, "tune");
-            if (best_us > 0.99 * before) break;
-        }
+        auto tune = [&]() {
+            for (int round = 0; best && round < 3 && now_ms() - start <= budget; ++round) {
+                const PlanSpec base = best->spec;
+                const double before = best_us;
+                for (const PlanSpec &n : ordered(neighbours(base, A.dtype), false)) evaluate(n, "tune");
+                if (best_us > 0.99 * before) break;
+            }
+        };
+        tune();
+        bool late_winner = false;
+        for (const PlanSpec &c : far) late_winner = evaluate(c, "design") || late_winner;
+        if (late_winner) tune();
     } catch (...) {
         cleanup();
         throw;
