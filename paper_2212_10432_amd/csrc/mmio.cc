@@ -114,34 +114,83 @@ void read_matrix_market(const char *path, spmv_dtype_t dtype, MmCsr &out) {
     // an entry line is at least four bytes ("1 1\n"): a count the file cannot hold is malformed
     if (L > (long long)(end - cur) / 4 + 1)
         fail(SPMV_ERR_INVALID_ARG, "Matrix Market: the size line announces " + std::to_string(L) + " entries, more than the file can hold");
+    // The entry lines are parsed in pieces that start at line starts, one piece per thread at a time;
+    // a piece keeps its entries and, when a line is malformed, which of its entries that was.
+    struct Piece {
+        std::vector<int32_t> ri, ci;
+        std::vector<double> va;
+        long long bad_at = -1;   // number of well-formed entries of the piece in front of the first bad line
+        spmv_status_t bad_code = SPMV_OK;
+        const char *bad_text = "";
+    };
+    const int threads = default_threads();
+    const int64_t bytes = (int64_t)(end - cur);
+    const int64_t npieces = std::max<int64_t>(1, std::min<int64_t>((int64_t)threads * 4, bytes / (1 << 16)));
+    std::vector<const char *> cut((size_t)npieces + 1);
+    cut[0] = cur;
+    cut[(size_t)npieces] = end;
+    for (int64_t t = 1; t < npieces; ++t) {
+        const char *q = cur + bytes * t / npieces;
+        while (q < end && q[-1] != '\n') ++q;   // a piece starts right after a newline
+        cut[(size_t)t] = q;
+    }
+    for (int64_t t = 1; t <= npieces; ++t) cut[(size_t)t] = std::max(cut[(size_t)t], cut[(size_t)t - 1]);
+    std::vector<Piece> pieces((size_t)npieces);
+    const bool skew = sym == "skew-symmetric";
+    parallel_for(npieces, 1, threads, [&](int64_t tb, int64_t te, int) {
+        for (int64_t t = tb; t < te; ++t) {
+            Piece &pc = pieces[(size_t)t];
+            const char *c2 = cut[(size_t)t], *e2 = cut[(size_t)t + 1], *lb = nullptr, *le = nullptr;
+            auto bad = [&](spmv_status_t code, const char *text) {
+                pc.bad_at = (long long)pc.ri.size();
+                pc.bad_code = code;
+                pc.bad_text = text;
+            };
+            while (pc.bad_at < 0 && next_line(c2, e2, lb, le)) {
+                if (lb == le || *lb == '%') continue;
+                char *q = nullptr;
+                errno = 0;
+                const long long i = std::strtoll(lb, &q, 10);
+                const char *q1 = q;
+                const long long j = std::strtoll(q1, &q, 10);
+                // a number that starts after the end of this line was taken from the next one
+                if (q1 == lb || q == q1 || errno || q > le) { bad(SPMV_ERR_INVALID_ARG, "bad entry line"); break; }
+                double v = 1.0;
+                if (!pattern) {
+                    const char *q2 = q;
+                    v = std::strtod(q2, &q);
+                    if (q == q2 || q > le) { bad(SPMV_ERR_INVALID_ARG, "an entry has no value"); break; }
+                }
+                if (i < 1 || i > M || j < 1 || j > N) { bad(SPMV_ERR_BAD_CSR, "an entry lies outside the matrix"); break; }
+                if (skew && i == j) { bad(SPMV_ERR_INVALID_ARG, "a skew-symmetric file stores no diagonal entry"); break; }
+                pc.ri.push_back((int32_t)(i - 1));
+                pc.ci.push_back((int32_t)(j - 1));
+                pc.va.push_back(v);
+            }
+        }
+    });
+    // in file order: the first L entries count, a malformed line among them is an error, what follows
+    // the L-th entry is not looked at
+    long long seen = 0;
+    for (const Piece &pc : pieces) {
+        if (seen >= L) break;
+        const long long take = std::min<long long>(L - seen, (long long)pc.ri.size());
+        if (pc.bad_at >= 0 && pc.bad_at < L - seen)
+            fail(pc.bad_code, "Matrix Market: entry " + std::to_string(seen + pc.bad_at + 1) + ": " + pc.bad_text);
+        seen += take;
+    }
+    if (seen != L) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: the file ends after " + std::to_string(seen) + " of " + std::to_string(L) + " entries");
     ri.reserve((size_t)L);
     ci.reserve((size_t)L);
     va.reserve((size_t)L);
-    long long seen = 0;
-    while (seen < L && next_line(cur, end, b, e)) {
-        if (b == e || *b == '%') continue;
-        char *q = nullptr;
-        errno = 0;
-        const long long i = std::strtoll(b, &q, 10);
-        const char *q1 = q;
-        const long long j = std::strtoll(q1, &q, 10);
-        if (q1 == b || q == q1 || errno || q > e) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: bad entry line " + std::to_string(seen + 1));
-        double v = 1.0;
-        if (!pattern) {
-            const char *q2 = q;
-            v = std::strtod(q2, &q);
-            if (q == q2 || q > e) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: entry " + std::to_string(seen + 1) + " has no value");
-        }
-        if (i < 1 || i > M || j < 1 || j > N)
-            fail(SPMV_ERR_BAD_CSR, "Matrix Market: entry " + std::to_string(seen + 1) + " lies outside the matrix");
-        if (sym == "skew-symmetric" && i == j)
-            fail(SPMV_ERR_INVALID_ARG, "Matrix Market: a skew-symmetric file stores no diagonal entry");
-        ri.push_back((int32_t)(i - 1));
-        ci.push_back((int32_t)(j - 1));
-        va.push_back(v);
-        ++seen;
+    for (const Piece &pc : pieces) {
+        const size_t take = (size_t)std::min<long long>(L - (long long)ri.size(), (long long)pc.ri.size());
+        ri.insert(ri.end(), pc.ri.begin(), pc.ri.begin() + (std::ptrdiff_t)take);
+        ci.insert(ci.end(), pc.ci.begin(), pc.ci.begin() + (std::ptrdiff_t)take);
+        va.insert(va.end(), pc.va.begin(), pc.va.begin() + (std::ptrdiff_t)take);
+        if ((long long)ri.size() >= L) break;
     }
-    if (seen != L) fail(SPMV_ERR_INVALID_ARG, "Matrix Market: the file ends after " + std::to_string(seen) + " of " + std::to_string(L) + " entries");
+    pieces.clear();
     // expand the symmetric forms
     if (sym != "general") {
         const double s = sym == "symmetric" ? 1.0 : -1.0;
@@ -155,12 +204,6 @@ void read_matrix_market(const char *path, spmv_dtype_t dtype, MmCsr &out) {
     }
     const int64_t nnz = (int64_t)ri.size();
     if (nnz >= ((int64_t)1 << 31)) fail(SPMV_ERR_UNSUPPORTED, "Matrix Market: nnz must be below 2^31");
-    // CSR: rows ascending, columns ascending inside a row, repeated positions in file order
-    std::vector<int64_t> order((size_t)nnz);
-    std::iota(order.begin(), order.end(), (int64_t)0);
-    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t c) {
-        return ri[(size_t)a] != ri[(size_t)c] ? ri[(size_t)a] < ri[(size_t)c] : ci[(size_t)a] < ci[(size_t)c];
-    });
     const size_t vs = dtype == SPMV_F64 ? 8 : 4;
     out.nrows = M;
     out.ncols = N;
@@ -175,14 +218,29 @@ void read_matrix_market(const char *path, spmv_dtype_t dtype, MmCsr &out) {
         out = MmCsr();
         fail(SPMV_ERR_ALLOC, "host allocation failed");
     }
+    // CSR: rows ascending (a counting sort, which keeps the file order inside a row), then columns
+    // ascending inside a row with repeated positions in file order (a stable sort per row, rows in parallel)
     for (int64_t k = 0; k < nnz; ++k) out.row_ptr[ri[(size_t)k] + 1] += 1;
     for (int64_t r = 0; r < M; ++r) out.row_ptr[r + 1] += out.row_ptr[r];
-    for (int64_t k = 0; k < nnz; ++k) {
-        const size_t src = (size_t)order[(size_t)k];
-        out.col[k] = ci[src];
-        if (dtype == SPMV_F64) ((double *)out.val)[k] = va[src];
-        else ((float *)out.val)[k] = (float)va[src];
+    std::vector<int32_t> where((size_t)nnz);
+    {
+        std::vector<int32_t> fill(out.row_ptr, out.row_ptr + M);
+        for (int64_t k = 0; k < nnz; ++k) where[(size_t)fill[(size_t)ri[(size_t)k]]++] = (int32_t)k;
     }
+    parallel_for(M, 4096, threads, [&](int64_t rb, int64_t re, int) {
+        for (int64_t r = rb; r < re; ++r) {
+            int32_t *w0 = where.data() + out.row_ptr[r], *w1 = where.data() + out.row_ptr[r + 1];
+            bool sorted = true;
+            for (int32_t *w = w0; w + 1 < w1 && sorted; ++w) sorted = ci[(size_t)w[0]] <= ci[(size_t)w[1]];
+            if (!sorted) std::stable_sort(w0, w1, [&](int32_t a, int32_t c) { return ci[(size_t)a] < ci[(size_t)c]; });
+            for (int64_t k = out.row_ptr[r]; k < out.row_ptr[r + 1]; ++k) {
+                const size_t src = (size_t)where[(size_t)k];
+                out.col[k] = ci[src];
+                if (dtype == SPMV_F64) ((double *)out.val)[k] = va[src];
+                else ((float *)out.val)[k] = (float)va[src];
+            }
+        }
+    });
 }
 
 }  // namespace spmv

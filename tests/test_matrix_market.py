@@ -138,3 +138,43 @@ def test_command_line_host_only(tmp_path):
     d = json.loads(out.stdout)
     assert d["nrows"] == 300 and d["nnz"] == 2000 and d["spec"].startswith("light=sell,sigma=64")
     assert "BMW_PAD" in d["operators"]
+
+
+def test_large_file_parsed_in_pieces(tmp_path):
+    """A file of several megabytes (many pieces for the threaded parser), comments and blank lines between the
+    entries, repeated positions, CRLF ends: same matrix as scipy reads; a malformed line is reported with its
+    entry number; what follows the announced entries is not looked at."""
+    rng = np.random.default_rng(9)
+    nrows, ncols, n = 3000, 2500, 250_000
+    i = rng.integers(1, nrows + 1, n); j = rng.integers(1, ncols + 1, n); v = rng.integers(-99, 100, n)
+    lines = [f"{a} {b} {c}.5" for a, b, c in zip(i, j, v)]
+    body = []
+    for k, l in enumerate(lines):
+        body.append(l)
+        if k % 5000 == 17:
+            body += ["% a comment in the middle", ""]
+    path = str(tmp_path / "big.mtx")
+    with open(path, "w", newline="") as f:
+        f.write("%%MatrixMarket matrix coordinate real general\r\n")
+        f.write(f"{nrows} {ncols} {n}\r\n")
+        f.write("\r\n".join(body) + "\r\n")
+        f.write("this line comes after the last announced entry and is never parsed\r\n")
+    assert os.path.getsize(path) > 3_000_000
+    nr, nc, rp, ci, va = lib.spmv_mm_read(path, np.float64)
+    want = sp.coo_matrix((v + np.where(v >= 0, 0.5, -0.5), (i - 1, j - 1)), shape=(nrows, ncols)).tocsr()
+    want.sort_indices()
+    got = as_csr(nr, nc, rp, ci, va)
+    assert np.array_equal(got.indptr, want.indptr) and np.array_equal(got.indices, want.indices)
+    assert np.allclose(got.data, want.data, rtol=0, atol=0)
+    for r in range(0, nr, 97):                      # columns ascend inside a row, repeats allowed
+        assert np.all(np.diff(ci[rp[r]:rp[r + 1]]) >= 0)
+    # the same file with entry 200001 broken
+    bad = list(lines)
+    bad[200_000] = "12 x 1.0"
+    with open(path, "w") as f:
+        f.write("%%MatrixMarket matrix coordinate real general\n")
+        f.write(f"{nrows} {ncols} {n}\n")
+        f.write("\n".join(bad) + "\n")
+    with pytest.raises(lib.SpmvError) as e:
+        lib.spmv_mm_read(path, np.float64)
+    assert e.value.status == lib.SPMV_ERR_INVALID_ARG and "200001" in str(e.value)
