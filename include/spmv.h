@@ -91,6 +91,11 @@ typedef struct {
      * appended to this file (census features, spec, microseconds).  NULL: SPMV_COST_LOG, else none. */
     const char *cost_model_path;
     const char *cost_log_path;
+    /* Non-zero (or the environment variable SPMV_SEARCH_COLD=1): candidates whose arrays, x and y would
+     * fit the 256 MB memory-side cache are timed one run at a time with 512 MB streamed through the
+     * cache before each, i.e. as a run that finds nothing in it.  Zero: candidates are timed back to back
+     * on the same buffers, as an iterative solver would run them. */
+    int search_cold;
 } spmv_options_t;
 
 /*

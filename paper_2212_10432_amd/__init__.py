@@ -41,7 +41,7 @@ class spmv_options_t(ctypes.Structure):
                 ("search_repeats", ctypes.c_int), ("host_threads", ctypes.c_int),
                 ("dev_alloc", _ALLOC_FN), ("dev_free", _FREE_FN), ("user", ctypes.c_void_p),
                 ("verbosity", ctypes.c_int), ("host_only", ctypes.c_int),
-                ("cost_model_path", ctypes.c_char_p), ("cost_log_path", ctypes.c_char_p)]
+                ("cost_model_path", ctypes.c_char_p), ("cost_log_path", ctypes.c_char_p), ("search_cold", ctypes.c_int)]
 
 
 # corpus of timed candidates shipped with the package: the search's cost model is trained from it
@@ -143,7 +143,8 @@ def _dtype_code(dt) -> int:
 
 def spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, *, force_plan=None,
                      search_budget_ms=0.0, search_repeats=0, host_threads=0, verbosity=0,
-                     host_only=False, nnz=None, allocator=None, cost_model="default", cost_log=None) -> int:
+                     host_only=False, nnz=None, allocator=None, cost_model="default", cost_log=None,
+                     search_cold=False) -> int:
     """Returns an opaque plan handle (int).  row_ptr / col_idx / values are host NumPy arrays.
     allocator = (alloc(nbytes) -> device address or 0, free(address)): Python callables the library
     uses for every device array of the plan (kept alive until spmv_plan_destroy)."""
@@ -170,6 +171,7 @@ def spmv_plan_create(nrows, ncols, row_ptr, col_idx, values, *, force_plan=None,
         cost_model = COST_CORPUS if os.path.exists(COST_CORPUS) else None
     opts.cost_model_path = os.fsencode(cost_model) if cost_model else None
     opts.cost_log_path = os.fsencode(cost_log) if cost_log else None
+    opts.search_cold = int(bool(search_cold))
     keep = None
     if allocator is not None:
         alloc_py, free_py = allocator

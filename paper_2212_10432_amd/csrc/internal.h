@@ -243,7 +243,12 @@ int stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps, d
 std::vector<PlanSpec> enumerate_candidates(const Census &cen, spmv_dtype_t dtype);
 std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spmv_options_t &opts,
                                   const Allocator &mem, int threads);
-double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream);
+// flush, when not NULL: flush_bytes of zero-filled device memory streamed through the caches before every
+// timed run (each run is then timed alone).
+double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream, void *flush = nullptr,
+                 size_t flush_bytes = 0);
+// Reads `bytes` bytes of the zero-filled buffer `buf` (kernels.hip).  Returns a hipError_t as int.
+int flush_read(void *buf, size_t bytes, void *stream);
 
 // ---- learned cost model of the search (cost.cc) -----------------------------------------------
 struct CostCensus {   // what a corpus line keeps of a census

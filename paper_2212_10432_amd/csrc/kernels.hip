@@ -365,6 +365,14 @@ __global__ __launch_bounds__(kWG) void k_stream_copy(const ceil_f4 *__restrict__
 
 }  // namespace
 
+int flush_read(void *buf, size_t bytes, void *stream) {
+    const int64_t n16 = (int64_t)(bytes / 16);
+    if (n16 == 0) return 0;
+    const unsigned grid = (unsigned)((n16 + kWG * 8 - 1) / (kWG * 8));
+    k_stream_read<<<grid, kWG, 0, (hipStream_t)stream>>>((const ceil_f4 *)buf, n16, (float *)buf);
+    return (int)hipGetLastError();
+}
+
 // Reads `bytes` bytes, then copies bytes/2 to the other half of the same buffer; best of `repeats`
 // timed launches each.  Returns a hipError_t as int.
 int stream_ceiling(size_t bytes, int repeats, void *stream, double *read_gbps, double *copy_gbps) {

@@ -416,7 +416,7 @@ static std::vector<PlanSpec> neighbours(const PlanSpec &b, spmv_dtype_t dtype) {
     return out;
 }
 
-double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream) {
+double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *stream, void *flush, size_t flush_bytes) {
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
@@ -434,10 +434,12 @@ double time_plan(const Plan &plan, const void *x, void *y, int repeats, void *st
     run();
     run();
     std::vector<double> samples;
+    if (flush) repeats = std::max(repeats, 61);   // single cold runs scatter more than batches of warm ones
     for (int r = 0; r < repeats; ++r) {
-        // batch enough runs that a sample lasts about a millisecond
+        // batch enough runs that a sample lasts about a millisecond (cold: one run after a flush)
         int m = 1;
-        if (!samples.empty() && samples.back() < 500.0) m = (int)std::min(64.0, 500.0 / std::max(samples.back(), 5.0)) + 1;
+        if (flush) (void)flush_read(flush, flush_bytes, stream);
+        else if (!samples.empty() && samples.back() < 500.0) m = (int)std::min(64.0, 500.0 / std::max(samples.back(), 5.0)) + 1;
         (void)hipEventRecord(e0, st);
         for (int i = 0; i < m; ++i) run();
         (void)hipEventRecord(e1, st);
@@ -501,7 +503,14 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
     void *x = mem.alloc(std::max<size_t>((size_t)A.ncols * v, 16), mem.user);
     void *y = mem.alloc(std::max<size_t>((size_t)A.nrows * v, 16), mem.user);
     hipStream_t st = nullptr;
+    // cold timing of candidates that the memory-side cache could hold (options / SPMV_SEARCH_COLD)
+    constexpr int64_t kCacheBytes = (int64_t)256 << 20;
+    constexpr size_t kFlushBytes = (size_t)512 << 20;
+    const char *cold_env = std::getenv("SPMV_SEARCH_COLD");
+    const bool cold = opts.search_cold != 0 || (cold_env && cold_env[0] == '1');
+    void *flush = nullptr;
     auto cleanup = [&]() {
+        if (flush) mem.free(flush, mem.user);
         if (st) (void)hipStreamDestroy(st);
         if (x) mem.free(x, mem.user);
         if (y) mem.free(y, mem.user);
@@ -552,7 +561,17 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
             return false;
         }
         l.build_ms = now_ms() - t0;
-        l.run_us = time_plan(*plan, x, y, repeats, st);
+        int64_t moved = (int64_t)(A.nrows + A.ncols) * (int64_t)v;
+        for (const Part &q : plan->parts) moved += q.bytes;
+        const bool cold_run = cold && moved < kCacheBytes;
+        if (cold_run && !flush) {   // allocated when the first small candidate shows up
+            flush = mem.alloc(kFlushBytes, mem.user);
+            if (flush && hipMemset(flush, 0, kFlushBytes) != hipSuccess) {
+                mem.free(flush, mem.user);
+                flush = nullptr;
+            }
+        }
+        l.run_us = time_plan(*plan, x, y, repeats, st, cold_run ? flush : nullptr, kFlushBytes);
         corpus_lines.push_back(cost_line(cc, l.spec, l.run_us));
         if (opts.verbosity > 0)
             std::fprintf(stderr, "[spmv search] %-6s %-70s build %8.1f ms  run %10.2f us  predicted %10.2f us\n", tag, l.spec.c_str(),

@@ -10,6 +10,7 @@ int launch_jit(const Part &, spmv_dtype_t, int64_t, int64_t, const void *, void 
 int prepare_device() { return 1; }
 int static_scratch(void **) { return 1; }
 int stream_ceiling(size_t, int, void *, double *, double *) { return 1; }
+int flush_read(void *, size_t, void *) { return 1; }
 const char *hip_error_text(int) { return "no device code in the sanitizer build"; }
 
 }  // namespace spmv

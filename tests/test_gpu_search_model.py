@@ -47,3 +47,26 @@ def test_second_search_uses_the_corpus_of_the_first(tmp_path, name):
     torch.cuda.synchronize()
     assert np.array_equal(yd.cpu().numpy(), oracle.spmv(m.row_ptr, m.col_idx, m.values, x, threads=8))
     P2.destroy()
+
+
+@pytest.mark.gpu
+def test_cold_search_times_cache_sized_candidates_one_run_at_a_time():
+    """search_cold: the candidates of a matrix that fits the memory-side cache are timed after a flush; the
+    plan it keeps is correct, and the times it logs are not below the warm ones (the cache only helps)."""
+    m = inputs.SMALL["C2"]()
+    x = inputs.vector(m.ncols)
+    dev = torch.device("cuda:0")
+    xd = torch.from_numpy(x).to(dev)
+    logs = {}
+    for cold in (False, True):
+        P = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, search_budget_ms=3000, search_cold=cold, cost_model=None)
+        yd = torch.full((m.nrows,), float("nan"), dtype=torch.float64, device=dev)
+        P.run(xd, yd)
+        torch.cuda.synchronize()
+        ok, worst = oracle.check(yd.cpu().numpy(), m.row_ptr, m.col_idx, m.values, x)
+        assert ok, worst
+        logs[cold] = {c["spec"]: c["run_us"] for c in P.describe()["search"] if c["run_us"] > 0}
+        P.destroy()
+    both = set(logs[False]) & set(logs[True])
+    assert len(both) >= 3
+    assert sum(logs[True][s] >= 0.8 * logs[False][s] for s in both) >= len(both) - 1
