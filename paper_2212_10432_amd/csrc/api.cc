@@ -100,7 +100,7 @@ std::string describe_json(const Plan &plan) {
     for (size_t i = 0; i < plan.log.size(); ++i) {
         const CandidateLog &l = plan.log[i];
         o << (i ? ", " : "") << "{\"spec\": \"" << json_escape(l.spec) << "\", \"build_ms\": " << l.build_ms
-          << ", \"run_us\": " << l.run_us << ", \"pred_us\": " << l.pred_us << ", \"note\": \"" << json_escape(l.note) << "\"}";
+          << ", \"run_us\": " << l.run_us << ", \"pred_us\": " << l.pred_us << ", \"playoff_us\": " << l.playoff_us << ", \"note\": \"" << json_escape(l.note) << "\"}";
     }
     o << "]}";
     return o.str();

@@ -184,6 +184,7 @@ struct CandidateLog {
     std::string spec;
     double build_ms = 0, run_us = -1;
     double pred_us = -1;      // the cost model's prediction (-1: no model)
+    double playoff_us = -1;   // median of its three times in the play-off of the near-ties (-1: did not take part)
     std::string note;
 };
 

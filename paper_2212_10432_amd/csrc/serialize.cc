@@ -4,7 +4,7 @@
 // codes can be directly called"; artifact description); here the kernels are part of the library,
 // so the file holds the plan spec, the census, the launch list and every format array.
 //
-// Layout (little endian): magic "SPMVPLN2", u64 payload size, u64 FNV-1a hash of the payload, then
+// Layout (little endian): magic "SPMVPLN3", u64 payload size, u64 FNV-1a hash of the payload, then
 // the payload: scalars and strings in the order written by save_plan below, every array as
 // (name, element size, count, flag, raw bytes).  Pointers inside a launch record are stored as
 // indices into the array list (-1: none); scratch buffers are stored as sizes only.
@@ -17,7 +17,7 @@
 namespace spmv {
 namespace {
 
-constexpr char kMagic[8] = {'S', 'P', 'M', 'V', 'P', 'L', 'N', '2'};
+constexpr char kMagic[8] = {'S', 'P', 'M', 'V', 'P', 'L', 'N', '3'};
 
 uint64_t fnv1a(const unsigned char *p, size_t n) {
     uint64_t h = 1469598103934665603ull;
@@ -166,6 +166,7 @@ void save_plan(const Plan &plan, const char *path) {
         w.f64(l.build_ms);
         w.f64(l.run_us);
         w.f64(l.pred_us);
+        w.f64(l.playoff_us);
         w.str(l.note);
     }
     FILE *f = std::fopen(path, "wb");
@@ -291,6 +292,7 @@ std::unique_ptr<Plan> load_plan(const char *path, const Allocator &mem) {
         l.build_ms = r.f64();
         l.run_us = r.f64();
         l.pred_us = r.f64();
+        l.playoff_us = r.f64();
         l.note = r.str();
         plan->log.push_back(l);
     }

@@ -21,7 +21,7 @@ def test_schema_and_operator_names():
     L = np.diff(m.row_ptr)
     assert c["max_len"] == L.max() and c["min_len"] == L.min() and abs(c["mean_len"] - L.mean()) < 1e-9 * L.mean()
     assert c["irregular"] is True and abs(c["var_len"] - L.var()) < 1e-9 * L.var()
-    assert d["search"] == [{"spec": d["spec"], "build_ms": 0, "run_us": -1, "pred_us": -1, "note": "forced"}]
+    assert d["search"] == [{"spec": d["spec"], "build_ms": 0, "run_us": -1, "pred_us": -1, "playoff_us": -1, "note": "forced"}]
     # the spec string round-trips
     P2 = lib.Plan(m.nrows, m.ncols, m.row_ptr, m.col_idx, m.values, host_only=True, force_plan=d["spec"])
     assert P2.describe()["spec"] == d["spec"]

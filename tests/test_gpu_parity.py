@@ -46,6 +46,18 @@ for _n in TREES:
 CASES = [(n, s) for n in SPECS for s in SPECS[n]]
 
 
+def _check_kept(kept, timed):
+    """The first pass keeps the earlier of two near-ties (a later one must be 0.5 % faster); up to three candidates
+    within 3 % of that one meet the kept plan again, one after the other, in a play-off that a challenger wins
+    only by more than 0.5 % (the times of different turns scatter by a percent or so among themselves)."""
+    assert all(kept["run_us"] <= 1.03 / 0.995 * c["run_us"] for c in timed)
+    field = [c for c in timed if c["playoff_us"] > 0]
+    if field:
+        assert kept["playoff_us"] > 0 and len(field) <= 4 and all(0.97 * kept["playoff_us"] <= c["playoff_us"] for c in field)
+    else:
+        assert all(0.995 * kept["run_us"] <= c["run_us"] for c in timed)
+
+
 def gpu_spmv(m, vals, x, spec=None, runs=1, **kw):
     """Returns (list of y as NumPy arrays, one per run; plan description)."""
     dev = torch.device("cuda:0")
@@ -92,7 +104,7 @@ def test_searched_plan_matches_oracle(name):
     timed = [c for c in d["search"] if c["run_us"] >= 0]
     kept = [c for c in timed if c["note"] == "kept"]
     assert len(kept) == 1 and kept[0]["spec"] == d["spec"]
-    assert all(0.995 * kept[0]["run_us"] <= c["run_us"] for c in timed)      # near-ties keep the earlier candidate
+    _check_kept(kept[0], timed)
 
 
 def test_device_arrays_equal_host_only_arrays():
