@@ -208,6 +208,9 @@ spmv_status_t spmv_plan_destroy(spmv_plan_t *plan);
 /*
  * JSON description: the plan-spec string, the same design spelled as a chain of the paper's
  * operators (Table II names), census statistics, per-part sizes and the search log.
+ * An entry of "search": "spec", "build_ms", "run_us" (median time; -1: not timed), "pred_us" (the cost
+ * model's prediction; -1: no model), "playoff_us" (median in the play-off of the near-ties at the end of
+ * the search; -1: did not take part) and "note" ("kept", "forced", or why it was skipped or rejected).
  * Writes at most cap bytes including the terminating NUL; *needed (may be NULL) receives the
  * full size including the NUL.
  */
