@@ -534,7 +534,10 @@ void build_stripe(Plan &plan, const HostCsr &A, const std::vector<int32_t> &hrow
                   bool acc, const std::vector<int64_t> &lens, int threads, HeavyFold *fold = nullptr) {
     const int64_t nh = (int64_t)hrows.size();
     if (nh == 0) return;
-    if ((size_t)tile * sizeof(T) > 65536) fail(SPMV_ERR_UNSUPPORTED, "heavy: tile does not fit 64 KiB of LDS");
+    // the x tile and one accumulator per heavy row share the 160 KiB of a compute unit (tiles above 64 KiB
+    // leave room for one workgroup only, which then has 1024 lanes)
+    if (((size_t)tile + (size_t)hrows.size()) * sizeof(T) > 160 * 1024 || (size_t)tile * sizeof(T) > 128 * 1024)
+        fail(SPMV_ERR_UNSUPPORTED, "heavy: x tile and row accumulators do not fit the LDS");
     if (nh > 8192) fail(SPMV_ERR_UNSUPPORTED, "heavy: more than 8192 heavy rows (their accumulators live in LDS)");
     const int64_t ns = (A.ncols + tile - 1) / tile;
     int64_t total = 0;

@@ -283,7 +283,7 @@ static std::vector<PlanSpec> leaf_neighbours(const PlanSpec &b, spmv_dtype_t dty
             p.heavy = b.heavy / 4 * 3;   // the heavy part holds at most 8192 rows: half the threshold often has too many
             add(p);
         }
-        if (b.tile * 2 * vsize <= 65536) {
+        if (b.tile * 2 * vsize <= 131072) {   // above 64 KiB one workgroup of 1024 lanes per compute unit
             p = b;
             p.tile = b.tile * 2;
             add(p);

@@ -30,7 +30,7 @@ SPECS = {
            "light=csrv,lpr=16"],
     "C5": ["heavy=64,tile=2048,light=wbm", "light=bin,smax=16,sigma=256,chunk=1024,wg=1", "heavy=64,tile=2048,light=xl,w=2048,rb=4096,chunk=4096", "light=xl,w=4096,rb=16384", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
            "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=64,tile=2048,hd=1,light=xl", "heavy=64,tile=8192,hd=1,light=csrv",
-           "heavy=64,tile=8192,hd=1,piece=64,light=csrv", "heavy=64,tile=2048,piece=8,light=xl,w=2048,rb=4096"],
+           "heavy=64,tile=8192,hd=1,piece=64,light=csrv", "heavy=64,tile=2048,piece=8,light=xl,w=2048,rb=4096", "heavy=64,tile=16384,hd=1,light=csrv"],
 }
 
 

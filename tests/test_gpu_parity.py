@@ -20,12 +20,12 @@ SPECS = {
            "light=bin,smax=4,sigma=128"],
     "C2": ["dia=1,dia_fill=0.999,light=wbm", "dia=1,dia_fill=0.999,light=xl,w=64,rb=64", "light=xl,w=512,rb=1024", "dia=1,dia_fill=0.999,light=coo", "dia=1,dia_fill=0.999,light=xnb,k=8,r=4", "light=xnb,k=24,r=16", "dia=1,dia_fill=0.999,light=nnzb,r=4", "light=nnzb,r=16", "dia=1,dia_fill=0.999,light=xs,k=8,sigma=64", "light=xs,k=24,sigma=4096", "dia=1,light=sell", "light=sell,sigma=64", "light=csrv,lpr=2,remap=1", "dia=1,dia_fill=0.999,light=csrv,lpr=1",
            "dia=1,drows=2,light=sell", "dia=1,dia_fill=0.999,drows=4,light=csrv,lpr=1"],
-    "C3": ["heavy=1024,tile=2048,piece=32,light=xl", "heavy=512,tile=4096,hd=1,piece=64,light=csrv,lpr=8", "light=wbm", "heavy=1024,tile=2048,light=wbm", "light=bin,smax=16,sigma=512,chunk=256,wg=1", "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=0,wg=1", "light=csrv,lpr=256,chunk=512", "light=xl,w=4096,rb=8192", "heavy=1024,tile=2048,light=xl,w=16384,rb=16384,chunk=20000", "heavy=1024,tile=2048,light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=8192", "light=csrv,chunk=512", "light=csrv,lpr=32", "light=bin,smax=16,sigma=512,chunk=256",
+    "C3": ["heavy=1024,tile=16384,piece=32,light=sell,sigma=128", "heavy=1024,tile=2048,piece=32,light=xl", "heavy=512,tile=4096,hd=1,piece=64,light=csrv,lpr=8", "light=wbm", "heavy=1024,tile=2048,light=wbm", "light=bin,smax=16,sigma=512,chunk=256,wg=1", "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=0,wg=1", "light=csrv,lpr=256,chunk=512", "light=xl,w=4096,rb=8192", "heavy=1024,tile=2048,light=xl,w=16384,rb=16384,chunk=20000", "heavy=1024,tile=2048,light=xl", "light=xnb,k=16,r=8", "heavy=1024,tile=2048,light=xnb,k=8,r=16", "light=nnzb,r=8", "light=nnzb,r=16", "heavy=1024,tile=2048,light=nnzb,r=4", "light=xs,k=16,sigma=512", "heavy=1024,tile=2048,light=xs,k=8,sigma=8192", "light=csrv,chunk=512", "light=csrv,lpr=32", "light=bin,smax=16,sigma=512,chunk=256",
            "heavy=1024,tile=2048,light=bin,smax=8,sigma=256,chunk=512", "heavy=600,tile=1024,light=csrv,lpr=8",
            "heavy=256,tile=512,light=sell,sigma=128", "heavy=2048,tile=8192,light=bin,chunk=1024", "heavy=1024,tile=2048,hd=1,light=xl", "heavy=256,tile=512,hd=1,light=sell,sigma=128"],
     "C4": ["light=bsell,block=3,sigma=256", "light=bsell,block=3,sigma=0,remap=1", "light=bsell,block=3,sigma=2048,xwin=1,remap=1", "light=sell,sigma=512",
            "light=csrv,lpr=16"],
-    "C5": ["heavy=64,tile=2048,piece=16,light=xl", "heavy=64,tile=8192,hd=1,piece=128,light=sell,sigma=1024", "heavy=64,tile=2048,light=wbm", "light=bin,smax=16,sigma=256,chunk=1024,wg=1", "heavy=64,tile=2048,light=xl,w=8192,rb=16384", "light=xl,w=2048,rb=4096,chunk=100000", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
+    "C5": ["heavy=64,tile=16384,hd=1,light=csrv", "heavy=64,tile=2048,piece=16,light=xl", "heavy=64,tile=8192,hd=1,piece=128,light=sell,sigma=1024", "heavy=64,tile=2048,light=wbm", "light=bin,smax=16,sigma=256,chunk=1024,wg=1", "heavy=64,tile=2048,light=xl,w=8192,rb=16384", "light=xl,w=2048,rb=4096,chunk=100000", "heavy=64,tile=2048,light=coo", "heavy=64,tile=2048,light=xnb,k=32,r=4", "heavy=64,tile=2048,light=nnzb,r=8", "heavy=64,tile=2048,light=xs,k=16,sigma=1024", "heavy=64,tile=2048,light=sell,sigma=1024", "light=bin,smax=16,sigma=256,chunk=1024",
            "heavy=1000,tile=4096,light=csrv,lpr=2", "heavy=100,tile=8192,light=bin,sigma=8192,remap=1", "heavy=64,tile=2048,hd=1,light=xl", "heavy=64,tile=8192,hd=1,light=csrv"],
 }
 # plan trees: ROW_DIV by length class, power-of-two BIN, the ratio cut after SORT, COL_DIV, nested
