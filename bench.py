@@ -36,7 +36,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--configs", default="C1,C2,C3,C4,C5,C5f32")
-    ap.add_argument("--budget-ms", type=float, default=8000.0, help="search budget per matrix")
+    ap.add_argument("--budget-ms", type=float, default=12000.0, help="search budget per matrix")
     ap.add_argument("--plan", default="", help="force this plan spec for every matrix (skips the search)")
     ap.add_argument("--plan-json", default="", help="JSON file {config: plan spec}: skip the search for those matrices")
     ap.add_argument("--save-plans", default="", help="write the chosen plan specs to this JSON file")

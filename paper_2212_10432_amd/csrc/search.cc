@@ -650,10 +650,10 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
         }
         for (const PlanSpec &c : near) evaluate(c, "design");
         // level two (Section VI-A: parameters of the kept design on a finer grid): halve and double
-        // every numeric parameter of the best plan, move to the best neighbour, repeat while that
-        // gains more than one percent and the budget lasts
+        // every numeric parameter of the best plan, move to the best neighbour, repeat while a
+        // neighbour is accepted and the budget lasts
         auto tune = [&]() {
-            for (int round = 0; best && round < 3 && now_ms() - start <= budget; ++round) {
+            for (int round = 0; best && round < 4 && now_ms() - start <= budget; ++round) {
                 const PlanSpec base = best->spec;
                 const double before = best_us;
                 for (const PlanSpec &n : ordered(neighbours(base, A.dtype), false)) {
@@ -663,7 +663,7 @@ std::unique_ptr<Plan> search_plan(const HostCsr &A, const Census &cen, const spm
                     if (cold && n.node == N_LEAF && n.dia && n.drows != base.drows) continue;
                     evaluate(n, "tune");
                 }
-                if (best_us > 0.99 * before) break;
+                if (best_us >= before) break;   // no neighbour was accepted (an accepted one is at least 0.5 % faster)
             }
         };
         tune();
